@@ -1,0 +1,181 @@
+/*
+ * agentx.h - C ABI of the MI355X extend / verify library.
+ *
+ * The library runs the target model's "extend" forward: T new tokens on top of a KV cache that
+ * already holds P earlier tokens.  That one call serves both halves of the paper's pipeline:
+ *   - prefill after prefix-cache reuse, where T is the uncached prompt suffix
+ *     (paper Sec. 2.3 "Prefix caching"; Sec. 4.2), and
+ *   - the verification phase of speculative decoding, where T = 1 + k: the most recent token
+ *     followed by k drafts from the n-gram lookup table (Sec. 2.3 "Speculative decoding",
+ *     Fig. 4; Sec. 4.3), after which rejected drafts are cut from the cache.
+ *
+ * Conventions
+ *   - Handles are opaque.  Every call returns ax_status; nothing throws or aborts.
+ *   - "device" pointers are HIP device allocations made by the caller (e.g. through PyTorch)
+ *     and BORROWED: weights, the KV pool memory, the workspace and every `out` buffer of
+ *     ax_extend*.  The library allocates no device memory.  It owns a few KB of pinned host
+ *     staging memory per model.
+ *   - "host" pointers (tokens, drafts, T_each, accepted, next_token) are ordinary host memory,
+ *     read or written before the call returns.
+ *   - `hip_stream` is a hipStream_t passed as void* (NULL = the default stream).  ax_extend*
+ *     only enqueues work; ax_verify waits for its own result.
+ *   - Calls on one model / pool must come from one host thread at a time.
+ *   - A call that fails with AX_ERR_INVALID, AX_ERR_OOM or AX_ERR_UNSUPPORTED has launched
+ *     nothing and has left every KV sequence exactly as it was.
+ *
+ * Decoder: pre-norm blocks with grouped-query attention (query head h reads KV head
+ * h / (n_q_heads / n_kv_heads)), rotary positions pairing (j, j + head_dim/2), SwiGLU MLP,
+ * RMSNorm, no biases, untied LM head.  Every matrix is row-major [out_features, in_features]
+ * and is applied as y = x * W^T.
+ */
+#ifndef AGENTX_H
+#define AGENTX_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    AX_OK = 0,
+    AX_ERR_INVALID = -1,     /* bad handle, NULL pointer, T <= 0, token id outside the vocabulary ... */
+    AX_ERR_OOM = -2,         /* not enough free KV blocks, or workspace / pool memory too small      */
+    AX_ERR_DEVICE = -3,      /* a HIP call failed                                                    */
+    AX_ERR_UNSUPPORTED = -4, /* shape the kernels do not cover (see ax_model_create)                 */
+    AX_ERR_STATE = -5        /* e.g. destroying a pool that still has live sequences                 */
+} ax_status;
+
+enum { AX_F32 = 0, AX_BF16 = 1 };            /* storage type of weights AND of the KV cache */
+
+enum {                                       /* what ax_extend writes to `out` (device memory)        */
+    AX_OUT_NONE = 0,                         /* nothing (building a prefix)                           */
+    AX_OUT_LAST_LOGITS = 1,                  /* float[n_seq][vocab]: last row of each sequence        */
+    AX_OUT_ALL_LOGITS = 2,                   /* float[sum T][vocab]                                   */
+    AX_OUT_LAST_ARGMAX = 3,                  /* int32[n_seq]: greedy token, lowest id on ties         */
+    AX_OUT_ALL_ARGMAX = 4                    /* int32[sum T]                                          */
+};
+
+typedef struct ax_model ax_model;
+typedef struct ax_pool ax_pool;
+typedef struct ax_kv ax_kv;
+
+typedef struct {
+    int n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ff, vocab;
+    float rms_eps, rope_base;
+    int dtype;        /* AX_F32 or AX_BF16                                                         */
+    int max_pos;      /* longest sequence (P + T) any KV of this model may reach                    */
+    int max_tokens;   /* most rows (sum of T over the sequences) one ax_extend* call may carry      */
+    int max_seqs;     /* most sequences one ax_extend_batch call may carry (>= 1)                   */
+} ax_model_config;
+
+/* Device pointers, borrowed for the life of the model.  Element type = config.dtype.
+ * Per-layer members are HOST arrays of n_layers device pointers (copied at create time). */
+typedef struct {
+    const void *tok_emb;            /* [vocab, d_model]                                             */
+    const void *lm_head;            /* [vocab, d_model]                                             */
+    const void *final_norm;         /* [d_model]                                                    */
+    const void *const *wqkv;        /* [(n_q + 2 n_kv) * head_dim, d_model]: q heads, k heads, v heads */
+    const void *const *wo;          /* [d_model, n_q * head_dim]                                    */
+    const void *const *w_gate;      /* [d_ff, d_model]                                              */
+    const void *const *w_up;        /* [d_ff, d_model]                                              */
+    const void *const *w_down;      /* [d_model, d_ff]                                              */
+    const void *const *norm_attn;   /* [d_model] gain of the norm before attention                  */
+    const void *const *norm_mlp;    /* [d_model] gain of the norm before the MLP                    */
+} ax_weights;
+
+/* Bytes of device workspace ax_model_create needs for this config; 0 if the config is invalid. */
+size_t ax_workspace_bytes(const ax_model_config *cfg);
+
+/* Build a model over borrowed weights.  `workspace` is device memory of at least
+ * ax_workspace_bytes(cfg) bytes, 256-byte aligned, owned by the caller and used by every call
+ * on this model (activations, rotary table, per-call descriptors, split-attention partials).
+ * AX_BF16 needs d_model, d_ff, head counts*head_dim and vocab to be multiples of 64 and
+ * head_dim in {64, 128}; AX_F32 takes any sizes with an even head_dim <= 256.
+ * Needs a GPU (uploads the rotary table).  Errors: INVALID, OOM (workspace too small),
+ * UNSUPPORTED, DEVICE. */
+ax_status ax_model_create(const ax_model_config *cfg, const ax_weights *weights,
+                          void *workspace, size_t workspace_bytes, ax_model **out);
+void ax_model_destroy(ax_model *m);
+
+/* ---- paged KV pool -------------------------------------------------------------------------
+ * The pool divides `dev_mem` into blocks of `block_tokens` positions (all layers, K and V).
+ * A sequence (ax_kv) is a list of block ids plus a length; blocks are reference counted so
+ * that sequences sharing a prefix share its blocks (prefix caching: the cache of a common
+ * prefix is valid for every continuation, Sec. 2.3).  Device layout, element type = dtype:
+ *   K: [layer][kv_head][block][token in block][head_dim]
+ *   V: [layer][kv_head][block][head_dim][token in block]      (token-minor)
+ * Block bookkeeping is host only and never touches or waits for the device.              */
+
+/* Bytes one block occupies = 2 * n_layers * n_kv_heads * head_dim * block_tokens * itemsize. */
+size_t ax_pool_block_bytes(const ax_model_config *cfg, int block_tokens);
+
+/* `dev_mem` may be NULL only for host-side bookkeeping tests (no ax_extend on such a pool).
+ * block_tokens must be 16.  The pool holds floor(bytes / block_bytes) blocks (>= 1).      */
+ax_status ax_pool_create(const ax_model_config *cfg, void *dev_mem, size_t bytes,
+                         int block_tokens, ax_pool **out);
+/* AX_ERR_STATE (and nothing destroyed) while sequences of the pool are alive. */
+ax_status ax_pool_destroy(ax_pool *p);
+/* Free blocks / total blocks / live sequences; any pointer may be NULL. */
+ax_status ax_pool_stats(const ax_pool *p, int64_t *free_blocks, int64_t *total_blocks,
+                        int64_t *live_seqs);
+
+/* New empty sequence. */
+ax_status ax_kv_alloc(ax_pool *p, ax_kv **out);
+/* New sequence holding the first n_tokens positions of src (-1 = all of them) by sharing its
+ * blocks (refcount + 1 each); no data moves.  A later append into a shared, partly filled
+ * last block copies that block first (copy on write).  Errors: INVALID (n_tokens > len). */
+ax_status ax_kv_fork(const ax_kv *src, int64_t n_tokens, ax_kv **out);
+/* Cut the sequence back to new_len <= len positions and release blocks wholly beyond it:
+ * rollback of rejected drafts (Sec. 2.3), or removal of the mismatched tail of a cached
+ * prompt (Sec. 4.2).  Device memory is not touched; stale slots are overwritten later. */
+ax_status ax_kv_truncate(ax_kv *kv, int64_t new_len);
+/* Length in tokens, or -1 for a bad handle. */
+int64_t ax_kv_len(const ax_kv *kv);
+/* Drop the sequence: refcount - 1 on each of its blocks, blocks reaching 0 return to the pool. */
+ax_status ax_kv_free(ax_kv *kv);
+/* Introspection for tests: copies up to cap block ids to ids (host), returns the block count
+ * (or -1); refcount of one block of a pool (or -1). */
+int64_t ax_kv_blocks(const ax_kv *kv, int32_t *ids, int64_t cap);
+int ax_pool_refcount(const ax_pool *p, int64_t block);
+/* Host half of an append, exposed so block logic can be tested without a GPU: reserves room
+ * for n more positions (allocating blocks, and replacing a shared partly filled last block by
+ * a private one), advances the length and reports the copy-on-write copy it would have
+ * launched as (*cow_src, *cow_dst), -1/-1 if none.  Errors: OOM with nothing changed. */
+ax_status ax_kv_reserve_host(ax_kv *kv, int64_t n, int32_t *cow_src, int32_t *cow_dst);
+
+/* ---- forward -------------------------------------------------------------------------------
+ * Runs tokens[0..T) (host, int32) at positions P..P+T-1 where P = ax_kv_len(kv), appends their
+ * K/V to kv (length becomes P + T) and writes what out_mode asks for to `out` (device).  Row i
+ * attends to positions 0..P+i.  kv must belong to a pool created with the same config as
+ * `model`.  Asynchronous on hip_stream.
+ * Errors: INVALID (T <= 0, T > max_tokens, P + T > max_pos, token outside [0, vocab), NULL out
+ * for a mode that writes), OOM (no free KV block; kv unchanged), DEVICE. */
+ax_status ax_extend(ax_model *model, ax_kv *kv, const int32_t *tokens, int T,
+                    int out_mode, void *out, void *hip_stream);
+
+/* The same for n sequences in one pass (weights are read once for all sum(T_each) rows).
+ * tokens_concat holds the sequences' tokens back to back; outputs are in the same order.
+ * The sequences must be distinct and live in one pool. */
+ax_status ax_extend_batch(ax_model *model, int n, ax_kv *const *kvs, const int32_t *tokens_concat,
+                          const int *T_each, int out_mode, void *out, void *hip_stream);
+
+/* One speculative round (Sec. 2.3 verification phase with greedy exact-match acceptance, as a
+ * lookup-table drafter has no logits of its own, Sec. 4.3).  kv holds everything before
+ * `pending`.  Runs [pending, drafts[0..k)] in one forward, takes the greedy token g_i after
+ * each row, accepts the longest prefix with drafts[i] == g_i, writes *accepted = a in 0..k
+ * and *next_token = g_a (host), and cuts kv back to P + 1 + a (prefix, pending, accepted
+ * drafts).  The round emits drafts[0..a) then *next_token, which becomes the next pending
+ * token and is not yet in kv.  k = 0 is plain one-token decoding (the fallback of Sec. 4.3).
+ * Waits for the result.  Errors as ax_extend; kv is unchanged on error. */
+ax_status ax_verify(ax_model *model, ax_kv *kv, int32_t pending, const int32_t *drafts, int k,
+                    int *accepted, int32_t *next_token, void *hip_stream);
+
+/* Text for the last failing call on this thread (static storage, never NULL). */
+const char *ax_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AGENTX_H */

@@ -1,0 +1,214 @@
+"""ctypes binding over the C ABI of libagentx.so (see include/agentx.h).
+
+Argument marshalling only: every step of the extend / verify path runs inside the library's
+HIP kernels.  PyTorch supplies device memory (weights, KV pool, workspace, outputs) and the
+stream.  There is no CPU fallback: a missing library raises at import of this module.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libagentx.so")
+
+AX_OK, AX_ERR_INVALID, AX_ERR_OOM, AX_ERR_DEVICE, AX_ERR_UNSUPPORTED, AX_ERR_STATE = 0, -1, -2, -3, -4, -5
+AX_F32, AX_BF16 = 0, 1
+AX_OUT_NONE, AX_OUT_LAST_LOGITS, AX_OUT_ALL_LOGITS, AX_OUT_LAST_ARGMAX, AX_OUT_ALL_ARGMAX = range(5)
+
+
+class ax_model_config(C.Structure):
+    _fields_ = [(n, C.c_int) for n in ("n_layers", "d_model", "n_q_heads", "n_kv_heads", "head_dim", "d_ff", "vocab")] + [
+        ("rms_eps", C.c_float), ("rope_base", C.c_float), ("dtype", C.c_int), ("max_pos", C.c_int),
+        ("max_tokens", C.c_int), ("max_seqs", C.c_int)]
+
+
+class ax_weights(C.Structure):
+    _fields_ = [("tok_emb", C.c_void_p), ("lm_head", C.c_void_p), ("final_norm", C.c_void_p)] + [
+        (n, C.POINTER(C.c_void_p)) for n in ("wqkv", "wo", "w_gate", "w_up", "w_down", "norm_attn", "norm_mlp")]
+
+
+def _load():
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2605_10380_amd.build` "
+                          "(there is no fallback path)")
+    lib = C.CDLL(LIB_PATH)
+    vp, i32p, i64 = C.c_void_p, C.POINTER(C.c_int32), C.c_int64
+    sig = {
+        "ax_last_error": (C.c_char_p, []),
+        "ax_workspace_bytes": (C.c_size_t, [C.POINTER(ax_model_config)]),
+        "ax_model_create": (C.c_int, [C.POINTER(ax_model_config), C.POINTER(ax_weights), vp, C.c_size_t, C.POINTER(vp)]),
+        "ax_model_destroy": (None, [vp]),
+        "ax_pool_block_bytes": (C.c_size_t, [C.POINTER(ax_model_config), C.c_int]),
+        "ax_pool_create": (C.c_int, [C.POINTER(ax_model_config), vp, C.c_size_t, C.c_int, C.POINTER(vp)]),
+        "ax_pool_destroy": (C.c_int, [vp]),
+        "ax_pool_stats": (C.c_int, [vp, C.POINTER(i64), C.POINTER(i64), C.POINTER(i64)]),
+        "ax_kv_alloc": (C.c_int, [vp, C.POINTER(vp)]),
+        "ax_kv_fork": (C.c_int, [vp, i64, C.POINTER(vp)]),
+        "ax_kv_truncate": (C.c_int, [vp, i64]),
+        "ax_kv_len": (i64, [vp]),
+        "ax_kv_free": (C.c_int, [vp]),
+        "ax_kv_blocks": (i64, [vp, i32p, i64]),
+        "ax_pool_refcount": (C.c_int, [vp, i64]),
+        "ax_kv_reserve_host": (C.c_int, [vp, i64, i32p, i32p]),
+        "ax_extend": (C.c_int, [vp, vp, i32p, C.c_int, C.c_int, vp, vp]),
+        "ax_extend_batch": (C.c_int, [vp, C.c_int, C.POINTER(vp), i32p, C.POINTER(C.c_int), C.c_int, vp, vp]),
+        "ax_dbg_gemm": (C.c_int, [C.c_int, C.c_int, vp, vp, vp, vp, C.c_int, C.c_int, C.c_int, vp]),
+        "ax_dbg_read": (C.c_int, [vp, C.c_int, vp, C.c_size_t]),
+        "ax_verify": (C.c_int, [vp, vp, C.c_int32, i32p, C.c_int, C.POINTER(C.c_int), i32p, vp]),
+    }
+    for name, (res, args) in sig.items():
+        fn = getattr(lib, name)
+        fn.restype, fn.argtypes = res, args
+    return lib
+
+
+lib = _load()
+
+
+class AxError(RuntimeError):
+    def __init__(self, status: int):
+        self.status = status
+        super().__init__(f"ax status {status}: {lib.ax_last_error().decode()}")
+
+
+def _check(status: int):
+    if status != AX_OK:
+        raise AxError(status)
+
+
+def make_config(shape, max_pos: int, max_tokens: int, max_seqs: int = 1) -> ax_model_config:
+    return ax_model_config(shape.n_layers, shape.d_model, shape.n_q_heads, shape.n_kv_heads, shape.head_dim,
+                           shape.d_ff, shape.vocab, shape.rms_eps, shape.rope_base,
+                           AX_F32 if shape.dtype == "f32" else AX_BF16, max_pos, max_tokens, max_seqs)
+
+
+def _i32(a):
+    a = np.ascontiguousarray(a, dtype=np.int32)
+    return a, a.ctypes.data_as(C.POINTER(C.c_int32))
+
+
+# ------------------------------------------------------------------ paged KV (host only)
+
+def ax_pool_block_bytes(cfg: ax_model_config, block_tokens: int = 16) -> int:
+    return lib.ax_pool_block_bytes(C.byref(cfg), block_tokens)
+
+
+def ax_pool_create(cfg: ax_model_config, dev_ptr: int, nbytes: int, block_tokens: int = 16) -> int:
+    out = C.c_void_p()
+    _check(lib.ax_pool_create(C.byref(cfg), C.c_void_p(dev_ptr), nbytes, block_tokens, C.byref(out)))
+    return out.value
+
+
+def ax_pool_destroy(pool: int):
+    _check(lib.ax_pool_destroy(pool))
+
+
+def ax_pool_stats(pool: int):
+    f, t, s = C.c_int64(), C.c_int64(), C.c_int64()
+    _check(lib.ax_pool_stats(pool, C.byref(f), C.byref(t), C.byref(s)))
+    return f.value, t.value, s.value
+
+
+def ax_kv_alloc(pool: int) -> int:
+    out = C.c_void_p()
+    _check(lib.ax_kv_alloc(pool, C.byref(out)))
+    return out.value
+
+
+def ax_kv_fork(src: int, n_tokens: int = -1) -> int:
+    out = C.c_void_p()
+    _check(lib.ax_kv_fork(src, n_tokens, C.byref(out)))
+    return out.value
+
+
+def ax_kv_truncate(kv: int, new_len: int):
+    _check(lib.ax_kv_truncate(kv, new_len))
+
+
+def ax_kv_len(kv: int) -> int:
+    return lib.ax_kv_len(kv)
+
+
+def ax_kv_free(kv: int):
+    _check(lib.ax_kv_free(kv))
+
+
+def ax_kv_blocks(kv: int):
+    n = lib.ax_kv_blocks(kv, None, 0)
+    if n < 0:
+        raise AxError(AX_ERR_INVALID)
+    ids = np.zeros(max(n, 1), dtype=np.int32)
+    lib.ax_kv_blocks(kv, ids.ctypes.data_as(C.POINTER(C.c_int32)), n)
+    return ids[:n]
+
+
+def ax_pool_refcount(pool: int, block: int) -> int:
+    return lib.ax_pool_refcount(pool, block)
+
+
+def ax_kv_reserve_host(kv: int, n: int):
+    s, d = C.c_int32(), C.c_int32()
+    _check(lib.ax_kv_reserve_host(kv, n, C.byref(s), C.byref(d)))
+    return s.value, d.value
+
+
+# ------------------------------------------------------------------ model and forward (GPU)
+
+def ax_workspace_bytes(cfg: ax_model_config) -> int:
+    return lib.ax_workspace_bytes(C.byref(cfg))
+
+
+def ax_model_create(cfg: ax_model_config, ptrs: dict, ws_ptr: int, ws_bytes: int) -> int:
+    """ptrs: {"tok_emb": int, ..., "wqkv": [int per layer], ...} of device addresses."""
+    w = ax_weights()
+    keep = []
+    for name in ("tok_emb", "lm_head", "final_norm"):
+        setattr(w, name, ptrs[name])
+    for name in ("wqkv", "wo", "w_gate", "w_up", "w_down", "norm_attn", "norm_mlp"):
+        arr = (C.c_void_p * cfg.n_layers)(*ptrs[name])
+        keep.append(arr)
+        setattr(w, name, C.cast(arr, C.POINTER(C.c_void_p)))
+    out = C.c_void_p()
+    _check(lib.ax_model_create(C.byref(cfg), C.byref(w), C.c_void_p(ws_ptr), ws_bytes, C.byref(out)))
+    return out.value
+
+
+def ax_model_destroy(model: int):
+    lib.ax_model_destroy(model)
+
+
+def ax_extend(model: int, kv: int, tokens, out_mode: int = AX_OUT_NONE, out_ptr: int = 0, stream: int = 0):
+    t, tp = _i32(tokens)
+    _check(lib.ax_extend(model, kv, tp, len(t), out_mode, C.c_void_p(out_ptr), C.c_void_p(stream)))
+
+
+def ax_extend_batch(model: int, kvs, tokens_concat, T_each, out_mode: int = AX_OUT_NONE, out_ptr: int = 0,
+                    stream: int = 0):
+    t, tp = _i32(tokens_concat)
+    te = (C.c_int * len(T_each))(*[int(v) for v in T_each])
+    ka = (C.c_void_p * len(kvs))(*kvs)
+    _check(lib.ax_extend_batch(model, len(kvs), ka, tp, te, out_mode, C.c_void_p(out_ptr), C.c_void_p(stream)))
+
+
+def ax_verify(model: int, kv: int, pending: int, drafts, stream: int = 0):
+    d, dp = _i32(drafts)
+    a, nxt = C.c_int(), C.c_int32()
+    _check(lib.ax_verify(model, kv, int(pending), dp if len(d) else None, len(d), C.byref(a), C.byref(nxt),
+                         C.c_void_p(stream)))
+    return a.value, nxt.value
+
+
+# ------------------------------------------------------------------ test-only entry points
+
+def ax_dbg_gemm(dtype: int, epilogue: int, A: int, W: int, W2: int, Cptr: int, M: int, N: int, K: int, stream: int = 0):
+    _check(lib.ax_dbg_gemm(dtype, epilogue, C.c_void_p(A), C.c_void_p(W), C.c_void_p(W2), C.c_void_p(Cptr), M, N, K,
+                           C.c_void_p(stream)))
+
+
+def ax_dbg_read(model: int, which: int, dst: np.ndarray):
+    assert dst.flags["C_CONTIGUOUS"]
+    _check(lib.ax_dbg_read(model, which, dst.ctypes.data_as(C.c_void_p), dst.nbytes))
+    return dst

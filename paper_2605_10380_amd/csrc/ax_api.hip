@@ -1,0 +1,577 @@
+// Host side of the C ABI: handle validation, paged-KV bookkeeping, per-call descriptors and the
+// kernel sequence of one extend forward.  No device memory is allocated here: weights, KV
+// pool and workspace are borrowed from the caller.
+#include "../../include/agentx.h"
+#include "../../include/agentx_debug.h"
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <vector>
+
+#include "block_manager.h"
+#include "kernels.h"
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+ax_status fail(ax_status st, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return st;
+}
+
+#define HIP_TRY(expr)                                                                       \
+    do {                                                                                    \
+        hipError_t e_ = (expr);                                                             \
+        if (e_ != hipSuccess) return fail(AX_ERR_DEVICE, "%s: %s", #expr, hipGetErrorString(e_)); \
+    } while (0)
+
+constexpr uint32_t MAGIC_MODEL = 0x41584d44, MAGIC_POOL = 0x4158504c, MAGIC_KV = 0x41584b56;
+constexpr int N_SLOTS = 4;            // staging ring for per-call descriptors
+constexpr int LOGIT_ROWS = 256;       // rows per LM-head pass when only the argmax is wanted
+constexpr int SPLIT_ITEMS = 2048;     // wavefronts the split attention aims for
+
+size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
+int isz(int dtype) { return dtype == AX_F32 ? 4 : 2; }
+
+bool config_ok(const ax_model_config* c, ax_status* why) {
+    *why = AX_ERR_INVALID;
+    if (!c) return false;
+    if (c->n_layers <= 0 || c->d_model <= 0 || c->n_q_heads <= 0 || c->n_kv_heads <= 0 ||
+        c->head_dim <= 0 || c->d_ff <= 0 || c->vocab <= 0 || c->max_pos <= 0 ||
+        c->max_tokens <= 0 || c->max_seqs <= 0)
+        return false;
+    if (c->n_q_heads % c->n_kv_heads != 0) return false;
+    if (c->dtype != AX_F32 && c->dtype != AX_BF16) return false;
+    if (!(c->rms_eps >= 0.f) || !(c->rope_base > 0.f)) return false;
+    *why = AX_ERR_UNSUPPORTED;
+    if (c->head_dim % 2 != 0 || c->head_dim > 256) return false;
+    if (c->dtype == AX_BF16) {
+        if (c->head_dim != 64 && c->head_dim != 128) return false;
+        if (c->d_model % 64 || c->d_ff % 64 || c->vocab % 64) return false;
+    }
+    return true;
+}
+
+struct Layout {                       // byte offsets into the workspace
+    size_t rope_cos, rope_sin, desc, x, h, qkv, q, attn, ffn, partials, logits, amax_scratch,
+        amax_out, result, total;
+    size_t desc_ints;                 // capacity of one descriptor slot
+    int max_tiles, max_bt;
+};
+
+Layout make_layout(const ax_model_config& c) {
+    Layout L{};
+    const size_t T = (size_t)c.max_tokens, S = (size_t)c.max_seqs, a = (size_t)isz(c.dtype);
+    const int G = c.n_q_heads / c.n_kv_heads;
+    L.max_tiles = (int)((T * G + 31) / 32 + S);
+    L.max_bt = (c.max_pos + 15) / 16;
+    L.desc_ints = 4 * T + 4 * S + S * (size_t)L.max_bt + 2 * (size_t)L.max_tiles + 16;
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes); return at; };
+    L.rope_cos = take((size_t)c.max_pos * (c.head_dim / 2) * 4);
+    L.rope_sin = take((size_t)c.max_pos * (c.head_dim / 2) * 4);
+    L.desc = take(N_SLOTS * align_up(L.desc_ints * 4));
+    L.x = take(T * c.d_model * 4);
+    L.h = take(T * c.d_model * a);
+    L.qkv = take(T * (size_t)(c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim * 4);
+    L.q = take(T * (size_t)c.n_q_heads * c.head_dim * a);
+    L.attn = take(T * (size_t)c.n_q_heads * c.head_dim * a);
+    L.ffn = take(T * (size_t)c.d_ff * a);
+    const size_t items = std::max<size_t>(SPLIT_ITEMS, (size_t)L.max_tiles * c.n_kv_heads);
+    L.partials = take(c.dtype == AX_BF16 ? items * ((size_t)c.head_dim * 32 + 64) * 4 : 0);
+    L.logits = take(std::min<size_t>(T, LOGIT_ROWS) * (size_t)c.vocab * 4);
+    L.amax_scratch = take(2 * std::min<size_t>(T, LOGIT_ROWS) * ax::ARGMAX_PARTS * 4);
+    L.amax_out = take(T * 4);
+    L.result = take(64);
+    L.total = o;
+    return L;
+}
+
+}  // namespace
+
+struct ax_model {
+    uint32_t magic;
+    ax_model_config cfg;
+    Layout lay;
+    char* ws;
+    const void *tok_emb, *lm_head, *final_norm;
+    std::vector<const void*> wqkv, wo, w_gate, w_up, w_down, norm_attn, norm_mlp;
+    int* stage;                       // pinned: N_SLOTS descriptor slots + result words
+    hipEvent_t slot_done[N_SLOTS];
+    int next_slot;
+    size_t slot_ints;
+};
+
+struct ax_pool {
+    uint32_t magic;
+    ax_model_config cfg;              // geometry fields only are compared with the model's
+    ax::KVGeom geom;
+    ax::BlockPool blocks;
+};
+
+struct ax_kv {
+    uint32_t magic;
+    ax_pool* pool;
+    ax::Sequence seq;
+};
+
+namespace {
+
+bool ok(const ax_model* m) { return m && m->magic == MAGIC_MODEL; }
+bool ok(const ax_pool* p) { return p && p->magic == MAGIC_POOL; }
+bool ok(const ax_kv* k) { return k && k->magic == MAGIC_KV && ok(k->pool); }
+
+// One forward over n sequences.  `verify_k` >= 0 turns the call into a verify round of the
+// single sequence: greedy tokens of all rows, acceptance on the device, result copied back.
+ax_status run_extend(ax_model* m, int n, ax_kv* const* kvs, const int32_t* tokens, const int* T_each,
+                     int out_mode, void* out, hipStream_t stream, int verify_k, int* host_result) {
+    const ax_model_config& c = m->cfg;
+    const Layout& L = m->lay;
+    if (n <= 0 || n > c.max_seqs) return fail(AX_ERR_INVALID, "n_seq %d outside 1..%d", n, c.max_seqs);
+    if (!kvs || !tokens || !T_each) return fail(AX_ERR_INVALID, "NULL argument");
+    if (out_mode < AX_OUT_NONE || out_mode > AX_OUT_ALL_ARGMAX) return fail(AX_ERR_INVALID, "bad out_mode");
+    if (out_mode != AX_OUT_NONE && !out) return fail(AX_ERR_INVALID, "out is NULL");
+
+    ax_pool* pool = nullptr;
+    long long n_rows = 0;
+    for (int s = 0; s < n; ++s) {
+        if (!ok(kvs[s])) return fail(AX_ERR_INVALID, "bad KV handle (sequence %d)", s);
+        if (s == 0) pool = kvs[s]->pool;
+        if (kvs[s]->pool != pool) return fail(AX_ERR_INVALID, "sequences live in different pools");
+        for (int u = 0; u < s; ++u)
+            if (kvs[u] == kvs[s]) return fail(AX_ERR_INVALID, "sequence %d given twice", s);
+        if (T_each[s] <= 0) return fail(AX_ERR_INVALID, "T <= 0 (sequence %d)", s);
+        if (kvs[s]->seq.len + T_each[s] > c.max_pos)
+            return fail(AX_ERR_INVALID, "P + T = %lld exceeds max_pos %d",
+                        (long long)(kvs[s]->seq.len + T_each[s]), c.max_pos);
+        n_rows += T_each[s];
+    }
+    if (n_rows > c.max_tokens) return fail(AX_ERR_INVALID, "%lld rows exceed max_tokens %d", n_rows, c.max_tokens);
+    const ax_model_config& pc = pool->cfg;
+    if (pc.n_layers != c.n_layers || pc.n_kv_heads != c.n_kv_heads || pc.head_dim != c.head_dim ||
+        pc.dtype != c.dtype)
+        return fail(AX_ERR_INVALID, "pool geometry does not match the model");
+    if (!pool->geom.base) return fail(AX_ERR_INVALID, "pool has no device memory");
+    for (long long i = 0; i < n_rows; ++i)
+        if (tokens[i] < 0 || tokens[i] >= c.vocab)
+            return fail(AX_ERR_INVALID, "token %d at row %lld outside the vocabulary", tokens[i], i);
+
+    // ---- reserve KV room for every sequence, or fail with nothing changed
+    std::vector<ax::AppendPlan> plans((size_t)n);
+    long long need = 0;
+    for (int s = 0; s < n; ++s) {
+        plans[(size_t)s] = ax::plan_append(pool->blocks, kvs[s]->seq, T_each[s]);
+        need += plans[(size_t)s].need();
+    }
+    if (need > pool->blocks.n_free())
+        return fail(AX_ERR_OOM, "need %lld KV blocks, %lld free", need, (long long)pool->blocks.n_free());
+
+    const int G = c.n_q_heads / c.n_kv_heads;
+    int n_tiles = 0, bt_total = 0;
+    for (int s = 0; s < n; ++s) {
+        n_tiles += (T_each[s] * G + 31) / 32;
+        bt_total += (int)ax::blocks_for(kvs[s]->seq.len + T_each[s], 16);
+    }
+    const int n_out = out_mode == AX_OUT_NONE ? 0
+                      : (out_mode == AX_OUT_LAST_LOGITS || out_mode == AX_OUT_LAST_ARGMAX) ? n
+                                                                                           : (int)n_rows;
+
+    // ---- descriptor slot (pinned host memory, reused round robin behind an event)
+    const int slot = m->next_slot;
+    m->next_slot = (slot + 1) % N_SLOTS;
+    HIP_TRY(hipEventSynchronize(m->slot_done[slot]));
+    int* d = m->stage + (size_t)slot * m->slot_ints;
+    int* dev_d = (int*)(m->ws + L.desc) + (size_t)slot * m->slot_ints;
+
+    std::vector<std::pair<int32_t, int32_t>> cows;
+    std::vector<int> P((size_t)n);
+    for (int s = 0; s < n; ++s) {
+        P[(size_t)s] = (int)kvs[s]->seq.len;
+        int32_t cs, cd;
+        ax::apply_append(pool->blocks, kvs[s]->seq, T_each[s], plans[(size_t)s], &cs, &cd);
+        if (cs >= 0) cows.push_back({cs, cd});
+    }
+
+    size_t at = 0;
+    auto region = [&](size_t ints) { size_t o = at; at += ints; return o; };
+    const size_t o_tok = region((size_t)n_rows), o_pos = region((size_t)n_rows), o_seq = region((size_t)n_rows),
+                 o_out = region((size_t)std::max(n_out, 1)), o_P = region((size_t)n), o_T = region((size_t)n),
+                 o_row0 = region((size_t)n), o_bt = region((size_t)n), o_tseq = region((size_t)n_tiles),
+                 o_tr0 = region((size_t)n_tiles), o_tab = region((size_t)bt_total);
+    int row = 0, tile = 0, tab = 0, oi = 0;
+    int max_steps = 1;
+    for (int s = 0; s < n; ++s) {
+        const int T = T_each[s];
+        d[o_P + s] = P[(size_t)s];
+        d[o_T + s] = T;
+        d[o_row0 + s] = row;
+        d[o_bt + s] = tab;
+        for (int32_t b : kvs[s]->seq.blocks) d[o_tab + tab++] = b;
+        for (int r0 = 0; r0 < T * G; r0 += 32) {
+            d[o_tseq + tile] = s;
+            d[o_tr0 + tile] = r0;
+            ++tile;
+        }
+        for (int t = 0; t < T; ++t, ++row) {
+            d[o_tok + row] = tokens[row];
+            d[o_pos + row] = P[(size_t)s] + t;
+            d[o_seq + row] = s;
+            if (out_mode == AX_OUT_ALL_LOGITS || out_mode == AX_OUT_ALL_ARGMAX) d[o_out + oi++] = row;
+        }
+        if (out_mode == AX_OUT_LAST_LOGITS || out_mode == AX_OUT_LAST_ARGMAX) d[o_out + oi++] = row - 1;
+        max_steps = std::max(max_steps, (P[(size_t)s] + T + 31) / 32);
+    }
+    HIP_TRY(hipMemcpyAsync(dev_d, d, at * sizeof(int), hipMemcpyHostToDevice, stream));
+
+    ax::StepView sv{};
+    sv.row_tok = dev_d + o_tok;  sv.row_pos = dev_d + o_pos;  sv.row_seq = dev_d + o_seq;
+    sv.out_rows = dev_d + o_out; sv.seq_P = dev_d + o_P;      sv.seq_T = dev_d + o_T;
+    sv.seq_row0 = dev_d + o_row0; sv.seq_bt = dev_d + o_bt;   sv.tile_seq = dev_d + o_tseq;
+    sv.tile_r0 = dev_d + o_tr0;  sv.bt = dev_d + o_tab;
+    sv.n_rows = (int)n_rows; sv.n_seq = n; sv.n_out = n_out; sv.n_tiles = n_tiles;
+
+    const ax::DType dt = c.dtype == AX_F32 ? ax::F32 : ax::BF16;
+    const ax::KVGeom& kg = pool->geom;
+    for (auto& cw : cows) ax::launch_block_copy(dt, kg, c.n_layers, cw.first, cw.second, stream);
+
+    // split the key range so that the attention launch has ~SPLIT_ITEMS wavefronts, each with
+    // at least two 32-key steps
+    const int items = n_tiles * c.n_kv_heads;
+    int n_splits = std::max(1, (SPLIT_ITEMS + items - 1) / items);
+    n_splits = std::min(n_splits, std::max(1, max_steps / 2));
+    n_splits = std::min(n_splits, std::max(1, (int)(std::max<size_t>(SPLIT_ITEMS, (size_t)L.max_tiles * c.n_kv_heads) / (size_t)items)));
+
+    char* ws = m->ws;
+    float* x = (float*)(ws + L.x);
+    void* h = ws + L.h;
+    float* qkv = (float*)(ws + L.qkv);
+    void* qb = ws + L.q;
+    void* attn = ws + L.attn;
+    void* ffn = ws + L.ffn;
+    const int d_model = c.d_model, qdim = c.n_q_heads * c.head_dim,
+              qkv_rows = (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim, R = (int)n_rows;
+
+    ax::launch_embed(dt, m->tok_emb, sv.row_tok, x, R, d_model, stream);
+    for (int l = 0; l < c.n_layers; ++l) {
+        ax::launch_rmsnorm(dt, x, m->norm_attn[(size_t)l], h, nullptr, R, d_model, c.rms_eps, stream);
+        ax::launch_gemm(dt, ax::EPI_STORE_F32, h, m->wqkv[(size_t)l], nullptr, qkv, R, qkv_rows, d_model, stream);
+        ax::launch_rope_kv(dt, qkv, qb, kg, l, sv, (const float*)(ws + L.rope_cos),
+                           (const float*)(ws + L.rope_sin), c.n_q_heads, stream);
+        ax::launch_attention(dt, qb, attn, kg, l, sv, c.n_q_heads, (float*)(ws + L.partials), n_splits, stream);
+        ax::launch_gemm(dt, ax::EPI_RESIDUAL, attn, m->wo[(size_t)l], nullptr, x, R, d_model, qdim, stream);
+        ax::launch_rmsnorm(dt, x, m->norm_mlp[(size_t)l], h, nullptr, R, d_model, c.rms_eps, stream);
+        ax::launch_gemm(dt, ax::EPI_SWIGLU, h, m->w_gate[(size_t)l], m->w_up[(size_t)l], ffn, R, c.d_ff, d_model, stream);
+        ax::launch_gemm(dt, ax::EPI_RESIDUAL, ffn, m->w_down[(size_t)l], nullptr, x, R, d_model, c.d_ff, stream);
+    }
+
+    if (n_out > 0) {
+        const size_t a = (size_t)isz(c.dtype);
+        ax::launch_rmsnorm(dt, x, m->final_norm, h, sv.out_rows, n_out, d_model, c.rms_eps, stream);
+        if (out_mode == AX_OUT_LAST_LOGITS || out_mode == AX_OUT_ALL_LOGITS) {
+            ax::launch_gemm(dt, ax::EPI_STORE_F32, h, m->lm_head, nullptr, out, n_out, c.vocab, d_model, stream);
+        } else {
+            float* logits = (float*)(ws + L.logits);
+            const int chunk = std::min(c.max_tokens, LOGIT_ROWS);
+            for (int r0 = 0; r0 < n_out; r0 += chunk) {
+                const int rows = std::min(chunk, n_out - r0);
+                ax::launch_gemm(dt, ax::EPI_STORE_F32, (const char*)h + (size_t)r0 * d_model * a, m->lm_head,
+                                nullptr, logits, rows, c.vocab, d_model, stream);
+                ax::launch_argmax(logits, rows, c.vocab, (int*)out + r0, (int*)(ws + L.amax_scratch), stream);
+            }
+        }
+    }
+    if (verify_k >= 0) {
+        int* res = (int*)(ws + L.result);
+        ax::launch_accept((const int*)out, sv.row_tok, verify_k, res, stream);
+        HIP_TRY(hipMemcpyAsync(host_result, res, 2 * sizeof(int), hipMemcpyDeviceToHost, stream));
+    }
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(hipEventRecord(m->slot_done[slot], stream));
+    return AX_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* ax_last_error(void) { return g_err; }
+
+size_t ax_workspace_bytes(const ax_model_config* cfg) {
+    ax_status why;
+    if (!config_ok(cfg, &why)) return 0;
+    return make_layout(*cfg).total;
+}
+
+ax_status ax_model_create(const ax_model_config* cfg, const ax_weights* w, void* workspace,
+                          size_t workspace_bytes, ax_model** out) {
+    ax_status why;
+    if (!out) return fail(AX_ERR_INVALID, "out is NULL");
+    *out = nullptr;
+    if (!config_ok(cfg, &why)) return fail(why, "model config rejected");
+    if (!w || !workspace) return fail(AX_ERR_INVALID, "NULL weights or workspace");
+    if (((uintptr_t)workspace & 255) != 0) return fail(AX_ERR_INVALID, "workspace not 256-byte aligned");
+    const Layout L = make_layout(*cfg);
+    if (workspace_bytes < L.total)
+        return fail(AX_ERR_OOM, "workspace has %zu bytes, %zu needed", workspace_bytes, L.total);
+    if (!w->tok_emb || !w->lm_head || !w->final_norm || !w->wqkv || !w->wo || !w->w_gate ||
+        !w->w_up || !w->w_down || !w->norm_attn || !w->norm_mlp)
+        return fail(AX_ERR_INVALID, "NULL weight pointer");
+    for (int l = 0; l < cfg->n_layers; ++l)
+        if (!w->wqkv[l] || !w->wo[l] || !w->w_gate[l] || !w->w_up[l] || !w->w_down[l] ||
+            !w->norm_attn[l] || !w->norm_mlp[l])
+            return fail(AX_ERR_INVALID, "NULL weight pointer in layer %d", l);
+
+    ax_model* m = new ax_model();
+    m->cfg = *cfg;
+    m->lay = L;
+    m->ws = (char*)workspace;
+    m->tok_emb = w->tok_emb;
+    m->lm_head = w->lm_head;
+    m->final_norm = w->final_norm;
+    const size_t nl = (size_t)cfg->n_layers;
+    m->wqkv.assign(w->wqkv, w->wqkv + nl);
+    m->wo.assign(w->wo, w->wo + nl);
+    m->w_gate.assign(w->w_gate, w->w_gate + nl);
+    m->w_up.assign(w->w_up, w->w_up + nl);
+    m->w_down.assign(w->w_down, w->w_down + nl);
+    m->norm_attn.assign(w->norm_attn, w->norm_attn + nl);
+    m->norm_mlp.assign(w->norm_mlp, w->norm_mlp + nl);
+    m->slot_ints = align_up(L.desc_ints * 4) / 4;
+    m->next_slot = 0;
+    m->stage = nullptr;
+    for (auto& e : m->slot_done) e = nullptr;
+
+    auto cleanup = [&]() {
+        for (auto& e : m->slot_done) if (e) (void)hipEventDestroy(e);
+        if (m->stage) (void)hipHostFree(m->stage);
+        delete m;
+    };
+    hipError_t e = hipHostMalloc((void**)&m->stage, (N_SLOTS * m->slot_ints + 16) * sizeof(int), hipHostMallocDefault);
+    if (e != hipSuccess) { m->stage = nullptr; cleanup(); return fail(AX_ERR_DEVICE, "hipHostMalloc: %s", hipGetErrorString(e)); }
+    for (auto& ev : m->slot_done) {
+        e = hipEventCreateWithFlags(&ev, hipEventDisableTiming);
+        if (e != hipSuccess) { ev = nullptr; cleanup(); return fail(AX_ERR_DEVICE, "hipEventCreate: %s", hipGetErrorString(e)); }
+    }
+    // rotary table: angle = pos * base^(-2j/hd), evaluated in double on the host
+    const int half = cfg->head_dim / 2;
+    std::vector<float> cs((size_t)cfg->max_pos * half), sn((size_t)cfg->max_pos * half);
+    for (int j = 0; j < half; ++j) {
+        const double theta = std::pow((double)cfg->rope_base, -2.0 * j / cfg->head_dim);
+        for (int p = 0; p < cfg->max_pos; ++p) {
+            cs[(size_t)p * half + j] = (float)std::cos(p * theta);
+            sn[(size_t)p * half + j] = (float)std::sin(p * theta);
+        }
+    }
+    e = hipMemcpy(m->ws + L.rope_cos, cs.data(), cs.size() * 4, hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(m->ws + L.rope_sin, sn.data(), sn.size() * 4, hipMemcpyHostToDevice);
+    if (e != hipSuccess) { cleanup(); return fail(AX_ERR_DEVICE, "rotary table upload: %s", hipGetErrorString(e)); }
+    m->magic = MAGIC_MODEL;
+    *out = m;
+    return AX_OK;
+}
+
+void ax_model_destroy(ax_model* m) {
+    if (!ok(m)) return;
+    (void)hipDeviceSynchronize();
+    for (auto& e : m->slot_done) (void)hipEventDestroy(e);
+    (void)hipHostFree(m->stage);
+    m->magic = 0;
+    delete m;
+}
+
+size_t ax_pool_block_bytes(const ax_model_config* cfg, int block_tokens) {
+    ax_status why;
+    if (!config_ok(cfg, &why) || block_tokens <= 0) return 0;
+    return (size_t)2 * cfg->n_layers * cfg->n_kv_heads * cfg->head_dim * block_tokens * isz(cfg->dtype);
+}
+
+ax_status ax_pool_create(const ax_model_config* cfg, void* dev_mem, size_t bytes, int block_tokens,
+                         ax_pool** out) {
+    ax_status why;
+    if (!out) return fail(AX_ERR_INVALID, "out is NULL");
+    *out = nullptr;
+    if (!config_ok(cfg, &why)) return fail(why, "model config rejected");
+    if (block_tokens != 16) return fail(AX_ERR_UNSUPPORTED, "block_tokens must be 16");
+    if (((uintptr_t)dev_mem & 255) != 0) return fail(AX_ERR_INVALID, "pool memory not 256-byte aligned");
+    const size_t bb = ax_pool_block_bytes(cfg, block_tokens);
+    const size_t nb = bytes / bb;
+    if (nb < 1) return fail(AX_ERR_OOM, "pool of %zu bytes holds no %zu-byte block", bytes, bb);
+    if (nb > 0x7fffffff) return fail(AX_ERR_INVALID, "too many blocks");
+    ax_pool* p = new ax_pool();
+    p->cfg = *cfg;
+    p->geom.base = dev_mem;
+    p->geom.n_blocks = (long long)nb;
+    p->geom.n_kv_heads = cfg->n_kv_heads;
+    p->geom.head_dim = cfg->head_dim;
+    p->geom.block_tokens = block_tokens;
+    p->blocks.init((int64_t)nb, block_tokens);
+    p->magic = MAGIC_POOL;
+    *out = p;
+    return AX_OK;
+}
+
+ax_status ax_pool_destroy(ax_pool* p) {
+    if (!ok(p)) return fail(AX_ERR_INVALID, "bad pool handle");
+    if (p->blocks.live_seqs != 0) return fail(AX_ERR_STATE, "%lld sequences still alive", (long long)p->blocks.live_seqs);
+    p->magic = 0;
+    delete p;
+    return AX_OK;
+}
+
+ax_status ax_pool_stats(const ax_pool* p, int64_t* free_blocks, int64_t* total_blocks, int64_t* live_seqs) {
+    if (!ok(p)) return fail(AX_ERR_INVALID, "bad pool handle");
+    if (free_blocks) *free_blocks = p->blocks.n_free();
+    if (total_blocks) *total_blocks = p->blocks.n_total();
+    if (live_seqs) *live_seqs = p->blocks.live_seqs;
+    return AX_OK;
+}
+
+ax_status ax_kv_alloc(ax_pool* p, ax_kv** out) {
+    if (!out) return fail(AX_ERR_INVALID, "out is NULL");
+    *out = nullptr;
+    if (!ok(p)) return fail(AX_ERR_INVALID, "bad pool handle");
+    ax_kv* k = new ax_kv();
+    k->pool = p;
+    k->magic = MAGIC_KV;
+    ++p->blocks.live_seqs;
+    *out = k;
+    return AX_OK;
+}
+
+ax_status ax_kv_fork(const ax_kv* src, int64_t n_tokens, ax_kv** out) {
+    if (!out) return fail(AX_ERR_INVALID, "out is NULL");
+    *out = nullptr;
+    if (!ok(src)) return fail(AX_ERR_INVALID, "bad KV handle");
+    if (n_tokens < 0) n_tokens = src->seq.len;
+    if (n_tokens > src->seq.len) return fail(AX_ERR_INVALID, "fork of %lld tokens from a sequence of %lld",
+                                             (long long)n_tokens, (long long)src->seq.len);
+    ax_kv* k = new ax_kv();
+    k->pool = src->pool;
+    ax::fork(src->pool->blocks, src->seq, n_tokens, k->seq);
+    k->magic = MAGIC_KV;
+    ++src->pool->blocks.live_seqs;
+    *out = k;
+    return AX_OK;
+}
+
+ax_status ax_kv_truncate(ax_kv* kv, int64_t new_len) {
+    if (!ok(kv)) return fail(AX_ERR_INVALID, "bad KV handle");
+    if (new_len < 0 || new_len > kv->seq.len)
+        return fail(AX_ERR_INVALID, "truncate to %lld, length is %lld", (long long)new_len, (long long)kv->seq.len);
+    ax::truncate(kv->pool->blocks, kv->seq, new_len);
+    return AX_OK;
+}
+
+int64_t ax_kv_len(const ax_kv* kv) { return ok(kv) ? kv->seq.len : -1; }
+
+ax_status ax_kv_free(ax_kv* kv) {
+    if (!ok(kv)) return fail(AX_ERR_INVALID, "bad KV handle (double free?)");
+    ax::truncate(kv->pool->blocks, kv->seq, 0);
+    --kv->pool->blocks.live_seqs;
+    kv->magic = 0;
+    delete kv;
+    return AX_OK;
+}
+
+int64_t ax_kv_blocks(const ax_kv* kv, int32_t* ids, int64_t cap) {
+    if (!ok(kv)) return -1;
+    const int64_t n = (int64_t)kv->seq.blocks.size();
+    if (ids) for (int64_t i = 0; i < n && i < cap; ++i) ids[i] = kv->seq.blocks[(size_t)i];
+    return n;
+}
+
+int ax_pool_refcount(const ax_pool* p, int64_t block) {
+    if (!ok(p) || block < 0 || block >= p->blocks.n_total()) return -1;
+    return p->blocks.refcount[(size_t)block];
+}
+
+ax_status ax_kv_reserve_host(ax_kv* kv, int64_t n, int32_t* cow_src, int32_t* cow_dst) {
+    if (!ok(kv)) return fail(AX_ERR_INVALID, "bad KV handle");
+    if (n <= 0 || !cow_src || !cow_dst) return fail(AX_ERR_INVALID, "bad argument");
+    ax::BlockPool& bp = kv->pool->blocks;
+    const ax::AppendPlan plan = ax::plan_append(bp, kv->seq, n);
+    if (plan.need() > bp.n_free())
+        return fail(AX_ERR_OOM, "need %lld KV blocks, %lld free", (long long)plan.need(), (long long)bp.n_free());
+    ax::apply_append(bp, kv->seq, n, plan, cow_src, cow_dst);
+    return AX_OK;
+}
+
+ax_status ax_extend(ax_model* model, ax_kv* kv, const int32_t* tokens, int T, int out_mode, void* out,
+                    void* hip_stream) {
+    if (!ok(model)) return fail(AX_ERR_INVALID, "bad model handle");
+    ax_kv* one[1] = {kv};
+    return run_extend(model, 1, one, tokens, &T, out_mode, out, (hipStream_t)hip_stream, -1, nullptr);
+}
+
+ax_status ax_extend_batch(ax_model* model, int n, ax_kv* const* kvs, const int32_t* tokens_concat,
+                          const int* T_each, int out_mode, void* out, void* hip_stream) {
+    if (!ok(model)) return fail(AX_ERR_INVALID, "bad model handle");
+    return run_extend(model, n, kvs, tokens_concat, T_each, out_mode, out, (hipStream_t)hip_stream, -1, nullptr);
+}
+
+ax_status ax_verify(ax_model* model, ax_kv* kv, int32_t pending, const int32_t* drafts, int k,
+                    int* accepted, int32_t* next_token, void* hip_stream) {
+    if (!ok(model)) return fail(AX_ERR_INVALID, "bad model handle");
+    if (!ok(kv)) return fail(AX_ERR_INVALID, "bad KV handle");
+    if (k < 0 || (k > 0 && !drafts) || !accepted || !next_token) return fail(AX_ERR_INVALID, "bad argument");
+    if (1 + k > model->cfg.max_tokens) return fail(AX_ERR_INVALID, "1 + k exceeds max_tokens");
+    std::vector<int32_t> toks((size_t)k + 1);
+    toks[0] = pending;
+    for (int i = 0; i < k; ++i) toks[(size_t)i + 1] = drafts[i];
+    const int T = 1 + k;
+    const int64_t P = kv->seq.len;
+    int* host_res = model->stage + N_SLOTS * model->slot_ints;      // pinned result words
+    ax_kv* one[1] = {kv};
+    hipStream_t stream = (hipStream_t)hip_stream;
+    ax_status st = run_extend(model, 1, one, toks.data(), &T, AX_OUT_ALL_ARGMAX,
+                              model->ws + model->lay.amax_out, stream, k, host_res);
+    if (st != AX_OK) {
+        if (kv->seq.len != P) ax::truncate(kv->pool->blocks, kv->seq, P);   // device error after the append
+        return st;
+    }
+    hipError_t e = hipStreamSynchronize(stream);
+    if (e != hipSuccess) {
+        ax::truncate(kv->pool->blocks, kv->seq, P);
+        return fail(AX_ERR_DEVICE, "hipStreamSynchronize: %s", hipGetErrorString(e));
+    }
+    const int a = host_res[0];
+    *accepted = a;
+    *next_token = host_res[1];
+    ax::truncate(kv->pool->blocks, kv->seq, P + 1 + a);                    // rollback of rejected drafts
+    return AX_OK;
+}
+
+ax_status ax_dbg_gemm(int dtype, int epilogue, const void* A, const void* W, const void* W2, void* C, int M,
+                      int N, int K, void* hip_stream) {
+    if (!A || !W || !C || M <= 0 || N <= 0 || K <= 0 || epilogue < 0 || epilogue > 2 ||
+        (epilogue == 2 && !W2) || (dtype != AX_F32 && dtype != AX_BF16))
+        return fail(AX_ERR_INVALID, "bad argument");
+    if (dtype == AX_BF16 && (K % 64 != 0 || N % 16 != 0)) return fail(AX_ERR_UNSUPPORTED, "bf16 needs K %% 64 == 0, N %% 16 == 0");
+    hipStream_t s = (hipStream_t)hip_stream;
+    ax::launch_gemm(dtype == AX_F32 ? ax::F32 : ax::BF16, (ax::Epilogue)epilogue, A, W, W2, C, M, N, K, s);
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(hipStreamSynchronize(s));
+    return AX_OK;
+}
+
+ax_status ax_dbg_read(ax_model* m, int which, void* host_dst, size_t bytes) {
+    if (!ok(m) || !host_dst) return fail(AX_ERR_INVALID, "bad argument");
+    const Layout& L = m->lay;
+    const size_t off[6] = {L.x, L.qkv, L.q, L.attn, L.ffn, L.h};
+    const size_t end[6] = {L.h, L.q, L.attn, L.ffn, L.partials, L.qkv};
+    if (which < 0 || which > 5) return fail(AX_ERR_INVALID, "bad buffer id");
+    HIP_TRY(hipDeviceSynchronize());
+    HIP_TRY(hipMemcpy(host_dst, m->ws + off[which], std::min(bytes, end[which] - off[which]), hipMemcpyDeviceToHost));
+    return AX_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,213 @@
+// Small memory-bound kernels of the extend forward: embedding gather, RMSNorm, rotary + paged
+// KV append, vocabulary argmax, greedy draft acceptance, copy-on-write block copy.
+#include "kernels.h"
+
+namespace ax {
+
+typedef __bf16 bf16;
+
+__device__ __forceinline__ float to_f32(float v) { return v; }
+__device__ __forceinline__ float to_f32(bf16 v) { return (float)v; }
+template <typename T> __device__ __forceinline__ T from_f32(float v);
+template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ bf16 from_f32<bf16>(float v) { return (bf16)v; }  // RNE
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+// ---------------------------------------------------------------- embedding gather
+template <typename T>
+__global__ void embed_kernel(const T* __restrict__ emb, const int* __restrict__ row_tok,
+                             float* __restrict__ x, int d) {
+    const int r = blockIdx.x;
+    const T* src = emb + (long long)row_tok[r] * d;
+    float* dst = x + (long long)r * d;
+    for (int c = threadIdx.x; c < d; c += blockDim.x) dst[c] = to_f32(src[c]);
+}
+
+void launch_embed(DType dt, const void* emb, const int* row_tok, float* x, int n_rows, int d,
+                  hipStream_t s) {
+    if (dt == F32)
+        embed_kernel<float><<<n_rows, 256, 0, s>>>((const float*)emb, row_tok, x, d);
+    else
+        embed_kernel<bf16><<<n_rows, 256, 0, s>>>((const bf16*)emb, row_tok, x, d);
+}
+
+// ---------------------------------------------------------------- RMSNorm
+// One 256-thread block per row: sum of squares in fp32 (wavefront shuffles, then LDS across the
+// four wavefronts), then x * rsqrt(mean + eps) * gain.
+template <typename T>
+__global__ void rmsnorm_kernel(const float* __restrict__ x, const T* __restrict__ gain,
+                               T* __restrict__ h, const int* __restrict__ rows, int d, float eps) {
+    __shared__ float part[4];
+    const int i = blockIdx.x;
+    const int r = rows ? rows[i] : i;
+    const float* xr = x + (long long)r * d;
+    float ss = 0.f;
+    for (int c = threadIdx.x; c < d; c += 256) {
+        float v = xr[c];
+        ss += v * v;
+    }
+    ss = wave_sum(ss);
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = ss;
+    __syncthreads();
+    const float tot = part[0] + part[1] + part[2] + part[3];
+    const float inv = 1.0f / sqrtf(tot / (float)d + eps);
+    T* hr = h + (long long)i * d;
+    for (int c = threadIdx.x; c < d; c += 256) hr[c] = from_f32<T>(xr[c] * inv * to_f32(gain[c]));
+}
+
+void launch_rmsnorm(DType dt, const float* x, const void* gain, void* h, const int* rows,
+                    int n_rows, int d, float eps, hipStream_t s) {
+    if (dt == F32)
+        rmsnorm_kernel<float><<<n_rows, 256, 0, s>>>(x, (const float*)gain, (float*)h, rows, d, eps);
+    else
+        rmsnorm_kernel<bf16><<<n_rows, 256, 0, s>>>(x, (const bf16*)gain, (bf16*)h, rows, d, eps);
+}
+
+// ---------------------------------------------------------------- rotary + paged KV append
+// grid (n_rows, Hq + 2*Hkv); one block per (row, head).  Pair (j, j + hd/2) is rotated by
+// the angle pos * base^(-2j/hd); cos / sin come from a host-built table [max_pos][hd/2].
+template <typename T>
+__global__ void rope_kv_kernel(const float* __restrict__ qkv, T* __restrict__ q_out, KVGeom kv,
+                               int layer, const int* __restrict__ row_pos,
+                               const int* __restrict__ row_seq, const int* __restrict__ seq_bt,
+                               const int* __restrict__ bt, const float* __restrict__ rope_cos,
+                               const float* __restrict__ rope_sin, int Hq) {
+    const int r = blockIdx.x, head = blockIdx.y;
+    const int hd = kv.head_dim, half = hd >> 1, Hkv = kv.n_kv_heads, B = kv.block_tokens;
+    const int pos = row_pos[r];
+    const float* src = qkv + (long long)r * (Hq + 2 * Hkv) * hd + (long long)head * hd;
+    T* pool = (T*)kv.base;
+    if (head < Hq + Hkv) {
+        const float* cs = rope_cos + (long long)pos * half;
+        const float* sn = rope_sin + (long long)pos * half;
+        T* dst;
+        if (head < Hq) {
+            dst = q_out + ((long long)r * Hq + head) * hd;
+        } else {
+            const int blk = bt[seq_bt[row_seq[r]] + pos / B];
+            dst = pool + kv.plane(layer, 0, head - Hq) + ((long long)blk * B + pos % B) * hd;
+        }
+        for (int j = threadIdx.x; j < half; j += blockDim.x) {
+            const float a = src[j], b = src[j + half], c = cs[j], sgn = sn[j];
+            dst[j] = from_f32<T>(a * c - b * sgn);
+            dst[j + half] = from_f32<T>(b * c + a * sgn);
+        }
+    } else {
+        const int blk = bt[seq_bt[row_seq[r]] + pos / B];
+        T* dst = pool + kv.plane(layer, 1, head - Hq - Hkv) + (long long)blk * B * hd + pos % B;
+        for (int c = threadIdx.x; c < hd; c += blockDim.x) dst[(long long)c * B] = from_f32<T>(src[c]);
+    }
+}
+
+void launch_rope_kv(DType dt, const float* qkv, void* q_out, KVGeom kv, int layer,
+                    const StepView& sv, const float* rope_cos, const float* rope_sin,
+                    int n_q_heads, hipStream_t s) {
+    dim3 grid(sv.n_rows, n_q_heads + 2 * kv.n_kv_heads);
+    if (dt == F32)
+        rope_kv_kernel<float><<<grid, 64, 0, s>>>(qkv, (float*)q_out, kv, layer, sv.row_pos, sv.row_seq,
+                                                  sv.seq_bt, sv.bt, rope_cos, rope_sin, n_q_heads);
+    else
+        rope_kv_kernel<bf16><<<grid, 64, 0, s>>>(qkv, (bf16*)q_out, kv, layer, sv.row_pos, sv.row_seq,
+                                                 sv.seq_bt, sv.bt, rope_cos, rope_sin, n_q_heads);
+}
+
+// ---------------------------------------------------------------- vocabulary argmax
+// Two stages.  Order is (value descending, index ascending): ties go to the lowest id.
+__device__ __forceinline__ void argmax_merge(float& bv, int& bi, float v, int i) {
+    if (v > bv || (v == bv && i < bi)) { bv = v; bi = i; }
+}
+
+__device__ __forceinline__ void argmax_wave(float& bv, int& bi) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        float v = __shfl_xor(bv, o, 64);
+        int i = __shfl_xor(bi, o, 64);
+        argmax_merge(bv, bi, v, i);
+    }
+}
+
+__global__ void argmax_stage1(const float* __restrict__ logits, int V, float* __restrict__ pv,
+                              int* __restrict__ pi) {
+    __shared__ float sv[4];
+    __shared__ int si[4];
+    const int r = blockIdx.y, part = blockIdx.x;
+    const int span = (V + ARGMAX_PARTS - 1) / ARGMAX_PARTS;
+    const int lo = part * span, hi = min(V, lo + span);
+    const float* row = logits + (long long)r * V;
+    float bv = -INFINITY;
+    int bi = 0x7fffffff;
+    for (int c = lo + threadIdx.x; c < hi; c += 256) argmax_merge(bv, bi, row[c], c);
+    argmax_wave(bv, bi);
+    if ((threadIdx.x & 63) == 0) { sv[threadIdx.x >> 6] = bv; si[threadIdx.x >> 6] = bi; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < 4; ++w) argmax_merge(bv, bi, sv[w], si[w]);
+        pv[r * ARGMAX_PARTS + part] = bv;
+        pi[r * ARGMAX_PARTS + part] = bi;
+    }
+}
+
+__global__ void argmax_stage2(const float* __restrict__ pv, const int* __restrict__ pi,
+                              int* __restrict__ out) {
+    const int r = blockIdx.x;
+    float bv = pv[r * ARGMAX_PARTS + threadIdx.x];
+    int bi = pi[r * ARGMAX_PARTS + threadIdx.x];
+    argmax_wave(bv, bi);
+    if (threadIdx.x == 0) out[r] = bi;
+}
+
+void launch_argmax(const float* logits, int rows, int V, int* out, int* scratch, hipStream_t s) {
+    static_assert(ARGMAX_PARTS == 64, "stage 2 is one wavefront");
+    float* pv = (float*)scratch;
+    int* pi = scratch + (size_t)rows * ARGMAX_PARTS;
+    argmax_stage1<<<dim3(ARGMAX_PARTS, rows), 256, 0, s>>>(logits, V, pv, pi);
+    argmax_stage2<<<rows, 64, 0, s>>>(pv, pi, out);
+}
+
+// ---------------------------------------------------------------- greedy draft acceptance
+// One wavefront: lane i < k votes drafts[i] == g[i]; the accepted length is the position of
+// the first lane whose vote is false (ballot + count trailing ones).
+__global__ void accept_kernel(const int* __restrict__ g, const int* __restrict__ row_tok, int k,
+                              int* __restrict__ result) {
+    const int lane = threadIdx.x;
+    int a = 0;
+    for (int base = 0; base < k; base += 64) {           // k > 64 only in principle
+        const int i = base + lane;
+        const bool ok = (i < k) && (row_tok[1 + i] == g[i]);
+        const unsigned long long mism = ~__ballot(ok);
+        const int first_bad = __ffsll((long long)mism) - 1;   // 0..63, or -1 if none
+        if (first_bad >= 0) { a = base + first_bad; break; }
+        a = base + 64;
+    }
+    if (a > k) a = k;
+    if (lane == 0) { result[0] = a; result[1] = g[a]; }
+}
+
+void launch_accept(const int* g, const int* row_tok, int k, int* result, hipStream_t s) {
+    accept_kernel<<<1, 64, 0, s>>>(g, row_tok, k, result);
+}
+
+// ---------------------------------------------------------------- copy-on-write block copy
+// grid = 2 * n_layers * Hkv planes; each block copies B*hd elements of one plane as 16-byte
+// words (B*hd*itemsize is a multiple of 16 for every supported shape).
+__global__ void block_copy_kernel(char* __restrict__ base, long long plane_bytes,
+                                  long long block_bytes, int src, int dst) {
+    const uint4* s = (const uint4*)(base + blockIdx.x * plane_bytes + (long long)src * block_bytes);
+    uint4* d = (uint4*)(base + blockIdx.x * plane_bytes + (long long)dst * block_bytes);
+    for (int i = threadIdx.x; i < block_bytes / 16; i += blockDim.x) d[i] = s[i];
+}
+
+void launch_block_copy(DType dt, KVGeom kv, int n_layers, int src, int dst, hipStream_t s) {
+    const long long isz = dt == F32 ? 4 : 2;
+    const long long block_bytes = (long long)kv.block_tokens * kv.head_dim * isz;
+    const long long plane_bytes = kv.n_blocks * block_bytes;
+    block_copy_kernel<<<2 * n_layers * kv.n_kv_heads, 64, 0, s>>>((char*)kv.base, plane_bytes,
+                                                                  block_bytes, src, dst);
+}
+
+}  // namespace ax

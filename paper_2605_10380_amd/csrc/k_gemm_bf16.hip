@@ -1,0 +1,278 @@
+// bf16 GEMMs with fp32 accumulation on the gfx950 matrix cores: C = A[M,K] * W[N,K]^T.
+// Both operands are K-contiguous, which is exactly what the MFMA operand layout wants: a lane
+// holds 8 consecutive k of one row (A) or one column (W), i.e. one 16-byte load.
+//
+//   * tile kernel   (M > 64, large-T extend: compute bound): 4 wavefronts, LDS-staged
+//     BM x BN x 64 tiles, v_mfma_f32_32x32x16_bf16, register prefetch of the next K slice.
+//   * skinny kernel (M <= 64, verify steps: pure weight streaming): one block owns 16 output
+//     columns, its wavefronts split K, W goes HBM -> registers -> v_mfma_f32_16x16x32_bf16
+//     with no LDS in the streaming loop; the per-wavefront partial sums meet in LDS.
+//
+// Epilogues: fp32 store, fp32 residual add, or SwiGLU (two weight matrices share the A
+// operand; the bf16 result is silu(A*Wg^T) * (A*Wu^T)).
+#include "kernels.h"
+
+namespace ax {
+
+typedef __bf16 bf16;
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+void launch_gemm_f32(Epilogue epi, const float* A, const float* W, const float* W2, float* C,
+                     int M, int N, int K, hipStream_t s);
+
+__device__ __forceinline__ float silu_f(float g) { return g / (1.0f + __expf(-g)); }
+
+// ------------------------------------------------------------------------------ tile kernel
+// MFMA 32x32x16 operand layout (wave64): lane l supplies row/col (l % 32) and the 8 k values
+// 8*(l/32) .. +7; result register r of lane l is C[(r/4)*8 + (l/32)*4 + r%4][l % 32].
+template <int EPI, int TM, int TN>
+__global__ __launch_bounds__(256) void gemm_bf16_tile_kernel(const bf16* __restrict__ A,
+                                                             const bf16* __restrict__ W,
+                                                             const bf16* __restrict__ W2,
+                                                             void* __restrict__ Cv, int M, int N,
+                                                             int K) {
+    constexpr int BM = 2 * TM * 32, BN = 2 * TN * 32, BK = 64, LS = BK + 8;  // LS: padded row
+    constexpr int NB = EPI == EPI_SWIGLU ? 2 : 1;
+    constexpr int A_CH = BM * 8 / 256, B_CH = BN * 8 / 256;                  // 16-byte chunks per thread
+    __shared__ __attribute__((aligned(16))) bf16 sA[BM * LS];
+    __shared__ __attribute__((aligned(16))) bf16 sB[NB][BN * LS];
+
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int lrow = lane & 31, lg = lane >> 5;
+    const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+
+    f32x16 acc[NB][TM][TN];
+#pragma unroll
+    for (int b = 0; b < NB; ++b)
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[b][i][j][r] = 0.f;
+
+    bf16x8 ra[A_CH], rb[NB][B_CH];
+    auto load_global = [&](int k0) {
+#pragma unroll
+        for (int i = 0; i < A_CH; ++i) {
+            const int c = tid + 256 * i, row = c >> 3, cc = c & 7;
+            const int gm = min(m0 + row, M - 1);
+            ra[i] = *(const bf16x8*)(A + (long long)gm * K + k0 + cc * 8);
+        }
+#pragma unroll
+        for (int i = 0; i < B_CH; ++i) {
+            const int c = tid + 256 * i, row = c >> 3, cc = c & 7;
+            const int gn = min(n0 + row, N - 1);
+            rb[0][i] = *(const bf16x8*)(W + (long long)gn * K + k0 + cc * 8);
+            if (NB == 2) rb[NB - 1][i] = *(const bf16x8*)(W2 + (long long)gn * K + k0 + cc * 8);
+        }
+    };
+    auto store_lds = [&]() {
+#pragma unroll
+        for (int i = 0; i < A_CH; ++i) {
+            const int c = tid + 256 * i, row = c >> 3, cc = c & 7;
+            *(bf16x8*)(sA + row * LS + cc * 8) = ra[i];
+        }
+#pragma unroll
+        for (int i = 0; i < B_CH; ++i) {
+            const int c = tid + 256 * i, row = c >> 3, cc = c & 7;
+#pragma unroll
+            for (int b = 0; b < NB; ++b) *(bf16x8*)(sB[b] + row * LS + cc * 8) = rb[b][i];
+        }
+    };
+
+    load_global(0);
+    for (int k0 = 0; k0 < K; k0 += BK) {
+        store_lds();
+        __syncthreads();
+        if (k0 + BK < K) load_global(k0 + BK);
+#pragma unroll
+        for (int kk = 0; kk < BK / 16; ++kk) {
+            bf16x8 fa[TM], fb[NB][TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+                fa[i] = *(const bf16x8*)(sA + ((wm * TM + i) * 32 + lrow) * LS + kk * 16 + lg * 8);
+#pragma unroll
+            for (int b = 0; b < NB; ++b)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    fb[b][j] = *(const bf16x8*)(sB[b] + ((wn * TN + j) * 32 + lrow) * LS + kk * 16 + lg * 8);
+#pragma unroll
+            for (int b = 0; b < NB; ++b)
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+                        acc[b][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[b][j], acc[b][i][j], 0, 0, 0);
+        }
+        __syncthreads();
+    }
+
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int n = n0 + (wn * TN + j) * 32 + lrow;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int m = m0 + (wm * TM + i) * 32 + (r >> 2) * 8 + lg * 4 + (r & 3);
+                if (m < M && n < N) {
+                    const long long o = (long long)m * N + n;
+                    if (EPI == EPI_STORE_F32) ((float*)Cv)[o] = acc[0][i][j][r];
+                    else if (EPI == EPI_RESIDUAL) ((float*)Cv)[o] += acc[0][i][j][r];
+                    else ((bf16*)Cv)[o] = (bf16)(silu_f(acc[0][i][j][r]) * acc[NB - 1][i][j][r]);
+                }
+            }
+        }
+}
+
+// ------------------------------------------------------------------------------ skinny kernel
+// MFMA 16x16x32 operand layout: lane l supplies row/col (l % 16) and the 8 k values
+// 8*(l/16) .. +7; result register r of lane l is D[4*(l/16) + r][l % 16].  Here D = W_tile * x^T:
+// D rows are output columns n, D columns are activation rows m, so a lane ends up with four
+// consecutive n of one row m (one 16-byte store).
+template <int EPI, int MT, int NW>
+__global__ __launch_bounds__(64 * NW) void gemm_bf16_skinny_kernel(const bf16* __restrict__ X,
+                                                                   const bf16* __restrict__ W,
+                                                                   const bf16* __restrict__ W2,
+                                                                   void* __restrict__ Cv, int M,
+                                                                   int N, int K) {
+    constexpr int NB = EPI == EPI_SWIGLU ? 2 : 1;
+    __shared__ __attribute__((aligned(16))) f32x4 red[NW][NB][MT][64];
+
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int lr = lane & 15, lg = lane >> 4;
+    const int n0 = blockIdx.x * 16;
+    const int kslice = K / NW, kbeg = wave * kslice, kend = kbeg + kslice;
+
+    const bf16* wp = W + (long long)min(n0 + lr, N - 1) * K + lg * 8;
+    const bf16* wp2 = NB == 2 ? W2 + (long long)min(n0 + lr, N - 1) * K + lg * 8 : nullptr;
+    const bf16* xp[MT];
+#pragma unroll
+    for (int t = 0; t < MT; ++t) xp[t] = X + (long long)min(t * 16 + lr, M - 1) * K + lg * 8;
+
+    f32x4 acc[NB][MT];
+#pragma unroll
+    for (int b = 0; b < NB; ++b)
+#pragma unroll
+        for (int t = 0; t < MT; ++t) acc[b][t] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+    int k = kbeg;
+    for (; k + 128 <= kend; k += 128) {           // 4 MFMA k-steps per trip: 4+ loads in flight
+        bf16x8 fw[NB][4], fx[MT][4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            fw[0][u] = *(const bf16x8*)(wp + k + 32 * u);
+            if (NB == 2) fw[NB - 1][u] = *(const bf16x8*)(wp2 + k + 32 * u);
+        }
+#pragma unroll
+        for (int t = 0; t < MT; ++t)
+#pragma unroll
+            for (int u = 0; u < 4; ++u) fx[t][u] = *(const bf16x8*)(xp[t] + k + 32 * u);
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int b = 0; b < NB; ++b)
+#pragma unroll
+                for (int t = 0; t < MT; ++t)
+                    acc[b][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fw[b][u], fx[t][u], acc[b][t], 0, 0, 0);
+    }
+    for (; k < kend; k += 32) {
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            const bf16x8 fw = *(const bf16x8*)((b == 0 ? wp : wp2) + k);
+#pragma unroll
+            for (int t = 0; t < MT; ++t) {
+                const bf16x8 fx = *(const bf16x8*)(xp[t] + k);
+                acc[b][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fw, fx, acc[b][t], 0, 0, 0);
+            }
+        }
+    }
+
+#pragma unroll
+    for (int b = 0; b < NB; ++b)
+#pragma unroll
+        for (int t = 0; t < MT; ++t) red[wave][b][t][lane] = acc[b][t];
+    __syncthreads();
+    if (wave != 0) return;
+
+#pragma unroll
+    for (int t = 0; t < MT; ++t) {
+        f32x4 sum[NB];
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            sum[b] = red[0][b][t][lane];
+#pragma unroll
+            for (int w = 1; w < NW; ++w) sum[b] += red[w][b][t][lane];
+        }
+        const int m = t * 16 + lr, n = n0 + lg * 4;
+        if (m >= M || n >= N) continue;
+        const long long o = (long long)m * N + n;
+        if (EPI == EPI_STORE_F32) {
+            *(f32x4*)((float*)Cv + o) = sum[0];
+        } else if (EPI == EPI_RESIDUAL) {
+            f32x4* c = (f32x4*)((float*)Cv + o);
+            *c = *c + sum[0];
+        } else {
+            bf16x4 h;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) h[r] = (bf16)(silu_f(sum[0][r]) * sum[NB - 1][r]);
+            *(bf16x4*)((bf16*)Cv + o) = h;
+        }
+    }
+}
+
+template <int EPI, int MT>
+static void launch_skinny_nw(const bf16* A, const bf16* W, const bf16* W2, void* C, int M, int N,
+                             int K, int nw, hipStream_t s) {
+    const int grid = (N + 15) / 16;
+    if (nw == 16) gemm_bf16_skinny_kernel<EPI, MT, 16><<<grid, 1024, 0, s>>>(A, W, W2, C, M, N, K);
+    else if (nw == 1) gemm_bf16_skinny_kernel<EPI, MT, 1><<<grid, 64, 0, s>>>(A, W, W2, C, M, N, K);
+    else if (nw == 2) gemm_bf16_skinny_kernel<EPI, MT, 2><<<grid, 128, 0, s>>>(A, W, W2, C, M, N, K);
+    else if (nw == 8) gemm_bf16_skinny_kernel<EPI, MT, 8><<<grid, 512, 0, s>>>(A, W, W2, C, M, N, K);
+    else gemm_bf16_skinny_kernel<EPI, MT, 4><<<grid, 256, 0, s>>>(A, W, W2, C, M, N, K);
+}
+
+template <int EPI>
+static void launch_bf16(const bf16* A, const bf16* W, const bf16* W2, void* C, int M, int N, int K,
+                        hipStream_t s) {
+    if (M <= 64) {
+        // wavefronts per block (= K slices): enough to keep ~2k wavefronts in flight, each with
+        // at least 128 of K; K / nw must stay a multiple of the MFMA k (32)
+        const long long tiles = (N + 15) / 16;
+        int nw = 1;
+        while (nw < 16 && tiles * nw < 2048 && K % (nw * 2 * 32) == 0 && K / (nw * 2) >= 128) nw *= 2;
+        if (EPI == EPI_SWIGLU && nw == 16) nw = 8;        // LDS reduction buffer stays <= 64 KB
+        if (M <= 16) launch_skinny_nw<EPI, 1>(A, W, W2, C, M, N, K, nw, s);
+        else if (M <= 32) launch_skinny_nw<EPI, 2>(A, W, W2, C, M, N, K, nw, s);
+        else launch_skinny_nw<EPI, 4>(A, W, W2, C, M, N, K, nw == 16 ? 8 : nw, s);
+        return;
+    }
+    // large M: 128x128 tiles when that still gives every CU a block, else 64x128
+    const long long big = (long long)((M + 127) / 128) * ((N + 127) / 128);
+    if (big >= 256 && EPI != EPI_SWIGLU) {
+        dim3 grid((N + 127) / 128, (M + 127) / 128);
+        gemm_bf16_tile_kernel<EPI, 2, 2><<<grid, 256, 0, s>>>(A, W, W2, C, M, N, K);
+    } else {
+        dim3 grid((N + 127) / 128, (M + 63) / 64);
+        gemm_bf16_tile_kernel<EPI, 1, 2><<<grid, 256, 0, s>>>(A, W, W2, C, M, N, K);
+    }
+}
+
+void launch_gemm(DType dt, Epilogue epi, const void* A, const void* W, const void* W2, void* C,
+                 int M, int N, int K, hipStream_t s) {
+    if (dt == F32) {
+        launch_gemm_f32(epi, (const float*)A, (const float*)W, (const float*)W2, (float*)C, M, N, K, s);
+        return;
+    }
+    const bf16 *a = (const bf16*)A, *w = (const bf16*)W, *w2 = (const bf16*)W2;
+    if (epi == EPI_STORE_F32) launch_bf16<EPI_STORE_F32>(a, w, w2, C, M, N, K, s);
+    else if (epi == EPI_RESIDUAL) launch_bf16<EPI_RESIDUAL>(a, w, w2, C, M, N, K, s);
+    else launch_bf16<EPI_SWIGLU>(a, w, w2, C, M, N, K, s);
+}
+
+}  // namespace ax

@@ -1,0 +1,75 @@
+// Internal interface between the C-ABI host code and the HIP kernels (gfx950 only).
+// Every launcher only enqueues work on `stream`; shapes are validated by the caller.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <cstdint>
+
+namespace ax {
+
+enum DType { F32 = 0, BF16 = 1 };
+
+// Geometry of the paged KV pool.  Element offsets (not bytes):
+//   K(l, hk, blk, slot, c) = (((l*2 + 0)*Hkv + hk)*n_blocks + blk)*B*hd + slot*hd + c
+//   V(l, hk, blk, c, slot) = (((l*2 + 1)*Hkv + hk)*n_blocks + blk)*B*hd + c*B + slot
+struct KVGeom {
+    void* base;
+    long long n_blocks;
+    int n_kv_heads, head_dim, block_tokens;
+    __host__ __device__ long long plane(int layer, int kv, int hk) const {
+        return ((long long)(layer * 2 + kv) * n_kv_heads + hk) * n_blocks * block_tokens * head_dim;
+    }
+};
+
+// Device views of the per-call descriptor (one packed int32 buffer uploaded per call).
+struct StepView {
+    const int* row_tok;     // [n_rows] token id
+    const int* row_pos;     // [n_rows] absolute position
+    const int* row_seq;     // [n_rows] sequence index within the call
+    const int* seq_P;       // [n_seq] cached length before the call
+    const int* seq_T;       // [n_seq] new rows
+    const int* seq_row0;    // [n_seq] first row
+    const int* seq_bt;      // [n_seq] offset of the sequence's block table inside bt
+    const int* bt;          // concatenated block tables
+    const int* out_rows;    // [n_out] rows that go through the LM head
+    const int* tile_seq;    // [n_tiles] attention q-tiles over stacked rows (t, g)
+    const int* tile_r0;     // [n_tiles] first stacked row of the tile
+    int n_rows, n_seq, n_out, n_tiles;
+};
+
+enum Epilogue { EPI_STORE_F32 = 0, EPI_RESIDUAL = 1, EPI_SWIGLU = 2 };
+
+// x[r, :] = emb[row_tok[r], :] widened to fp32
+void launch_embed(DType dt, const void* emb, const int* row_tok, float* x, int n_rows, int d,
+                  hipStream_t s);
+// h[i, :] = rmsnorm(x[rows ? rows[i] : i, :]) * gain, written in the activation type
+void launch_rmsnorm(DType dt, const float* x, const void* gain, void* h, const int* rows,
+                    int n_rows, int d, float eps, hipStream_t s);
+// C = A[M,K] * W[N,K]^T with fp32 accumulation.  A and W are of type dt (the activation type
+// equals the weight type).  EPI_STORE_F32: C float [M,N].  EPI_RESIDUAL: C float [M,N] += .
+// EPI_SWIGLU: C (type dt) [M,N] = silu(A*W^T) * (A*W2^T).
+void launch_gemm(DType dt, Epilogue epi, const void* A, const void* W, const void* W2, void* C,
+                 int M, int N, int K, hipStream_t s);
+// rotary on q and k heads of qkv (fp32 [n_rows, (Hq+2Hkv)*hd]); q -> q_out [n_rows, Hq, hd]
+// (activation type), k and v -> pages of `layer`.
+void launch_rope_kv(DType dt, const float* qkv, void* q_out, KVGeom kv, int layer,
+                    const StepView& sv, const float* rope_cos, const float* rope_sin,
+                    int n_q_heads, hipStream_t s);
+// Causal attention of the new rows over the paged cache (which already holds the new rows).
+// out [n_rows, Hq, hd] in the activation type.  `partials` is fp32 scratch for the split-KV
+// path (bf16 only); n_splits >= 1.
+void launch_attention(DType dt, const void* q, void* out, KVGeom kv, int layer,
+                      const StepView& sv, int n_q_heads, float* partials, int n_splits,
+                      hipStream_t s);
+// Floats of `partials` launch_attention needs for n_tiles tiles and n_splits splits.
+size_t attention_partial_floats(int n_tiles, int n_kv_heads, int head_dim, int n_splits);
+// out[r] = argmax of logits[r, 0..V), lowest index on ties.  scratch: 2*rows*ARGMAX_PARTS ints.
+constexpr int ARGMAX_PARTS = 64;
+void launch_argmax(const float* logits, int rows, int V, int* out, int* scratch, hipStream_t s);
+// Greedy acceptance: g[0..k] greedy tokens after each verify row, row_tok[1..k] the drafts.
+// result[0] = a (longest prefix with drafts[i] == g[i]), result[1] = g[a].
+void launch_accept(const int* g, const int* row_tok, int k, int* result, hipStream_t s);
+// Copy one KV block (all layers, K and V, all heads) src -> dst: copy on write.
+void launch_block_copy(DType dt, KVGeom kv, int n_layers, int src, int dst, hipStream_t s);
+
+}  // namespace ax
