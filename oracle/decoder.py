@@ -27,11 +27,36 @@ from __future__ import annotations
 import numpy as np
 
 
-def widen(t: np.ndarray) -> np.ndarray:
-    """Storage format -> float64, exactly.  uint16 arrays are bfloat16 bit patterns."""
+_WIDE = {}                      # id(array) -> (array, float64 copy); see widen()
+_WIDE_BYTES = [0]
+WIDE_CACHE_LIMIT = 24 << 30     # bytes of float64 copies kept; beyond it tensors are widened per use
+
+
+def _to_f64(t: np.ndarray) -> np.ndarray:
     if t.dtype == np.uint16:
         return (t.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
     return t.astype(np.float64)
+
+
+def widen(t: np.ndarray) -> np.ndarray:
+    """Storage format -> float64, exactly.  uint16 arrays are bfloat16 bit patterns.
+
+    Whole weight tensors (base arrays) are memoised so that repeated forwards do not convert
+    gigabytes again; the cache holds the source array too, so an id is never reused.
+    """
+    hit = _WIDE.get(id(t))
+    if hit is not None and hit[0] is t:
+        return hit[1]
+    out = _to_f64(t)
+    if t.ndim == 2 and _WIDE_BYTES[0] + out.nbytes <= WIDE_CACHE_LIMIT:
+        _WIDE[id(t)] = (t, out)
+        _WIDE_BYTES[0] += out.nbytes
+    return out
+
+
+def clear_widen_cache() -> None:
+    _WIDE.clear()
+    _WIDE_BYTES[0] = 0
 
 
 class KVCache:
@@ -112,19 +137,20 @@ def silu(z: np.ndarray) -> np.ndarray:
     return z / (1.0 + np.exp(-z))
 
 
-def forward(shape, weights: dict, tokens, kv: KVCache) -> np.ndarray:
+def forward(shape, weights: dict, tokens, kv: KVCache, trace: dict = None) -> np.ndarray:
     """Run `tokens` on top of the cache (length P before, P + T after); logits [T, vocab].
 
     `shape` needs n_layers, n_q_heads, n_kv_heads, head_dim, rms_eps, rope_base; `weights`
     is {"tok_emb", "lm_head", "final_norm", and per-layer lists "wqkv", "wo", "w_gate",
-    "w_up", "w_down", "norm_attn", "norm_mlp"} in storage format.
+    "w_up", "w_down", "norm_attn", "norm_mlp"} in storage format.  If `trace` is a dict it
+    receives the last layer's intermediates (for tests that localise a mismatch).
     """
     tokens = np.asarray(tokens, dtype=np.int64)
     T = tokens.shape[0]
     Hq, Hkv, hd = shape.n_q_heads, shape.n_kv_heads, shape.head_dim
     pos = len(kv) + np.arange(T)
 
-    x = widen(weights["tok_emb"][tokens])
+    x = _to_f64(weights["tok_emb"][tokens])
     for l in range(shape.n_layers):
         h = rmsnorm(x, widen(weights["norm_attn"][l]), shape.rms_eps)
         qkv = h @ widen(weights["wqkv"][l]).T
@@ -139,7 +165,12 @@ def forward(shape, weights: dict, tokens, kv: KVCache) -> np.ndarray:
         h2 = rmsnorm(x, widen(weights["norm_mlp"][l]), shape.rms_eps)
         act = silu(h2 @ widen(weights["w_gate"][l]).T) * (h2 @ widen(weights["w_up"][l]).T)
         x = x + act @ widen(weights["w_down"][l]).T
-    return rmsnorm(x, widen(weights["final_norm"]), shape.rms_eps) @ widen(weights["lm_head"]).T
+        if trace is not None:
+            trace.update(qkv=qkv, q=q, attn=o, ffn=act)
+    h_out = rmsnorm(x, widen(weights["final_norm"]), shape.rms_eps)
+    if trace is not None:
+        trace.update(x=x, h_out=h_out)
+    return h_out @ widen(weights["lm_head"]).T
 
 
 def argmax_lowest(row: np.ndarray) -> int:

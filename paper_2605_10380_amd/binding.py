@@ -212,3 +212,89 @@ def ax_dbg_read(model: int, which: int, dst: np.ndarray):
     assert dst.flags["C_CONTIGUOUS"]
     _check(lib.ax_dbg_read(model, which, dst.ctypes.data_as(C.c_void_p), dst.nbytes))
     return dst
+
+
+# ------------------------------------------------------------------ device memory through PyTorch
+
+class DeviceModel:
+    """Owns the torch tensors a model borrows (weights, workspace, KV pool) and the handles.
+
+    weights: the dict produced by inputs.make_weights (numpy, storage format) or a dict of
+    torch device tensors of the right dtype.  PyTorch is used for allocation and the stream only.
+    """
+
+    def __init__(self, shape, weights: dict, max_pos: int, max_tokens: int, pool_tokens: int,
+                 max_seqs: int = 1, device: str = "cuda:0"):
+        import torch
+        if not torch.cuda.is_available():
+            raise RuntimeError("no GPU: the extend / verify path has no CPU fallback")
+        self.torch, self.shape, self.device = torch, shape, torch.device(device)
+        tdt = torch.float32 if shape.dtype == "f32" else torch.bfloat16
+
+        def up(a):
+            if isinstance(a, torch.Tensor):
+                assert a.dtype == tdt and a.is_cuda and a.is_contiguous()
+                return a
+            t = torch.from_numpy(np.ascontiguousarray(a))
+            if a.dtype == np.uint16:
+                t = t.view(torch.bfloat16)
+            return t.to(self.device)
+
+        self.w = {k: ([up(a) for a in v] if isinstance(v, list) else up(v)) for k, v in weights.items()}
+        self.cfg = make_config(shape, max_pos, max_tokens, max_seqs)
+        ws_bytes = ax_workspace_bytes(self.cfg)
+        if ws_bytes == 0:
+            raise AxError(AX_ERR_UNSUPPORTED)
+        self.ws = torch.zeros(ws_bytes, dtype=torch.uint8, device=self.device)
+        ptrs = {k: ([t.data_ptr() for t in v] if isinstance(v, list) else v.data_ptr()) for k, v in self.w.items()}
+        self.model = ax_model_create(self.cfg, ptrs, self.ws.data_ptr(), ws_bytes)
+        bb = ax_pool_block_bytes(self.cfg)
+        n_blocks = -(-pool_tokens // 16)
+        # zero-filled: masked key slots are multiplied by probability 0 and must be finite
+        self.pool_mem = torch.zeros(n_blocks * bb, dtype=torch.uint8, device=self.device)
+        self.pool = ax_pool_create(self.cfg, self.pool_mem.data_ptr(), n_blocks * bb)
+
+    @property
+    def stream(self) -> int:
+        return self.torch.cuda.current_stream(self.device).cuda_stream
+
+    def new_kv(self) -> int:
+        return ax_kv_alloc(self.pool)
+
+    def extend(self, kv: int, tokens, out_mode: int = AX_OUT_NONE):
+        """Runs ax_extend on the current stream; returns a device tensor (or None)."""
+        torch = self.torch
+        n = len(tokens)
+        out = None
+        if out_mode == AX_OUT_LAST_LOGITS:
+            out = torch.empty((1, self.shape.vocab), dtype=torch.float32, device=self.device)
+        elif out_mode == AX_OUT_ALL_LOGITS:
+            out = torch.empty((n, self.shape.vocab), dtype=torch.float32, device=self.device)
+        elif out_mode == AX_OUT_LAST_ARGMAX:
+            out = torch.empty(1, dtype=torch.int32, device=self.device)
+        elif out_mode == AX_OUT_ALL_ARGMAX:
+            out = torch.empty(n, dtype=torch.int32, device=self.device)
+        ax_extend(self.model, kv, tokens, out_mode, out.data_ptr() if out is not None else 0, self.stream)
+        return out
+
+    def extend_batch(self, kvs, token_lists, out_mode: int = AX_OUT_NONE):
+        torch = self.torch
+        T_each = [len(t) for t in token_lists]
+        rows = {AX_OUT_NONE: 0, AX_OUT_LAST_LOGITS: len(kvs), AX_OUT_LAST_ARGMAX: len(kvs)}.get(out_mode, sum(T_each))
+        out = None
+        if out_mode in (AX_OUT_LAST_LOGITS, AX_OUT_ALL_LOGITS):
+            out = torch.empty((rows, self.shape.vocab), dtype=torch.float32, device=self.device)
+        elif out_mode != AX_OUT_NONE:
+            out = torch.empty(rows, dtype=torch.int32, device=self.device)
+        ax_extend_batch(self.model, list(kvs), np.concatenate([np.asarray(t, dtype=np.int32) for t in token_lists]),
+                        T_each, out_mode, out.data_ptr() if out is not None else 0, self.stream)
+        return out
+
+    def verify(self, kv: int, pending: int, drafts):
+        return ax_verify(self.model, kv, pending, drafts, self.stream)
+
+    def close(self):
+        if self.model:
+            self.torch.cuda.synchronize(self.device)
+            ax_model_destroy(self.model)
+            self.model = 0

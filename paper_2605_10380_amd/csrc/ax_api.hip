@@ -184,6 +184,8 @@ ax_status run_extend(ax_model* m, int n, ax_kv* const* kvs, const int32_t* token
     const int n_out = out_mode == AX_OUT_NONE ? 0
                       : (out_mode == AX_OUT_LAST_LOGITS || out_mode == AX_OUT_LAST_ARGMAX) ? n
                                                                                            : (int)n_rows;
+    if ((size_t)(3 * n_rows + std::max(n_out, 1) + 4 * n + 2 * n_tiles + bt_total) > m->slot_ints)
+        return fail(AX_ERR_INVALID, "call descriptor does not fit its slot");
 
     // ---- descriptor slot (pinned host memory, reused round robin behind an event)
     const int slot = m->next_slot;

@@ -11,6 +11,7 @@ so the oracle and the GPU path can be fed identical bits without sharing any sta
 """
 from __future__ import annotations
 
+import os
 import zlib
 from dataclasses import dataclass, replace
 
@@ -115,17 +116,38 @@ def weight_names(shape: DecoderShape):
         yield "norm_mlp", l, (d,)
 
 
+_CHUNK = 1 << 21          # elements per independently keyed chunk of a large tensor
+
+
+def _fill_chunk(args):
+    out, lo, hi, seed, stream, gain, as_bf16 = args
+    g = _rng(seed, f"{stream}#{lo // _CHUNK}")
+    w = g.standard_normal(hi - lo, dtype=np.float32)
+    w *= np.float32(0.02)
+    if gain:
+        w += np.float32(1.0)
+    out[lo:hi] = f32_to_bf16_bits(w) if as_bf16 else w
+
+
 def make_tensor(shape: DecoderShape, seed: int, name: str, layer, dims) -> np.ndarray:
     """One weight tensor in storage format: float32, or uint16 bf16 bit patterns.
 
     Matrices are N(0, 0.02); norm gains are 1 + N(0, 0.02) so that a gain-indexing mistake
-    shows up while logits keep a usable scale.
+    shows up while logits keep a usable scale.  A tensor is cut into fixed-size chunks, each
+    with its own counter-based stream, so generation is order independent (and threaded).
     """
-    g = _rng(seed, f"{name}/{layer}")
-    w = g.standard_normal(dims, dtype=np.float32) * np.float32(0.02)
-    if len(dims) == 1:
-        w = w + np.float32(1.0)
-    return w if shape.dtype == "f32" else f32_to_bf16_bits(w)
+    n = int(np.prod(dims))
+    as_bf16 = shape.dtype != "f32"
+    out = np.empty(n, dtype=np.uint16 if as_bf16 else np.float32)
+    jobs = [(out, lo, min(n, lo + _CHUNK), seed, f"{name}/{layer}", len(dims) == 1, as_bf16)
+            for lo in range(0, n, _CHUNK)]
+    if len(jobs) > 1:
+        from concurrent.futures import ThreadPoolExecutor
+        with ThreadPoolExecutor(max_workers=min(16, os.cpu_count() or 1)) as ex:
+            list(ex.map(_fill_chunk, jobs))
+    else:
+        _fill_chunk(jobs[0])
+    return out.reshape(dims)
 
 
 def make_weights(shape: DecoderShape, seed: int) -> dict:

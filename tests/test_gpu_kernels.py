@@ -1,0 +1,125 @@
+"""GPU: single kernels and per-stage intermediates against the CPU oracle (localises faults)."""
+import numpy as np
+import pytest
+
+from oracle import decoder as O
+from paper_2605_10380_amd import inputs as I
+
+pytestmark = pytest.mark.gpu
+
+
+def _bf16_round(x):
+    return I.bf16_bits_to_f32(I.f32_to_bf16_bits(x.astype(np.float32))).astype(np.float64)
+
+
+@pytest.fixture(scope="module")
+def torch_cuda():
+    import torch
+    assert torch.cuda.is_available()
+    return torch
+
+
+# M values: skinny path (<= 64, MT 1/2/4, ragged) and tile path (> 64, ragged); K / N pick
+# different wavefront counts in the skinny kernel and both tile shapes
+GEMM_CASES = [(1, 64, 64), (9, 3072, 2048), (9, 2048, 8192), (17, 512, 256), (33, 128, 1024), (64, 2064, 192),
+              (65, 384, 128), (100, 200 * 16, 320), (256, 3072, 2048), (300, 1024, 512), (512, 33 * 128, 256)]
+
+
+@pytest.mark.parametrize("M,N,K", GEMM_CASES)
+@pytest.mark.parametrize("epi", [0, 1, 2])
+def test_bf16_gemm(torch_cuda, M, N, K, epi):
+    torch = torch_cuda
+    from paper_2605_10380_amd import binding as B
+    rng = np.random.default_rng(M * 7 + N + K + epi)
+    A = I.f32_to_bf16_bits(rng.standard_normal((M, K), dtype=np.float32))
+    W = I.f32_to_bf16_bits(rng.standard_normal((N, K), dtype=np.float32) * 0.05)
+    W2 = I.f32_to_bf16_bits(rng.standard_normal((N, K), dtype=np.float32) * 0.05)
+    C0 = rng.standard_normal((M, N), dtype=np.float32)
+    dev = lambda a: torch.from_numpy(a).view(torch.bfloat16).cuda() if a.dtype == np.uint16 else torch.from_numpy(a).cuda()
+    dA, dW, dW2 = dev(A), dev(W), dev(W2)
+    ref = O.widen(A) @ O.widen(W).T
+    if epi == 2:
+        dC = torch.zeros((M, N), dtype=torch.bfloat16, device="cuda")
+    else:
+        dC = dev(C0.copy())
+    B.ax_dbg_gemm(B.AX_BF16, epi, dA.data_ptr(), dW.data_ptr(), dW2.data_ptr(), dC.data_ptr(), M, N, K)
+    got = dC.float().cpu().numpy().astype(np.float64)
+    scale = np.abs(ref).max()
+    if epi == 0:
+        assert np.abs(got - ref).max() <= 2e-5 * scale + 1e-6
+    elif epi == 1:
+        assert np.abs(got - (C0 + ref)).max() <= 2e-5 * scale + 1e-5
+    else:
+        want = O.silu(ref) * (O.widen(A) @ O.widen(W2).T)
+        assert np.abs(got - want).max() <= 2 ** -8 * np.abs(want).max() + 1e-6
+
+
+@pytest.mark.parametrize("M,N,K", [(5, 37, 19), (64, 688, 256), (70, 256, 688), (130, 4096, 256)])
+@pytest.mark.parametrize("epi", [0, 1, 2])
+def test_f32_gemm(torch_cuda, M, N, K, epi):
+    torch = torch_cuda
+    from paper_2605_10380_amd import binding as B
+    rng = np.random.default_rng(M + N + K + epi)
+    A = rng.standard_normal((M, K), dtype=np.float32)
+    W = rng.standard_normal((N, K), dtype=np.float32) * np.float32(0.05)
+    W2 = rng.standard_normal((N, K), dtype=np.float32) * np.float32(0.05)
+    C0 = rng.standard_normal((M, N), dtype=np.float32)
+    dA, dW, dW2, dC = (torch.from_numpy(a.copy()).cuda() for a in (A, W, W2, C0))
+    B.ax_dbg_gemm(B.AX_F32, epi, dA.data_ptr(), dW.data_ptr(), dW2.data_ptr(), dC.data_ptr(), M, N, K)
+    got = dC.cpu().numpy().astype(np.float64)
+    ref = A.astype(np.float64) @ W.astype(np.float64).T
+    want = ref if epi == 0 else C0 + ref if epi == 1 else O.silu(ref) * (A.astype(np.float64) @ W2.astype(np.float64).T)
+    assert np.abs(got - want).max() <= 1e-5 * max(1.0, np.abs(want).max())
+
+
+STAGE_SHAPES = {
+    "f32": I.DecoderShape("st-f32", 1, 256, 4, 2, 64, 688, 512, "f32"),
+    "bf16-hd64": I.DecoderShape("st-b64", 1, 256, 8, 2, 64, 512, 512, "bf16"),
+    "bf16-hd128-g3": I.DecoderShape("st-b128", 1, 384, 6, 2, 128, 512, 512, "bf16"),
+}
+
+
+@pytest.mark.parametrize("which", list(STAGE_SHAPES))
+@pytest.mark.parametrize("P,T", [(0, 5), (37, 9), (100, 70)])
+def test_single_layer_stages(torch_cuda, which, P, T):
+    """Each stage of a one-layer model against the oracle's intermediates: pre-rotary qkv,
+    rotated q, attention output, SwiGLU activations, residual stream, normed LM-head input."""
+    from paper_2605_10380_amd import binding as B
+    sh = STAGE_SHAPES[which]
+    w = I.make_weights(sh, 5)
+    toks = I.templated_prompt(sh.vocab, 5, P + T)
+    dm = B.DeviceModel(sh, w, max_pos=512, max_tokens=128, pool_tokens=1024)
+    kv = dm.new_kv()
+    if P:
+        dm.extend(kv, toks[:P])
+    logits = dm.extend(kv, toks[P:], B.AX_OUT_ALL_LOGITS).cpu().numpy().astype(np.float64)
+    okv = O.KVCache(sh.n_layers, sh.n_kv_heads, sh.head_dim)
+    if P:
+        O.forward(sh, w, toks[:P], okv)
+    tr = {}
+    ref = O.forward(sh, w, toks[P:], okv, trace=tr)
+    bf = sh.dtype == "bf16"
+    Hq, hd = sh.n_q_heads, sh.head_dim
+
+    def read(which_buf, cols, act):
+        if act and bf:
+            a = np.zeros((T, cols), dtype=np.uint16)
+            B.ax_dbg_read(dm.model, which_buf, a)
+            return I.bf16_bits_to_f32(a).astype(np.float64)
+        a = np.zeros((T, cols), dtype=np.float32)
+        B.ax_dbg_read(dm.model, which_buf, a)
+        return a.astype(np.float64)
+
+    tol = 2e-2 if bf else 2e-5      # relative to the stage's largest magnitude
+    stages = [("qkv", read(1, sh.qkv_rows, False), tr["qkv"]),
+              ("q", read(2, Hq * hd, True), tr["q"].reshape(T, -1)),
+              ("attn", read(3, Hq * hd, True), tr["attn"].reshape(T, -1)),
+              ("ffn", read(4, sh.d_ff, True), tr["ffn"]),
+              ("x", read(0, sh.d_model, False), tr["x"]),
+              ("h_out", read(5, sh.d_model, True), tr["h_out"]),
+              ("logits", logits, ref)]
+    errs = {name: float(np.abs(g - r).max() / np.abs(r).max()) for name, g, r in stages}
+    print(which, P, T, {k: f"{v:.2e}" for k, v in errs.items()})
+    for name, e in errs.items():
+        assert e <= tol, (name, errs)
+    dm.close()
