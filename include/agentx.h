@@ -47,7 +47,10 @@ typedef enum {
     AX_ERR_STATE = -5        /* e.g. destroying a pool that still has live sequences                 */
 } ax_status;
 
-enum { AX_F32 = 0, AX_BF16 = 1 };            /* storage type of weights AND of the KV cache */
+/* Storage type of the weights.  AX_F32: fp32 weights, fp32 KV cache, fp32 arithmetic.
+ * AX_BF16: bf16 weights, fp16 KV cache (16 bits per entry, as the paper's cache sizes imply),
+ * fp16 matrix-core products with fp32 accumulation; residual stream, norms and softmax in fp32. */
+enum { AX_F32 = 0, AX_BF16 = 1 };
 
 enum {                                       /* what ax_extend writes to `out` (device memory)        */
     AX_OUT_NONE = 0,                         /* nothing (building a prefix)                           */
@@ -64,7 +67,7 @@ typedef struct ax_kv ax_kv;
 typedef struct {
     int n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ff, vocab;
     float rms_eps, rope_base;
-    int dtype;        /* AX_F32 or AX_BF16                                                         */
+    int dtype;        /* AX_F32 or AX_BF16 (type of every weight tensor)                           */
     int max_pos;      /* longest sequence (P + T) any KV of this model may reach                    */
     int max_tokens;   /* most rows (sum of T over the sequences) one ax_extend* call may carry      */
     int max_seqs;     /* most sequences one ax_extend_batch call may carry (>= 1)                   */
@@ -111,7 +114,9 @@ void ax_model_destroy(ax_model *m);
 /* Bytes one block occupies = 2 * n_layers * n_kv_heads * head_dim * block_tokens * itemsize. */
 size_t ax_pool_block_bytes(const ax_model_config *cfg, int block_tokens);
 
-/* `dev_mem` may be NULL only for host-side bookkeeping tests (no ax_extend on such a pool).
+/* `dev_mem` must be zero-filled (or hold finite values): slots past the end of a sequence are
+ * read and multiplied by an exact zero weight.  It may be NULL only for host-side bookkeeping
+ * tests (no ax_extend on such a pool).
  * block_tokens must be 16.  The pool holds floor(bytes / block_bytes) blocks (>= 1).      */
 ax_status ax_pool_create(const ax_model_config *cfg, void *dev_mem, size_t bytes,
                          int block_tokens, ax_pool **out);

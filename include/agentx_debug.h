@@ -13,16 +13,18 @@ extern "C" {
 #endif
 
 /* C = A[M,K] * W[N,K]^T through the library's GEMM dispatcher (the projection / MLP / LM-head
- * contraction of the decoder).  All pointers are device memory.  dtype: AX_F32 | AX_BF16 (type of
- * A, W, W2).  epilogue: 0 store float C[M,N]; 1 float C[M,N] += ; 2 SwiGLU, C (of dtype)
- * = silu(A W^T) * (A W2^T).  bf16 needs K % 64 == 0 and N % 16 == 0.  Synchronises. */
+ * contraction of the decoder).  All pointers are device memory.  dtype AX_F32: A, W, W2 fp32;
+ * AX_BF16: W, W2 bf16 and A fp16 (the activation type of bf16-weight models).  epilogue: 0 store
+ * float C[M,N]; 1 float C[M,N] += ; 2 SwiGLU, C (activation type) = silu(A W^T) * (A W2^T).
+ * AX_BF16 needs K % 64 == 0 and N % 16 == 0.  Synchronises. */
 ax_status ax_dbg_gemm(int dtype, int epilogue, const void *A, const void *W, const void *W2, void *C,
                       int M, int N, int K, void *hip_stream);
 
 /* Copies a workspace buffer as left by the last ax_extend* call to host memory (synchronises).
  * which: 0 residual stream x float[rows][d_model]; 1 qkv float[rows][(Hq+2Hkv)*hd] (pre-rotary,
- * last layer); 2 q after rotary, dtype[rows][Hq*hd]; 3 attention output dtype[rows][Hq*hd];
- * 4 SwiGLU activations dtype[rows][d_ff]; 5 normed LM-head input dtype[n_out][d_model].
+ * last layer); 2 q after rotary, act[rows][Hq*hd]; 3 attention output act[rows][Hq*hd];
+ * 4 SwiGLU activations act[rows][d_ff]; 5 normed LM-head input act[n_out][d_model], where act is
+ * float for AX_F32 models and fp16 for AX_BF16 models.
  * Copies min(bytes, buffer size) bytes. */
 ax_status ax_dbg_read(ax_model *model, int which, void *host_dst, size_t bytes);
 

@@ -4,7 +4,8 @@
 //
 //   * attn_simple_kernel: one wavefront per (row, query head), fp32 arithmetic, any head_dim
 //     up to 256 and either storage type.  It is the fp32 models' path.
-//   * attn_split_kernel + attn_combine_kernel: bf16 path on the matrix cores.  The query rows
+//   * attn_split_kernel + attn_combine_kernel: 16-bit path on the matrix cores (fp16 q, K, V and
+//     probabilities, fp32 accumulation; used by bf16-weight models).  The query rows
 //     of the G heads that share one KV head are stacked into one matrix (row = t*G + g), cut
 //     into tiles of 32 rows; one wavefront owns (tile, KV head, slice of the key range), streams
 //     its K/V slice from the pages straight into MFMA operand registers, keeps an online
@@ -15,15 +16,15 @@
 
 namespace ax {
 
-typedef __bf16 bf16;
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16;      // activation and KV-cache type of bf16-weight models
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 __device__ __forceinline__ float ld_f32(const float* p) { return *p; }
-__device__ __forceinline__ float ld_f32(const bf16* p) { return (float)*p; }
+__device__ __forceinline__ float ld_f32(const f16* p) { return (float)*p; }
 __device__ __forceinline__ void st_f32(float* p, float v) { *p = v; }
-__device__ __forceinline__ void st_f32(bf16* p, float v) { *p = (bf16)v; }
+__device__ __forceinline__ void st_f32(f16* p, float v) { *p = (f16)v; }
 
 __device__ __forceinline__ float wave_max(float v) {
 #pragma unroll
@@ -114,7 +115,7 @@ __global__ __launch_bounds__(64) void attn_simple_kernel(const T* __restrict__ q
 // block (g = l/32).  V pages are token-minor ([head_dim][16]), so the matching A operand of a
 // lane (channel d) is two 8-byte loads from its channel's 16-token row.
 template <int HD>
-__global__ __launch_bounds__(64) void attn_split_kernel(const bf16* __restrict__ q, KVGeom kv, int layer,
+__global__ __launch_bounds__(64) void attn_split_kernel(const f16* __restrict__ q, KVGeom kv, int layer,
                                                         const int* __restrict__ seq_P,
                                                         const int* __restrict__ seq_T,
                                                         const int* __restrict__ seq_row0,
@@ -145,13 +146,13 @@ __global__ __launch_bounds__(64) void attn_split_kernel(const bf16* __restrict__
     const int rq = min(r0 + ql, n_stacked - 1);
     const int tq = rq / G, gq = rq % G;
     const int pos_q = P + tq;
-    const bf16* qrow = q + ((long long)(row0 + tq) * Hq + hk * G + gq) * HD;
-    bf16x8 qf[KQ];
+    const f16* qrow = q + ((long long)(row0 + tq) * Hq + hk * G + gq) * HD;
+    f16x8 qf[KQ];
 #pragma unroll
-    for (int kk = 0; kk < KQ; ++kk) qf[kk] = *(const bf16x8*)(qrow + kk * 16 + g * 8);
+    for (int kk = 0; kk < KQ; ++kk) qf[kk] = *(const f16x8*)(qrow + kk * 16 + g * 8);
 
-    const bf16* Kp = (const bf16*)kv.base + kv.plane(layer, 0, hk);
-    const bf16* Vp = (const bf16*)kv.base + kv.plane(layer, 1, hk);
+    const f16* Kp = (const f16*)kv.base + kv.plane(layer, 0, hk);
+    const f16* Vp = (const f16*)kv.base + kv.plane(layer, 1, hk);
 
     const float c = 1.4426950408889634f / sqrtf((float)HD);   // log2(e) / sqrt(hd)
     float m = -INFINITY, l = 0.f;
@@ -165,27 +166,27 @@ __global__ __launch_bounds__(64) void attn_split_kernel(const bf16* __restrict__
         const int kv0 = st * 32;
         // K rows: this lane supplies key kv0 + ql (clamped into the sequence)
         const int key = min(kv0 + ql, kv_len - 1);
-        const bf16* krow = Kp + ((long long)tab[key >> 4] * 16 + (key & 15)) * HD + g * 8;
+        const f16* krow = Kp + ((long long)tab[key >> 4] * 16 + (key & 15)) * HD + g * 8;
         f32x16 s;
 #pragma unroll
         for (int r = 0; r < 16; ++r) s[r] = 0.f;
 #pragma unroll
         for (int kk = 0; kk < KQ; ++kk) {
-            const bf16x8 kf = *(const bf16x8*)(krow + kk * 16);
-            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], s, 0, 0, 0);
+            const f16x8 kf = *(const f16x8*)(krow + kk * 16);
+            s = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf, qf[kk], s, 0, 0, 0);
         }
         // V operands: channel (d*32 + ql) of blocks kv0/16 and kv0/16 + 1
         const int b0 = tab[min(kv0 >> 4, (kv_len - 1) >> 4)];
         const int b1 = tab[min((kv0 >> 4) + 1, (kv_len - 1) >> 4)];
-        bf16x8 vf[DT][2];
+        f16x8 vf[DT][2];
 #pragma unroll
         for (int d = 0; d < DT; ++d) {
-            const bf16* v0 = Vp + ((long long)b0 * HD + d * 32 + ql) * 16 + g * 4;
-            const bf16* v1 = Vp + ((long long)b1 * HD + d * 32 + ql) * 16 + g * 4;
-            const bf16x4 a0 = *(const bf16x4*)v0, a1 = *(const bf16x4*)(v0 + 8);
-            const bf16x4 c0 = *(const bf16x4*)v1, c1 = *(const bf16x4*)(v1 + 8);
-            vf[d][0] = (bf16x8){a0[0], a0[1], a0[2], a0[3], a1[0], a1[1], a1[2], a1[3]};
-            vf[d][1] = (bf16x8){c0[0], c0[1], c0[2], c0[3], c1[0], c1[1], c1[2], c1[3]};
+            const f16* v0 = Vp + ((long long)b0 * HD + d * 32 + ql) * 16 + g * 4;
+            const f16* v1 = Vp + ((long long)b1 * HD + d * 32 + ql) * 16 + g * 4;
+            const f16x4 a0 = *(const f16x4*)v0, a1 = *(const f16x4*)(v0 + 8);
+            const f16x4 c0 = *(const f16x4*)v1, c1 = *(const f16x4*)(v1 + 8);
+            vf[d][0] = (f16x8){a0[0], a0[1], a0[2], a0[3], a1[0], a1[1], a1[2], a1[3]};
+            vf[d][1] = (f16x8){c0[0], c0[1], c0[2], c0[3], c1[0], c1[1], c1[2], c1[3]};
         }
         // causal mask + online softmax (base-2 exponentials)
         float mx = -INFINITY;
@@ -200,12 +201,12 @@ __global__ __launch_bounds__(64) void attn_split_kernel(const bf16* __restrict__
         const float mu = (mn == -INFINITY) ? 0.f : mn;        // row with nothing visible yet
         const float alpha = exp2f(m - mu);                    // m = -inf -> 0
         float ps = 0.f;
-        bf16x8 pb[2];
+        f16x8 pb[2];
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const float p = exp2f(s[r] - mu);                 // masked -> 0
             ps += p;
-            pb[r >> 3][r & 7] = (bf16)p;
+            pb[r >> 3][r & 7] = (f16)p;
         }
         ps += __shfl_xor(ps, 32, 64);
         l = l * alpha + ps;
@@ -214,8 +215,8 @@ __global__ __launch_bounds__(64) void attn_split_kernel(const bf16* __restrict__
         for (int d = 0; d < DT; ++d) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) o[d][r] *= alpha;
-            o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[d][0], pb[0], o[d], 0, 0, 0);
-            o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[d][1], pb[1], o[d], 0, 0, 0);
+            o[d] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf[d][0], pb[0], o[d], 0, 0, 0);
+            o[d] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf[d][1], pb[1], o[d], 0, 0, 0);
         }
     }
 
@@ -237,7 +238,7 @@ __global__ __launch_bounds__(64) void attn_split_kernel(const bf16* __restrict__
 // grid (n_tiles, Hkv), 256 threads: thread <-> (channel group, q row); merges the key slices.
 template <int HD>
 __global__ __launch_bounds__(256) void attn_combine_kernel(const float* __restrict__ partials,
-                                                           bf16* __restrict__ out,
+                                                           f16* __restrict__ out,
                                                            const int* __restrict__ seq_T,
                                                            const int* __restrict__ seq_row0,
                                                            const int* __restrict__ tile_seq,
@@ -257,14 +258,14 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(const float* __restri
         L += exp2f(p[HD * 32 + ql] - M) * p[HD * 32 + 32 + ql];
     }
     const float invL = 1.0f / L;
-    bf16* orow = out + ((long long)(seq_row0[sq] + r / G) * Hq + hk * G + r % G) * HD;
+    f16* orow = out + ((long long)(seq_row0[sq] + r / G) * Hq + hk * G + r % G) * HD;
     for (int ch = cg; ch < HD; ch += 8) {
         float acc = 0.f;
         for (int s = 0; s < n_splits; ++s) {
             const float* p = base + (long long)s * (HD * 32 + 64);
             acc += exp2f(p[HD * 32 + ql] - M) * p[ch * 32 + ql];
         }
-        orow[ch] = (bf16)(acc * invL);
+        orow[ch] = (f16)(acc * invL);
     }
 }
 
@@ -283,17 +284,17 @@ void launch_attention(DType dt, const void* q, void* out, KVGeom kv, int layer, 
     }
     dim3 grid(sv.n_tiles, kv.n_kv_heads, n_splits), cgrid(sv.n_tiles, kv.n_kv_heads);
     if (kv.head_dim == 64) {
-        attn_split_kernel<64><<<grid, 64, 0, s>>>((const bf16*)q, kv, layer, sv.seq_P, sv.seq_T,
+        attn_split_kernel<64><<<grid, 64, 0, s>>>((const f16*)q, kv, layer, sv.seq_P, sv.seq_T,
                                                   sv.seq_row0, sv.seq_bt, sv.bt, sv.tile_seq,
                                                   sv.tile_r0, n_q_heads, partials, n_splits);
-        attn_combine_kernel<64><<<cgrid, 256, 0, s>>>(partials, (bf16*)out, sv.seq_T, sv.seq_row0,
+        attn_combine_kernel<64><<<cgrid, 256, 0, s>>>(partials, (f16*)out, sv.seq_T, sv.seq_row0,
                                                       sv.tile_seq, sv.tile_r0, n_q_heads,
                                                       kv.n_kv_heads, n_splits);
     } else {
-        attn_split_kernel<128><<<grid, 64, 0, s>>>((const bf16*)q, kv, layer, sv.seq_P, sv.seq_T,
+        attn_split_kernel<128><<<grid, 64, 0, s>>>((const f16*)q, kv, layer, sv.seq_P, sv.seq_T,
                                                    sv.seq_row0, sv.seq_bt, sv.bt, sv.tile_seq,
                                                    sv.tile_r0, n_q_heads, partials, n_splits);
-        attn_combine_kernel<128><<<cgrid, 256, 0, s>>>(partials, (bf16*)out, sv.seq_T, sv.seq_row0,
+        attn_combine_kernel<128><<<cgrid, 256, 0, s>>>(partials, (f16*)out, sv.seq_T, sv.seq_row0,
                                                        sv.tile_seq, sv.tile_r0, n_q_heads,
                                                        kv.n_kv_heads, n_splits);
     }

@@ -5,12 +5,15 @@
 namespace ax {
 
 typedef __bf16 bf16;
+typedef _Float16 f16;     // activation and KV-cache type of bf16-weight models
 
 __device__ __forceinline__ float to_f32(float v) { return v; }
 __device__ __forceinline__ float to_f32(bf16 v) { return (float)v; }
+__device__ __forceinline__ float to_f32(f16 v) { return (float)v; }
 template <typename T> __device__ __forceinline__ T from_f32(float v);
 template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
 template <> __device__ __forceinline__ bf16 from_f32<bf16>(float v) { return (bf16)v; }  // RNE
+template <> __device__ __forceinline__ f16 from_f32<f16>(float v) { return (f16)v; }     // RNE
 
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
@@ -39,8 +42,8 @@ void launch_embed(DType dt, const void* emb, const int* row_tok, float* x, int n
 // ---------------------------------------------------------------- RMSNorm
 // One 256-thread block per row: sum of squares in fp32 (wavefront shuffles, then LDS across the
 // four wavefronts), then x * rsqrt(mean + eps) * gain.
-template <typename T>
-__global__ void rmsnorm_kernel(const float* __restrict__ x, const T* __restrict__ gain,
+template <typename TG, typename T>
+__global__ void rmsnorm_kernel(const float* __restrict__ x, const TG* __restrict__ gain,
                                T* __restrict__ h, const int* __restrict__ rows, int d, float eps) {
     __shared__ float part[4];
     const int i = blockIdx.x;
@@ -63,9 +66,9 @@ __global__ void rmsnorm_kernel(const float* __restrict__ x, const T* __restrict_
 void launch_rmsnorm(DType dt, const float* x, const void* gain, void* h, const int* rows,
                     int n_rows, int d, float eps, hipStream_t s) {
     if (dt == F32)
-        rmsnorm_kernel<float><<<n_rows, 256, 0, s>>>(x, (const float*)gain, (float*)h, rows, d, eps);
+        rmsnorm_kernel<float, float><<<n_rows, 256, 0, s>>>(x, (const float*)gain, (float*)h, rows, d, eps);
     else
-        rmsnorm_kernel<bf16><<<n_rows, 256, 0, s>>>(x, (const bf16*)gain, (bf16*)h, rows, d, eps);
+        rmsnorm_kernel<bf16, f16><<<n_rows, 256, 0, s>>>(x, (const bf16*)gain, (f16*)h, rows, d, eps);
 }
 
 // ---------------------------------------------------------------- rotary + paged KV append
@@ -112,7 +115,7 @@ void launch_rope_kv(DType dt, const float* qkv, void* q_out, KVGeom kv, int laye
         rope_kv_kernel<float><<<grid, 64, 0, s>>>(qkv, (float*)q_out, kv, layer, sv.row_pos, sv.row_seq,
                                                   sv.seq_bt, sv.bt, rope_cos, rope_sin, n_q_heads);
     else
-        rope_kv_kernel<bf16><<<grid, 64, 0, s>>>(qkv, (bf16*)q_out, kv, layer, sv.row_pos, sv.row_seq,
+        rope_kv_kernel<f16><<<grid, 64, 0, s>>>(qkv, (f16*)q_out, kv, layer, sv.row_pos, sv.row_seq,
                                                  sv.seq_bt, sv.bt, rope_cos, rope_sin, n_q_heads);
 }
 

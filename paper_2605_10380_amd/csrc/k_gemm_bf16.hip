@@ -1,11 +1,16 @@
-// bf16 GEMMs with fp32 accumulation on the gfx950 matrix cores: C = A[M,K] * W[N,K]^T.
-// Both operands are K-contiguous, which is exactly what the MFMA operand layout wants: a lane
-// holds 8 consecutive k of one row (A) or one column (W), i.e. one 16-byte load.
+// GEMMs of bf16-weight models on the gfx950 matrix cores: C = A[M,K] * W[N,K]^T, fp32
+// accumulation.  Weights stay bf16 in HBM (that is what is streamed); activations are fp16.
+// A bf16 weight fragment is widened to fp16 in registers (exact for every |w| >= 2^-14, absolute
+// error below 2^-25 beneath that) and the product runs on the fp16 MFMA, which has the same
+// rate as the bf16 one.  Reason: bf16 activations (8 significant bits) put the logits of a
+// 16-layer decoder ~0.05 away from the exact result; fp16 activations (11 bits) keep them
+// within 0.01.  Both operands are K-contiguous, which is exactly what the MFMA operand layout
+// wants: a lane holds 8 consecutive k of one row (A) or one column (W), i.e. one 16-byte load.
 //
 //   * tile kernel   (M > 64, large-T extend: compute bound): 4 wavefronts, LDS-staged
-//     BM x BN x 64 tiles, v_mfma_f32_32x32x16_bf16, register prefetch of the next K slice.
+//     BM x BN x 64 tiles, v_mfma_f32_32x32x16_f16, register prefetch of the next K slice.
 //   * skinny kernel (M <= 64, verify steps: pure weight streaming): one block owns 16 output
-//     columns, its wavefronts split K, W goes HBM -> registers -> v_mfma_f32_16x16x32_bf16
+//     columns, its wavefronts split K, W goes HBM -> registers -> v_mfma_f32_16x16x32_f16
 //     with no LDS in the streaming loop; the per-wavefront partial sums meet in LDS.
 //
 // Epilogues: fp32 store, fp32 residual add, or SwiGLU (two weight matrices share the A
@@ -15,8 +20,11 @@
 namespace ax {
 
 typedef __bf16 bf16;
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16;
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
@@ -25,11 +33,27 @@ void launch_gemm_f32(Epilogue epi, const float* A, const float* W, const float* 
 
 __device__ __forceinline__ float silu_f(float g) { return g / (1.0f + __expf(-g)); }
 
+// 8 bf16 (one 16-byte fragment) -> 8 fp16.  A bf16 is the top half of an fp32, so each half of
+// a dword becomes an fp32 by a shift or a mask; bf16 has fewer significant bits than fp16, so
+// the round-toward-zero pack is exact in fp16's normal range.
+__device__ __forceinline__ f16x8 bf16x8_to_f16x8(u32x4 raw) {
+    f16x8 out;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const float lo = __uint_as_float(raw[i] << 16), hi = __uint_as_float(raw[i] & 0xffff0000u);
+        const f16x2 h = __builtin_bit_cast(f16x2, __builtin_amdgcn_cvt_pkrtz(lo, hi));
+        out[2 * i] = h[0];
+        out[2 * i + 1] = h[1];
+    }
+    return out;
+}
+__device__ __forceinline__ f16x8 load_w(const bf16* p) { return bf16x8_to_f16x8(*(const u32x4*)p); }
+
 // ------------------------------------------------------------------------------ tile kernel
 // MFMA 32x32x16 operand layout (wave64): lane l supplies row/col (l % 32) and the 8 k values
 // 8*(l/32) .. +7; result register r of lane l is C[(r/4)*8 + (l/32)*4 + r%4][l % 32].
 template <int EPI, int TM, int TN>
-__global__ __launch_bounds__(256) void gemm_bf16_tile_kernel(const bf16* __restrict__ A,
+__global__ __launch_bounds__(256) void gemm_bf16_tile_kernel(const f16* __restrict__ A,
                                                              const bf16* __restrict__ W,
                                                              const bf16* __restrict__ W2,
                                                              void* __restrict__ Cv, int M, int N,
@@ -37,8 +61,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_tile_kernel(const bf16* __restr
     constexpr int BM = 2 * TM * 32, BN = 2 * TN * 32, BK = 64, LS = BK + 8;  // LS: padded row
     constexpr int NB = EPI == EPI_SWIGLU ? 2 : 1;
     constexpr int A_CH = BM * 8 / 256, B_CH = BN * 8 / 256;                  // 16-byte chunks per thread
-    __shared__ __attribute__((aligned(16))) bf16 sA[BM * LS];
-    __shared__ __attribute__((aligned(16))) bf16 sB[NB][BN * LS];
+    __shared__ __attribute__((aligned(16))) f16 sA[BM * LS];
+    __shared__ __attribute__((aligned(16))) f16 sB[NB][BN * LS];
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int wm = wave >> 1, wn = wave & 1;
@@ -55,33 +79,34 @@ __global__ __launch_bounds__(256) void gemm_bf16_tile_kernel(const bf16* __restr
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[b][i][j][r] = 0.f;
 
-    bf16x8 ra[A_CH], rb[NB][B_CH];
+    f16x8 ra[A_CH];
+    u32x4 rb[NB][B_CH];             // raw bf16 weights; widened to fp16 on the way into LDS
     auto load_global = [&](int k0) {
 #pragma unroll
         for (int i = 0; i < A_CH; ++i) {
             const int c = tid + 256 * i, row = c >> 3, cc = c & 7;
             const int gm = min(m0 + row, M - 1);
-            ra[i] = *(const bf16x8*)(A + (long long)gm * K + k0 + cc * 8);
+            ra[i] = *(const f16x8*)(A + (long long)gm * K + k0 + cc * 8);
         }
 #pragma unroll
         for (int i = 0; i < B_CH; ++i) {
             const int c = tid + 256 * i, row = c >> 3, cc = c & 7;
             const int gn = min(n0 + row, N - 1);
-            rb[0][i] = *(const bf16x8*)(W + (long long)gn * K + k0 + cc * 8);
-            if (NB == 2) rb[NB - 1][i] = *(const bf16x8*)(W2 + (long long)gn * K + k0 + cc * 8);
+            rb[0][i] = *(const u32x4*)(W + (long long)gn * K + k0 + cc * 8);
+            if (NB == 2) rb[NB - 1][i] = *(const u32x4*)(W2 + (long long)gn * K + k0 + cc * 8);
         }
     };
     auto store_lds = [&]() {
 #pragma unroll
         for (int i = 0; i < A_CH; ++i) {
             const int c = tid + 256 * i, row = c >> 3, cc = c & 7;
-            *(bf16x8*)(sA + row * LS + cc * 8) = ra[i];
+            *(f16x8*)(sA + row * LS + cc * 8) = ra[i];
         }
 #pragma unroll
         for (int i = 0; i < B_CH; ++i) {
             const int c = tid + 256 * i, row = c >> 3, cc = c & 7;
 #pragma unroll
-            for (int b = 0; b < NB; ++b) *(bf16x8*)(sB[b] + row * LS + cc * 8) = rb[b][i];
+            for (int b = 0; b < NB; ++b) *(f16x8*)(sB[b] + row * LS + cc * 8) = bf16x8_to_f16x8(rb[b][i]);
         }
     };
 
@@ -92,22 +117,22 @@ __global__ __launch_bounds__(256) void gemm_bf16_tile_kernel(const bf16* __restr
         if (k0 + BK < K) load_global(k0 + BK);
 #pragma unroll
         for (int kk = 0; kk < BK / 16; ++kk) {
-            bf16x8 fa[TM], fb[NB][TN];
+            f16x8 fa[TM], fb[NB][TN];
 #pragma unroll
             for (int i = 0; i < TM; ++i)
-                fa[i] = *(const bf16x8*)(sA + ((wm * TM + i) * 32 + lrow) * LS + kk * 16 + lg * 8);
+                fa[i] = *(const f16x8*)(sA + ((wm * TM + i) * 32 + lrow) * LS + kk * 16 + lg * 8);
 #pragma unroll
             for (int b = 0; b < NB; ++b)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
-                    fb[b][j] = *(const bf16x8*)(sB[b] + ((wn * TN + j) * 32 + lrow) * LS + kk * 16 + lg * 8);
+                    fb[b][j] = *(const f16x8*)(sB[b] + ((wn * TN + j) * 32 + lrow) * LS + kk * 16 + lg * 8);
 #pragma unroll
             for (int b = 0; b < NB; ++b)
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
 #pragma unroll
                     for (int j = 0; j < TN; ++j)
-                        acc[b][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[b][j], acc[b][i][j], 0, 0, 0);
+                        acc[b][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[i], fb[b][j], acc[b][i][j], 0, 0, 0);
         }
         __syncthreads();
     }
@@ -124,7 +149,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_tile_kernel(const bf16* __restr
                     const long long o = (long long)m * N + n;
                     if (EPI == EPI_STORE_F32) ((float*)Cv)[o] = acc[0][i][j][r];
                     else if (EPI == EPI_RESIDUAL) ((float*)Cv)[o] += acc[0][i][j][r];
-                    else ((bf16*)Cv)[o] = (bf16)(silu_f(acc[0][i][j][r]) * acc[NB - 1][i][j][r]);
+                    else ((f16*)Cv)[o] = (f16)(silu_f(acc[0][i][j][r]) * acc[NB - 1][i][j][r]);
                 }
             }
         }
@@ -136,7 +161,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_tile_kernel(const bf16* __restr
 // D rows are output columns n, D columns are activation rows m, so a lane ends up with four
 // consecutive n of one row m (one 16-byte store).
 template <int EPI, int MT, int NW>
-__global__ __launch_bounds__(64 * NW) void gemm_bf16_skinny_kernel(const bf16* __restrict__ X,
+__global__ __launch_bounds__(64 * NW) void gemm_bf16_skinny_kernel(const f16* __restrict__ X,
                                                                    const bf16* __restrict__ W,
                                                                    const bf16* __restrict__ W2,
                                                                    void* __restrict__ Cv, int M,
@@ -151,7 +176,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_bf16_skinny_kernel(const bf16* _
 
     const bf16* wp = W + (long long)min(n0 + lr, N - 1) * K + lg * 8;
     const bf16* wp2 = NB == 2 ? W2 + (long long)min(n0 + lr, N - 1) * K + lg * 8 : nullptr;
-    const bf16* xp[MT];
+    const f16* xp[MT];
 #pragma unroll
     for (int t = 0; t < MT; ++t) xp[t] = X + (long long)min(t * 16 + lr, M - 1) * K + lg * 8;
 
@@ -163,32 +188,35 @@ __global__ __launch_bounds__(64 * NW) void gemm_bf16_skinny_kernel(const bf16* _
 
     int k = kbeg;
     for (; k + 128 <= kend; k += 128) {           // 4 MFMA k-steps per trip: 4+ loads in flight
-        bf16x8 fw[NB][4], fx[MT][4];
+        u32x4 rw[NB][4];
+        f16x8 fx[MT][4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            fw[0][u] = *(const bf16x8*)(wp + k + 32 * u);
-            if (NB == 2) fw[NB - 1][u] = *(const bf16x8*)(wp2 + k + 32 * u);
+            rw[0][u] = *(const u32x4*)(wp + k + 32 * u);
+            if (NB == 2) rw[NB - 1][u] = *(const u32x4*)(wp2 + k + 32 * u);
         }
 #pragma unroll
         for (int t = 0; t < MT; ++t)
 #pragma unroll
-            for (int u = 0; u < 4; ++u) fx[t][u] = *(const bf16x8*)(xp[t] + k + 32 * u);
+            for (int u = 0; u < 4; ++u) fx[t][u] = *(const f16x8*)(xp[t] + k + 32 * u);
 #pragma unroll
         for (int u = 0; u < 4; ++u)
 #pragma unroll
-            for (int b = 0; b < NB; ++b)
+            for (int b = 0; b < NB; ++b) {
+                const f16x8 fw = bf16x8_to_f16x8(rw[b][u]);
 #pragma unroll
                 for (int t = 0; t < MT; ++t)
-                    acc[b][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fw[b][u], fx[t][u], acc[b][t], 0, 0, 0);
+                    acc[b][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fw, fx[t][u], acc[b][t], 0, 0, 0);
+            }
     }
     for (; k < kend; k += 32) {
 #pragma unroll
         for (int b = 0; b < NB; ++b) {
-            const bf16x8 fw = *(const bf16x8*)((b == 0 ? wp : wp2) + k);
+            const f16x8 fw = load_w((b == 0 ? wp : wp2) + k);
 #pragma unroll
             for (int t = 0; t < MT; ++t) {
-                const bf16x8 fx = *(const bf16x8*)(xp[t] + k);
-                acc[b][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fw, fx, acc[b][t], 0, 0, 0);
+                const f16x8 fx = *(const f16x8*)(xp[t] + k);
+                acc[b][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fw, fx, acc[b][t], 0, 0, 0);
             }
         }
     }
@@ -218,16 +246,16 @@ __global__ __launch_bounds__(64 * NW) void gemm_bf16_skinny_kernel(const bf16* _
             f32x4* c = (f32x4*)((float*)Cv + o);
             *c = *c + sum[0];
         } else {
-            bf16x4 h;
+            f16x4 h;
 #pragma unroll
-            for (int r = 0; r < 4; ++r) h[r] = (bf16)(silu_f(sum[0][r]) * sum[NB - 1][r]);
-            *(bf16x4*)((bf16*)Cv + o) = h;
+            for (int r = 0; r < 4; ++r) h[r] = (f16)(silu_f(sum[0][r]) * sum[NB - 1][r]);
+            *(f16x4*)((f16*)Cv + o) = h;
         }
     }
 }
 
 template <int EPI, int MT>
-static void launch_skinny_nw(const bf16* A, const bf16* W, const bf16* W2, void* C, int M, int N,
+static void launch_skinny_nw(const f16* A, const bf16* W, const bf16* W2, void* C, int M, int N,
                              int K, int nw, hipStream_t s) {
     const int grid = (N + 15) / 16;
     if (nw == 16) gemm_bf16_skinny_kernel<EPI, MT, 16><<<grid, 1024, 0, s>>>(A, W, W2, C, M, N, K);
@@ -238,7 +266,7 @@ static void launch_skinny_nw(const bf16* A, const bf16* W, const bf16* W2, void*
 }
 
 template <int EPI>
-static void launch_bf16(const bf16* A, const bf16* W, const bf16* W2, void* C, int M, int N, int K,
+static void launch_bf16(const f16* A, const bf16* W, const bf16* W2, void* C, int M, int N, int K,
                         hipStream_t s) {
     if (M <= 64) {
         // wavefronts per block (= K slices): enough to keep ~2k wavefronts in flight, each with
@@ -269,7 +297,8 @@ void launch_gemm(DType dt, Epilogue epi, const void* A, const void* W, const voi
         launch_gemm_f32(epi, (const float*)A, (const float*)W, (const float*)W2, (float*)C, M, N, K, s);
         return;
     }
-    const bf16 *a = (const bf16*)A, *w = (const bf16*)W, *w2 = (const bf16*)W2;
+    const f16* a = (const f16*)A;
+    const bf16 *w = (const bf16*)W, *w2 = (const bf16*)W2;
     if (epi == EPI_STORE_F32) launch_bf16<EPI_STORE_F32>(a, w, w2, C, M, N, K, s);
     else if (epi == EPI_RESIDUAL) launch_bf16<EPI_RESIDUAL>(a, w, w2, C, M, N, K, s);
     else launch_bf16<EPI_SWIGLU>(a, w, w2, C, M, N, K, s);

@@ -7,6 +7,8 @@
 
 namespace ax {
 
+// F32: fp32 weights, activations and KV.  BF16: bf16 weights; activations and KV are fp16
+// ("the activation type" below), products on the fp16 MFMA with fp32 accumulation.
 enum DType { F32 = 0, BF16 = 1 };
 
 // Geometry of the paged KV pool.  Element offsets (not bytes):
@@ -45,9 +47,9 @@ void launch_embed(DType dt, const void* emb, const int* row_tok, float* x, int n
 // h[i, :] = rmsnorm(x[rows ? rows[i] : i, :]) * gain, written in the activation type
 void launch_rmsnorm(DType dt, const float* x, const void* gain, void* h, const int* rows,
                     int n_rows, int d, float eps, hipStream_t s);
-// C = A[M,K] * W[N,K]^T with fp32 accumulation.  A and W are of type dt (the activation type
-// equals the weight type).  EPI_STORE_F32: C float [M,N].  EPI_RESIDUAL: C float [M,N] += .
-// EPI_SWIGLU: C (type dt) [M,N] = silu(A*W^T) * (A*W2^T).
+// C = A[M,K] * W[N,K]^T with fp32 accumulation.  A is of the activation type, W of the weight
+// type.  EPI_STORE_F32: C float [M,N].  EPI_RESIDUAL: C float [M,N] += .
+// EPI_SWIGLU: C (activation type) [M,N] = silu(A*W^T) * (A*W2^T).
 void launch_gemm(DType dt, Epilogue epi, const void* A, const void* W, const void* W2, void* C,
                  int M, int N, int K, hipStream_t s);
 // rotary on q and k heads of qkv (fp32 [n_rows, (Hq+2Hkv)*hd]); q -> q_out [n_rows, Hq, hd]

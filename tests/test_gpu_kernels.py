@@ -31,15 +31,16 @@ def test_bf16_gemm(torch_cuda, M, N, K, epi):
     torch = torch_cuda
     from paper_2605_10380_amd import binding as B
     rng = np.random.default_rng(M * 7 + N + K + epi)
-    A = I.f32_to_bf16_bits(rng.standard_normal((M, K), dtype=np.float32))
+    A = rng.standard_normal((M, K), dtype=np.float32).astype(np.float16)      # activations are fp16
     W = I.f32_to_bf16_bits(rng.standard_normal((N, K), dtype=np.float32) * 0.05)
     W2 = I.f32_to_bf16_bits(rng.standard_normal((N, K), dtype=np.float32) * 0.05)
     C0 = rng.standard_normal((M, N), dtype=np.float32)
     dev = lambda a: torch.from_numpy(a).view(torch.bfloat16).cuda() if a.dtype == np.uint16 else torch.from_numpy(a).cuda()
     dA, dW, dW2 = dev(A), dev(W), dev(W2)
-    ref = O.widen(A) @ O.widen(W).T
+    A64 = A.astype(np.float64)
+    ref = A64 @ O.widen(W).T
     if epi == 2:
-        dC = torch.zeros((M, N), dtype=torch.bfloat16, device="cuda")
+        dC = torch.zeros((M, N), dtype=torch.float16, device="cuda")
     else:
         dC = dev(C0.copy())
     B.ax_dbg_gemm(B.AX_BF16, epi, dA.data_ptr(), dW.data_ptr(), dW2.data_ptr(), dC.data_ptr(), M, N, K)
@@ -50,8 +51,8 @@ def test_bf16_gemm(torch_cuda, M, N, K, epi):
     elif epi == 1:
         assert np.abs(got - (C0 + ref)).max() <= 2e-5 * scale + 1e-5
     else:
-        want = O.silu(ref) * (O.widen(A) @ O.widen(W2).T)
-        assert np.abs(got - want).max() <= 2 ** -8 * np.abs(want).max() + 1e-6
+        want = O.silu(ref) * (A64 @ O.widen(W2).T)
+        assert np.abs(got - want).max() <= 2 ** -11 * np.abs(want).max() + 1e-6
 
 
 @pytest.mark.parametrize("M,N,K", [(5, 37, 19), (64, 688, 256), (70, 256, 688), (130, 4096, 256)])
@@ -103,14 +104,14 @@ def test_single_layer_stages(torch_cuda, which, P, T):
 
     def read(which_buf, cols, act):
         if act and bf:
-            a = np.zeros((T, cols), dtype=np.uint16)
+            a = np.zeros((T, cols), dtype=np.float16)
             B.ax_dbg_read(dm.model, which_buf, a)
-            return I.bf16_bits_to_f32(a).astype(np.float64)
+            return a.astype(np.float64)
         a = np.zeros((T, cols), dtype=np.float32)
         B.ax_dbg_read(dm.model, which_buf, a)
         return a.astype(np.float64)
 
-    tol = 2e-2 if bf else 2e-5      # relative to the stage's largest magnitude
+    tol = 4e-3 if bf else 2e-5      # relative to the stage's largest magnitude
     stages = [("qkv", read(1, sh.qkv_rows, False), tr["qkv"]),
               ("q", read(2, Hq * hd, True), tr["q"].reshape(T, -1)),
               ("attn", read(3, Hq * hd, True), tr["attn"].reshape(T, -1)),

@@ -42,6 +42,16 @@ def check_logits(sh, got, ref, what):
     return err
 
 
+def assert_argmax_of(idx, logits, slack=1e-5):
+    """idx[r] is the argmax of logits[r] up to summation-order noise: its logit is within
+    `slack` of the row maximum, and it is the exact argmax wherever the top-2 gap is larger."""
+    for r, i in enumerate(idx):
+        row = logits[r]
+        assert 0 <= i < len(row) and row[i] >= row.max() - slack, (r, int(i), int(np.argmax(row)))
+        if O.top2_margin(row.astype(np.float64)) > slack:
+            assert i == int(np.argmax(row))
+
+
 def run_verify_rounds(B, dm, sh, w, kv, ref_kv, pending, rounds, k, make_drafts):
     """Feeds both sides the same (pending, drafts) each round.  Where the results differ and the
     oracle's deciding row has a top-2 margin <= MARGIN the round is exempt and the GPU sequence
@@ -121,13 +131,14 @@ def test_extend_logits_small(B, which, P, T):
     # the other output modes agree with these logits
     B.ax_kv_truncate(kv, P)
     last = dm.extend(kv, toks[P:], B.AX_OUT_LAST_LOGITS).cpu().numpy()
-    np.testing.assert_array_equal(last[0], got[-1])
+    # (a different row count picks a different GEMM kernel, hence a different summation order)
+    np.testing.assert_allclose(last[0], got[-1], rtol=0, atol=1e-5)
     B.ax_kv_truncate(kv, P)
     am = dm.extend(kv, toks[P:], B.AX_OUT_ALL_ARGMAX).cpu().numpy()
-    np.testing.assert_array_equal(am, np.argmax(got, axis=-1))
+    assert_argmax_of(am, got)
     B.ax_kv_truncate(kv, P)
     la = dm.extend(kv, toks[P:], B.AX_OUT_LAST_ARGMAX).cpu().numpy()
-    assert la[0] == am[-1]
+    assert_argmax_of(la, got[-1:])
     B.ax_kv_free(kv)
     dm.close()
 
@@ -250,7 +261,7 @@ def test_batched_mixed_length_equals_separate(B, which):
         B.ax_kv_truncate(kvs[s], B.ax_kv_len(kvs[s]) - T_each[s])
     last = dm.extend_batch(kvs, news, B.AX_OUT_LAST_ARGMAX).cpu().numpy()
     ends = np.cumsum(T_each) - 1
-    np.testing.assert_array_equal(last, np.argmax(got[ends], axis=-1))
+    assert_argmax_of(last, got[ends])
     for kv in kvs + [root]:
         B.ax_kv_free(kv)
     dm.close()
