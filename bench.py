@@ -1,0 +1,244 @@
+#!/usr/bin/env python3
+"""Benchmark of the extend / verify hot path on one MI355X.
+
+A step is one pass of the whole path over the ~1B-class workload: the KV is cut back to the
+cached prefix (P = 4096), ONE extend of the uncached suffix (T = 256) is run, then 64 verify
+rounds at k = 8 with prompt-copied drafts (forward of 1 + k rows, vocabulary argmax, greedy
+acceptance, rollback).  Weights are random N(0, 0.02) bf16, tokens are synthetic templated
+Zipf draws; everything is resident in HBM before the timed region starts.
+
+Prints ONE JSON line.  `value` is extend tokens/s (T / time of the extend calls); the verify
+rate, the per-kernel roofline of the dominant kernel and the CPU oracle's rate on a bounded
+sample ride along.  One GPU only.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0           # MI355X HBM3E
+MFMA16_PEAK_TFLOPS = 2500.0     # dense bf16 / fp16 MFMA
+
+
+def torch_weights(torch, shape, seed, device):
+    """Random-init weights of the decoder on the device (N(0, 0.02); gains 1 + N(0, 0.02))."""
+    from paper_2605_10380_amd import inputs as I
+    g = torch.Generator(device=device)
+    g.manual_seed(seed)
+    tdt = torch.float32 if shape.dtype == "f32" else torch.bfloat16
+    out = {}
+    for name, layer, dims in I.weight_names(shape):
+        t = torch.randn(dims, generator=g, device=device, dtype=torch.float32) * 0.02
+        if len(dims) == 1:
+            t = t + 1.0
+        t = t.to(tdt).contiguous()
+        if layer is None:
+            out[name] = t
+        else:
+            out.setdefault(name, []).append(t)
+    return out
+
+
+def to_numpy_storage(torch, t):
+    if t.dtype == torch.bfloat16:
+        return t.view(torch.uint16).cpu().numpy() if hasattr(torch, "uint16") else t.view(torch.int16).cpu().numpy().view(np.uint16)
+    return t.cpu().numpy()
+
+
+def algorithmic(shape, P, T, k):
+    """Algorithmic bytes / FLOPs of the calls (weights and KV read once; causal attention)."""
+    L, d, hd, Hq, Hkv, F, V = (shape.n_layers, shape.d_model, shape.head_dim, shape.n_q_heads,
+                               shape.n_kv_heads, shape.d_ff, shape.vocab)
+    isz = shape.itemsize
+    kv_tok = 2 * L * Hkv * hd * isz
+    w_layers = L * shape.layer_params * isz
+    w_lm = V * d * isz
+    out = {}
+    R = 1 + k
+    Pv = P + T                      # verify rounds run after the extend
+    out["verify_bytes"] = w_layers + w_lm + (Pv + R) * kv_tok + R * kv_tok + R * d * isz
+    out["extend_bytes"] = w_layers + w_lm + (P + T) * kv_tok + T * kv_tok + T * d * isz
+    out["extend_flops"] = (2 * T * L * shape.layer_params + 2 * V * d
+                           + 4 * T * (P + (T + 1) / 2) * hd * Hq * L)
+    # per launch of each GEMM class: weight bytes + activation in + out; flops 2 M N K
+    def gemm(M, N, K, n_w=1, out_isz=4):
+        return {"bytes": n_w * N * K * isz + M * K * 2 + M * N * out_isz, "flops": 2.0 * M * N * K * n_w}
+    for tag, M, Mlm in (("verify", R, R), ("extend", T, 1)):
+        out[tag] = {
+            "qkv_proj": gemm(M, (Hq + 2 * Hkv) * hd, d),
+            "o_proj": gemm(M, d, Hq * hd),
+            "swiglu_gate_up": gemm(M, F, d, n_w=2, out_isz=2),
+            "down_proj": gemm(M, d, F),
+            "lm_head": gemm(Mlm, V, d),
+            "attention": {"bytes": (P + T) * 2 * Hkv * hd * isz + 2 * M * Hq * hd * 2,
+                          "flops": 4.0 * M * (P + (T if tag == "verify" else (T + 1) / 2)) * hd * Hq},
+        }
+    return out
+
+
+def cpu_oracle_baseline(torch, shape, w_dev, prompt, P, T, layers=2):
+    """The CPU oracle, as it stands, on a bounded sample of the same workload: the first
+    `layers` layers at full width over the full prefix, time scaled to the full depth."""
+    from oracle import decoder as O
+    sh = shape.with_layers(layers)
+    w = {k: ([to_numpy_storage(torch, t) for t in v[:layers]] if isinstance(v, list) else to_numpy_storage(torch, v))
+         for k, v in w_dev.items()}
+    kv = O.KVCache(sh.n_layers, sh.n_kv_heads, sh.head_dim)
+    O.forward(sh, w, prompt[:P], kv, rows=[-1])                      # prefix: not timed
+    t0 = time.perf_counter()
+    O.forward(sh, w, prompt[P:P + T], kv, rows=[-1])
+    t_ext = time.perf_counter() - t0
+    O.clear_widen_cache()
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    scale = shape.n_layers / layers
+    return {"value": T / (t_ext * scale), "unit": "extend tok/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"float64 numpy oracle, first {layers} of {shape.n_layers} layers at full width, "
+                      f"P={P}, one extend of T={T} took {t_ext:.2f} s; rate scaled by {layers}/{shape.n_layers}"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", type=int, default=2, help="configuration id (2 = ~1B headline, 3, 4)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--seed", type=int, default=2000)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (sessions would shard across GPUs with no "
+                 "collective; see DESIGN.md); run with --gpus 1")
+
+    import torch
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible; the extend / verify path has no CPU fallback")
+    from paper_2605_10380_amd import binding as B
+    from paper_2605_10380_amd import inputs as I
+
+    wl = I.WORKLOADS[args.workload]
+    sh, P, T, k, rounds = wl.shape, wl.P, wl.T, wl.k, wl.rounds
+    dev = torch.device("cuda:0")
+    w = torch_weights(torch, sh, args.seed, dev)
+    prompt = I.templated_prompt(sh.vocab, args.seed, P + T)
+    max_pos = P + T + rounds * (k + 1) + 64
+    dm = B.DeviceModel(sh, w, max_pos=max_pos, max_tokens=512, pool_tokens=max_pos + 64)
+    kv = dm.new_kv()
+    for at in range(0, P, 512):                                      # cached prefix, untimed
+        dm.extend(kv, prompt[at:at + 512])
+    drafts = [I.prompt_copied_drafts(prompt, args.seed, r, k) for r in range(rounds)]
+    torch.cuda.synchronize()
+
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+
+    def step(timers=None):
+        B.ax_kv_truncate(kv, P)
+        e0, e1 = ev(), ev()
+        e0.record()
+        first = dm.extend(kv, prompt[P:], B.AX_OUT_LAST_ARGMAX)
+        e1.record()
+        pending = int(first.cpu()[0])
+        t0 = time.perf_counter()
+        acc = 0
+        for r in range(rounds):
+            a, pending = dm.verify(kv, pending, drafts[r])
+            acc += a
+        t_ver = time.perf_counter() - t0
+        if timers is not None:
+            timers.append((e0.elapsed_time(e1), t_ver * 1e3, acc))
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    timers = []
+    t_begin = time.perf_counter()
+    for _ in range(args.steps):
+        step(timers)
+    torch.cuda.synchronize()
+    t_total = time.perf_counter() - t_begin
+
+    ext_ms = float(np.mean([t[0] for t in timers]))
+    ver_ms = float(np.mean([t[1] for t in timers])) / rounds
+    alg = algorithmic(sh, P, T, k)
+
+    # per-kernel timing with HIP events, on extra steps outside the timed region
+    prof = {}
+    for tag in ("extend", "verify"):
+        B.ax_kv_truncate(kv, P)
+        if tag == "verify":
+            pending = int(dm.extend(kv, prompt[P:], B.AX_OUT_LAST_ARGMAX).cpu()[0])
+        B.ax_dbg_profile(dm.model, True)
+        if tag == "extend":
+            dm.extend(kv, prompt[P:], B.AX_OUT_LAST_ARGMAX)
+        else:
+            for r in range(rounds):
+                _, pending = dm.verify(kv, pending, drafts[r])
+        B.ax_dbg_profile(dm.model, False)
+        prof[tag] = B.ax_dbg_profile_read(dm.model)
+
+    def kernel_roofline(tag, name):
+        ms, n = prof[tag][name]
+        if n == 0:
+            return None
+        avg_s = ms / n * 1e-3
+        a = alg[tag][name]
+        gbs, tfs = a["bytes"] / avg_s / 1e9, a["flops"] / avg_s / 1e12
+        hbm_frac, mfma_frac = gbs / HBM_PEAK_GBS, tfs / MFMA16_PEAK_TFLOPS
+        bound = "hbm" if hbm_frac >= mfma_frac else "mfma"
+        return {"kernel": f"{name} ({tag}, M={1 + k if tag == 'verify' else T})", "bound": bound,
+                "achieved": round(gbs if bound == "hbm" else tfs, 2),
+                "peak": HBM_PEAK_GBS if bound == "hbm" else MFMA16_PEAK_TFLOPS,
+                "unit": "GB/s" if bound == "hbm" else "TFLOP/s",
+                "frac": round(max(hbm_frac, mfma_frac), 4), "traffic": None,
+                "avg_launch_us": round(avg_s * 1e6, 2), "launches": int(n),
+                "share_of_phase": round(ms / max(1e-9, sum(v[0] for v in prof[tag].values())), 3)}
+
+    dominant = {tag: max(prof[tag], key=lambda nme: prof[tag][nme][0]) for tag in prof}
+    # the kernel with the largest share of the whole step: verify runs `rounds` times per step
+    tot = {tag: prof[tag][dominant[tag]][0] for tag in prof}
+    main_tag = max(tot, key=tot.get)
+
+    out = {
+        "metric": f"extend tok/s at P={P}, T={T} (target-model forward over a cached prefix)",
+        "value": round(T / (ext_ms * 1e-3), 1),
+        "unit": "tok/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(t_total / args.steps * 1e3, 3),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16 products of bf16 weights, f32 accumulate" if sh.dtype == "bf16" else "f32",
+        "data": "synthetic",
+        "config": {"workload": f"config {args.workload}: {sh.name} decoder ({sh.n_layers} layers, d {sh.d_model}, "
+                               f"{sh.n_q_heads}/{sh.n_kv_heads} heads x {sh.head_dim}, ffn {sh.d_ff}, vocab {sh.vocab}), "
+                               f"P={P}, extend T={T}, then {rounds} verify rounds at k={k}, paged KV blocks of 16",
+                   "step": "truncate to P, one extend, all verify rounds"},
+        "extend_ms": round(ext_ms, 4),
+        "extend_tflops": round(alg["extend_flops"] / (ext_ms * 1e-3) / 1e12, 2),
+        "extend_frac_of_mfma_peak": round(alg["extend_flops"] / (ext_ms * 1e-3) / 1e12 / MFMA16_PEAK_TFLOPS, 4),
+        "verify_steps_per_s": round(1e3 / ver_ms, 1),
+        "verify_ms_per_step": round(ver_ms, 4),
+        "verify_gbs": round(alg["verify_bytes"] / (ver_ms * 1e-3) / 1e9, 1),
+        "verify_frac_of_hbm_peak": round(alg["verify_bytes"] / (ver_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+        "accepted_drafts_per_step": float(np.mean([t[2] for t in timers])),
+        "roofline": kernel_roofline(main_tag, dominant[main_tag]),
+        "roofline_extend": kernel_roofline("extend", dominant["extend"]),
+        "roofline_verify": kernel_roofline("verify", dominant["verify"]),
+        "kernel_ms": {tag: {n: round(v[0], 4) for n, v in prof[tag].items()} for tag in prof},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_oracle_baseline(torch, sh, w, prompt, P, T)
+    B.ax_kv_free(kv)
+    dm.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

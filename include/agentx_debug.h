@@ -28,6 +28,16 @@ ax_status ax_dbg_gemm(int dtype, int epilogue, const void *A, const void *W, con
  * Copies min(bytes, buffer size) bytes. */
 ax_status ax_dbg_read(ax_model *model, int which, void *host_dst, size_t bytes);
 
+/* Per-kernel timing with HIP events on the caller's stream.  While enabled, every launch of the
+ * classes below inside ax_extend* / ax_verify is bracketed by a pair of events (this perturbs
+ * the step a little, so enable it only for steps whose total time is not reported).
+ * Classes: 0 QKV projection, 1 attention (split + combine), 2 O projection, 3 SwiGLU gate/up,
+ * 4 down projection, 5 LM head.  ax_dbg_profile_read synchronises, adds up the elapsed
+ * milliseconds and the launch count of each class since the last read and clears them. */
+#define AX_DBG_PROFILE_CLASSES 6
+ax_status ax_dbg_profile(ax_model *model, int enable);
+ax_status ax_dbg_profile_read(ax_model *model, double *ms_by_class, int64_t *launches_by_class);
+
 #ifdef __cplusplus
 }
 #endif

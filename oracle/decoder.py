@@ -137,13 +137,15 @@ def silu(z: np.ndarray) -> np.ndarray:
     return z / (1.0 + np.exp(-z))
 
 
-def forward(shape, weights: dict, tokens, kv: KVCache, trace: dict = None) -> np.ndarray:
+def forward(shape, weights: dict, tokens, kv: KVCache, trace: dict = None, rows=None) -> np.ndarray:
     """Run `tokens` on top of the cache (length P before, P + T after); logits [T, vocab].
 
     `shape` needs n_layers, n_q_heads, n_kv_heads, head_dim, rms_eps, rope_base; `weights`
     is {"tok_emb", "lm_head", "final_norm", and per-layer lists "wqkv", "wo", "w_gate",
     "w_up", "w_down", "norm_attn", "norm_mlp"} in storage format.  If `trace` is a dict it
-    receives the last layer's intermediates (for tests that localise a mismatch).
+    receives the last layer's intermediates (for tests that localise a mismatch).  `rows`
+    (indices into the T new rows) limits the LM head to those rows, e.g. [-1] for a prefill
+    that only needs the first output token.
     """
     tokens = np.asarray(tokens, dtype=np.int64)
     T = tokens.shape[0]
@@ -170,6 +172,8 @@ def forward(shape, weights: dict, tokens, kv: KVCache, trace: dict = None) -> np
     h_out = rmsnorm(x, widen(weights["final_norm"]), shape.rms_eps)
     if trace is not None:
         trace.update(x=x, h_out=h_out)
+    if rows is not None:
+        h_out = h_out[np.asarray(rows)]
     return h_out @ widen(weights["lm_head"]).T
 
 

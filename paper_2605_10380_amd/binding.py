@@ -57,6 +57,8 @@ def _load():
         "ax_extend_batch": (C.c_int, [vp, C.c_int, C.POINTER(vp), i32p, C.POINTER(C.c_int), C.c_int, vp, vp]),
         "ax_dbg_gemm": (C.c_int, [C.c_int, C.c_int, vp, vp, vp, vp, C.c_int, C.c_int, C.c_int, vp]),
         "ax_dbg_read": (C.c_int, [vp, C.c_int, vp, C.c_size_t]),
+        "ax_dbg_profile": (C.c_int, [vp, C.c_int]),
+        "ax_dbg_profile_read": (C.c_int, [vp, C.POINTER(C.c_double), C.POINTER(i64)]),
         "ax_verify": (C.c_int, [vp, vp, C.c_int32, i32p, C.c_int, C.POINTER(C.c_int), i32p, vp]),
     }
     for name, (res, args) in sig.items():
@@ -212,6 +214,20 @@ def ax_dbg_read(model: int, which: int, dst: np.ndarray):
     assert dst.flags["C_CONTIGUOUS"]
     _check(lib.ax_dbg_read(model, which, dst.ctypes.data_as(C.c_void_p), dst.nbytes))
     return dst
+
+
+PROFILE_CLASSES = ("qkv_proj", "attention", "o_proj", "swiglu_gate_up", "down_proj", "lm_head")
+
+
+def ax_dbg_profile(model: int, enable: bool):
+    _check(lib.ax_dbg_profile(model, int(enable)))
+
+
+def ax_dbg_profile_read(model: int) -> dict:
+    ms = (C.c_double * len(PROFILE_CLASSES))()
+    n = (C.c_int64 * len(PROFILE_CLASSES))()
+    _check(lib.ax_dbg_profile_read(model, ms, n))
+    return {name: (ms[i], n[i]) for i, name in enumerate(PROFILE_CLASSES)}
 
 
 # ------------------------------------------------------------------ device memory through PyTorch

@@ -109,6 +109,11 @@ struct ax_model {
     hipEvent_t slot_done[N_SLOTS];
     int next_slot;
     size_t slot_ints;
+    // optional per-kernel timing (test / benchmark instrumentation, off by default)
+    bool prof_on = false;
+    struct ProfSpan { int cls; hipEvent_t a, b; };
+    std::vector<ProfSpan> prof_spans;      // recorded spans since the last read
+    std::vector<hipEvent_t> prof_free;     // events ready for reuse
 };
 
 struct ax_pool {
@@ -129,6 +134,23 @@ namespace {
 bool ok(const ax_model* m) { return m && m->magic == MAGIC_MODEL; }
 bool ok(const ax_pool* p) { return p && p->magic == MAGIC_POOL; }
 bool ok(const ax_kv* k) { return k && k->magic == MAGIC_KV && ok(k->pool); }
+
+struct ProfScope {                     // records a pair of events around one launch when profiling
+    ax_model* m; hipStream_t st; hipEvent_t b = nullptr;
+    ProfScope(ax_model* m_, int cls, hipStream_t st_) : m(m_), st(st_) {
+        if (!m->prof_on) return;
+        hipEvent_t ev[2] = {nullptr, nullptr};
+        for (auto& e : ev) {
+            if (!m->prof_free.empty()) { e = m->prof_free.back(); m->prof_free.pop_back(); }
+            else if (hipEventCreate(&e) != hipSuccess) { e = nullptr; }
+        }
+        if (!ev[0] || !ev[1]) return;
+        (void)hipEventRecord(ev[0], st);
+        b = ev[1];
+        m->prof_spans.push_back({cls, ev[0], ev[1]});
+    }
+    ~ProfScope() { if (b) (void)hipEventRecord(b, st); }
+};
 
 // One forward over n sequences.  `verify_k` >= 0 turns the call into a verify round of the
 // single sequence: greedy tokens of all rows, acceptance on the device, result copied back.
@@ -265,28 +287,35 @@ ax_status run_extend(ax_model* m, int n, ax_kv* const* kvs, const int32_t* token
     ax::launch_embed(dt, m->tok_emb, sv.row_tok, x, R, d_model, stream);
     for (int l = 0; l < c.n_layers; ++l) {
         ax::launch_rmsnorm(dt, x, m->norm_attn[(size_t)l], h, nullptr, R, d_model, c.rms_eps, stream);
-        ax::launch_gemm(dt, ax::EPI_STORE_F32, h, m->wqkv[(size_t)l], nullptr, qkv, R, qkv_rows, d_model, stream);
+        { ProfScope ps(m, 0, stream);
+          ax::launch_gemm(dt, ax::EPI_STORE_F32, h, m->wqkv[(size_t)l], nullptr, qkv, R, qkv_rows, d_model, stream); }
         ax::launch_rope_kv(dt, qkv, qb, kg, l, sv, (const float*)(ws + L.rope_cos),
                            (const float*)(ws + L.rope_sin), c.n_q_heads, stream);
-        ax::launch_attention(dt, qb, attn, kg, l, sv, c.n_q_heads, (float*)(ws + L.partials), n_splits, stream);
-        ax::launch_gemm(dt, ax::EPI_RESIDUAL, attn, m->wo[(size_t)l], nullptr, x, R, d_model, qdim, stream);
+        { ProfScope ps(m, 1, stream);
+          ax::launch_attention(dt, qb, attn, kg, l, sv, c.n_q_heads, (float*)(ws + L.partials), n_splits, stream); }
+        { ProfScope ps(m, 2, stream);
+          ax::launch_gemm(dt, ax::EPI_RESIDUAL, attn, m->wo[(size_t)l], nullptr, x, R, d_model, qdim, stream); }
         ax::launch_rmsnorm(dt, x, m->norm_mlp[(size_t)l], h, nullptr, R, d_model, c.rms_eps, stream);
-        ax::launch_gemm(dt, ax::EPI_SWIGLU, h, m->w_gate[(size_t)l], m->w_up[(size_t)l], ffn, R, c.d_ff, d_model, stream);
-        ax::launch_gemm(dt, ax::EPI_RESIDUAL, ffn, m->w_down[(size_t)l], nullptr, x, R, d_model, c.d_ff, stream);
+        { ProfScope ps(m, 3, stream);
+          ax::launch_gemm(dt, ax::EPI_SWIGLU, h, m->w_gate[(size_t)l], m->w_up[(size_t)l], ffn, R, c.d_ff, d_model, stream); }
+        { ProfScope ps(m, 4, stream);
+          ax::launch_gemm(dt, ax::EPI_RESIDUAL, ffn, m->w_down[(size_t)l], nullptr, x, R, d_model, c.d_ff, stream); }
     }
 
     if (n_out > 0) {
         const size_t a = (size_t)isz(c.dtype);
         ax::launch_rmsnorm(dt, x, m->final_norm, h, sv.out_rows, n_out, d_model, c.rms_eps, stream);
         if (out_mode == AX_OUT_LAST_LOGITS || out_mode == AX_OUT_ALL_LOGITS) {
+            ProfScope ps(m, 5, stream);
             ax::launch_gemm(dt, ax::EPI_STORE_F32, h, m->lm_head, nullptr, out, n_out, c.vocab, d_model, stream);
         } else {
             float* logits = (float*)(ws + L.logits);
             const int chunk = std::min(c.max_tokens, LOGIT_ROWS);
             for (int r0 = 0; r0 < n_out; r0 += chunk) {
                 const int rows = std::min(chunk, n_out - r0);
-                ax::launch_gemm(dt, ax::EPI_STORE_F32, (const char*)h + (size_t)r0 * d_model * a, m->lm_head,
-                                nullptr, logits, rows, c.vocab, d_model, stream);
+                { ProfScope ps(m, 5, stream);
+                  ax::launch_gemm(dt, ax::EPI_STORE_F32, (const char*)h + (size_t)r0 * d_model * a, m->lm_head,
+                                  nullptr, logits, rows, c.vocab, d_model, stream); }
                 ax::launch_argmax(logits, rows, c.vocab, (int*)out + r0, (int*)(ws + L.amax_scratch), stream);
             }
         }
@@ -385,6 +414,8 @@ void ax_model_destroy(ax_model* m) {
     if (!ok(m)) return;
     (void)hipDeviceSynchronize();
     for (auto& e : m->slot_done) (void)hipEventDestroy(e);
+    for (auto& sp : m->prof_spans) { (void)hipEventDestroy(sp.a); (void)hipEventDestroy(sp.b); }
+    for (auto& e : m->prof_free) (void)hipEventDestroy(e);
     (void)hipHostFree(m->stage);
     m->magic = 0;
     delete m;
@@ -573,6 +604,28 @@ ax_status ax_dbg_read(ax_model* m, int which, void* host_dst, size_t bytes) {
     if (which < 0 || which > 5) return fail(AX_ERR_INVALID, "bad buffer id");
     HIP_TRY(hipDeviceSynchronize());
     HIP_TRY(hipMemcpy(host_dst, m->ws + off[which], std::min(bytes, end[which] - off[which]), hipMemcpyDeviceToHost));
+    return AX_OK;
+}
+
+ax_status ax_dbg_profile(ax_model* m, int enable) {
+    if (!ok(m)) return fail(AX_ERR_INVALID, "bad model handle");
+    m->prof_on = enable != 0;
+    return AX_OK;
+}
+
+ax_status ax_dbg_profile_read(ax_model* m, double* ms_by_class, int64_t* launches_by_class) {
+    if (!ok(m) || !ms_by_class || !launches_by_class) return fail(AX_ERR_INVALID, "bad argument");
+    HIP_TRY(hipDeviceSynchronize());
+    for (int i = 0; i < AX_DBG_PROFILE_CLASSES; ++i) { ms_by_class[i] = 0.0; launches_by_class[i] = 0; }
+    for (auto& sp : m->prof_spans) {
+        float ms = 0.f;
+        HIP_TRY(hipEventElapsedTime(&ms, sp.a, sp.b));
+        ms_by_class[sp.cls] += ms;
+        ++launches_by_class[sp.cls];
+        m->prof_free.push_back(sp.a);
+        m->prof_free.push_back(sp.b);
+    }
+    m->prof_spans.clear();
     return AX_OK;
 }
 
