@@ -10,6 +10,7 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <vector>
 
@@ -79,7 +80,7 @@ Layout make_layout(const ax_model_config& c) {
     auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes); return at; };
     L.rope_cos = take((size_t)c.max_pos * (c.head_dim / 2) * 4);
     L.rope_sin = take((size_t)c.max_pos * (c.head_dim / 2) * 4);
-    L.desc = take(N_SLOTS * align_up(L.desc_ints * 4));
+    L.desc = take((N_SLOTS + 1) * align_up(L.desc_ints * 4));   // ring + the slot of captured graphs
     L.x = take(T * c.d_model * 4);
     L.h = take(T * c.d_model * a);
     L.qkv = take(T * (size_t)(c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim * 4);
@@ -105,10 +106,15 @@ struct ax_model {
     char* ws;
     const void *tok_emb, *lm_head, *final_norm;
     std::vector<const void*> wqkv, wo, w_gate, w_up, w_down, norm_attn, norm_mlp;
-    int* stage;                       // pinned: N_SLOTS descriptor slots + result words
+    int* stage;                       // pinned: N_SLOTS + 1 descriptor slots + result words
     hipEvent_t slot_done[N_SLOTS];
     int next_slot;
     size_t slot_ints;
+    // captured verify steps, keyed by (rows, key slices, pool)
+    struct Graph { uint64_t key; uint64_t pool_uid; hipGraphExec_t exec; };
+    std::vector<Graph> graphs;
+    hipStream_t capture_stream = nullptr;
+    bool use_graphs = true;
     // optional per-kernel timing (test / benchmark instrumentation, off by default)
     bool prof_on = false;
     struct ProfSpan { int cls; hipEvent_t a, b; };
@@ -118,6 +124,7 @@ struct ax_model {
 
 struct ax_pool {
     uint32_t magic;
+    uint64_t uid;                     // never reused: captured graphs are keyed by it
     ax_model_config cfg;              // geometry fields only are compared with the model's
     ax::KVGeom geom;
     ax::BlockPool blocks;
@@ -152,12 +159,32 @@ struct ProfScope {                     // records a pair of events around one la
     ~ProfScope() { if (b) (void)hipEventRecord(b, st); }
 };
 
-// One forward over n sequences.  `verify_k` >= 0 turns the call into a verify round of the
-// single sequence: greedy tokens of all rows, acceptance on the device, result copied back.
-ax_status run_extend(ax_model* m, int n, ax_kv* const* kvs, const int32_t* tokens, const int* T_each,
-                     int out_mode, void* out, hipStream_t stream, int verify_k, int* host_result) {
+// Key slices of the split attention: enough wavefronts to fill the chip (~SPLIT_ITEMS), each
+// with at least two 32-key steps, rounded down to a power of two so that the choice (a launch
+// dimension, hence part of a captured graph) changes only when the cache length doubles.
+int choose_splits(const ax_model* m, int items, int max_steps) {
+    int want = std::max(1, (SPLIT_ITEMS + items - 1) / items);
+    want = std::min(want, std::max(1, max_steps / 2));
+    const size_t cap = std::max<size_t>(SPLIT_ITEMS, (size_t)m->lay.max_tiles * m->cfg.n_kv_heads) / (size_t)items;
+    want = std::min(want, std::max(1, (int)cap));
+    int p2 = 1;
+    while (p2 * 2 <= want) p2 *= 2;
+    return p2;
+}
+
+// Host half of a call: validation, KV reservation (all or nothing) and the descriptor, written
+// into a pinned staging slot.  Nothing is launched here.
+struct CallPlan {
+    int n = 0, n_rows = 0, n_out = 0, n_tiles = 0, bt_total = 0, max_steps = 1, out_mode = 0, slot = 0;
+    size_t o_tok = 0, o_pos = 0, o_seq = 0, o_out = 0, o_P = 0, o_T = 0, o_row0 = 0, o_bt = 0, o_tseq = 0,
+           o_tr0 = 0, o_tab = 0, ints = 0;
+    ax_pool* pool = nullptr;
+    std::vector<std::pair<int32_t, int32_t>> cows;
+};
+
+ax_status prepare_call(ax_model* m, int n, ax_kv* const* kvs, const int32_t* tokens, const int* T_each,
+                       int out_mode, const void* out, bool graph_slot, CallPlan& cp) {
     const ax_model_config& c = m->cfg;
-    const Layout& L = m->lay;
     if (n <= 0 || n > c.max_seqs) return fail(AX_ERR_INVALID, "n_seq %d outside 1..%d", n, c.max_seqs);
     if (!kvs || !tokens || !T_each) return fail(AX_ERR_INVALID, "NULL argument");
     if (out_mode < AX_OUT_NONE || out_mode > AX_OUT_ALL_ARGMAX) return fail(AX_ERR_INVALID, "bad out_mode");
@@ -198,81 +225,94 @@ ax_status run_extend(ax_model* m, int n, ax_kv* const* kvs, const int32_t* token
         return fail(AX_ERR_OOM, "need %lld KV blocks, %lld free", need, (long long)pool->blocks.n_free());
 
     const int G = c.n_q_heads / c.n_kv_heads;
-    int n_tiles = 0, bt_total = 0;
+    cp.n = n;
+    cp.n_rows = (int)n_rows;
+    cp.out_mode = out_mode;
+    cp.pool = pool;
+    cp.n_tiles = cp.bt_total = 0;
     for (int s = 0; s < n; ++s) {
-        n_tiles += (T_each[s] * G + 31) / 32;
-        bt_total += (int)ax::blocks_for(kvs[s]->seq.len + T_each[s], 16);
+        cp.n_tiles += (T_each[s] * G + 31) / 32;
+        cp.bt_total += (int)ax::blocks_for(kvs[s]->seq.len + T_each[s], 16);
     }
-    const int n_out = out_mode == AX_OUT_NONE ? 0
-                      : (out_mode == AX_OUT_LAST_LOGITS || out_mode == AX_OUT_LAST_ARGMAX) ? n
-                                                                                           : (int)n_rows;
-    if ((size_t)(3 * n_rows + std::max(n_out, 1) + 4 * n + 2 * n_tiles + bt_total) > m->slot_ints)
+    cp.n_out = out_mode == AX_OUT_NONE ? 0
+               : (out_mode == AX_OUT_LAST_LOGITS || out_mode == AX_OUT_LAST_ARGMAX) ? n : (int)n_rows;
+    size_t at = 0;
+    auto region = [&](size_t ints) { size_t o = at; at += ints; return o; };
+    cp.o_tok = region((size_t)n_rows); cp.o_pos = region((size_t)n_rows); cp.o_seq = region((size_t)n_rows);
+    cp.o_out = region((size_t)std::max(cp.n_out, 1)); cp.o_P = region((size_t)n); cp.o_T = region((size_t)n);
+    cp.o_row0 = region((size_t)n); cp.o_bt = region((size_t)n); cp.o_tseq = region((size_t)cp.n_tiles);
+    cp.o_tr0 = region((size_t)cp.n_tiles);
+    cp.o_tab = region((size_t)(graph_slot ? m->lay.max_bt : cp.bt_total));   // fixed extent inside a graph
+    cp.ints = at;
+    if (cp.ints > m->slot_ints || cp.bt_total > n * m->lay.max_bt)
         return fail(AX_ERR_INVALID, "call descriptor does not fit its slot");
 
-    // ---- descriptor slot (pinned host memory, reused round robin behind an event)
-    const int slot = m->next_slot;
-    m->next_slot = (slot + 1) % N_SLOTS;
-    HIP_TRY(hipEventSynchronize(m->slot_done[slot]));
-    int* d = m->stage + (size_t)slot * m->slot_ints;
-    int* dev_d = (int*)(m->ws + L.desc) + (size_t)slot * m->slot_ints;
+    // ---- staging slot: the ring behind events, or the slot reserved for captured graphs
+    if (graph_slot) {
+        cp.slot = N_SLOTS;
+    } else {
+        cp.slot = m->next_slot;
+        m->next_slot = (cp.slot + 1) % N_SLOTS;
+        HIP_TRY(hipEventSynchronize(m->slot_done[cp.slot]));
+    }
+    int* d = m->stage + (size_t)cp.slot * m->slot_ints;
 
-    std::vector<std::pair<int32_t, int32_t>> cows;
+    // ---- from here on the call cannot fail on the host side: commit the KV reservation
     std::vector<int> P((size_t)n);
     for (int s = 0; s < n; ++s) {
         P[(size_t)s] = (int)kvs[s]->seq.len;
         int32_t cs, cd;
         ax::apply_append(pool->blocks, kvs[s]->seq, T_each[s], plans[(size_t)s], &cs, &cd);
-        if (cs >= 0) cows.push_back({cs, cd});
+        if (cs >= 0) cp.cows.push_back({cs, cd});
     }
-
-    size_t at = 0;
-    auto region = [&](size_t ints) { size_t o = at; at += ints; return o; };
-    const size_t o_tok = region((size_t)n_rows), o_pos = region((size_t)n_rows), o_seq = region((size_t)n_rows),
-                 o_out = region((size_t)std::max(n_out, 1)), o_P = region((size_t)n), o_T = region((size_t)n),
-                 o_row0 = region((size_t)n), o_bt = region((size_t)n), o_tseq = region((size_t)n_tiles),
-                 o_tr0 = region((size_t)n_tiles), o_tab = region((size_t)bt_total);
     int row = 0, tile = 0, tab = 0, oi = 0;
-    int max_steps = 1;
+    cp.max_steps = 1;
     for (int s = 0; s < n; ++s) {
         const int T = T_each[s];
-        d[o_P + s] = P[(size_t)s];
-        d[o_T + s] = T;
-        d[o_row0 + s] = row;
-        d[o_bt + s] = tab;
-        for (int32_t b : kvs[s]->seq.blocks) d[o_tab + tab++] = b;
+        d[cp.o_P + s] = P[(size_t)s];
+        d[cp.o_T + s] = T;
+        d[cp.o_row0 + s] = row;
+        d[cp.o_bt + s] = tab;
+        for (int32_t b : kvs[s]->seq.blocks) d[cp.o_tab + tab++] = b;
         for (int r0 = 0; r0 < T * G; r0 += 32) {
-            d[o_tseq + tile] = s;
-            d[o_tr0 + tile] = r0;
+            d[cp.o_tseq + tile] = s;
+            d[cp.o_tr0 + tile] = r0;
             ++tile;
         }
         for (int t = 0; t < T; ++t, ++row) {
-            d[o_tok + row] = tokens[row];
-            d[o_pos + row] = P[(size_t)s] + t;
-            d[o_seq + row] = s;
-            if (out_mode == AX_OUT_ALL_LOGITS || out_mode == AX_OUT_ALL_ARGMAX) d[o_out + oi++] = row;
+            d[cp.o_tok + row] = tokens[row];
+            d[cp.o_pos + row] = P[(size_t)s] + t;
+            d[cp.o_seq + row] = s;
+            if (out_mode == AX_OUT_ALL_LOGITS || out_mode == AX_OUT_ALL_ARGMAX) d[cp.o_out + oi++] = row;
         }
-        if (out_mode == AX_OUT_LAST_LOGITS || out_mode == AX_OUT_LAST_ARGMAX) d[o_out + oi++] = row - 1;
-        max_steps = std::max(max_steps, (P[(size_t)s] + T + 31) / 32);
+        if (out_mode == AX_OUT_LAST_LOGITS || out_mode == AX_OUT_LAST_ARGMAX) d[cp.o_out + oi++] = row - 1;
+        cp.max_steps = std::max(cp.max_steps, (P[(size_t)s] + T + 31) / 32);
     }
-    HIP_TRY(hipMemcpyAsync(dev_d, d, at * sizeof(int), hipMemcpyHostToDevice, stream));
+    return AX_OK;
+}
+
+// Device half: descriptor upload and the kernel sequence of one forward.  `verify_k` >= 0
+// appends the greedy acceptance and the copy of (accepted, next token) to host_result.  With
+// `capturing` the launches go into a stream capture: no event is recorded and the kernel
+// arguments must not depend on anything but (n_rows, n_splits).
+ax_status enqueue_call(ax_model* m, const CallPlan& cp, void* out, hipStream_t stream, int n_splits,
+                       int verify_k, int* host_result, bool capturing) {
+    const ax_model_config& c = m->cfg;
+    const Layout& L = m->lay;
+    int* d = m->stage + (size_t)cp.slot * m->slot_ints;
+    int* dev_d = (int*)(m->ws + L.desc) + (size_t)cp.slot * m->slot_ints;
+    HIP_TRY(hipMemcpyAsync(dev_d, d, cp.ints * sizeof(int), hipMemcpyHostToDevice, stream));
 
     ax::StepView sv{};
-    sv.row_tok = dev_d + o_tok;  sv.row_pos = dev_d + o_pos;  sv.row_seq = dev_d + o_seq;
-    sv.out_rows = dev_d + o_out; sv.seq_P = dev_d + o_P;      sv.seq_T = dev_d + o_T;
-    sv.seq_row0 = dev_d + o_row0; sv.seq_bt = dev_d + o_bt;   sv.tile_seq = dev_d + o_tseq;
-    sv.tile_r0 = dev_d + o_tr0;  sv.bt = dev_d + o_tab;
-    sv.n_rows = (int)n_rows; sv.n_seq = n; sv.n_out = n_out; sv.n_tiles = n_tiles;
+    sv.row_tok = dev_d + cp.o_tok;  sv.row_pos = dev_d + cp.o_pos;  sv.row_seq = dev_d + cp.o_seq;
+    sv.out_rows = dev_d + cp.o_out; sv.seq_P = dev_d + cp.o_P;      sv.seq_T = dev_d + cp.o_T;
+    sv.seq_row0 = dev_d + cp.o_row0; sv.seq_bt = dev_d + cp.o_bt;   sv.tile_seq = dev_d + cp.o_tseq;
+    sv.tile_r0 = dev_d + cp.o_tr0;  sv.bt = dev_d + cp.o_tab;
+    sv.n_rows = cp.n_rows; sv.n_seq = cp.n; sv.n_out = cp.n_out; sv.n_tiles = cp.n_tiles;
 
     const ax::DType dt = c.dtype == AX_F32 ? ax::F32 : ax::BF16;
-    const ax::KVGeom& kg = pool->geom;
-    for (auto& cw : cows) ax::launch_block_copy(dt, kg, c.n_layers, cw.first, cw.second, stream);
-
-    // split the key range so that the attention launch has ~SPLIT_ITEMS wavefronts, each with
-    // at least two 32-key steps
-    const int items = n_tiles * c.n_kv_heads;
-    int n_splits = std::max(1, (SPLIT_ITEMS + items - 1) / items);
-    n_splits = std::min(n_splits, std::max(1, max_steps / 2));
-    n_splits = std::min(n_splits, std::max(1, (int)(std::max<size_t>(SPLIT_ITEMS, (size_t)L.max_tiles * c.n_kv_heads) / (size_t)items)));
+    const ax::KVGeom& kg = cp.pool->geom;
+    const int out_mode = cp.out_mode, n_out = cp.n_out;
 
     char* ws = m->ws;
     float* x = (float*)(ws + L.x);
@@ -282,7 +322,7 @@ ax_status run_extend(ax_model* m, int n, ax_kv* const* kvs, const int32_t* token
     void* attn = ws + L.attn;
     void* ffn = ws + L.ffn;
     const int d_model = c.d_model, qdim = c.n_q_heads * c.head_dim,
-              qkv_rows = (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim, R = (int)n_rows;
+              qkv_rows = (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim, R = cp.n_rows;
 
     ax::launch_embed(dt, m->tok_emb, sv.row_tok, x, R, d_model, stream);
     for (int l = 0; l < c.n_layers; ++l) {
@@ -325,8 +365,57 @@ ax_status run_extend(ax_model* m, int n, ax_kv* const* kvs, const int32_t* token
         ax::launch_accept((const int*)out, sv.row_tok, verify_k, res, stream);
         HIP_TRY(hipMemcpyAsync(host_result, res, 2 * sizeof(int), hipMemcpyDeviceToHost, stream));
     }
-    HIP_TRY(hipGetLastError());
-    HIP_TRY(hipEventRecord(m->slot_done[slot], stream));
+    if (!capturing) {
+        HIP_TRY(hipGetLastError());
+        HIP_TRY(hipEventRecord(m->slot_done[cp.slot], stream));
+    }
+    return AX_OK;
+}
+
+// Eager call: prepare, copy-on-write copies, launches.
+ax_status run_extend(ax_model* m, int n, ax_kv* const* kvs, const int32_t* tokens, const int* T_each,
+                     int out_mode, void* out, hipStream_t stream, int verify_k, int* host_result) {
+    CallPlan cp;
+    ax_status st = prepare_call(m, n, kvs, tokens, T_each, out_mode, out, false, cp);
+    if (st != AX_OK) return st;
+    const ax::DType dt = m->cfg.dtype == AX_F32 ? ax::F32 : ax::BF16;
+    for (auto& cw : cp.cows) ax::launch_block_copy(dt, cp.pool->geom, m->cfg.n_layers, cw.first, cw.second, stream);
+    const int n_splits = choose_splits(m, cp.n_tiles * m->cfg.n_kv_heads, cp.max_steps);
+    return enqueue_call(m, cp, out, stream, n_splits, verify_k, host_result, false);
+}
+
+// Verify round through a captured graph: the ~9 launches per layer of a (1 + k)-row step cost
+// more host time than GPU time when enqueued one by one.  The graph for (k, n_splits) is
+// captured once on the model's own stream (the caller's may be the default stream, which
+// cannot be captured) and replayed on the caller's stream; everything that changes from round
+// to round (tokens, positions, cache length, block table) lives in the descriptor that the
+// graph's first node uploads from the reserved pinned slot.
+ax_status run_verify_graph(ax_model* m, ax_kv* kv, const int32_t* toks, int T, void* out, hipStream_t stream,
+                           int k, int* host_result) {
+    CallPlan cp;
+    ax_kv* one[1] = {kv};
+    ax_status st = prepare_call(m, 1, one, toks, &T, AX_OUT_ALL_ARGMAX, out, true, cp);
+    if (st != AX_OK) return st;
+    const ax::DType dt = m->cfg.dtype == AX_F32 ? ax::F32 : ax::BF16;
+    for (auto& cw : cp.cows) ax::launch_block_copy(dt, cp.pool->geom, m->cfg.n_layers, cw.first, cw.second, stream);
+    const int n_splits = choose_splits(m, cp.n_tiles * m->cfg.n_kv_heads, cp.max_steps);
+    const uint64_t key = ((uint64_t)(uint32_t)T << 32) | (uint32_t)n_splits;
+    hipGraphExec_t exec = nullptr;
+    for (auto& g : m->graphs)
+        if (g.key == key && g.pool_uid == cp.pool->uid) exec = g.exec;
+    if (!exec) {
+        hipGraph_t graph = nullptr;
+        HIP_TRY(hipStreamBeginCapture(m->capture_stream, hipStreamCaptureModeThreadLocal));
+        st = enqueue_call(m, cp, out, m->capture_stream, n_splits, k, host_result, true);
+        hipError_t e = hipStreamEndCapture(m->capture_stream, &graph);
+        if (st != AX_OK) { if (graph) (void)hipGraphDestroy(graph); return st; }
+        if (e != hipSuccess) return fail(AX_ERR_DEVICE, "hipStreamEndCapture: %s", hipGetErrorString(e));
+        e = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+        (void)hipGraphDestroy(graph);
+        if (e != hipSuccess) return fail(AX_ERR_DEVICE, "hipGraphInstantiate: %s", hipGetErrorString(e));
+        m->graphs.push_back({key, cp.pool->uid, exec});
+    }
+    HIP_TRY(hipGraphLaunch(exec, stream));
     return AX_OK;
 }
 
@@ -382,16 +471,21 @@ ax_status ax_model_create(const ax_model_config* cfg, const ax_weights* w, void*
     for (auto& e : m->slot_done) e = nullptr;
 
     auto cleanup = [&]() {
+        if (m->capture_stream) (void)hipStreamDestroy(m->capture_stream);
         for (auto& e : m->slot_done) if (e) (void)hipEventDestroy(e);
         if (m->stage) (void)hipHostFree(m->stage);
         delete m;
     };
-    hipError_t e = hipHostMalloc((void**)&m->stage, (N_SLOTS * m->slot_ints + 16) * sizeof(int), hipHostMallocDefault);
+    hipError_t e = hipHostMalloc((void**)&m->stage, ((N_SLOTS + 1) * m->slot_ints + 16) * sizeof(int), hipHostMallocDefault);
     if (e != hipSuccess) { m->stage = nullptr; cleanup(); return fail(AX_ERR_DEVICE, "hipHostMalloc: %s", hipGetErrorString(e)); }
     for (auto& ev : m->slot_done) {
         e = hipEventCreateWithFlags(&ev, hipEventDisableTiming);
         if (e != hipSuccess) { ev = nullptr; cleanup(); return fail(AX_ERR_DEVICE, "hipEventCreate: %s", hipGetErrorString(e)); }
     }
+    e = hipStreamCreateWithFlags(&m->capture_stream, hipStreamNonBlocking);
+    if (e != hipSuccess) { m->capture_stream = nullptr; cleanup(); return fail(AX_ERR_DEVICE, "hipStreamCreate: %s", hipGetErrorString(e)); }
+    const char* no_graph = std::getenv("AX_NO_GRAPH");
+    m->use_graphs = !(no_graph && no_graph[0] == '1');
     // rotary table: angle = pos * base^(-2j/hd), evaluated in double on the host
     const int half = cfg->head_dim / 2;
     std::vector<float> cs((size_t)cfg->max_pos * half), sn((size_t)cfg->max_pos * half);
@@ -414,6 +508,8 @@ void ax_model_destroy(ax_model* m) {
     if (!ok(m)) return;
     (void)hipDeviceSynchronize();
     for (auto& e : m->slot_done) (void)hipEventDestroy(e);
+    for (auto& g : m->graphs) (void)hipGraphExecDestroy(g.exec);
+    (void)hipStreamDestroy(m->capture_stream);
     for (auto& sp : m->prof_spans) { (void)hipEventDestroy(sp.a); (void)hipEventDestroy(sp.b); }
     for (auto& e : m->prof_free) (void)hipEventDestroy(e);
     (void)hipHostFree(m->stage);
@@ -447,6 +543,8 @@ ax_status ax_pool_create(const ax_model_config* cfg, void* dev_mem, size_t bytes
     p->geom.head_dim = cfg->head_dim;
     p->geom.block_tokens = block_tokens;
     p->blocks.init((int64_t)nb, block_tokens);
+    static uint64_t next_uid = 1;
+    p->uid = next_uid++;
     p->magic = MAGIC_POOL;
     *out = p;
     return AX_OK;
@@ -562,11 +660,13 @@ ax_status ax_verify(ax_model* model, ax_kv* kv, int32_t pending, const int32_t* 
     for (int i = 0; i < k; ++i) toks[(size_t)i + 1] = drafts[i];
     const int T = 1 + k;
     const int64_t P = kv->seq.len;
-    int* host_res = model->stage + N_SLOTS * model->slot_ints;      // pinned result words
+    int* host_res = model->stage + (N_SLOTS + 1) * model->slot_ints;      // pinned result words
     ax_kv* one[1] = {kv};
     hipStream_t stream = (hipStream_t)hip_stream;
-    ax_status st = run_extend(model, 1, one, toks.data(), &T, AX_OUT_ALL_ARGMAX,
-                              model->ws + model->lay.amax_out, stream, k, host_res);
+    ax_status st = (model->use_graphs && !model->prof_on)
+                       ? run_verify_graph(model, kv, toks.data(), T, model->ws + model->lay.amax_out, stream, k, host_res)
+                       : run_extend(model, 1, one, toks.data(), &T, AX_OUT_ALL_ARGMAX,
+                                    model->ws + model->lay.amax_out, stream, k, host_res);
     if (st != AX_OK) {
         if (kv->seq.len != P) ax::truncate(kv->pool->blocks, kv->seq, P);   // device error after the append
         return st;

@@ -235,7 +235,9 @@ __global__ __launch_bounds__(64) void attn_split_kernel(const f16* __restrict__ 
     }
 }
 
-// grid (n_tiles, Hkv), 256 threads: thread <-> (channel group, q row); merges the key slices.
+// Merges the key slices of one (tile, KV head).  grid (n_tiles * Hkv, HD / 4), 256 threads =
+// 32 query rows x 8 slice groups; a block produces 4 output channels.  Each thread folds the
+// slices s = sg, sg + 8, ... (weights 2^(m_s - M)), the 8 groups meet in LDS.
 template <int HD>
 __global__ __launch_bounds__(256) void attn_combine_kernel(const float* __restrict__ partials,
                                                            f16* __restrict__ out,
@@ -244,29 +246,41 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(const float* __restri
                                                            const int* __restrict__ tile_seq,
                                                            const int* __restrict__ tile_r0, int Hq,
                                                            int Hkv, int n_splits) {
-    const int tile = blockIdx.x, hk = blockIdx.y;
-    const int ql = threadIdx.x & 31, cg = threadIdx.x >> 5;      // 8 channel groups
+    constexpr int PS = HD * 32 + 64;                 // floats per partial
+    __shared__ float red[8][6][32];
+    const int tile = blockIdx.x / Hkv, hk = blockIdx.x % Hkv, ch0 = blockIdx.y * 4;
+    const int ql = threadIdx.x & 31, sg = threadIdx.x >> 5;
+    const float* base = partials + (long long)(tile * Hkv + hk) * n_splits * PS;
+
+    float mloc = -INFINITY;
+    for (int s = sg; s < n_splits; s += 8) mloc = fmaxf(mloc, base[(long long)s * PS + HD * 32 + ql]);
+    red[sg][0][ql] = mloc;
+    __syncthreads();
+    float M = red[0][0][ql];
+#pragma unroll
+    for (int i = 1; i < 8; ++i) M = fmaxf(M, red[i][0][ql]);   // finite: slice 0 always sees key 0
+    __syncthreads();
+
+    float l = 0.f, acc[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int s = sg; s < n_splits; s += 8) {
+        const float* p = base + (long long)s * PS;
+        const float w = exp2f(p[HD * 32 + ql] - M);
+        l += w * p[HD * 32 + 32 + ql];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) acc[c] += w * p[(ch0 + c) * 32 + ql];
+    }
+    red[sg][1][ql] = l;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) red[sg][2 + c][ql] = acc[c];
+    __syncthreads();
+    if (sg >= 4) return;                             // 128 threads finish: (channel sg, row ql)
     const int G = Hq / Hkv;
     const int sq = tile_seq[tile], r = tile_r0[tile] + ql;
     if (r >= seq_T[sq] * G) return;
-    const float* base = partials + (long long)(tile * Hkv + hk) * n_splits * (HD * 32 + 64);
-    float M = -INFINITY;
-    for (int s = 0; s < n_splits; ++s) M = fmaxf(M, base[(long long)s * (HD * 32 + 64) + HD * 32 + ql]);
-    float L = 0.f;
-    for (int s = 0; s < n_splits; ++s) {
-        const float* p = base + (long long)s * (HD * 32 + 64);
-        L += exp2f(p[HD * 32 + ql] - M) * p[HD * 32 + 32 + ql];
-    }
-    const float invL = 1.0f / L;
-    f16* orow = out + ((long long)(seq_row0[sq] + r / G) * Hq + hk * G + r % G) * HD;
-    for (int ch = cg; ch < HD; ch += 8) {
-        float acc = 0.f;
-        for (int s = 0; s < n_splits; ++s) {
-            const float* p = base + (long long)s * (HD * 32 + 64);
-            acc += exp2f(p[HD * 32 + ql] - M) * p[ch * 32 + ql];
-        }
-        orow[ch] = (f16)(acc * invL);
-    }
+    float L = 0.f, o = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { L += red[i][1][ql]; o += red[i][2 + sg][ql]; }
+    out[((long long)(seq_row0[sq] + r / G) * Hq + hk * G + r % G) * HD + ch0 + sg] = (f16)(o / L);
 }
 
 size_t attention_partial_floats(int n_tiles, int n_kv_heads, int head_dim, int n_splits) {
@@ -282,7 +296,7 @@ void launch_attention(DType dt, const void* q, void* out, KVGeom kv, int layer, 
                                                            n_q_heads);
         return;
     }
-    dim3 grid(sv.n_tiles, kv.n_kv_heads, n_splits), cgrid(sv.n_tiles, kv.n_kv_heads);
+    dim3 grid(sv.n_tiles, kv.n_kv_heads, n_splits), cgrid(sv.n_tiles * kv.n_kv_heads, kv.head_dim / 4);
     if (kv.head_dim == 64) {
         attn_split_kernel<64><<<grid, 64, 0, s>>>((const f16*)q, kv, layer, sv.seq_P, sv.seq_T,
                                                   sv.seq_row0, sv.seq_bt, sv.bt, sv.tile_seq,

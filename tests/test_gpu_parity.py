@@ -320,3 +320,43 @@ def test_full_width_two_layers(B, name, P, T, k):
     print(sh.name, "accepted", hist, "exempt", exempt)
     B.ax_kv_free(kv)
     dm.close()
+
+
+def test_graph_replays_match_eager_verify(B, monkeypatch):
+    """Verify rounds replay a captured graph.  Several replays, with eager extends and
+    synchronisations in between and the cache growing across a block boundary and across a
+    change of the key-slice count, must give exactly what the uncaptured path gives."""
+    sh = SMALL["bf16-hd64-g4"]
+    w = I.make_weights(sh, 17)
+    prompt = I.templated_prompt(sh.vocab, 17, 400)
+    monkeypatch.setenv("AX_NO_GRAPH", "1")
+    eager = B.DeviceModel(sh, w, max_pos=1024, max_tokens=128, pool_tokens=2048)
+    monkeypatch.setenv("AX_NO_GRAPH", "0")
+    graph = B.DeviceModel(sh, w, max_pos=1024, max_tokens=128, pool_tokens=2048)
+    ke, kg = eager.new_kv(), graph.new_kv()
+    eager.extend(ke, prompt[:100])
+    graph.extend(kg, prompt[:100])
+    pending = int(prompt[100])
+    at = 101
+    for r in range(24):
+        k = (4, 8, 0, 4)[r % 4]
+        drafts = prompt[at:at + k].copy()
+        if r % 3 == 0 and k:
+            drafts[k // 2] = (drafts[k // 2] + 1) % sh.vocab
+        res_e = eager.verify(ke, pending, drafts)
+        res_g = graph.verify(kg, pending, drafts)
+        assert res_e == res_g, (r, res_e, res_g)
+        assert B.ax_kv_len(ke) == B.ax_kv_len(kg)
+        if r % 5 == 4:                                   # eager work between replays
+            chunk = prompt[at:at + 37]
+            le = eager.extend(ke, chunk, B.AX_OUT_LAST_LOGITS).cpu().numpy()
+            lg = graph.extend(kg, chunk, B.AX_OUT_LAST_LOGITS).cpu().numpy()
+            np.testing.assert_array_equal(le, lg)
+            at += 37
+        pending = res_e[1]
+    le = eager.extend(ke, prompt[300:310], B.AX_OUT_ALL_LOGITS).cpu().numpy()
+    lg = graph.extend(kg, prompt[300:310], B.AX_OUT_ALL_LOGITS).cpu().numpy()
+    np.testing.assert_array_equal(le, lg)
+    for dm, kv in ((eager, ke), (graph, kg)):
+        B.ax_kv_free(kv)
+        dm.close()
