@@ -23,8 +23,10 @@ ax_status ax_dbg_gemm(int dtype, int epilogue, const void *A, const void *W, con
 /* Copies a workspace buffer as left by the last ax_extend* call to host memory (synchronises).
  * which: 0 residual stream x float[rows][d_model]; 1 qkv float[rows][(Hq+2Hkv)*hd] (pre-rotary,
  * last layer); 2 q after rotary, act[rows][Hq*hd]; 3 attention output act[rows][Hq*hd];
- * 4 SwiGLU activations act[rows][d_ff]; 5 normed LM-head input act[n_out][d_model], where act is
- * float for AX_F32 models and fp16 for AX_BF16 models.
+ * 4 SwiGLU activations act[rows][d_ff]; 5 LM-head input, where act is float for AX_F32 models
+ * and fp16 for AX_BF16 models.  AX_F32: buffer 5 is rmsnorm(x) * gain of the n_out output rows.
+ * AX_BF16: buffer 1 is unused and buffer 5 is fp16(x * final gain) of all rows (the division by
+ * the rms happens inside the LM-head GEMM).
  * Copies min(bytes, buffer size) bytes. */
 ax_status ax_dbg_read(ax_model *model, int which, void *host_dst, size_t bytes);
 

@@ -63,7 +63,7 @@ bool config_ok(const ax_model_config* c, ax_status* why) {
 }
 
 struct Layout {                       // byte offsets into the workspace
-    size_t rope_cos, rope_sin, desc, x, h, qkv, q, attn, ffn, partials, logits, amax_scratch,
+    size_t rope_cos, rope_sin, desc, x, h, ssq, qkv, q, attn, ffn, partials, logits, amax_scratch,
         amax_out, result, total;
     size_t desc_ints;                 // capacity of one descriptor slot
     int max_tiles, max_bt;
@@ -83,6 +83,7 @@ Layout make_layout(const ax_model_config& c) {
     L.desc = take((N_SLOTS + 1) * align_up(L.desc_ints * 4));   // ring + the slot of captured graphs
     L.x = take(T * c.d_model * 4);
     L.h = take(T * c.d_model * a);
+    L.ssq = take(T * (size_t)(c.d_model / 16 + 1) * 4);       // sum-of-squares partials per row
     L.qkv = take(T * (size_t)(c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim * 4);
     L.q = take(T * (size_t)c.n_q_heads * c.head_dim * a);
     L.attn = take(T * (size_t)c.n_q_heads * c.head_dim * a);
@@ -324,39 +325,109 @@ ax_status enqueue_call(ax_model* m, const CallPlan& cp, void* out, hipStream_t s
     const int d_model = c.d_model, qdim = c.n_q_heads * c.head_dim,
               qkv_rows = (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim, R = cp.n_rows;
 
-    ax::launch_embed(dt, m->tok_emb, sv.row_tok, x, R, d_model, stream);
-    for (int l = 0; l < c.n_layers; ++l) {
-        ax::launch_rmsnorm(dt, x, m->norm_attn[(size_t)l], h, nullptr, R, d_model, c.rms_eps, stream);
-        { ProfScope ps(m, 0, stream);
-          ax::launch_gemm(dt, ax::EPI_STORE_F32, h, m->wqkv[(size_t)l], nullptr, qkv, R, qkv_rows, d_model, stream); }
-        ax::launch_rope_kv(dt, qkv, qb, kg, l, sv, (const float*)(ws + L.rope_cos),
-                           (const float*)(ws + L.rope_sin), c.n_q_heads, stream);
-        { ProfScope ps(m, 1, stream);
-          ax::launch_attention(dt, qb, attn, kg, l, sv, c.n_q_heads, (float*)(ws + L.partials), n_splits, stream); }
-        { ProfScope ps(m, 2, stream);
-          ax::launch_gemm(dt, ax::EPI_RESIDUAL, attn, m->wo[(size_t)l], nullptr, x, R, d_model, qdim, stream); }
-        ax::launch_rmsnorm(dt, x, m->norm_mlp[(size_t)l], h, nullptr, R, d_model, c.rms_eps, stream);
-        { ProfScope ps(m, 3, stream);
-          ax::launch_gemm(dt, ax::EPI_SWIGLU, h, m->w_gate[(size_t)l], m->w_up[(size_t)l], ffn, R, c.d_ff, d_model, stream); }
-        { ProfScope ps(m, 4, stream);
-          ax::launch_gemm(dt, ax::EPI_RESIDUAL, ffn, m->w_down[(size_t)l], nullptr, x, R, d_model, c.d_ff, stream); }
-    }
-
-    if (n_out > 0) {
-        const size_t a = (size_t)isz(c.dtype);
-        ax::launch_rmsnorm(dt, x, m->final_norm, h, sv.out_rows, n_out, d_model, c.rms_eps, stream);
-        if (out_mode == AX_OUT_LAST_LOGITS || out_mode == AX_OUT_ALL_LOGITS) {
-            ProfScope ps(m, 5, stream);
-            ax::launch_gemm(dt, ax::EPI_STORE_F32, h, m->lm_head, nullptr, out, n_out, c.vocab, d_model, stream);
-        } else {
-            float* logits = (float*)(ws + L.logits);
-            const int chunk = std::min(c.max_tokens, LOGIT_ROWS);
-            for (int r0 = 0; r0 < n_out; r0 += chunk) {
-                const int rows = std::min(chunk, n_out - r0);
-                { ProfScope ps(m, 5, stream);
-                  ax::launch_gemm(dt, ax::EPI_STORE_F32, (const char*)h + (size_t)r0 * d_model * a, m->lm_head,
-                                  nullptr, logits, rows, c.vocab, d_model, stream); }
-                ax::launch_argmax(logits, rows, c.vocab, (int*)out + r0, (int*)(ws + L.amax_scratch), stream);
+    if (dt == ax::F32) {
+        // fp32 models: one kernel per operation (the exactness configuration)
+        ax::launch_embed(dt, m->tok_emb, sv.row_tok, x, R, d_model, stream);
+        for (int l = 0; l < c.n_layers; ++l) {
+            ax::launch_rmsnorm(dt, x, m->norm_attn[(size_t)l], h, nullptr, R, d_model, c.rms_eps, stream);
+            { ProfScope ps(m, 0, stream);
+              ax::launch_gemm(dt, ax::EPI_STORE_F32, h, m->wqkv[(size_t)l], nullptr, qkv, R, qkv_rows, d_model, stream); }
+            ax::launch_rope_kv(dt, qkv, qb, kg, l, sv, (const float*)(ws + L.rope_cos),
+                               (const float*)(ws + L.rope_sin), c.n_q_heads, stream);
+            { ProfScope ps(m, 1, stream);
+              ax::launch_attention(dt, qb, attn, kg, l, sv, c.n_q_heads, nullptr, 1, stream); }
+            { ProfScope ps(m, 2, stream);
+              ax::launch_gemm(dt, ax::EPI_RESIDUAL, attn, m->wo[(size_t)l], nullptr, x, R, d_model, qdim, stream); }
+            ax::launch_rmsnorm(dt, x, m->norm_mlp[(size_t)l], h, nullptr, R, d_model, c.rms_eps, stream);
+            { ProfScope ps(m, 3, stream);
+              ax::launch_gemm(dt, ax::EPI_SWIGLU, h, m->w_gate[(size_t)l], m->w_up[(size_t)l], ffn, R, c.d_ff, d_model, stream); }
+            { ProfScope ps(m, 4, stream);
+              ax::launch_gemm(dt, ax::EPI_RESIDUAL, ffn, m->w_down[(size_t)l], nullptr, x, R, d_model, c.d_ff, stream); }
+        }
+        if (n_out > 0) {
+            ax::launch_rmsnorm(dt, x, m->final_norm, h, sv.out_rows, n_out, d_model, c.rms_eps, stream);
+            if (out_mode == AX_OUT_LAST_LOGITS || out_mode == AX_OUT_ALL_LOGITS) {
+                ProfScope ps(m, 5, stream);
+                ax::launch_gemm(dt, ax::EPI_STORE_F32, h, m->lm_head, nullptr, out, n_out, c.vocab, d_model, stream);
+            } else {
+                float* logits = (float*)(ws + L.logits);
+                const int chunk = std::min(c.max_tokens, LOGIT_ROWS);
+                for (int r0 = 0; r0 < n_out; r0 += chunk) {
+                    const int rows = std::min(chunk, n_out - r0);
+                    { ProfScope ps(m, 5, stream);
+                      ax::launch_gemm(dt, ax::EPI_STORE_F32, (const char*)h + (size_t)r0 * d_model * 4, m->lm_head,
+                                      nullptr, logits, rows, c.vocab, d_model, stream); }
+                    ax::launch_argmax(logits, rows, c.vocab, (int*)out + r0, (int*)(ws + L.amax_scratch), stream);
+                }
+            }
+        }
+    } else {
+        // bf16-weight models: six launches per layer.  RMSNorm is split between the GEMM that
+        // writes x (gain-scaled fp16 copy + per-row partial sums of x^2) and the GEMM that reads
+        // it (1/rms in the epilogue); rotary embedding and the KV append live in the QKV epilogue.
+        float* ssq = (float*)(ws + L.ssq);
+        const int nparts = ax::gemm_ssq_parts(R, d_model);
+        ax::GemmArgs base{};
+        base.M = R;
+        auto normed = [&](ax::GemmArgs& g) { g.A = h; g.ssq = ssq; g.nparts = nparts; g.d_norm = d_model; g.eps = c.rms_eps; g.K = d_model; };
+        ax::launch_embed_norm(m->tok_emb, sv.row_tok, m->norm_attn[0], x, h, ssq, nparts, R, d_model, stream);
+        for (int l = 0; l < c.n_layers; ++l) {
+            {
+                ax::GemmArgs g = base;
+                normed(g);
+                g.W = m->wqkv[(size_t)l]; g.N = qkv_rows;
+                g.rope.kv = kg; g.rope.layer = l; g.rope.n_q_heads = c.n_q_heads; g.rope.q_out = qb;
+                g.rope.row_pos = sv.row_pos; g.rope.row_seq = sv.row_seq; g.rope.seq_bt = sv.seq_bt; g.rope.bt = sv.bt;
+                g.rope.cos = (const float*)(ws + L.rope_cos); g.rope.sin = (const float*)(ws + L.rope_sin);
+                ProfScope ps(m, 0, stream);
+                ax::launch_gemm_bf16(ax::EPI_QKV, g, stream);
+            }
+            { ProfScope ps(m, 1, stream);
+              ax::launch_attention(dt, qb, attn, kg, l, sv, c.n_q_heads, (float*)(ws + L.partials), n_splits, stream); }
+            {
+                ax::GemmArgs g = base;
+                g.A = attn; g.K = qdim; g.W = m->wo[(size_t)l]; g.N = d_model;
+                g.Cf = x; g.C16 = h; g.gain_next = m->norm_mlp[(size_t)l]; g.ssq_out = ssq;
+                ProfScope ps(m, 2, stream);
+                ax::launch_gemm_bf16(ax::EPI_RESIDUAL, g, stream);
+            }
+            {
+                ax::GemmArgs g = base;
+                normed(g);
+                g.W = m->w_gate[(size_t)l]; g.W2 = m->w_up[(size_t)l]; g.N = c.d_ff; g.C16 = ffn;
+                ProfScope ps(m, 3, stream);
+                ax::launch_gemm_bf16(ax::EPI_SWIGLU, g, stream);
+            }
+            {
+                ax::GemmArgs g = base;
+                g.A = ffn; g.K = c.d_ff; g.W = m->w_down[(size_t)l]; g.N = d_model;
+                g.Cf = x; g.C16 = h; g.ssq_out = ssq;
+                g.gain_next = l + 1 < c.n_layers ? m->norm_attn[(size_t)l + 1] : m->final_norm;
+                ProfScope ps(m, 4, stream);
+                ax::launch_gemm_bf16(ax::EPI_RESIDUAL, g, stream);
+            }
+        }
+        if (n_out > 0) {
+            ax::GemmArgs g = base;
+            normed(g);
+            g.W = m->lm_head; g.N = c.vocab;
+            g.a_rows = n_out == R ? nullptr : sv.out_rows;
+            if (out_mode == AX_OUT_LAST_LOGITS || out_mode == AX_OUT_ALL_LOGITS) {
+                g.M = n_out; g.Cf = (float*)out;
+                ProfScope ps(m, 5, stream);
+                ax::launch_gemm_bf16(ax::EPI_STORE_F32, g, stream);
+            } else {
+                float* logits = (float*)(ws + L.logits);
+                const int chunk = std::min(c.max_tokens, LOGIT_ROWS);
+                for (int r0 = 0; r0 < n_out; r0 += chunk) {
+                    const int rows = std::min(chunk, n_out - r0);
+                    ax::GemmArgs gc = g;
+                    gc.M = rows; gc.Cf = logits;
+                    gc.a_rows = sv.out_rows + r0;            // out_rows lists every row in ALL modes
+                    { ProfScope ps(m, 5, stream);
+                      ax::launch_gemm_bf16(ax::EPI_STORE_F32, gc, stream); }
+                    ax::launch_argmax(logits, rows, c.vocab, (int*)out + r0, (int*)(ws + L.amax_scratch), stream);
+                }
             }
         }
     }
@@ -700,7 +771,7 @@ ax_status ax_dbg_read(ax_model* m, int which, void* host_dst, size_t bytes) {
     if (!ok(m) || !host_dst) return fail(AX_ERR_INVALID, "bad argument");
     const Layout& L = m->lay;
     const size_t off[6] = {L.x, L.qkv, L.q, L.attn, L.ffn, L.h};
-    const size_t end[6] = {L.h, L.q, L.attn, L.ffn, L.partials, L.qkv};
+    const size_t end[6] = {L.h, L.q, L.attn, L.ffn, L.partials, L.ssq};
     if (which < 0 || which > 5) return fail(AX_ERR_INVALID, "bad buffer id");
     HIP_TRY(hipDeviceSynchronize());
     HIP_TRY(hipMemcpy(host_dst, m->ws + off[which], std::min(bytes, end[which] - off[which]), hipMemcpyDeviceToHost));

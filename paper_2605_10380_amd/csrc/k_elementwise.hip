@@ -39,6 +39,35 @@ void launch_embed(DType dt, const void* emb, const int* row_tok, float* x, int n
         embed_kernel<bf16><<<n_rows, 256, 0, s>>>((const bf16*)emb, row_tok, x, d);
 }
 
+// Embedding gather that also prepares the first RMSNorm of bf16-weight models: the fp16 copy
+// scaled by the norm gain and the row's sum of squares (in partial 0; the other partials are
+// zeroed so that the row looks like the output of a GEMM with `nparts` column blocks).
+__global__ void embed_norm_kernel(const bf16* __restrict__ emb, const int* __restrict__ row_tok,
+                                  const bf16* __restrict__ gain, float* __restrict__ x,
+                                  f16* __restrict__ a, float* __restrict__ ssq, int nparts, int d) {
+    __shared__ float part[4];
+    const int r = blockIdx.x;
+    const bf16* src = emb + (long long)row_tok[r] * d;
+    float ss = 0.f;
+    for (int c = threadIdx.x; c < d; c += 256) {
+        const float v = (float)src[c];
+        x[(long long)r * d + c] = v;
+        a[(long long)r * d + c] = (f16)(v * (float)gain[c]);
+        ss += v * v;
+    }
+    ss = wave_sum(ss);
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = ss;
+    __syncthreads();
+    for (int p = threadIdx.x; p < nparts; p += 256)
+        ssq[(long long)r * nparts + p] = p == 0 ? part[0] + part[1] + part[2] + part[3] : 0.f;
+}
+
+void launch_embed_norm(const void* emb, const int* row_tok, const void* gain, float* x, void* a,
+                       float* ssq, int nparts, int n_rows, int d, hipStream_t s) {
+    embed_norm_kernel<<<n_rows, 256, 0, s>>>((const bf16*)emb, row_tok, (const bf16*)gain, x, (f16*)a, ssq,
+                                             nparts, d);
+}
+
 // ---------------------------------------------------------------- RMSNorm
 // One 256-thread block per row: sum of squares in fp32 (wavefront shuffles, then LDS across the
 // four wavefronts), then x * rsqrt(mean + eps) * gain.

@@ -13,8 +13,14 @@
 //     columns, its wavefronts split K, W goes HBM -> registers -> v_mfma_f32_16x16x32_f16
 //     with no LDS in the streaming loop; the per-wavefront partial sums meet in LDS.
 //
-// Epilogues: fp32 store, fp32 residual add, or SwiGLU (two weight matrices share the A
-// operand; the bf16 result is silu(A*Wg^T) * (A*Wu^T)).
+// RMSNorm is folded into the GEMMs around it.  The GEMM that produces the residual stream x
+// also writes a = fp16(x * gain_next) and, per row and per block of columns, a partial sum of
+// x^2.  The GEMM that consumes a multiplies its accumulators by 1 / sqrt(mean(x^2) + eps) in
+// the epilogue: (x * g / rms) W^T = (1 / rms) * ((x * g) W^T).  No separate norm kernel runs.
+//
+// Epilogues: fp32 store (optionally rms-scaled), residual add (+ norm preparation), SwiGLU
+// (two weight matrices share the A operand), and QKV (rms scale, rotary embedding, q to the
+// activation buffer, k and v straight into the KV pages).
 #include "kernels.h"
 
 namespace ax {
@@ -49,21 +55,36 @@ __device__ __forceinline__ f16x8 bf16x8_to_f16x8(u32x4 raw) {
 }
 __device__ __forceinline__ f16x8 load_w(const bf16* p) { return bf16x8_to_f16x8(*(const u32x4*)p); }
 
+// 1 / rms of A-row `row` from the column-block partial sums of x^2 its producer left behind.
+// Called by a whole wavefront (lanes stride over the partials); every lane gets the result.
+__device__ __forceinline__ float wave_inv_rms(const float* __restrict__ ssq, int row, int nparts,
+                                              int d_norm, float eps, int lane) {
+    float v = 0.f;
+    for (int p = lane; p < nparts; p += 64) v += ssq[(long long)row * nparts + p];
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return 1.0f / sqrtf(v / (float)d_norm + eps);
+}
+
 // ------------------------------------------------------------------------------ tile kernel
 // MFMA 32x32x16 operand layout (wave64): lane l supplies row/col (l % 32) and the 8 k values
 // 8*(l/32) .. +7; result register r of lane l is C[(r/4)*8 + (l/32)*4 + r%4][l % 32].
+// Block = 2 x 2 wavefronts, wavefront tile = (TM*32) x (TN*32).  For EPI_QKV the wavefront's
+// TN*32 columns are exactly one head, so a rotary pair (c, c + hd/2) sits in the same lane and
+// register of tiles j and j + TN/2.
 template <int EPI, int TM, int TN>
-__global__ __launch_bounds__(256) void gemm_bf16_tile_kernel(const f16* __restrict__ A,
-                                                             const bf16* __restrict__ W,
-                                                             const bf16* __restrict__ W2,
-                                                             void* __restrict__ Cv, int M, int N,
-                                                             int K) {
+__global__ __launch_bounds__(256) void gemm_bf16_tile_kernel(GemmArgs g) {
     constexpr int BM = 2 * TM * 32, BN = 2 * TN * 32, BK = 64, LS = BK + 8;  // LS: padded row
     constexpr int NB = EPI == EPI_SWIGLU ? 2 : 1;
     constexpr int A_CH = BM * 8 / 256, B_CH = BN * 8 / 256;                  // 16-byte chunks per thread
     __shared__ __attribute__((aligned(16))) f16 sA[BM * LS];
     __shared__ __attribute__((aligned(16))) f16 sB[NB][BN * LS];
+    __shared__ float s_inv[BM];
 
+    const f16* __restrict__ A = (const f16*)g.A;
+    const bf16* __restrict__ W = (const bf16*)g.W;
+    const bf16* __restrict__ W2 = (const bf16*)g.W2;
+    const int M = g.M, N = g.N, K = g.K;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int wm = wave >> 1, wn = wave & 1;
     const int lrow = lane & 31, lg = lane >> 5;
@@ -81,13 +102,16 @@ __global__ __launch_bounds__(256) void gemm_bf16_tile_kernel(const f16* __restri
 
     f16x8 ra[A_CH];
     u32x4 rb[NB][B_CH];             // raw bf16 weights; widened to fp16 on the way into LDS
+    long long a_off[A_CH];
+#pragma unroll
+    for (int i = 0; i < A_CH; ++i) {
+        const int c = tid + 256 * i, row = c >> 3, cc = c & 7;
+        const int gm = min(m0 + row, M - 1);
+        a_off[i] = (long long)(g.a_rows ? g.a_rows[gm] : gm) * K + cc * 8;
+    }
     auto load_global = [&](int k0) {
 #pragma unroll
-        for (int i = 0; i < A_CH; ++i) {
-            const int c = tid + 256 * i, row = c >> 3, cc = c & 7;
-            const int gm = min(m0 + row, M - 1);
-            ra[i] = *(const f16x8*)(A + (long long)gm * K + k0 + cc * 8);
-        }
+        for (int i = 0; i < A_CH; ++i) ra[i] = *(const f16x8*)(A + a_off[i] + k0);
 #pragma unroll
         for (int i = 0; i < B_CH; ++i) {
             const int c = tid + 256 * i, row = c >> 3, cc = c & 7;
@@ -111,6 +135,13 @@ __global__ __launch_bounds__(256) void gemm_bf16_tile_kernel(const f16* __restri
     };
 
     load_global(0);
+    if (g.ssq) {                     // deferred RMSNorm: 1/rms of this block's rows
+        for (int r = wave; r < BM; r += 4) {
+            const int gm = min(m0 + r, M - 1);
+            const float inv = wave_inv_rms(g.ssq, g.a_rows ? g.a_rows[gm] : gm, g.nparts, g.d_norm, g.eps, lane);
+            if (lane == 0) s_inv[r] = inv;
+        }
+    }
     for (int k0 = 0; k0 < K; k0 += BK) {
         store_lds();
         __syncthreads();
@@ -138,21 +169,79 @@ __global__ __launch_bounds__(256) void gemm_bf16_tile_kernel(const f16* __restri
     }
 
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+    for (int i = 0; i < TM; ++i) {
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int n = n0 + (wn * TN + j) * 32 + lrow;
+        for (int r = 0; r < 16; ++r) {
+            const int ml = (wm * TM + i) * 32 + (r >> 2) * 8 + lg * 4 + (r & 3);
+            const int m = m0 + ml;
+            const bool mok = m < M;
+            const float inv = g.ssq ? s_inv[ml] : 1.0f;
+            if (EPI == EPI_STORE_F32) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int m = m0 + (wm * TM + i) * 32 + (r >> 2) * 8 + lg * 4 + (r & 3);
-                if (m < M && n < N) {
-                    const long long o = (long long)m * N + n;
-                    if (EPI == EPI_STORE_F32) ((float*)Cv)[o] = acc[0][i][j][r];
-                    else if (EPI == EPI_RESIDUAL) ((float*)Cv)[o] += acc[0][i][j][r];
-                    else ((f16*)Cv)[o] = (f16)(silu_f(acc[0][i][j][r]) * acc[NB - 1][i][j][r]);
+                for (int j = 0; j < TN; ++j) {
+                    const int n = n0 + (wn * TN + j) * 32 + lrow;
+                    if (mok && n < N) g.Cf[(long long)m * N + n] = acc[0][i][j][r] * inv;
+                }
+            } else if (EPI == EPI_SWIGLU) {
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    const int n = n0 + (wn * TN + j) * 32 + lrow;
+                    if (mok && n < N)
+                        ((f16*)g.C16)[(long long)m * N + n] =
+                            (f16)(silu_f(acc[0][i][j][r] * inv) * (acc[NB - 1][i][j][r] * inv));
+                }
+            } else if (EPI == EPI_RESIDUAL) {
+                float ss = 0.f;
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    const int n = n0 + (wn * TN + j) * 32 + lrow;
+                    if (mok && n < N) {
+                        const long long o = (long long)m * N + n;
+                        const float xn = g.Cf[o] + acc[0][i][j][r];
+                        g.Cf[o] = xn;
+                        if (g.gain_next) {
+                            ((f16*)g.C16)[o] = (f16)(xn * (float)((const bf16*)g.gain_next)[n]);
+                            ss += xn * xn;
+                        }
+                    }
+                }
+                if (g.gain_next) {   // partial sum of squares over this wavefront's TN*32 columns
+#pragma unroll
+                    for (int o = 16; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
+                    if (lrow == 0 && mok) g.ssq_out[(long long)m * (N / (TN * 32)) + (n0 / (TN * 32)) + wn] = ss;
+                }
+            } else {                 // EPI_QKV: one head per wavefront, rotary pairs (j, j + TN/2)
+                const int head = n0 / (TN * 32) + wn;
+                const RopeArgs& ro = g.rope;
+                const int Hq = ro.n_q_heads, Hkv = ro.kv.n_kv_heads, hd = TN * 32;
+                if (!mok || head >= Hq + 2 * Hkv) continue;
+                const int pos = ro.row_pos[m];
+                f16* pool = (f16*)ro.kv.base;
+                if (head < Hq + Hkv) {
+                    f16* dst;
+                    if (head < Hq) {
+                        dst = (f16*)ro.q_out + ((long long)m * Hq + head) * hd;
+                    } else {
+                        const int blk = ro.bt[ro.seq_bt[ro.row_seq[m]] + (pos >> 4)];
+                        dst = pool + ro.kv.plane(ro.layer, 0, head - Hq) + ((long long)blk * 16 + (pos & 15)) * hd;
+                    }
+#pragma unroll
+                    for (int j = 0; j < TN / 2; ++j) {
+                        const int c = j * 32 + lrow;
+                        const float cs = ro.cos[(long long)pos * (hd / 2) + c], sn = ro.sin[(long long)pos * (hd / 2) + c];
+                        const float a = acc[0][i][j][r] * inv, b = acc[0][i][j + TN / 2][r] * inv;
+                        dst[c] = (f16)(a * cs - b * sn);
+                        dst[c + hd / 2] = (f16)(b * cs + a * sn);
+                    }
+                } else {
+                    const int blk = ro.bt[ro.seq_bt[ro.row_seq[m]] + (pos >> 4)];
+                    f16* dst = pool + ro.kv.plane(ro.layer, 1, head - Hq - Hkv) + (long long)blk * 16 * hd + (pos & 15);
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) dst[(long long)(j * 32 + lrow) * 16] = (f16)(acc[0][i][j][r] * inv);
                 }
             }
         }
+    }
 }
 
 // ------------------------------------------------------------------------------ skinny kernel
@@ -160,25 +249,43 @@ __global__ __launch_bounds__(256) void gemm_bf16_tile_kernel(const f16* __restri
 // 8*(l/16) .. +7; result register r of lane l is D[4*(l/16) + r][l % 16].  Here D = W_tile * x^T:
 // D rows are output columns n, D columns are activation rows m, so a lane ends up with four
 // consecutive n of one row m (one 16-byte store).
+//
+// For EPI_QKV the 16 columns of a block are 8 + 8 rotary partners of one head: local columns
+// 0..7 are channels j0..j0+7, local columns 8..15 are channels hd/2 + j0 .. +7, so the partner
+// of a lane's value lives in lane ^ 32.
 template <int EPI, int MT, int NW>
-__global__ __launch_bounds__(64 * NW) void gemm_bf16_skinny_kernel(const f16* __restrict__ X,
-                                                                   const bf16* __restrict__ W,
-                                                                   const bf16* __restrict__ W2,
-                                                                   void* __restrict__ Cv, int M,
-                                                                   int N, int K) {
+__global__ __launch_bounds__(64 * NW) void gemm_bf16_skinny_kernel(GemmArgs g) {
     constexpr int NB = EPI == EPI_SWIGLU ? 2 : 1;
     __shared__ __attribute__((aligned(16))) f32x4 red[NW][NB][MT][64];
+    __shared__ float s_inv[MT * 16];
 
+    const f16* __restrict__ X = (const f16*)g.A;
+    const bf16* __restrict__ W = (const bf16*)g.W;
+    const bf16* __restrict__ W2 = (const bf16*)g.W2;
+    const int M = g.M, N = g.N, K = g.K;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int lr = lane & 15, lg = lane >> 4;
     const int n0 = blockIdx.x * 16;
     const int kslice = K / NW, kbeg = wave * kslice, kend = kbeg + kslice;
 
-    const bf16* wp = W + (long long)min(n0 + lr, N - 1) * K + lg * 8;
-    const bf16* wp2 = NB == 2 ? W2 + (long long)min(n0 + lr, N - 1) * K + lg * 8 : nullptr;
+    int wrow;                            // weight row this lane streams
+    int q_head = 0, q_j0 = 0;            // EPI_QKV: head and first channel of the block
+    if (EPI == EPI_QKV) {
+        const int hd = g.rope.kv.head_dim, per = hd / 16;
+        q_head = blockIdx.x / per;
+        q_j0 = (blockIdx.x % per) * 8;
+        wrow = q_head * hd + (lr < 8 ? q_j0 + lr : hd / 2 + q_j0 + lr - 8);
+    } else {
+        wrow = min(n0 + lr, N - 1);
+    }
+    const bf16* wp = W + (long long)wrow * K + lg * 8;
+    const bf16* wp2 = NB == 2 ? W2 + (long long)wrow * K + lg * 8 : nullptr;
     const f16* xp[MT];
 #pragma unroll
-    for (int t = 0; t < MT; ++t) xp[t] = X + (long long)min(t * 16 + lr, M - 1) * K + lg * 8;
+    for (int t = 0; t < MT; ++t) {
+        const int m = min(t * 16 + lr, M - 1);
+        xp[t] = X + (long long)(g.a_rows ? g.a_rows[m] : m) * K + lg * 8;
+    }
 
     f32x4 acc[NB][MT];
 #pragma unroll
@@ -225,6 +332,13 @@ __global__ __launch_bounds__(64 * NW) void gemm_bf16_skinny_kernel(const f16* __
     for (int b = 0; b < NB; ++b)
 #pragma unroll
         for (int t = 0; t < MT; ++t) red[wave][b][t][lane] = acc[b][t];
+    if (g.ssq) {                         // deferred RMSNorm: the wavefronts share the rows
+        for (int r = wave; r < MT * 16; r += NW) {
+            const int m = min(r, M - 1);
+            const float inv = wave_inv_rms(g.ssq, g.a_rows ? g.a_rows[m] : m, g.nparts, g.d_norm, g.eps, lane);
+            if (lane == 0) s_inv[r] = inv;
+        }
+    }
     __syncthreads();
     if (wave != 0) return;
 
@@ -238,36 +352,89 @@ __global__ __launch_bounds__(64 * NW) void gemm_bf16_skinny_kernel(const f16* __
             for (int w = 1; w < NW; ++w) sum[b] += red[w][b][t][lane];
         }
         const int m = t * 16 + lr, n = n0 + lg * 4;
-        if (m >= M || n >= N) continue;
+        const bool mok = m < M;
+        const float inv = g.ssq ? s_inv[t * 16 + lr] : 1.0f;
         const long long o = (long long)m * N + n;
         if (EPI == EPI_STORE_F32) {
-            *(f32x4*)((float*)Cv + o) = sum[0];
-        } else if (EPI == EPI_RESIDUAL) {
-            f32x4* c = (f32x4*)((float*)Cv + o);
-            *c = *c + sum[0];
-        } else {
-            f16x4 h;
+            if (mok && n < N) *(f32x4*)(g.Cf + o) = sum[0] * inv;
+        } else if (EPI == EPI_SWIGLU) {
+            if (mok && n < N) {
+                f16x4 h;
 #pragma unroll
-            for (int r = 0; r < 4; ++r) h[r] = (f16)(silu_f(sum[0][r]) * sum[NB - 1][r]);
-            *(f16x4*)((f16*)Cv + o) = h;
+                for (int r = 0; r < 4; ++r) h[r] = (f16)(silu_f(sum[0][r] * inv) * (sum[NB - 1][r] * inv));
+                *(f16x4*)((f16*)g.C16 + o) = h;
+            }
+        } else if (EPI == EPI_RESIDUAL) {
+            float ss = 0.f;
+            if (mok && n < N) {
+                f32x4* c = (f32x4*)(g.Cf + o);
+                const f32x4 xn = *c + sum[0];
+                *c = xn;
+                if (g.gain_next) {
+                    f16x4 h;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        h[r] = (f16)(xn[r] * (float)((const bf16*)g.gain_next)[n + r]);
+                        ss += xn[r] * xn[r];
+                    }
+                    *(f16x4*)((f16*)g.C16 + o) = h;
+                }
+            }
+            if (g.gain_next) {           // sum of squares over the block's 16 columns, per row
+                ss += __shfl_xor(ss, 16, 64);
+                ss += __shfl_xor(ss, 32, 64);
+                if (lg == 0 && mok) g.ssq_out[(long long)m * (N / 16) + blockIdx.x] = ss;
+            }
+        } else {                         // EPI_QKV
+            const RopeArgs& ro = g.rope;
+            const int Hq = ro.n_q_heads, Hkv = ro.kv.n_kv_heads, hd = ro.kv.head_dim;
+            const int mm = min(m, M - 1);
+            const int pos = ro.row_pos[mm];
+            f16* pool = (f16*)ro.kv.base;
+            const int chan = (lg < 2 ? q_j0 + lg * 4 : hd / 2 + q_j0 + (lg - 2) * 4);   // first of 4 channels
+            f32x4 own = sum[0] * inv, other;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) other[r] = __shfl_xor(own[r], 32, 64);
+            if (q_head < Hq + Hkv) {
+                const int jj = q_j0 + (lg & 1) * 4;                                     // angle index of r = 0
+                const float* cs = ro.cos + (long long)pos * (hd / 2) + jj;
+                const float* sn = ro.sin + (long long)pos * (hd / 2) + jj;
+                f16x4 h;
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    h[r] = lg < 2 ? (f16)(own[r] * cs[r] - other[r] * sn[r])            // first half: a c - b s
+                                  : (f16)(own[r] * cs[r] + other[r] * sn[r]);           // second half: b c + a s
+                f16* dst;
+                if (q_head < Hq) {
+                    dst = (f16*)ro.q_out + ((long long)mm * Hq + q_head) * hd;
+                } else {
+                    const int blk = ro.bt[ro.seq_bt[ro.row_seq[mm]] + (pos >> 4)];
+                    dst = pool + ro.kv.plane(ro.layer, 0, q_head - Hq) + ((long long)blk * 16 + (pos & 15)) * hd;
+                }
+                if (mok) *(f16x4*)(dst + chan) = h;
+            } else if (mok) {
+                const int blk = ro.bt[ro.seq_bt[ro.row_seq[mm]] + (pos >> 4)];
+                f16* dst = pool + ro.kv.plane(ro.layer, 1, q_head - Hq - Hkv) + (long long)blk * 16 * hd + (pos & 15);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) dst[(long long)(chan + r) * 16] = (f16)own[r];
+            }
         }
     }
 }
 
 template <int EPI, int MT>
-static void launch_skinny_nw(const f16* A, const bf16* W, const bf16* W2, void* C, int M, int N,
-                             int K, int nw, hipStream_t s) {
-    const int grid = (N + 15) / 16;
-    if (nw == 16) gemm_bf16_skinny_kernel<EPI, MT, 16><<<grid, 1024, 0, s>>>(A, W, W2, C, M, N, K);
-    else if (nw == 1) gemm_bf16_skinny_kernel<EPI, MT, 1><<<grid, 64, 0, s>>>(A, W, W2, C, M, N, K);
-    else if (nw == 2) gemm_bf16_skinny_kernel<EPI, MT, 2><<<grid, 128, 0, s>>>(A, W, W2, C, M, N, K);
-    else if (nw == 8) gemm_bf16_skinny_kernel<EPI, MT, 8><<<grid, 512, 0, s>>>(A, W, W2, C, M, N, K);
-    else gemm_bf16_skinny_kernel<EPI, MT, 4><<<grid, 256, 0, s>>>(A, W, W2, C, M, N, K);
+static void launch_skinny_nw(const GemmArgs& g, int nw, hipStream_t s) {
+    const int grid = (g.N + 15) / 16;
+    if (nw == 16) gemm_bf16_skinny_kernel<EPI, MT, 16><<<grid, 1024, 0, s>>>(g);
+    else if (nw == 1) gemm_bf16_skinny_kernel<EPI, MT, 1><<<grid, 64, 0, s>>>(g);
+    else if (nw == 2) gemm_bf16_skinny_kernel<EPI, MT, 2><<<grid, 128, 0, s>>>(g);
+    else if (nw == 8) gemm_bf16_skinny_kernel<EPI, MT, 8><<<grid, 512, 0, s>>>(g);
+    else gemm_bf16_skinny_kernel<EPI, MT, 4><<<grid, 256, 0, s>>>(g);
 }
 
 template <int EPI>
-static void launch_bf16(const f16* A, const bf16* W, const bf16* W2, void* C, int M, int N, int K,
-                        hipStream_t s) {
+static void launch_bf16(const GemmArgs& g, hipStream_t s) {
+    const int M = g.M, N = g.N, K = g.K;
     if (M <= 64) {
         // wavefronts per block (= K slices): enough to keep ~2k wavefronts in flight, each with
         // at least 128 of K; K / nw must stay a multiple of the MFMA k (32)
@@ -275,20 +442,37 @@ static void launch_bf16(const f16* A, const bf16* W, const bf16* W2, void* C, in
         int nw = 1;
         while (nw < 16 && tiles * nw < 2048 && K % (nw * 2 * 32) == 0 && K / (nw * 2) >= 128) nw *= 2;
         if (EPI == EPI_SWIGLU && nw == 16) nw = 8;        // LDS reduction buffer stays <= 64 KB
-        if (M <= 16) launch_skinny_nw<EPI, 1>(A, W, W2, C, M, N, K, nw, s);
-        else if (M <= 32) launch_skinny_nw<EPI, 2>(A, W, W2, C, M, N, K, nw, s);
-        else launch_skinny_nw<EPI, 4>(A, W, W2, C, M, N, K, nw == 16 ? 8 : nw, s);
+        if (M <= 16) launch_skinny_nw<EPI, 1>(g, nw, s);
+        else if (M <= 32) launch_skinny_nw<EPI, 2>(g, nw, s);
+        else launch_skinny_nw<EPI, 4>(g, nw == 16 ? 8 : nw, s);
         return;
     }
-    // large M: 128x128 tiles when that still gives every CU a block, else 64x128
+    if (EPI == EPI_QKV) {                                 // one head per wavefront: BN = 2 heads
+        const int hd = g.rope.kv.head_dim;
+        dim3 grid((N + 2 * hd - 1) / (2 * hd), (M + 63) / 64);
+        if (hd == 64) gemm_bf16_tile_kernel<EPI_QKV, 1, 2><<<grid, 256, 0, s>>>(g);
+        else gemm_bf16_tile_kernel<EPI_QKV, 1, 4><<<grid, 256, 0, s>>>(g);
+        return;
+    }
+    // large M: 128x128 tiles when that still gives every CU a block, else 64x128.  The residual
+    // epilogue always uses 64x128 so that its sum-of-squares partials are per 64 columns.
     const long long big = (long long)((M + 127) / 128) * ((N + 127) / 128);
-    if (big >= 256 && EPI != EPI_SWIGLU) {
+    if (big >= 256 && EPI == EPI_STORE_F32) {
         dim3 grid((N + 127) / 128, (M + 127) / 128);
-        gemm_bf16_tile_kernel<EPI, 2, 2><<<grid, 256, 0, s>>>(A, W, W2, C, M, N, K);
+        gemm_bf16_tile_kernel<EPI, 2, 2><<<grid, 256, 0, s>>>(g);
     } else {
         dim3 grid((N + 127) / 128, (M + 63) / 64);
-        gemm_bf16_tile_kernel<EPI, 1, 2><<<grid, 256, 0, s>>>(A, W, W2, C, M, N, K);
+        gemm_bf16_tile_kernel<EPI, 1, 2><<<grid, 256, 0, s>>>(g);
     }
+}
+
+int gemm_ssq_parts(int M, int N) { return M <= 64 ? N / 16 : N / 64; }
+
+void launch_gemm_bf16(Epilogue epi, const GemmArgs& g, hipStream_t s) {
+    if (epi == EPI_STORE_F32) launch_bf16<EPI_STORE_F32>(g, s);
+    else if (epi == EPI_RESIDUAL) launch_bf16<EPI_RESIDUAL>(g, s);
+    else if (epi == EPI_SWIGLU) launch_bf16<EPI_SWIGLU>(g, s);
+    else launch_bf16<EPI_QKV>(g, s);
 }
 
 void launch_gemm(DType dt, Epilogue epi, const void* A, const void* W, const void* W2, void* C,
@@ -297,11 +481,11 @@ void launch_gemm(DType dt, Epilogue epi, const void* A, const void* W, const voi
         launch_gemm_f32(epi, (const float*)A, (const float*)W, (const float*)W2, (float*)C, M, N, K, s);
         return;
     }
-    const f16* a = (const f16*)A;
-    const bf16 *w = (const bf16*)W, *w2 = (const bf16*)W2;
-    if (epi == EPI_STORE_F32) launch_bf16<EPI_STORE_F32>(a, w, w2, C, M, N, K, s);
-    else if (epi == EPI_RESIDUAL) launch_bf16<EPI_RESIDUAL>(a, w, w2, C, M, N, K, s);
-    else launch_bf16<EPI_SWIGLU>(a, w, w2, C, M, N, K, s);
+    GemmArgs g{};
+    g.A = A; g.W = W; g.W2 = W2; g.M = M; g.N = N; g.K = K;
+    g.Cf = (float*)C;
+    g.C16 = C;
+    launch_gemm_bf16(epi, g, s);
 }
 
 }  // namespace ax

@@ -39,7 +39,40 @@ struct StepView {
     int n_rows, n_seq, n_out, n_tiles;
 };
 
-enum Epilogue { EPI_STORE_F32 = 0, EPI_RESIDUAL = 1, EPI_SWIGLU = 2 };
+enum Epilogue { EPI_STORE_F32 = 0, EPI_RESIDUAL = 1, EPI_SWIGLU = 2, EPI_QKV = 3 };
+
+// Rotary + KV-append part of the QKV epilogue (bf16-weight models).
+struct RopeArgs {
+    KVGeom kv;
+    int layer, n_q_heads;
+    void* q_out;                      // fp16 [n_rows, Hq, hd]
+    const int *row_pos, *row_seq, *seq_bt, *bt;
+    const float *cos, *sin;           // [max_pos][hd/2]
+};
+
+// One GEMM of a bf16-weight model: C = A[M,K] * W[N,K]^T, A fp16, W bf16.
+struct GemmArgs {
+    const void* A;                    // fp16 [rows, K]
+    const int* a_rows;                // optional gather: A row of output row m is a_rows[m]
+    const void *W, *W2;               // bf16 [N, K]; W2 only for EPI_SWIGLU
+    int M, N, K;
+    // deferred RMSNorm of the A rows: ssq[row][nparts] partial sums of x^2 over d_norm columns;
+    // the accumulators are scaled by 1 / sqrt(sum / d_norm + eps).  NULL = no scaling.
+    const float* ssq;
+    int nparts, d_norm;
+    float eps;
+    float* Cf;                        // EPI_STORE_F32: out [M,N]; EPI_RESIDUAL: x [M,N], updated in place
+    void* C16;                        // EPI_SWIGLU: fp16 out [M,N]; EPI_RESIDUAL: fp16(x * gain_next) [M,N]
+    const void* gain_next;            // EPI_RESIDUAL: bf16 [N] gain of the next norm, NULL = plain residual add
+    float* ssq_out;                   // EPI_RESIDUAL: [M][gemm_ssq_parts(M, N)] partial sums of x^2
+    RopeArgs rope;                    // EPI_QKV
+};
+void launch_gemm_bf16(Epilogue epi, const GemmArgs& g, hipStream_t s);
+// Number of sum-of-squares partials per row that an EPI_RESIDUAL launch with this M, N writes.
+int gemm_ssq_parts(int M, int N);
+// bf16-weight models: x[r,:] = emb[tok], a[r,:] = fp16(x * gain), ssq[r][0] = sum x^2, ssq[r][1..nparts) = 0
+void launch_embed_norm(const void* emb, const int* row_tok, const void* gain, float* x, void* a,
+                       float* ssq, int nparts, int n_rows, int d, hipStream_t s);
 
 // x[r, :] = emb[row_tok[r], :] widened to fp32
 void launch_embed(DType dt, const void* emb, const int* row_tok, float* x, int n_rows, int d,

@@ -112,13 +112,16 @@ def test_single_layer_stages(torch_cuda, which, P, T):
         return a.astype(np.float64)
 
     tol = 4e-3 if bf else 2e-5      # relative to the stage's largest magnitude
-    stages = [("qkv", read(1, sh.qkv_rows, False), tr["qkv"]),
-              ("q", read(2, Hq * hd, True), tr["q"].reshape(T, -1)),
+    stages = [("q", read(2, Hq * hd, True), tr["q"].reshape(T, -1)),
               ("attn", read(3, Hq * hd, True), tr["attn"].reshape(T, -1)),
               ("ffn", read(4, sh.d_ff, True), tr["ffn"]),
               ("x", read(0, sh.d_model, False), tr["x"]),
-              ("h_out", read(5, sh.d_model, True), tr["h_out"]),
               ("logits", logits, ref)]
+    if bf:      # the norm's division happens inside the consuming GEMM: buffer 5 is x * gain
+        stages.append(("x*gain", read(5, sh.d_model, True), tr["x"] * O.widen(w["final_norm"])))
+    else:
+        stages += [("qkv", read(1, sh.qkv_rows, False), tr["qkv"]),
+                   ("h_out", read(5, sh.d_model, True), tr["h_out"])]
     errs = {name: float(np.abs(g - r).max() / np.abs(r).max()) for name, g, r in stages}
     print(which, P, T, {k: f"{v:.2e}" for k, v in errs.items()})
     for name, e in errs.items():
