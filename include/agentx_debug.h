@@ -20,6 +20,14 @@ extern "C" {
 ax_status ax_dbg_gemm(int dtype, int epilogue, const void *A, const void *W, const void *W2, void *C,
                       int M, int N, int K, void *hip_stream);
 
+/* Times `iters` back-to-back launches of the same GEMM with HIP events on hip_stream and writes the
+ * average microseconds per launch to *avg_us.  Launch i reads its weights at W + (i % w_count) *
+ * w_stride_bytes (same for W2), so that a set of weight copies larger than the caches can be
+ * cycled through (w_count = 1: always the same weights).  Arguments otherwise as ax_dbg_gemm. */
+ax_status ax_dbg_gemm_time(int dtype, int epilogue, const void *A, const void *W, const void *W2, void *C,
+                           int M, int N, int K, int iters, size_t w_stride_bytes, int w_count,
+                           float *avg_us, void *hip_stream);
+
 /* Copies a workspace buffer as left by the last ax_extend* call to host memory (synchronises).
  * which: 0 residual stream x float[rows][d_model]; 1 qkv float[rows][(Hq+2Hkv)*hd] (pre-rotary,
  * last layer); 2 q after rotary, act[rows][Hq*hd]; 3 attention output act[rows][Hq*hd];

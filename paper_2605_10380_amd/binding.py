@@ -56,6 +56,8 @@ def _load():
         "ax_extend": (C.c_int, [vp, vp, i32p, C.c_int, C.c_int, vp, vp]),
         "ax_extend_batch": (C.c_int, [vp, C.c_int, C.POINTER(vp), i32p, C.POINTER(C.c_int), C.c_int, vp, vp]),
         "ax_dbg_gemm": (C.c_int, [C.c_int, C.c_int, vp, vp, vp, vp, C.c_int, C.c_int, C.c_int, vp]),
+        "ax_dbg_gemm_time": (C.c_int, [C.c_int, C.c_int, vp, vp, vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_size_t,
+                                       C.c_int, C.POINTER(C.c_float), vp]),
         "ax_dbg_read": (C.c_int, [vp, C.c_int, vp, C.c_size_t]),
         "ax_dbg_profile": (C.c_int, [vp, C.c_int]),
         "ax_dbg_profile_read": (C.c_int, [vp, C.POINTER(C.c_double), C.POINTER(i64)]),
@@ -208,6 +210,14 @@ def ax_verify(model: int, kv: int, pending: int, drafts, stream: int = 0):
 def ax_dbg_gemm(dtype: int, epilogue: int, A: int, W: int, W2: int, Cptr: int, M: int, N: int, K: int, stream: int = 0):
     _check(lib.ax_dbg_gemm(dtype, epilogue, C.c_void_p(A), C.c_void_p(W), C.c_void_p(W2), C.c_void_p(Cptr), M, N, K,
                            C.c_void_p(stream)))
+
+
+def ax_dbg_gemm_time(dtype: int, epilogue: int, A: int, W: int, W2: int, Cptr: int, M: int, N: int, K: int, iters: int,
+                     w_stride_bytes: int = 0, w_count: int = 1, stream: int = 0) -> float:
+    us = C.c_float()
+    _check(lib.ax_dbg_gemm_time(dtype, epilogue, C.c_void_p(A), C.c_void_p(W), C.c_void_p(W2), C.c_void_p(Cptr), M, N, K,
+                                iters, w_stride_bytes, w_count, C.byref(us), C.c_void_p(stream)))
+    return us.value
 
 
 def ax_dbg_read(model: int, which: int, dst: np.ndarray):

@@ -767,6 +767,37 @@ ax_status ax_dbg_gemm(int dtype, int epilogue, const void* A, const void* W, con
     return AX_OK;
 }
 
+ax_status ax_dbg_gemm_time(int dtype, int epilogue, const void* A, const void* W, const void* W2, void* C, int M,
+                           int N, int K, int iters, size_t w_stride_bytes, int w_count, float* avg_us,
+                           void* hip_stream) {
+    if (!A || !W || !C || !avg_us || M <= 0 || N <= 0 || K <= 0 || iters <= 0 || w_count <= 0 || epilogue < 0 ||
+        epilogue > 2 || (epilogue == 2 && !W2) || (dtype != AX_F32 && dtype != AX_BF16))
+        return fail(AX_ERR_INVALID, "bad argument");
+    if (dtype == AX_BF16 && (K % 64 != 0 || N % 16 != 0)) return fail(AX_ERR_UNSUPPORTED, "bf16 needs K %% 64 == 0, N %% 16 == 0");
+    hipStream_t s = (hipStream_t)hip_stream;
+    hipEvent_t e0, e1;
+    HIP_TRY(hipEventCreate(&e0));
+    HIP_TRY(hipEventCreate(&e1));
+    const ax::DType dt = dtype == AX_F32 ? ax::F32 : ax::BF16;
+    auto run = [&](int i) {
+        const size_t off = (size_t)(i % w_count) * w_stride_bytes;
+        ax::launch_gemm(dt, (ax::Epilogue)epilogue, A, (const char*)W + off, W2 ? (const char*)W2 + off : nullptr, C,
+                        M, N, K, s);
+    };
+    for (int i = 0; i < std::min(iters, 3); ++i) run(i);
+    (void)hipEventRecord(e0, s);
+    for (int i = 0; i < iters; ++i) run(i);
+    (void)hipEventRecord(e1, s);
+    hipError_t e = hipEventSynchronize(e1);
+    float ms = 0.f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (e != hipSuccess) return fail(AX_ERR_DEVICE, "timing: %s", hipGetErrorString(e));
+    *avg_us = ms * 1000.f / (float)iters;
+    return AX_OK;
+}
+
 ax_status ax_dbg_read(ax_model* m, int which, void* host_dst, size_t bytes) {
     if (!ok(m) || !host_dst) return fail(AX_ERR_INVALID, "bad argument");
     const Layout& L = m->lay;

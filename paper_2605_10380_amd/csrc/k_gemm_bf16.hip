@@ -8,7 +8,7 @@
 // wants: a lane holds 8 consecutive k of one row (A) or one column (W), i.e. one 16-byte load.
 //
 //   * tile kernel   (M > 64, large-T extend: compute bound): 4 wavefronts, LDS-staged
-//     BM x BN x 64 tiles, v_mfma_f32_32x32x16_f16, register prefetch of the next K slice.
+//     BM x BN x 64 tiles, v_mfma_f32_32x32x16_f16, global loads several K slices ahead.
 //   * skinny kernel (M <= 64, verify steps: pure weight streaming): one block owns 16 output
 //     columns, its wavefronts split K, W goes HBM -> registers -> v_mfma_f32_16x16x32_f16
 //     with no LDS in the streaming loop; the per-wavefront partial sums meet in LDS.
@@ -77,8 +77,9 @@ __global__ __launch_bounds__(256) void gemm_bf16_tile_kernel(GemmArgs g) {
     constexpr int BM = 2 * TM * 32, BN = 2 * TN * 32, BK = 64, LS = BK + 8;  // LS: padded row
     constexpr int NB = EPI == EPI_SWIGLU ? 2 : 1;
     constexpr int A_CH = BM * 8 / 256, B_CH = BN * 8 / 256;                  // 16-byte chunks per thread
-    __shared__ __attribute__((aligned(16))) f16 sA[BM * LS];
-    __shared__ __attribute__((aligned(16))) f16 sB[NB][BN * LS];
+    constexpr int D = NB == 2 ? 2 : 4;                                       // prefetch distance (even)
+    __shared__ __attribute__((aligned(16))) f16 sA[2][BM * LS];
+    __shared__ __attribute__((aligned(16))) f16 sB[2][NB][BN * LS];
     __shared__ float s_inv[BM];
 
     const f16* __restrict__ A = (const f16*)g.A;
@@ -100,63 +101,57 @@ __global__ __launch_bounds__(256) void gemm_bf16_tile_kernel(GemmArgs g) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[b][i][j][r] = 0.f;
 
-    f16x8 ra[A_CH];
-    u32x4 rb[NB][B_CH];             // raw bf16 weights; widened to fp16 on the way into LDS
-    long long a_off[A_CH];
+    // Software pipeline: global loads run D k-steps ahead in a register ring (slot = step % D),
+    // LDS is double buffered, one barrier per k-step.  At step s: issue the loads of s + D,
+    // multiply out of LDS buffer s % 2, move the registers of s + 1 into the other buffer.
+    f16x8 ra[D][A_CH];
+    u32x4 rb[D][NB][B_CH];          // raw bf16 weights; widened to fp16 on the way into LDS
+    long long a_off[A_CH], b_off[B_CH];
 #pragma unroll
     for (int i = 0; i < A_CH; ++i) {
         const int c = tid + 256 * i, row = c >> 3, cc = c & 7;
         const int gm = min(m0 + row, M - 1);
         a_off[i] = (long long)(g.a_rows ? g.a_rows[gm] : gm) * K + cc * 8;
     }
-    auto load_global = [&](int k0) {
 #pragma unroll
-        for (int i = 0; i < A_CH; ++i) ra[i] = *(const f16x8*)(A + a_off[i] + k0);
+    for (int i = 0; i < B_CH; ++i) {
+        const int c = tid + 256 * i, row = c >> 3, cc = c & 7;
+        b_off[i] = (long long)min(n0 + row, N - 1) * K + cc * 8;
+    }
+    auto load_global = [&](int slot, int k0) {
+#pragma unroll
+        for (int i = 0; i < A_CH; ++i) ra[slot][i] = *(const f16x8*)(A + a_off[i] + k0);
 #pragma unroll
         for (int i = 0; i < B_CH; ++i) {
-            const int c = tid + 256 * i, row = c >> 3, cc = c & 7;
-            const int gn = min(n0 + row, N - 1);
-            rb[0][i] = *(const u32x4*)(W + (long long)gn * K + k0 + cc * 8);
-            if (NB == 2) rb[NB - 1][i] = *(const u32x4*)(W2 + (long long)gn * K + k0 + cc * 8);
+            rb[slot][0][i] = *(const u32x4*)(W + b_off[i] + k0);
+            if (NB == 2) rb[slot][NB - 1][i] = *(const u32x4*)(W2 + b_off[i] + k0);
         }
     };
-    auto store_lds = [&]() {
+    auto store_lds = [&](int slot, int buf) {
 #pragma unroll
         for (int i = 0; i < A_CH; ++i) {
             const int c = tid + 256 * i, row = c >> 3, cc = c & 7;
-            *(f16x8*)(sA + row * LS + cc * 8) = ra[i];
+            *(f16x8*)(sA[buf] + row * LS + cc * 8) = ra[slot][i];
         }
 #pragma unroll
         for (int i = 0; i < B_CH; ++i) {
             const int c = tid + 256 * i, row = c >> 3, cc = c & 7;
 #pragma unroll
-            for (int b = 0; b < NB; ++b) *(f16x8*)(sB[b] + row * LS + cc * 8) = bf16x8_to_f16x8(rb[b][i]);
+            for (int b = 0; b < NB; ++b) *(f16x8*)(sB[buf][b] + row * LS + cc * 8) = bf16x8_to_f16x8(rb[slot][b][i]);
         }
     };
-
-    load_global(0);
-    if (g.ssq) {                     // deferred RMSNorm: 1/rms of this block's rows
-        for (int r = wave; r < BM; r += 4) {
-            const int gm = min(m0 + r, M - 1);
-            const float inv = wave_inv_rms(g.ssq, g.a_rows ? g.a_rows[gm] : gm, g.nparts, g.d_norm, g.eps, lane);
-            if (lane == 0) s_inv[r] = inv;
-        }
-    }
-    for (int k0 = 0; k0 < K; k0 += BK) {
-        store_lds();
-        __syncthreads();
-        if (k0 + BK < K) load_global(k0 + BK);
+    auto multiply = [&](int buf) {
 #pragma unroll
         for (int kk = 0; kk < BK / 16; ++kk) {
             f16x8 fa[TM], fb[NB][TN];
 #pragma unroll
             for (int i = 0; i < TM; ++i)
-                fa[i] = *(const f16x8*)(sA + ((wm * TM + i) * 32 + lrow) * LS + kk * 16 + lg * 8);
+                fa[i] = *(const f16x8*)(sA[buf] + ((wm * TM + i) * 32 + lrow) * LS + kk * 16 + lg * 8);
 #pragma unroll
             for (int b = 0; b < NB; ++b)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
-                    fb[b][j] = *(const f16x8*)(sB[b] + ((wn * TN + j) * 32 + lrow) * LS + kk * 16 + lg * 8);
+                    fb[b][j] = *(const f16x8*)(sB[buf][b] + ((wn * TN + j) * 32 + lrow) * LS + kk * 16 + lg * 8);
 #pragma unroll
             for (int b = 0; b < NB; ++b)
 #pragma unroll
@@ -165,7 +160,45 @@ __global__ __launch_bounds__(256) void gemm_bf16_tile_kernel(GemmArgs g) {
                     for (int j = 0; j < TN; ++j)
                         acc[b][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[i], fb[b][j], acc[b][i][j], 0, 0, 0);
         }
-        __syncthreads();
+    };
+
+    const int nsteps = K / BK;
+#pragma unroll
+    for (int s = 0; s < D; ++s)
+        if (s < nsteps) load_global(s, s * BK);
+    if (g.ssq) {                     // deferred RMSNorm: 1/rms of this block's rows
+        for (int r = wave; r < BM; r += 4) {
+            const int gm = min(m0 + r, M - 1);
+            const float inv = wave_inv_rms(g.ssq, g.a_rows ? g.a_rows[gm] : gm, g.nparts, g.d_norm, g.eps, lane);
+            if (lane == 0) s_inv[r] = inv;
+        }
+    }
+    store_lds(0, 0);
+    __syncthreads();
+    // steady state: groups of D steps with every load and store unconditional (branch-free, so
+    // the loads of the next D steps stay in flight across the barriers)
+    int step0 = 0;
+    for (; step0 + 2 * D <= nsteps; step0 += D) {
+#pragma unroll
+        for (int u = 0; u < D; ++u) {                    // D is even: buffer = u % 2, slot = u
+            load_global(u, (step0 + u + D) * BK);
+            multiply(u & 1);
+            store_lds((u + 1) % D, (u + 1) & 1);
+            __syncthreads();
+        }
+    }
+    // drain: at most 2 D - 1 steps, loads only while there is something left to load
+    for (; step0 < nsteps; step0 += D) {
+#pragma unroll
+        for (int u = 0; u < D; ++u) {
+            const int step = step0 + u;
+            if (step < nsteps) {
+                if (step + D < nsteps) load_global(u, (step + D) * BK);
+                multiply(u & 1);
+                if (step + 1 < nsteps) store_lds((u + 1) % D, (u + 1) & 1);
+                __syncthreads();
+            }
+        }
     }
 
 #pragma unroll
