@@ -75,7 +75,7 @@ Layout make_layout(const ax_model_config& c) {
     const int G = c.n_q_heads / c.n_kv_heads;
     L.max_tiles = (int)((T * G + 31) / 32 + S);
     L.max_bt = (c.max_pos + 15) / 16;
-    L.desc_ints = 4 * T + 4 * S + S * (size_t)L.max_bt + 2 * (size_t)L.max_tiles + 16;
+    L.desc_ints = 5 * T + 4 * S + S * (size_t)L.max_bt + 8 * (size_t)L.max_tiles + 32;
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes); return at; };
     L.rope_cos = take((size_t)c.max_pos * (c.head_dim / 2) * 4);
@@ -163,10 +163,10 @@ struct ProfScope {                     // records a pair of events around one la
 // Key slices of the split attention: enough wavefronts to fill the chip (~SPLIT_ITEMS), each
 // with at least two 32-key steps, rounded down to a power of two so that the choice (a launch
 // dimension, hence part of a captured graph) changes only when the cache length doubles.
-int choose_splits(const ax_model* m, int items, int max_steps) {
+int choose_splits(const ax_model* m, int items, int nq, int max_steps) {
     int want = std::max(1, (SPLIT_ITEMS + items - 1) / items);
     want = std::min(want, std::max(1, max_steps / 2));
-    const size_t cap = std::max<size_t>(SPLIT_ITEMS, (size_t)m->lay.max_tiles * m->cfg.n_kv_heads) / (size_t)items;
+    const size_t cap = std::max<size_t>(SPLIT_ITEMS, (size_t)m->lay.max_tiles * m->cfg.n_kv_heads) / ((size_t)items * nq);
     want = std::min(want, std::max(1, (int)cap));
     int p2 = 1;
     while (p2 * 2 <= want) p2 *= 2;
@@ -176,9 +176,9 @@ int choose_splits(const ax_model* m, int items, int max_steps) {
 // Host half of a call: validation, KV reservation (all or nothing) and the descriptor, written
 // into a pinned staging slot.  Nothing is launched here.
 struct CallPlan {
-    int n = 0, n_rows = 0, n_out = 0, n_tiles = 0, bt_total = 0, max_steps = 1, out_mode = 0, slot = 0;
-    size_t o_tok = 0, o_pos = 0, o_seq = 0, o_out = 0, o_P = 0, o_T = 0, o_row0 = 0, o_bt = 0, o_tseq = 0,
-           o_tr0 = 0, o_tab = 0, ints = 0;
+    int n = 0, n_rows = 0, n_out = 0, n_tiles = 0, tile_nq = 1, bt_total = 0, max_steps = 1, out_mode = 0, slot = 0;
+    size_t o_tok = 0, o_pos = 0, o_seq = 0, o_slot = 0, o_out = 0, o_P = 0, o_T = 0, o_row0 = 0, o_bt = 0, o_tinfo = 0,
+           o_tab = 0, ints = 0;
     ax_pool* pool = nullptr;
     std::vector<std::pair<int32_t, int32_t>> cows;
 };
@@ -230,9 +230,14 @@ ax_status prepare_call(ax_model* m, int n, ax_kv* const* kvs, const int32_t* tok
     cp.n_rows = (int)n_rows;
     cp.out_mode = out_mode;
     cp.pool = pool;
+    // attention q tiles are grouped in pairs when every sequence's stacked rows fit one pair
+    // (verify steps): the pair shares its K/V loads
+    cp.tile_nq = 2;
+    for (int s = 0; s < n; ++s)
+        if (T_each[s] * G > 64) cp.tile_nq = 1;
     cp.n_tiles = cp.bt_total = 0;
     for (int s = 0; s < n; ++s) {
-        cp.n_tiles += (T_each[s] * G + 31) / 32;
+        cp.n_tiles += (T_each[s] * G + 32 * cp.tile_nq - 1) / (32 * cp.tile_nq);
         cp.bt_total += (int)ax::blocks_for(kvs[s]->seq.len + T_each[s], 16);
     }
     cp.n_out = out_mode == AX_OUT_NONE ? 0
@@ -240,9 +245,11 @@ ax_status prepare_call(ax_model* m, int n, ax_kv* const* kvs, const int32_t* tok
     size_t at = 0;
     auto region = [&](size_t ints) { size_t o = at; at += ints; return o; };
     cp.o_tok = region((size_t)n_rows); cp.o_pos = region((size_t)n_rows); cp.o_seq = region((size_t)n_rows);
+    cp.o_slot = region((size_t)n_rows);
     cp.o_out = region((size_t)std::max(cp.n_out, 1)); cp.o_P = region((size_t)n); cp.o_T = region((size_t)n);
-    cp.o_row0 = region((size_t)n); cp.o_bt = region((size_t)n); cp.o_tseq = region((size_t)cp.n_tiles);
-    cp.o_tr0 = region((size_t)cp.n_tiles);
+    cp.o_row0 = region((size_t)n); cp.o_bt = region((size_t)n);
+    at = (at + 7) / 8 * 8;                                                   // 32-byte aligned tile records
+    cp.o_tinfo = region((size_t)cp.n_tiles * 8);
     cp.o_tab = region((size_t)(graph_slot ? m->lay.max_bt : cp.bt_total));   // fixed extent inside a graph
     cp.ints = at;
     if (cp.ints > m->slot_ints || cp.bt_total > n * m->lay.max_bt)
@@ -275,15 +282,16 @@ ax_status prepare_call(ax_model* m, int n, ax_kv* const* kvs, const int32_t* tok
         d[cp.o_row0 + s] = row;
         d[cp.o_bt + s] = tab;
         for (int32_t b : kvs[s]->seq.blocks) d[cp.o_tab + tab++] = b;
-        for (int r0 = 0; r0 < T * G; r0 += 32) {
-            d[cp.o_tseq + tile] = s;
-            d[cp.o_tr0 + tile] = r0;
+        for (int r0 = 0; r0 < T * G; r0 += 32 * cp.tile_nq) {
+            int* ti = d + cp.o_tinfo + (size_t)tile * 8;
+            ti[0] = s; ti[1] = r0; ti[2] = P[(size_t)s]; ti[3] = T; ti[4] = row; ti[5] = d[cp.o_bt + s]; ti[6] = ti[7] = 0;
             ++tile;
         }
         for (int t = 0; t < T; ++t, ++row) {
             d[cp.o_tok + row] = tokens[row];
             d[cp.o_pos + row] = P[(size_t)s] + t;
             d[cp.o_seq + row] = s;
+            d[cp.o_slot + row] = kvs[s]->seq.blocks[(size_t)((P[(size_t)s] + t) >> 4)] * 16 + ((P[(size_t)s] + t) & 15);
             if (out_mode == AX_OUT_ALL_LOGITS || out_mode == AX_OUT_ALL_ARGMAX) d[cp.o_out + oi++] = row;
         }
         if (out_mode == AX_OUT_LAST_LOGITS || out_mode == AX_OUT_LAST_ARGMAX) d[cp.o_out + oi++] = row - 1;
@@ -305,11 +313,11 @@ ax_status enqueue_call(ax_model* m, const CallPlan& cp, void* out, hipStream_t s
     HIP_TRY(hipMemcpyAsync(dev_d, d, cp.ints * sizeof(int), hipMemcpyHostToDevice, stream));
 
     ax::StepView sv{};
-    sv.row_tok = dev_d + cp.o_tok;  sv.row_pos = dev_d + cp.o_pos;  sv.row_seq = dev_d + cp.o_seq;
+    sv.row_tok = dev_d + cp.o_tok;  sv.row_pos = dev_d + cp.o_pos;  sv.row_seq = dev_d + cp.o_seq; sv.row_slot = dev_d + cp.o_slot;
     sv.out_rows = dev_d + cp.o_out; sv.seq_P = dev_d + cp.o_P;      sv.seq_T = dev_d + cp.o_T;
-    sv.seq_row0 = dev_d + cp.o_row0; sv.seq_bt = dev_d + cp.o_bt;   sv.tile_seq = dev_d + cp.o_tseq;
-    sv.tile_r0 = dev_d + cp.o_tr0;  sv.bt = dev_d + cp.o_tab;
-    sv.n_rows = cp.n_rows; sv.n_seq = cp.n; sv.n_out = cp.n_out; sv.n_tiles = cp.n_tiles;
+    sv.seq_row0 = dev_d + cp.o_row0; sv.seq_bt = dev_d + cp.o_bt;   sv.tile_info = dev_d + cp.o_tinfo;
+    sv.bt = dev_d + cp.o_tab;
+    sv.n_rows = cp.n_rows; sv.n_seq = cp.n; sv.n_out = cp.n_out; sv.n_tiles = cp.n_tiles; sv.tile_nq = cp.tile_nq;
 
     const ax::DType dt = c.dtype == AX_F32 ? ax::F32 : ax::BF16;
     const ax::KVGeom& kg = cp.pool->geom;
@@ -377,7 +385,7 @@ ax_status enqueue_call(ax_model* m, const CallPlan& cp, void* out, hipStream_t s
                 normed(g);
                 g.W = m->wqkv[(size_t)l]; g.N = qkv_rows;
                 g.rope.kv = kg; g.rope.layer = l; g.rope.n_q_heads = c.n_q_heads; g.rope.q_out = qb;
-                g.rope.row_pos = sv.row_pos; g.rope.row_seq = sv.row_seq; g.rope.seq_bt = sv.seq_bt; g.rope.bt = sv.bt;
+                g.rope.row_pos = sv.row_pos; g.rope.row_slot = sv.row_slot;
                 g.rope.cos = (const float*)(ws + L.rope_cos); g.rope.sin = (const float*)(ws + L.rope_sin);
                 ProfScope ps(m, 0, stream);
                 ax::launch_gemm_bf16(ax::EPI_QKV, g, stream);
@@ -451,7 +459,7 @@ ax_status run_extend(ax_model* m, int n, ax_kv* const* kvs, const int32_t* token
     if (st != AX_OK) return st;
     const ax::DType dt = m->cfg.dtype == AX_F32 ? ax::F32 : ax::BF16;
     for (auto& cw : cp.cows) ax::launch_block_copy(dt, cp.pool->geom, m->cfg.n_layers, cw.first, cw.second, stream);
-    const int n_splits = choose_splits(m, cp.n_tiles * m->cfg.n_kv_heads, cp.max_steps);
+    const int n_splits = choose_splits(m, cp.n_tiles * m->cfg.n_kv_heads, cp.tile_nq, cp.max_steps);
     return enqueue_call(m, cp, out, stream, n_splits, verify_k, host_result, false);
 }
 
@@ -469,7 +477,7 @@ ax_status run_verify_graph(ax_model* m, ax_kv* kv, const int32_t* toks, int T, v
     if (st != AX_OK) return st;
     const ax::DType dt = m->cfg.dtype == AX_F32 ? ax::F32 : ax::BF16;
     for (auto& cw : cp.cows) ax::launch_block_copy(dt, cp.pool->geom, m->cfg.n_layers, cw.first, cw.second, stream);
-    const int n_splits = choose_splits(m, cp.n_tiles * m->cfg.n_kv_heads, cp.max_steps);
+    const int n_splits = choose_splits(m, cp.n_tiles * m->cfg.n_kv_heads, cp.tile_nq, cp.max_steps);
     const uint64_t key = ((uint64_t)(uint32_t)T << 32) | (uint32_t)n_splits;
     hipGraphExec_t exec = nullptr;
     for (auto& g : m->graphs)

@@ -104,7 +104,9 @@ __global__ __launch_bounds__(64) void attn_simple_kernel(const T* __restrict__ q
 }
 
 // ------------------------------------------------------------------------------ MFMA split kernel
-// One wavefront = one (q tile of 32 stacked rows, KV head, key slice).
+// One wavefront = one (group of NQ q tiles of 32 stacked rows, KV head, key slice).  With NQ > 1
+// the K and V operands of a 32-key step are loaded once and used for every q tile of the group:
+// a verify step (T = 1 + k rows, (1 + k) * G stacked rows) is then a single group per KV head.
 //
 // S^T = K * Q^T is computed so that the score tile comes out with lane <-> query row
 // (column l % 32) and registers <-> keys: register r of lane l is key (r/4)*8 + (l/32)*4 + r%4
@@ -114,146 +116,216 @@ __global__ __launch_bounds__(64) void attn_simple_kernel(const T* __restrict__ q
 // {4g..4g+3, 8+4g..8+4g+3} of the first 16-key block, registers 8..15 the same of the second
 // block (g = l/32).  V pages are token-minor ([head_dim][16]), so the matching A operand of a
 // lane (channel d) is two 8-byte loads from its channel's 16-token row.
-template <int HD>
-__global__ __launch_bounds__(64) void attn_split_kernel(const f16* __restrict__ q, KVGeom kv, int layer,
-                                                        const int* __restrict__ seq_P,
-                                                        const int* __restrict__ seq_T,
-                                                        const int* __restrict__ seq_row0,
-                                                        const int* __restrict__ seq_bt,
-                                                        const int* __restrict__ bt,
-                                                        const int* __restrict__ tile_seq,
-                                                        const int* __restrict__ tile_r0, int Hq,
-                                                        float* __restrict__ partials, int n_splits) {
+struct AttnArgs {
+    const f16* q;
+    f16* out;
+    KVGeom kv;
+    int layer, Hq, n_splits;
+    const int* tile_info;      // per q-tile group, 8 ints: seq, first stacked row, P, T, row0, block-table offset
+    const int* bt;
+    float* partials;
+};
+
+// Everything a step needs from memory is requested as early as possible, because at verify
+// sizes the kernel is a chain of dependent memory latencies, not a bandwidth problem: the tile
+// record is one 32-byte load, the block-table entries of the whole key slice are fetched by
+// one wavefront-wide load (and handed out with shuffles), and the K/V operands of step s + 1
+// are in flight while step s is multiplied.
+template <int HD, int NQ>
+__global__ __launch_bounds__(64) void attn_split_kernel(AttnArgs a) {
     constexpr int KQ = HD / 16;          // MFMA k-steps of the score product
     constexpr int DT = HD / 32;          // 32-channel tiles of the output
+    constexpr int PS = HD * 32 + 64;     // floats of one partial: O^T [HD][32], m[32], l[32]
     const int tile = blockIdx.x, hk = blockIdx.y, split = blockIdx.z;
     const int lane = threadIdx.x, ql = lane & 31, g = lane >> 5;
-    const int Hkv = kv.n_kv_heads, G = Hq / Hkv;
-    const int sq = tile_seq[tile], r0 = tile_r0[tile];
-    const int P = seq_P[sq], T = seq_T[sq], row0 = seq_row0[sq];
+    const int Hq = a.Hq, Hkv = a.kv.n_kv_heads, G = Hq / Hkv;
+    const int4 ti0 = *(const int4*)(a.tile_info + tile * 8), ti1 = *(const int4*)(a.tile_info + tile * 8 + 4);
+    const int r0 = ti0.y, P = ti0.z, T = ti0.w, row0 = ti1.x;
     const int n_stacked = T * G;
-    const int* tab = bt + seq_bt[sq];
-    const int kv_len = P + T;
+    const int* tab = a.bt + ti1.y;
+    const int kv_len = P + T, last_blk = (kv_len - 1) >> 4;
 
-    // keys this tile can see at all: up to the position of its last valid row
-    const int r_last = min(r0 + 31, n_stacked - 1);
+    // keys this group can see at all: up to the position of its last valid row
+    const int r_last = min(r0 + NQ * 32 - 1, n_stacked - 1);
     const int kv_end = P + r_last / G + 1;
     const int steps = (kv_end + 31) / 32;
-    const int per = (steps + n_splits - 1) / n_splits;
+    const int per = (steps + a.n_splits - 1) / a.n_splits;
     const int s_lo = split * per, s_hi = min(steps, s_lo + per);
 
-    // this lane's query row (clamped rows compute garbage that is never written)
-    const int rq = min(r0 + ql, n_stacked - 1);
-    const int tq = rq / G, gq = rq % G;
-    const int pos_q = P + tq;
-    const f16* qrow = q + ((long long)(row0 + tq) * Hq + hk * G + gq) * HD;
-    f16x8 qf[KQ];
+    // this lane's query rows (clamped rows compute garbage that is never written)
+    int pos_q[NQ];
+    f16x8 qf[NQ][KQ];
 #pragma unroll
-    for (int kk = 0; kk < KQ; ++kk) qf[kk] = *(const f16x8*)(qrow + kk * 16 + g * 8);
+    for (int t = 0; t < NQ; ++t) {
+        const int rq = min(r0 + t * 32 + ql, n_stacked - 1);
+        const int tq = rq / G, gq = rq % G;
+        pos_q[t] = P + tq;
+        const f16* qrow = a.q + ((long long)(row0 + tq) * Hq + hk * G + gq) * HD;
+#pragma unroll
+        for (int kk = 0; kk < KQ; ++kk) qf[t][kk] = *(const f16x8*)(qrow + kk * 16 + g * 8);
+    }
 
-    const f16* Kp = (const f16*)kv.base + kv.plane(layer, 0, hk);
-    const f16* Vp = (const f16*)kv.base + kv.plane(layer, 1, hk);
+    const f16* Kp = (const f16*)a.kv.base + a.kv.plane(a.layer, 0, hk);
+    const f16* Vp = (const f16*)a.kv.base + a.kv.plane(a.layer, 1, hk);
 
     const float c = 1.4426950408889634f / sqrtf((float)HD);   // log2(e) / sqrt(hd)
-    float m = -INFINITY, l = 0.f;
-    f32x16 o[DT];
+    float m[NQ], l[NQ];
+    f32x16 o[NQ][DT];
 #pragma unroll
-    for (int d = 0; d < DT; ++d)
+    for (int t = 0; t < NQ; ++t) {
+        m[t] = -INFINITY;
+        l[t] = 0.f;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) o[d][r] = 0.f;
+        for (int d = 0; d < DT; ++d)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) o[t][d][r] = 0.f;
+    }
 
-    for (int st = s_lo; st < s_hi; ++st) {
+    f16x8 kf[2][KQ];                     // K / V operands of the current and the next step
+    f16x4 vq[2][DT][4];
+    int tabv = 0;                        // block ids of steps [chunk, chunk + 32): lane i holds block 2*chunk + i
+    auto fetch = [&](int buf, int st, int chunk) {
         const int kv0 = st * 32;
-        // K rows: this lane supplies key kv0 + ql (clamped into the sequence)
         const int key = min(kv0 + ql, kv_len - 1);
-        const f16* krow = Kp + ((long long)tab[key >> 4] * 16 + (key & 15)) * HD + g * 8;
-        f32x16 s;
+        const int kblk = __shfl(tabv, min(key >> 4, last_blk) - 2 * chunk, 64);
+        const f16* krow = Kp + ((long long)kblk * 16 + (key & 15)) * HD + g * 8;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) s[r] = 0.f;
-#pragma unroll
-        for (int kk = 0; kk < KQ; ++kk) {
-            const f16x8 kf = *(const f16x8*)(krow + kk * 16);
-            s = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf, qf[kk], s, 0, 0, 0);
-        }
-        // V operands: channel (d*32 + ql) of blocks kv0/16 and kv0/16 + 1
-        const int b0 = tab[min(kv0 >> 4, (kv_len - 1) >> 4)];
-        const int b1 = tab[min((kv0 >> 4) + 1, (kv_len - 1) >> 4)];
-        f16x8 vf[DT][2];
+        for (int kk = 0; kk < KQ; ++kk) kf[buf][kk] = *(const f16x8*)(krow + kk * 16);
+        const int b0 = __shfl(tabv, min(kv0 >> 4, last_blk) - 2 * chunk, 64);
+        const int b1 = __shfl(tabv, min((kv0 >> 4) + 1, last_blk) - 2 * chunk, 64);
 #pragma unroll
         for (int d = 0; d < DT; ++d) {
             const f16* v0 = Vp + ((long long)b0 * HD + d * 32 + ql) * 16 + g * 4;
             const f16* v1 = Vp + ((long long)b1 * HD + d * 32 + ql) * 16 + g * 4;
-            const f16x4 a0 = *(const f16x4*)v0, a1 = *(const f16x4*)(v0 + 8);
-            const f16x4 c0 = *(const f16x4*)v1, c1 = *(const f16x4*)(v1 + 8);
-            vf[d][0] = (f16x8){a0[0], a0[1], a0[2], a0[3], a1[0], a1[1], a1[2], a1[3]};
-            vf[d][1] = (f16x8){c0[0], c0[1], c0[2], c0[3], c1[0], c1[1], c1[2], c1[3]};
+            vq[buf][d][0] = *(const f16x4*)v0;
+            vq[buf][d][1] = *(const f16x4*)(v0 + 8);
+            vq[buf][d][2] = *(const f16x4*)v1;
+            vq[buf][d][3] = *(const f16x4*)(v1 + 8);
         }
-        // causal mask + online softmax (base-2 exponentials)
-        float mx = -INFINITY;
+    };
+    auto process = [&](int buf, int st) {
+        const int kv0 = st * 32;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int kj = kv0 + (r >> 2) * 8 + g * 4 + (r & 3);
-            s[r] = (kj <= pos_q) ? s[r] * c : -INFINITY;
-            mx = fmaxf(mx, s[r]);
+        for (int t = 0; t < NQ; ++t) {
+            f32x16 s;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) s[r] = 0.f;
+#pragma unroll
+            for (int kk = 0; kk < KQ; ++kk) s = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf[buf][kk], qf[t][kk], s, 0, 0, 0);
+            // causal mask + online softmax (base-2 exponentials)
+            float mx = -INFINITY;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int kj = kv0 + (r >> 2) * 8 + g * 4 + (r & 3);
+                s[r] = (kj <= pos_q[t]) ? s[r] * c : -INFINITY;
+                mx = fmaxf(mx, s[r]);
+            }
+            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+            const float mn = fmaxf(m[t], mx);
+            const float mu = (mn == -INFINITY) ? 0.f : mn;        // row with nothing visible yet
+            const float alpha = exp2f(m[t] - mu);                 // m = -inf -> 0
+            float ps = 0.f;
+            f16x8 pb[2];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float p = exp2f(s[r] - mu);                 // masked -> 0
+                ps += p;
+                pb[r >> 3][r & 7] = (f16)p;
+            }
+            ps += __shfl_xor(ps, 32, 64);
+            l[t] = l[t] * alpha + ps;
+            m[t] = mn;
+#pragma unroll
+            for (int d = 0; d < DT; ++d) {
+                const f16x4 *v = vq[buf][d];
+                const f16x8 va = {v[0][0], v[0][1], v[0][2], v[0][3], v[1][0], v[1][1], v[1][2], v[1][3]};
+                const f16x8 vb = {v[2][0], v[2][1], v[2][2], v[2][3], v[3][0], v[3][1], v[3][2], v[3][3]};
+#pragma unroll
+                for (int r = 0; r < 16; ++r) o[t][d][r] *= alpha;
+                o[t][d] = __builtin_amdgcn_mfma_f32_32x32x16_f16(va, pb[0], o[t][d], 0, 0, 0);
+                o[t][d] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vb, pb[1], o[t][d], 0, 0, 0);
+            }
         }
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float mn = fmaxf(m, mx);
-        const float mu = (mn == -INFINITY) ? 0.f : mn;        // row with nothing visible yet
-        const float alpha = exp2f(m - mu);                    // m = -inf -> 0
-        float ps = 0.f;
-        f16x8 pb[2];
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const float p = exp2f(s[r] - mu);                 // masked -> 0
-            ps += p;
-            pb[r >> 3][r & 7] = (f16)p;
-        }
-        ps += __shfl_xor(ps, 32, 64);
-        l = l * alpha + ps;
-        m = mn;
-#pragma unroll
-        for (int d = 0; d < DT; ++d) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) o[d][r] *= alpha;
-            o[d] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf[d][0], pb[0], o[d], 0, 0, 0);
-            o[d] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf[d][1], pb[1], o[d], 0, 0, 0);
+    };
+
+    for (int chunk = s_lo; chunk < s_hi; chunk += 32) {          // 32 steps = 64 blocks = one table load
+        tabv = tab[min(2 * chunk + lane, last_blk)];
+        const int c_hi = min(s_hi, chunk + 32);
+        fetch(0, chunk, chunk);
+        for (int st = chunk; st < c_hi; st += 2) {
+            if (st + 1 < c_hi) fetch(1, st + 1, chunk);
+            process(0, st);
+            if (st + 1 < c_hi) {
+                if (st + 2 < c_hi) fetch(0, st + 2, chunk);
+                process(1, st + 1);
+            }
         }
     }
 
-    // partial layout per (tile, hk, split): O^T [HD][32] floats, then m[32], l[32] (base-2 domain)
-    float* part = partials + ((long long)(tile * Hkv + hk) * n_splits + split) * (HD * 32 + 64);
+    // partials of the group: NQ consecutive (O^T, m, l) records per (group, KV head, slice);
+    // rows past the end of the sequence are not written (and never read)
 #pragma unroll
-    for (int d = 0; d < DT; ++d)
+    for (int t = 0; t < NQ; ++t) {
+        if (r0 + t * 32 + ql >= n_stacked) continue;
+        float* part = a.partials + (((long long)(tile * Hkv + hk) * a.n_splits + split) * NQ + t) * PS;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int ch = d * 32 + (r >> 2) * 8 + g * 4 + (r & 3);
-            part[ch * 32 + ql] = o[d][r];
+        for (int d = 0; d < DT; ++d)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int ch = d * 32 + (r >> 2) * 8 + g * 4 + (r & 3);
+                part[ch * 32 + ql] = o[t][d][r];
+            }
+        if (g == 0) {
+            part[HD * 32 + ql] = m[t];
+            part[HD * 32 + 32 + ql] = l[t];
         }
-    if (g == 0) {
-        part[HD * 32 + ql] = m;
-        part[HD * 32 + 32 + ql] = l;
     }
 }
 
-// Merges the key slices of one (tile, KV head).  grid (n_tiles * Hkv, HD / 4), 256 threads =
-// 32 query rows x 8 slice groups; a block produces 4 output channels.  Each thread folds the
-// slices s = sg, sg + 8, ... (weights 2^(m_s - M)), the 8 groups meet in LDS.
-template <int HD>
-__global__ __launch_bounds__(256) void attn_combine_kernel(const float* __restrict__ partials,
-                                                           f16* __restrict__ out,
-                                                           const int* __restrict__ seq_T,
-                                                           const int* __restrict__ seq_row0,
-                                                           const int* __restrict__ tile_seq,
-                                                           const int* __restrict__ tile_r0, int Hq,
-                                                           int Hkv, int n_splits) {
-    constexpr int PS = HD * 32 + 64;                 // floats per partial
+// Merges the key slices of one q tile.  grid (n_groups * Hkv * NQ, HD / 4), 256 threads =
+// 32 query rows x 8 slice groups; a block produces 4 output channels.  A thread loads the
+// (m, l, 4 channels) of its slices s = sg, sg + 8, ... in one go (up to 16 slices in registers),
+// the row maximum and then the weighted sums meet in LDS.
+template <int HD, int NQ>
+__global__ __launch_bounds__(256) void attn_combine_kernel(AttnArgs a) {
+    constexpr int PS = HD * 32 + 64;
+    constexpr int MAXS = 16;                                   // slices per thread held in registers
     __shared__ float red[8][6][32];
-    const int tile = blockIdx.x / Hkv, hk = blockIdx.x % Hkv, ch0 = blockIdx.y * 4;
+    const int Hkv = a.kv.n_kv_heads, G = a.Hq / Hkv;
+    const int t = blockIdx.x % NQ, hk = (blockIdx.x / NQ) % Hkv, tile = blockIdx.x / (NQ * Hkv);
+    const int ch0 = blockIdx.y * 4;
     const int ql = threadIdx.x & 31, sg = threadIdx.x >> 5;
-    const float* base = partials + (long long)(tile * Hkv + hk) * n_splits * PS;
+    const int4 ti0 = *(const int4*)(a.tile_info + tile * 8);
+    const int row0 = a.tile_info[tile * 8 + 4];
+    const int r_first = ti0.y + t * 32, n_stacked = ti0.w * G;
+    if (r_first >= n_stacked) return;                          // whole q tile past the end (block-uniform)
+    const int r = r_first + ql;
+    const bool valid = r < n_stacked;
+    const int n_splits = a.n_splits;
+    const float* base = a.partials + ((long long)(tile * Hkv + hk) * n_splits * NQ + t) * PS;
+    const long long stride = (long long)NQ * PS;               // between slices
 
+    float mv[MAXS], lv[MAXS], ov[MAXS][4];
     float mloc = -INFINITY;
-    for (int s = sg; s < n_splits; s += 8) mloc = fmaxf(mloc, base[(long long)s * PS + HD * 32 + ql]);
+#pragma unroll
+    for (int i = 0; i < MAXS; ++i) {
+        const int s = sg + 8 * i;
+        mv[i] = -INFINITY;
+        lv[i] = 0.f;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) ov[i][c] = 0.f;
+        if (valid && s < n_splits) {
+            const float* p = base + s * stride;
+            mv[i] = p[HD * 32 + ql];
+            lv[i] = p[HD * 32 + 32 + ql];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) ov[i][c] = p[(ch0 + c) * 32 + ql];
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < MAXS; ++i) mloc = fmaxf(mloc, mv[i]);
+    if (valid)                                                 // more than 128 slices: the rest from memory
+        for (int s = sg + 8 * MAXS; s < n_splits; s += 8) mloc = fmaxf(mloc, base[s * stride + HD * 32 + ql]);
     red[sg][0][ql] = mloc;
     __syncthreads();
     float M = red[0][0][ql];
@@ -262,29 +334,41 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(const float* __restri
     __syncthreads();
 
     float l = 0.f, acc[4] = {0.f, 0.f, 0.f, 0.f};
-    for (int s = sg; s < n_splits; s += 8) {
-        const float* p = base + (long long)s * PS;
-        const float w = exp2f(p[HD * 32 + ql] - M);
-        l += w * p[HD * 32 + 32 + ql];
 #pragma unroll
-        for (int c = 0; c < 4; ++c) acc[c] += w * p[(ch0 + c) * 32 + ql];
+    for (int i = 0; i < MAXS; ++i) {
+        const float w = exp2f(mv[i] - M);                      // absent slices: 2^-inf = 0
+        l += w * lv[i];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) acc[c] += w * ov[i][c];
     }
+    if (valid)
+        for (int s = sg + 8 * MAXS; s < n_splits; s += 8) {
+            const float* p = base + s * stride;
+            const float w = exp2f(p[HD * 32 + ql] - M);
+            l += w * p[HD * 32 + 32 + ql];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) acc[c] += w * p[(ch0 + c) * 32 + ql];
+        }
     red[sg][1][ql] = l;
 #pragma unroll
     for (int c = 0; c < 4; ++c) red[sg][2 + c][ql] = acc[c];
     __syncthreads();
-    if (sg >= 4) return;                             // 128 threads finish: (channel sg, row ql)
-    const int G = Hq / Hkv;
-    const int sq = tile_seq[tile], r = tile_r0[tile] + ql;
-    if (r >= seq_T[sq] * G) return;
+    if (sg >= 4 || !valid) return;                   // 128 threads finish: (channel sg, row ql)
     float L = 0.f, o = 0.f;
 #pragma unroll
     for (int i = 0; i < 8; ++i) { L += red[i][1][ql]; o += red[i][2 + sg][ql]; }
-    out[((long long)(seq_row0[sq] + r / G) * Hq + hk * G + r % G) * HD + ch0 + sg] = (f16)(o / L);
+    a.out[((long long)(row0 + r / G) * a.Hq + hk * G + r % G) * HD + ch0 + sg] = (f16)(o / L);
 }
 
 size_t attention_partial_floats(int n_tiles, int n_kv_heads, int head_dim, int n_splits) {
     return (size_t)n_tiles * n_kv_heads * n_splits * ((size_t)head_dim * 32 + 64);
+}
+
+template <int HD, int NQ>
+static void launch_attn_mfma(const AttnArgs& a, int n_groups, hipStream_t s) {
+    dim3 grid(n_groups, a.kv.n_kv_heads, a.n_splits), cgrid(n_groups * a.kv.n_kv_heads * NQ, HD / 4);
+    attn_split_kernel<HD, NQ><<<grid, 64, 0, s>>>(a);
+    attn_combine_kernel<HD, NQ><<<cgrid, 256, 0, s>>>(a);
 }
 
 void launch_attention(DType dt, const void* q, void* out, KVGeom kv, int layer, const StepView& sv,
@@ -296,21 +380,14 @@ void launch_attention(DType dt, const void* q, void* out, KVGeom kv, int layer, 
                                                            n_q_heads);
         return;
     }
-    dim3 grid(sv.n_tiles, kv.n_kv_heads, n_splits), cgrid(sv.n_tiles * kv.n_kv_heads, kv.head_dim / 4);
-    if (kv.head_dim == 64) {
-        attn_split_kernel<64><<<grid, 64, 0, s>>>((const f16*)q, kv, layer, sv.seq_P, sv.seq_T,
-                                                  sv.seq_row0, sv.seq_bt, sv.bt, sv.tile_seq,
-                                                  sv.tile_r0, n_q_heads, partials, n_splits);
-        attn_combine_kernel<64><<<cgrid, 256, 0, s>>>(partials, (f16*)out, sv.seq_T, sv.seq_row0,
-                                                      sv.tile_seq, sv.tile_r0, n_q_heads,
-                                                      kv.n_kv_heads, n_splits);
+    AttnArgs a{};
+    a.q = (const f16*)q; a.out = (f16*)out; a.kv = kv; a.layer = layer; a.Hq = n_q_heads; a.n_splits = n_splits;
+    a.tile_info = sv.tile_info; a.bt = sv.bt; a.partials = partials;
+    const int hd = kv.head_dim;
+    if (sv.tile_nq == 2) {
+        if (hd == 64) launch_attn_mfma<64, 2>(a, sv.n_tiles, s); else launch_attn_mfma<128, 2>(a, sv.n_tiles, s);
     } else {
-        attn_split_kernel<128><<<grid, 64, 0, s>>>((const f16*)q, kv, layer, sv.seq_P, sv.seq_T,
-                                                   sv.seq_row0, sv.seq_bt, sv.bt, sv.tile_seq,
-                                                   sv.tile_r0, n_q_heads, partials, n_splits);
-        attn_combine_kernel<128><<<cgrid, 256, 0, s>>>(partials, (f16*)out, sv.seq_T, sv.seq_row0,
-                                                       sv.tile_seq, sv.tile_r0, n_q_heads,
-                                                       kv.n_kv_heads, n_splits);
+        if (hd == 64) launch_attn_mfma<64, 1>(a, sv.n_tiles, s); else launch_attn_mfma<128, 1>(a, sv.n_tiles, s);
     }
 }
 

@@ -21,6 +21,9 @@
 // Epilogues: fp32 store (optionally rms-scaled), residual add (+ norm preparation), SwiGLU
 // (two weight matrices share the A operand), and QKV (rms scale, rotary embedding, q to the
 // activation buffer, k and v straight into the KV pages).
+#include <cstdlib>
+#include <type_traits>
+
 #include "kernels.h"
 
 namespace ax {
@@ -255,8 +258,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_tile_kernel(GemmArgs g) {
                     if (head < Hq) {
                         dst = (f16*)ro.q_out + ((long long)m * Hq + head) * hd;
                     } else {
-                        const int blk = ro.bt[ro.seq_bt[ro.row_seq[m]] + (pos >> 4)];
-                        dst = pool + ro.kv.plane(ro.layer, 0, head - Hq) + ((long long)blk * 16 + (pos & 15)) * hd;
+                        dst = pool + ro.kv.plane(ro.layer, 0, head - Hq) + (long long)ro.row_slot[m] * hd;
                     }
 #pragma unroll
                     for (int j = 0; j < TN / 2; ++j) {
@@ -267,8 +269,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_tile_kernel(GemmArgs g) {
                         dst[c + hd / 2] = (f16)(b * cs + a * sn);
                     }
                 } else {
-                    const int blk = ro.bt[ro.seq_bt[ro.row_seq[m]] + (pos >> 4)];
-                    f16* dst = pool + ro.kv.plane(ro.layer, 1, head - Hq - Hkv) + (long long)blk * 16 * hd + (pos & 15);
+                    const int slot = ro.row_slot[m];
+                    f16* dst = pool + ro.kv.plane(ro.layer, 1, head - Hq - Hkv) + (long long)(slot >> 4) * 16 * hd + (slot & 15);
 #pragma unroll
                     for (int j = 0; j < TN; ++j) dst[(long long)(j * 32 + lrow) * 16] = (f16)(acc[0][i][j][r] * inv);
                 }
@@ -287,7 +289,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_tile_kernel(GemmArgs g) {
 // 0..7 are channels j0..j0+7, local columns 8..15 are channels hd/2 + j0 .. +7, so the partner
 // of a lane's value lives in lane ^ 32.
 template <int EPI, int MT, int NW>
-__global__ __launch_bounds__(64 * NW) void gemm_bf16_skinny_kernel(GemmArgs g) {
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(1, NW >= 8 ? 4 : 8)))
+void gemm_bf16_skinny_kernel(GemmArgs g) {
     constexpr int NB = EPI == EPI_SWIGLU ? 2 : 1;
     __shared__ __attribute__((aligned(16))) f32x4 red[NW][NB][MT][64];
     __shared__ float s_inv[MT * 16];
@@ -326,21 +329,51 @@ __global__ __launch_bounds__(64 * NW) void gemm_bf16_skinny_kernel(GemmArgs g) {
 #pragma unroll
         for (int t = 0; t < MT; ++t) acc[b][t] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-    int k = kbeg;
-    for (; k + 128 <= kend; k += 128) {           // 4 MFMA k-steps per trip: 4+ loads in flight
-        u32x4 rw[NB][4];
-        f16x8 fx[MT][4];
+    // Epilogue operands that do not depend on the product are requested now, by the wavefront
+    // that will run the epilogue: at these sizes a kernel is a chain of memory latencies, and
+    // anything loaded after the K loop would add a full round trip to it.
+    f32x4 pre_x[MT], pre_cs[MT], pre_sn[MT];
+    float pre_g[4] = {0.f, 0.f, 0.f, 0.f};
+    int pre_pos[MT], pre_slot[MT];
+    if (wave == 0) {
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int t = 0; t < MT; ++t) {
+            const int m = min(t * 16 + lr, M - 1);
+            if (EPI == EPI_RESIDUAL) {
+                pre_x[t] = *(const f32x4*)(g.Cf + (long long)m * N + min(n0 + lg * 4, N - 4));
+            } else if (EPI == EPI_QKV) {
+                const int hd = g.rope.kv.head_dim;
+                pre_pos[t] = g.rope.row_pos[m];
+                pre_slot[t] = g.rope.row_slot[m];
+                const long long ao = (long long)pre_pos[t] * (hd / 2) + q_j0 + (lg & 1) * 4;
+                pre_cs[t] = *(const f32x4*)(g.rope.cos + ao);
+                pre_sn[t] = *(const f32x4*)(g.rope.sin + ao);
+            }
+        }
+        if (EPI == EPI_RESIDUAL && g.gain_next) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) pre_g[r] = (float)((const bf16*)g.gain_next)[min(n0 + lg * 4 + r, N - 1)];
+        }
+    }
+
+    // U MFMA k-steps (32 each) per trip: all U weight loads (and the matching activation loads)
+    // are issued before the first product, so a wavefront keeps U KB of weights in flight.
+    int k = kbeg;
+    auto trip = [&](auto u_tag) {
+        constexpr int U = decltype(u_tag)::value;
+        u32x4 rw[NB][U];
+        f16x8 fx[MT][U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
             rw[0][u] = *(const u32x4*)(wp + k + 32 * u);
             if (NB == 2) rw[NB - 1][u] = *(const u32x4*)(wp2 + k + 32 * u);
         }
 #pragma unroll
         for (int t = 0; t < MT; ++t)
 #pragma unroll
-            for (int u = 0; u < 4; ++u) fx[t][u] = *(const f16x8*)(xp[t] + k + 32 * u);
+            for (int u = 0; u < U; ++u) fx[t][u] = *(const f16x8*)(xp[t] + k + 32 * u);
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
+        for (int u = 0; u < U; ++u)
 #pragma unroll
             for (int b = 0; b < NB; ++b) {
                 const f16x8 fw = bf16x8_to_f16x8(rw[b][u]);
@@ -348,7 +381,10 @@ __global__ __launch_bounds__(64 * NW) void gemm_bf16_skinny_kernel(GemmArgs g) {
                 for (int t = 0; t < MT; ++t)
                     acc[b][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fw, fx[t][u], acc[b][t], 0, 0, 0);
             }
-    }
+    };
+    if constexpr (MT <= 2 && NW <= 4)      // long K slices only: 8 KB of weights in flight per wavefront
+        for (; k + 256 <= kend; k += 256) trip(std::integral_constant<int, 8>{});
+    for (; k + 128 <= kend; k += 128) trip(std::integral_constant<int, 4>{});
     for (; k < kend; k += 32) {
 #pragma unroll
         for (int b = 0; b < NB; ++b) {
@@ -400,14 +436,13 @@ __global__ __launch_bounds__(64 * NW) void gemm_bf16_skinny_kernel(GemmArgs g) {
         } else if (EPI == EPI_RESIDUAL) {
             float ss = 0.f;
             if (mok && n < N) {
-                f32x4* c = (f32x4*)(g.Cf + o);
-                const f32x4 xn = *c + sum[0];
-                *c = xn;
+                const f32x4 xn = pre_x[t] + sum[0];
+                *(f32x4*)(g.Cf + o) = xn;
                 if (g.gain_next) {
                     f16x4 h;
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
-                        h[r] = (f16)(xn[r] * (float)((const bf16*)g.gain_next)[n + r]);
+                        h[r] = (f16)(xn[r] * pre_g[r]);
                         ss += xn[r] * xn[r];
                     }
                     *(f16x4*)((f16*)g.C16 + o) = h;
@@ -422,16 +457,13 @@ __global__ __launch_bounds__(64 * NW) void gemm_bf16_skinny_kernel(GemmArgs g) {
             const RopeArgs& ro = g.rope;
             const int Hq = ro.n_q_heads, Hkv = ro.kv.n_kv_heads, hd = ro.kv.head_dim;
             const int mm = min(m, M - 1);
-            const int pos = ro.row_pos[mm];
             f16* pool = (f16*)ro.kv.base;
             const int chan = (lg < 2 ? q_j0 + lg * 4 : hd / 2 + q_j0 + (lg - 2) * 4);   // first of 4 channels
             f32x4 own = sum[0] * inv, other;
 #pragma unroll
             for (int r = 0; r < 4; ++r) other[r] = __shfl_xor(own[r], 32, 64);
             if (q_head < Hq + Hkv) {
-                const int jj = q_j0 + (lg & 1) * 4;                                     // angle index of r = 0
-                const float* cs = ro.cos + (long long)pos * (hd / 2) + jj;
-                const float* sn = ro.sin + (long long)pos * (hd / 2) + jj;
+                const f32x4 cs = pre_cs[t], sn = pre_sn[t];      // angles q_j0 + (lg & 1) * 4 + r at the row's position
                 f16x4 h;
 #pragma unroll
                 for (int r = 0; r < 4; ++r)
@@ -441,13 +473,11 @@ __global__ __launch_bounds__(64 * NW) void gemm_bf16_skinny_kernel(GemmArgs g) {
                 if (q_head < Hq) {
                     dst = (f16*)ro.q_out + ((long long)mm * Hq + q_head) * hd;
                 } else {
-                    const int blk = ro.bt[ro.seq_bt[ro.row_seq[mm]] + (pos >> 4)];
-                    dst = pool + ro.kv.plane(ro.layer, 0, q_head - Hq) + ((long long)blk * 16 + (pos & 15)) * hd;
+                    dst = pool + ro.kv.plane(ro.layer, 0, q_head - Hq) + (long long)pre_slot[t] * hd;
                 }
                 if (mok) *(f16x4*)(dst + chan) = h;
             } else if (mok) {
-                const int blk = ro.bt[ro.seq_bt[ro.row_seq[mm]] + (pos >> 4)];
-                f16* dst = pool + ro.kv.plane(ro.layer, 1, q_head - Hq - Hkv) + (long long)blk * 16 * hd + (pos & 15);
+                f16* dst = pool + ro.kv.plane(ro.layer, 1, q_head - Hq - Hkv) + (long long)(pre_slot[t] >> 4) * 16 * hd + (pre_slot[t] & 15);
 #pragma unroll
                 for (int r = 0; r < 4; ++r) dst[(long long)(chan + r) * 16] = (f16)own[r];
             }
@@ -465,6 +495,12 @@ static void launch_skinny_nw(const GemmArgs& g, int nw, hipStream_t s) {
     else gemm_bf16_skinny_kernel<EPI, MT, 4><<<grid, 256, 0, s>>>(g);
 }
 
+static int env_int(const char* name, int dflt) {
+    const char* v = std::getenv(name);
+    return v && *v ? std::atoi(v) : dflt;
+}
+static const int kForceNW = env_int("AX_SKINNY_NW", 0);   // experiment knob: wavefronts per block, 0 = automatic
+
 template <int EPI>
 static void launch_bf16(const GemmArgs& g, hipStream_t s) {
     const int M = g.M, N = g.N, K = g.K;
@@ -474,6 +510,7 @@ static void launch_bf16(const GemmArgs& g, hipStream_t s) {
         const long long tiles = (N + 15) / 16;
         int nw = 1;
         while (nw < 16 && tiles * nw < 2048 && K % (nw * 2 * 32) == 0 && K / (nw * 2) >= 128) nw *= 2;
+        if (kForceNW && K % (kForceNW * 32) == 0) nw = kForceNW;
         if (EPI == EPI_SWIGLU && nw == 16) nw = 8;        // LDS reduction buffer stays <= 64 KB
         if (M <= 16) launch_skinny_nw<EPI, 1>(g, nw, s);
         else if (M <= 32) launch_skinny_nw<EPI, 2>(g, nw, s);

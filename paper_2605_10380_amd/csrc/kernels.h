@@ -28,15 +28,17 @@ struct StepView {
     const int* row_tok;     // [n_rows] token id
     const int* row_pos;     // [n_rows] absolute position
     const int* row_seq;     // [n_rows] sequence index within the call
+    const int* row_slot;    // [n_rows] KV slot the row is written to: block id * 16 + position % 16
     const int* seq_P;       // [n_seq] cached length before the call
     const int* seq_T;       // [n_seq] new rows
     const int* seq_row0;    // [n_seq] first row
     const int* seq_bt;      // [n_seq] offset of the sequence's block table inside bt
     const int* bt;          // concatenated block tables
     const int* out_rows;    // [n_out] rows that go through the LM head
-    const int* tile_seq;    // [n_tiles] attention q-tiles over stacked rows (t, g)
-    const int* tile_r0;     // [n_tiles] first stacked row of the tile
-    int n_rows, n_seq, n_out, n_tiles;
+    const int* tile_info;   // [n_tiles][8] attention q-tile groups over stacked rows (t, g): sequence,
+                            // first stacked row, P, T, first row of the sequence, block-table offset, 0, 0
+                            // (a group = tile_nq tiles of 32 rows; 32-byte aligned records)
+    int n_rows, n_seq, n_out, n_tiles, tile_nq;
 };
 
 enum Epilogue { EPI_STORE_F32 = 0, EPI_RESIDUAL = 1, EPI_SWIGLU = 2, EPI_QKV = 3 };
@@ -46,7 +48,8 @@ struct RopeArgs {
     KVGeom kv;
     int layer, n_q_heads;
     void* q_out;                      // fp16 [n_rows, Hq, hd]
-    const int *row_pos, *row_seq, *seq_bt, *bt;
+    const int *row_pos;               // [n_rows] absolute position
+    const int *row_slot;              // [n_rows] KV slot of the row: block id * 16 + position % 16
     const float *cos, *sin;           // [max_pos][hd/2]
 };
 
@@ -96,7 +99,7 @@ void launch_rope_kv(DType dt, const float* qkv, void* q_out, KVGeom kv, int laye
 void launch_attention(DType dt, const void* q, void* out, KVGeom kv, int layer,
                       const StepView& sv, int n_q_heads, float* partials, int n_splits,
                       hipStream_t s);
-// Floats of `partials` launch_attention needs for n_tiles tiles and n_splits splits.
+// Floats of `partials` launch_attention needs for n_tiles q tiles (of 32 rows) and n_splits splits.
 size_t attention_partial_floats(int n_tiles, int n_kv_heads, int head_dim, int n_splits);
 // out[r] = argmax of logits[r, 0..V), lowest index on ties.  scratch: 2*rows*ARGMAX_PARTS ints.
 constexpr int ARGMAX_PARTS = 64;
