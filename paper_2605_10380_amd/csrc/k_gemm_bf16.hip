@@ -58,8 +58,12 @@ __device__ __forceinline__ f16x8 bf16x8_to_f16x8(u32x4 raw) {
 }
 __device__ __forceinline__ f16x8 load_w(const bf16* p) { return bf16x8_to_f16x8(*(const u32x4*)p); }
 
-// 1 / rms of A-row `row` from the column-block partial sums of x^2 its producer left behind.
-// Called by a whole wavefront (lanes stride over the partials); every lane gets the result.
+// 1 / rms of A rows from the column-block partial sums of x^2 their producer left behind.
+// Block-wide: 1 / rms of `rows` A-rows into s_inv[0..rows).  Half a wavefront (32 lanes)
+// owns a row; the partial sums of all of a thread's rows are requested before anything is
+// reduced, so the whole table costs one memory round trip instead of one per row.
+// The caller synchronises before reading s_inv.
+// One row by one wavefront (lanes stride over the partials); every lane gets the result.
 __device__ __forceinline__ float wave_inv_rms(const float* __restrict__ ssq, int row, int nparts,
                                               int d_norm, float eps, int lane) {
     float v = 0.f;
@@ -67,6 +71,39 @@ __device__ __forceinline__ float wave_inv_rms(const float* __restrict__ ssq, int
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
     return 1.0f / sqrtf(v / (float)d_norm + eps);
+}
+
+constexpr int INV_BATCH = 8;                           // rows per thread whose loads are in flight together
+__device__ __forceinline__ void inv_rms_load(const GemmArgs& g, int first_row, int rows, int base, float (&v)[INV_BATCH]) {
+    const int hw = threadIdx.x >> 5, hl = threadIdx.x & 31, nhw = blockDim.x >> 5;
+#pragma unroll
+    for (int p = 0; p < INV_BATCH; ++p) {
+        const int r = base + p * nhw + hw;
+        v[p] = 0.f;
+        if (r < rows) {
+            const int gm = min(first_row + r, g.M - 1);
+            const float* src = g.ssq + (long long)(g.a_rows ? g.a_rows[gm] : gm) * g.nparts;
+            for (int q = hl; q < g.nparts; q += 32) v[p] += src[q];
+        }
+    }
+}
+__device__ __forceinline__ void inv_rms_finish(const GemmArgs& g, int rows, int base, float (&v)[INV_BATCH], float* s_inv) {
+    const int hw = threadIdx.x >> 5, hl = threadIdx.x & 31, nhw = blockDim.x >> 5;
+#pragma unroll
+    for (int p = 0; p < INV_BATCH; ++p) {
+#pragma unroll
+        for (int o = 16; o > 0; o >>= 1) v[p] += __shfl_xor(v[p], o, 64);
+        const int r = base + p * nhw + hw;
+        if (hl == 0 && r < rows) s_inv[r] = 1.0f / sqrtf(v[p] / (float)g.d_norm + g.eps);
+    }
+}
+__device__ __forceinline__ void block_inv_rms(const GemmArgs& g, int first_row, int rows, float* s_inv) {
+    const int nhw = blockDim.x >> 5;
+    for (int base = 0; base < rows; base += INV_BATCH * nhw) {
+        float v[INV_BATCH];
+        inv_rms_load(g, first_row, rows, base, v);
+        inv_rms_finish(g, rows, base, v, s_inv);
+    }
 }
 
 // ------------------------------------------------------------------------------ tile kernel
@@ -169,13 +206,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_tile_kernel(GemmArgs g) {
 #pragma unroll
     for (int s = 0; s < D; ++s)
         if (s < nsteps) load_global(s, s * BK);
-    if (g.ssq) {                     // deferred RMSNorm: 1/rms of this block's rows
-        for (int r = wave; r < BM; r += 4) {
-            const int gm = min(m0 + r, M - 1);
-            const float inv = wave_inv_rms(g.ssq, g.a_rows ? g.a_rows[gm] : gm, g.nparts, g.d_norm, g.eps, lane);
-            if (lane == 0) s_inv[r] = inv;
-        }
-    }
+    if (g.ssq) block_inv_rms(g, m0, BM, s_inv);   // deferred RMSNorm: 1/rms of this block's rows
     store_lds(0, 0);
     __syncthreads();
     // steady state: groups of D steps with every load and store unconditional (branch-free, so
@@ -204,39 +235,70 @@ __global__ __launch_bounds__(256) void gemm_bf16_tile_kernel(GemmArgs g) {
         }
     }
 
+    // Epilogues.  Each one first requests everything it needs from memory for all of the
+    // thread's 16 * TM * TN outputs and only then computes and stores: stores and loads through
+    // the same pointers would otherwise be kept in program order, one round trip per element.
+    auto row_of = [&](int i, int r) { return (wm * TM + i) * 32 + (r >> 2) * 8 + lg * 4 + (r & 3); };
+    auto col_of = [&](int j) { return n0 + (wn * TN + j) * 32 + lrow; };
+    float inv[TM][16];
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int ml = (wm * TM + i) * 32 + (r >> 2) * 8 + lg * 4 + (r & 3);
-            const int m = m0 + ml;
-            const bool mok = m < M;
-            const float inv = g.ssq ? s_inv[ml] : 1.0f;
-            if (EPI == EPI_STORE_F32) {
+        for (int r = 0; r < 16; ++r) inv[i][r] = g.ssq ? s_inv[row_of(i, r)] : 1.0f;
+
+    if constexpr (EPI == EPI_STORE_F32) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
 #pragma unroll
                 for (int j = 0; j < TN; ++j) {
-                    const int n = n0 + (wn * TN + j) * 32 + lrow;
-                    if (mok && n < N) g.Cf[(long long)m * N + n] = acc[0][i][j][r] * inv;
+                    const int m = m0 + row_of(i, r), n = col_of(j);
+                    if (m < M && n < N) g.Cf[(long long)m * N + n] = acc[0][i][j][r] * inv[i][r];
                 }
-            } else if (EPI == EPI_SWIGLU) {
+    } else if constexpr (EPI == EPI_SWIGLU) {
+        f16* __restrict__ out = (f16*)g.C16;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
 #pragma unroll
                 for (int j = 0; j < TN; ++j) {
-                    const int n = n0 + (wn * TN + j) * 32 + lrow;
-                    if (mok && n < N)
-                        ((f16*)g.C16)[(long long)m * N + n] =
-                            (f16)(silu_f(acc[0][i][j][r] * inv) * (acc[NB - 1][i][j][r] * inv));
+                    const int m = m0 + row_of(i, r), n = col_of(j);
+                    if (m < M && n < N)
+                        out[(long long)m * N + n] =
+                            (f16)(silu_f(acc[0][i][j][r] * inv[i][r]) * (acc[NB - 1][i][j][r] * inv[i][r]));
                 }
-            } else if (EPI == EPI_RESIDUAL) {
+    } else if constexpr (EPI == EPI_RESIDUAL) {
+        float gain[TN];
+#pragma unroll
+        for (int j = 0; j < TN; ++j) gain[j] = g.gain_next ? (float)((const bf16*)g.gain_next)[min(col_of(j), N - 1)] : 0.f;
+        float xv[TM][TN][16];
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int m = min(m0 + row_of(i, r), M - 1), n = min(col_of(j), N - 1);
+                    xv[i][j][r] = g.Cf[(long long)m * N + n];
+                }
+        f16* __restrict__ a16 = (f16*)g.C16;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int m = m0 + row_of(i, r);
                 float ss = 0.f;
 #pragma unroll
                 for (int j = 0; j < TN; ++j) {
-                    const int n = n0 + (wn * TN + j) * 32 + lrow;
-                    if (mok && n < N) {
+                    const int n = col_of(j);
+                    if (m < M && n < N) {
                         const long long o = (long long)m * N + n;
-                        const float xn = g.Cf[o] + acc[0][i][j][r];
+                        const float xn = xv[i][j][r] + acc[0][i][j][r];
                         g.Cf[o] = xn;
                         if (g.gain_next) {
-                            ((f16*)g.C16)[o] = (f16)(xn * (float)((const bf16*)g.gain_next)[n]);
+                            a16[o] = (f16)(xn * gain[j]);
                             ss += xn * xn;
                         }
                     }
@@ -244,37 +306,65 @@ __global__ __launch_bounds__(256) void gemm_bf16_tile_kernel(GemmArgs g) {
                 if (g.gain_next) {   // partial sum of squares over this wavefront's TN*32 columns
 #pragma unroll
                     for (int o = 16; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
-                    if (lrow == 0 && mok) g.ssq_out[(long long)m * (N / (TN * 32)) + (n0 / (TN * 32)) + wn] = ss;
+                    if (lrow == 0 && m < M) g.ssq_out[(long long)m * (N / (TN * 32)) + (n0 / (TN * 32)) + wn] = ss;
                 }
-            } else {                 // EPI_QKV: one head per wavefront, rotary pairs (j, j + TN/2)
-                const int head = n0 / (TN * 32) + wn;
-                const RopeArgs& ro = g.rope;
-                const int Hq = ro.n_q_heads, Hkv = ro.kv.n_kv_heads, hd = TN * 32;
-                if (!mok || head >= Hq + 2 * Hkv) continue;
-                const int pos = ro.row_pos[m];
-                f16* pool = (f16*)ro.kv.base;
-                if (head < Hq + Hkv) {
-                    f16* dst;
-                    if (head < Hq) {
-                        dst = (f16*)ro.q_out + ((long long)m * Hq + head) * hd;
-                    } else {
-                        dst = pool + ro.kv.plane(ro.layer, 0, head - Hq) + (long long)ro.row_slot[m] * hd;
+            }
+    } else {                         // EPI_QKV: one head per wavefront, rotary pairs (j, j + TN/2)
+        const int head = n0 / (TN * 32) + wn;
+        const RopeArgs& ro = g.rope;
+        const int Hq = ro.n_q_heads, Hkv = ro.kv.n_kv_heads;
+        constexpr int hd = TN * 32;
+        if (head >= Hq + 2 * Hkv) return;
+        f16* pool = (f16*)ro.kv.base;
+        int pos[TM][16], slot[TM][16];
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int m = min(m0 + row_of(i, r), M - 1);
+                pos[i][r] = ro.row_pos[m];
+                slot[i][r] = ro.row_slot[m];
+            }
+        if (head < Hq + Hkv) {
+            float cs[TM][16][TN / 2], sn[TM][16][TN / 2];
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+#pragma unroll
+                    for (int j = 0; j < TN / 2; ++j) {
+                        const long long ao = (long long)pos[i][r] * (hd / 2) + j * 32 + lrow;
+                        cs[i][r][j] = ro.cos[ao];
+                        sn[i][r][j] = ro.sin[ao];
                     }
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int m = m0 + row_of(i, r);
+                    if (m >= M) continue;
+                    f16* dst = head < Hq ? (f16*)ro.q_out + ((long long)m * Hq + head) * hd
+                                         : pool + ro.kv.plane(ro.layer, 0, head - Hq) + (long long)slot[i][r] * hd;
 #pragma unroll
                     for (int j = 0; j < TN / 2; ++j) {
                         const int c = j * 32 + lrow;
-                        const float cs = ro.cos[(long long)pos * (hd / 2) + c], sn = ro.sin[(long long)pos * (hd / 2) + c];
-                        const float a = acc[0][i][j][r] * inv, b = acc[0][i][j + TN / 2][r] * inv;
-                        dst[c] = (f16)(a * cs - b * sn);
-                        dst[c + hd / 2] = (f16)(b * cs + a * sn);
+                        const float a = acc[0][i][j][r] * inv[i][r], b = acc[0][i][j + TN / 2][r] * inv[i][r];
+                        dst[c] = (f16)(a * cs[i][r][j] - b * sn[i][r][j]);
+                        dst[c + hd / 2] = (f16)(b * cs[i][r][j] + a * sn[i][r][j]);
                     }
-                } else {
-                    const int slot = ro.row_slot[m];
-                    f16* dst = pool + ro.kv.plane(ro.layer, 1, head - Hq - Hkv) + (long long)(slot >> 4) * 16 * hd + (slot & 15);
-#pragma unroll
-                    for (int j = 0; j < TN; ++j) dst[(long long)(j * 32 + lrow) * 16] = (f16)(acc[0][i][j][r] * inv);
                 }
-            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int m = m0 + row_of(i, r);
+                    if (m >= M) continue;
+                    f16* dst = pool + ro.kv.plane(ro.layer, 1, head - Hq - Hkv) +
+                               (long long)(slot[i][r] >> 4) * 16 * hd + (slot[i][r] & 15);
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) dst[(long long)(j * 32 + lrow) * 16] = (f16)(acc[0][i][j][r] * inv[i][r]);
+                }
         }
     }
 }
@@ -328,6 +418,7 @@ void gemm_bf16_skinny_kernel(GemmArgs g) {
     for (int b = 0; b < NB; ++b)
 #pragma unroll
         for (int t = 0; t < MT; ++t) acc[b][t] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
 
     // Epilogue operands that do not depend on the product are requested now, by the wavefront
     // that will run the epilogue: at these sizes a kernel is a chain of memory latencies, and
