@@ -106,6 +106,20 @@ def cpu_oracle_baseline(torch, shape, w_dev, prompt, P, T, layers=2):
                       f"P={P}, one extend of T={T} took {t_ext:.2f} s; rate scaled by {layers}/{shape.n_layers}"}
 
 
+def load_traffic(workload):
+    """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, each scaled by a
+    copy kernel of known size), kept as a text table under profiles/: `phase kernel_class fetch_MiB
+    write_MiB`.  Missing table -> no traffic figures."""
+    path = os.path.join(ROOT, "profiles", f"config{workload}_hbm_traffic.txt")
+    out = {}
+    if os.path.exists(path):
+        for line in open(path):
+            f = line.split()
+            if len(f) == 4 and not line.startswith("#"):
+                out[(f[0], f[1])] = int((float(f[2]) + float(f[3])) * (1 << 20))
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -113,6 +127,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", type=int, default=2, help="configuration id (2 = ~1B headline, 3, 4)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 256 MiB copy kernel three times (known traffic, for scaling "
+                         "hardware-counter readings taken under rocprofv3 --pmc)")
     ap.add_argument("--seed", type=int, default=2000)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -137,6 +154,15 @@ def main():
         dm.extend(kv, prompt[at:at + 512])
     drafts = [I.prompt_copied_drafts(prompt, args.seed, r, k) for r in range(rounds)]
     torch.cuda.synchronize()
+
+    if args.calibrate_copy:
+        n = 256 << 20
+        src = torch.ones(n, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            B.ax_dbg_copy(dst.data_ptr(), src.data_ptr(), n, dm.stream)
+        torch.cuda.synchronize()
+        del src, dst
 
     ev = lambda: torch.cuda.Event(enable_timing=True)
 
@@ -185,11 +211,17 @@ def main():
         B.ax_dbg_profile(dm.model, False)
         prof[tag] = B.ax_dbg_profile_read(dm.model)
 
+    traffic = load_traffic(args.workload)
+
     def kernel_roofline(tag, name):
         ms, n = prof[tag][name]
         if n == 0:
             return None
-        avg_s = ms / n * 1e-3
+        # a pair of events around nothing also measures something: subtract that
+        e_ms, e_n = prof[tag].get("empty_bracket", (0.0, 0))
+        overhead = e_ms / e_n if e_n else 0.0
+        launches_per_bracket = 2 if name == "attention" else 1       # split + combine kernels
+        avg_s = max(ms / n - overhead, 1e-6) * 1e-3
         a = alg[tag][name]
         gbs, tfs = a["bytes"] / avg_s / 1e9, a["flops"] / avg_s / 1e12
         hbm_frac, mfma_frac = gbs / HBM_PEAK_GBS, tfs / MFMA16_PEAK_TFLOPS
@@ -198,11 +230,14 @@ def main():
                 "achieved": round(gbs if bound == "hbm" else tfs, 2),
                 "peak": HBM_PEAK_GBS if bound == "hbm" else MFMA16_PEAK_TFLOPS,
                 "unit": "GB/s" if bound == "hbm" else "TFLOP/s",
-                "frac": round(max(hbm_frac, mfma_frac), 4), "traffic": None,
-                "avg_launch_us": round(avg_s * 1e6, 2), "launches": int(n),
-                "share_of_phase": round(ms / max(1e-9, sum(v[0] for v in prof[tag].values())), 3)}
+                "frac": round(max(hbm_frac, mfma_frac), 4), "traffic": traffic.get((tag, name)),
+                "algorithmic_bytes": int(a["bytes"]), "algorithmic_flops": int(a["flops"]),
+                "avg_launch_us": round(avg_s * 1e6, 2), "event_pair_overhead_us": round(overhead * 1e3, 2),
+                "kernels_per_launch": launches_per_bracket, "launches": int(n),
+                "share_of_phase": round(ms / max(1e-9, sum(v[0] for k_, v in prof[tag].items() if k_ != "empty_bracket")), 3)}
 
-    dominant = {tag: max(prof[tag], key=lambda nme: prof[tag][nme][0]) for tag in prof}
+    dominant = {tag: max((k_ for k_ in prof[tag] if k_ != "empty_bracket"), key=lambda nme: prof[tag][nme][0])
+                for tag in prof}
     # the kernel with the largest share of the whole step: verify runs `rounds` times per step
     tot = {tag: prof[tag][dominant[tag]][0] for tag in prof}
     main_tag = max(tot, key=tot.get)

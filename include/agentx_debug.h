@@ -28,6 +28,10 @@ ax_status ax_dbg_gemm_time(int dtype, int epilogue, const void *A, const void *W
                            int M, int N, int K, int iters, size_t w_stride_bytes, int w_count,
                            float *avg_us, void *hip_stream);
 
+/* Plain device-to-device copy kernel (16-byte words, grid-stride) of `bytes` bytes (a multiple of
+ * 16): the kernel of known traffic that hardware-counter readings are scaled against. */
+ax_status ax_dbg_copy(void *dst, const void *src, size_t bytes, void *hip_stream);
+
 /* Copies a workspace buffer as left by the last ax_extend* call to host memory (synchronises).
  * which: 0 residual stream x float[rows][d_model]; 1 qkv float[rows][(Hq+2Hkv)*hd] (pre-rotary,
  * last layer); 2 q after rotary, act[rows][Hq*hd]; 3 attention output act[rows][Hq*hd];
@@ -42,9 +46,10 @@ ax_status ax_dbg_read(ax_model *model, int which, void *host_dst, size_t bytes);
  * classes below inside ax_extend* / ax_verify is bracketed by a pair of events (this perturbs
  * the step a little, so enable it only for steps whose total time is not reported).
  * Classes: 0 QKV projection, 1 attention (split + combine), 2 O projection, 3 SwiGLU gate/up,
- * 4 down projection, 5 LM head.  ax_dbg_profile_read synchronises, adds up the elapsed
+ * 4 down projection, 5 LM head, 6 an empty bracket (once per layer of a bf16-weight model): what a
+ * pair of events measures around nothing, to be subtracted.  ax_dbg_profile_read synchronises, adds up the elapsed
  * milliseconds and the launch count of each class since the last read and clears them. */
-#define AX_DBG_PROFILE_CLASSES 6
+#define AX_DBG_PROFILE_CLASSES 7
 ax_status ax_dbg_profile(ax_model *model, int enable);
 ax_status ax_dbg_profile_read(ax_model *model, double *ms_by_class, int64_t *launches_by_class);
 

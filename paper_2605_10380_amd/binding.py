@@ -58,6 +58,7 @@ def _load():
         "ax_dbg_gemm": (C.c_int, [C.c_int, C.c_int, vp, vp, vp, vp, C.c_int, C.c_int, C.c_int, vp]),
         "ax_dbg_gemm_time": (C.c_int, [C.c_int, C.c_int, vp, vp, vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_size_t,
                                        C.c_int, C.POINTER(C.c_float), vp]),
+        "ax_dbg_copy": (C.c_int, [vp, vp, C.c_size_t, vp]),
         "ax_dbg_read": (C.c_int, [vp, C.c_int, vp, C.c_size_t]),
         "ax_dbg_profile": (C.c_int, [vp, C.c_int]),
         "ax_dbg_profile_read": (C.c_int, [vp, C.POINTER(C.c_double), C.POINTER(i64)]),
@@ -220,13 +221,17 @@ def ax_dbg_gemm_time(dtype: int, epilogue: int, A: int, W: int, W2: int, Cptr: i
     return us.value
 
 
+def ax_dbg_copy(dst: int, src: int, nbytes: int, stream: int = 0):
+    _check(lib.ax_dbg_copy(C.c_void_p(dst), C.c_void_p(src), nbytes, C.c_void_p(stream)))
+
+
 def ax_dbg_read(model: int, which: int, dst: np.ndarray):
     assert dst.flags["C_CONTIGUOUS"]
     _check(lib.ax_dbg_read(model, which, dst.ctypes.data_as(C.c_void_p), dst.nbytes))
     return dst
 
 
-PROFILE_CLASSES = ("qkv_proj", "attention", "o_proj", "swiglu_gate_up", "down_proj", "lm_head")
+PROFILE_CLASSES = ("qkv_proj", "attention", "o_proj", "swiglu_gate_up", "down_proj", "lm_head", "empty_bracket")
 
 
 def ax_dbg_profile(model: int, enable: bool):

@@ -392,6 +392,7 @@ ax_status enqueue_call(ax_model* m, const CallPlan& cp, void* out, hipStream_t s
             }
             { ProfScope ps(m, 1, stream);
               ax::launch_attention(dt, qb, attn, kg, l, sv, c.n_q_heads, (float*)(ws + L.partials), n_splits, stream); }
+            { ProfScope empty(m, 6, stream); }         // bracket around nothing: the cost of the two events
             {
                 ax::GemmArgs g = base;
                 g.A = attn; g.K = qdim; g.W = m->wo[(size_t)l]; g.N = d_model;
@@ -803,6 +804,13 @@ ax_status ax_dbg_gemm_time(int dtype, int epilogue, const void* A, const void* W
     (void)hipEventDestroy(e1);
     if (e != hipSuccess) return fail(AX_ERR_DEVICE, "timing: %s", hipGetErrorString(e));
     *avg_us = ms * 1000.f / (float)iters;
+    return AX_OK;
+}
+
+ax_status ax_dbg_copy(void* dst, const void* src, size_t bytes, void* hip_stream) {
+    if (!dst || !src || bytes == 0 || bytes % 16 != 0) return fail(AX_ERR_INVALID, "bad argument");
+    ax::launch_plain_copy(dst, src, bytes / 16, (hipStream_t)hip_stream);
+    HIP_TRY(hipGetLastError());
     return AX_OK;
 }
 

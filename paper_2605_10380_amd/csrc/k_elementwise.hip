@@ -234,6 +234,15 @@ __global__ void block_copy_kernel(char* __restrict__ base, long long plane_bytes
     for (int i = threadIdx.x; i < block_bytes / 16; i += blockDim.x) d[i] = s[i];
 }
 
+__global__ void plain_copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n16) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+
+void launch_plain_copy(void* dst, const void* src, size_t n16, hipStream_t s) {
+    plain_copy_kernel<<<4096, 256, 0, s>>>((const uint4*)src, (uint4*)dst, n16);
+}
+
 void launch_block_copy(DType dt, KVGeom kv, int n_layers, int src, int dst, hipStream_t s) {
     const long long isz = dt == F32 ? 4 : 2;
     const long long block_bytes = (long long)kv.block_tokens * kv.head_dim * isz;

@@ -107,6 +107,8 @@ void launch_argmax(const float* logits, int rows, int V, int* out, int* scratch,
 // Greedy acceptance: g[0..k] greedy tokens after each verify row, row_tok[1..k] the drafts.
 // result[0] = a (longest prefix with drafts[i] == g[i]), result[1] = g[a].
 void launch_accept(const int* g, const int* row_tok, int k, int* result, hipStream_t s);
+// Plain copy of n16 16-byte words (calibration kernel for hardware counters).
+void launch_plain_copy(void* dst, const void* src, size_t n16, hipStream_t s);
 // Copy one KV block (all layers, K and V, all heads) src -> dst: copy on write.
 void launch_block_copy(DType dt, KVGeom kv, int n_layers, int src, int dst, hipStream_t s);
 
