@@ -63,7 +63,7 @@ bool config_ok(const ax_model_config* c, ax_status* why) {
 }
 
 struct Layout {                       // byte offsets into the workspace
-    size_t rope_cos, rope_sin, desc, x, h, ssq, qkv, q, attn, ffn, partials, logits, amax_scratch,
+    size_t rope_cos, rope_sin, desc, x, h, ssq, qkv, q, attn, ffn, partials, splitk, logits, amax_scratch,
         amax_out, result, total;
     size_t desc_ints;                 // capacity of one descriptor slot
     int max_tiles, max_bt;
@@ -90,6 +90,7 @@ Layout make_layout(const ax_model_config& c) {
     L.ffn = take(T * (size_t)c.d_ff * a);
     const size_t items = std::max<size_t>(SPLIT_ITEMS, (size_t)L.max_tiles * c.n_kv_heads);
     L.partials = take(c.dtype == AX_BF16 ? items * ((size_t)c.head_dim * 32 + 64) * 4 : 0);
+    L.splitk = take(c.dtype == AX_BF16 ? T * c.d_model * 4 * ax::SPLITK_MAX : 0);   // K-slice partials of residual GEMMs
     L.logits = take(std::min<size_t>(T, LOGIT_ROWS) * (size_t)c.vocab * 4);
     L.amax_scratch = take(2 * std::min<size_t>(T, LOGIT_ROWS) * ax::ARGMAX_PARTS * 4);
     L.amax_out = take(T * 4);
@@ -230,8 +231,11 @@ ax_status prepare_call(ax_model* m, int n, ax_kv* const* kvs, const int32_t* tok
     cp.n_rows = (int)n_rows;
     cp.out_mode = out_mode;
     cp.pool = pool;
-    // attention q tiles are grouped in pairs when every sequence's stacked rows fit one pair
-    // (verify steps): the pair shares its K/V loads
+    // attention q tiles (32 stacked rows): a verify step's rows (<= 64 stacked rows per sequence)
+    // form one pair handled by one wavefront, which loads each K/V operand once for both tiles.
+    // Long extends keep one tile per wavefront: measured, larger groups lengthen the serial
+    // softmax chain per key step more than they save in K/V loads (0.87 / 0.91 / 1.25 ms per
+    // extend of 256 rows at 1, 2, 4 tiles per wavefront).
     cp.tile_nq = 2;
     for (int s = 0; s < n; ++s)
         if (T_each[s] * G > 64) cp.tile_nq = 1;
@@ -377,6 +381,8 @@ ax_status enqueue_call(ax_model* m, const CallPlan& cp, void* out, hipStream_t s
         const int nparts = ax::gemm_ssq_parts(R, d_model);
         ax::GemmArgs base{};
         base.M = R;
+        base.split_ws = (float*)(ws + L.splitk);
+        base.split_ws_bytes = (size_t)c.max_tokens * c.d_model * 4 * ax::SPLITK_MAX;
         auto normed = [&](ax::GemmArgs& g) { g.A = h; g.ssq = ssq; g.nparts = nparts; g.d_norm = d_model; g.eps = c.rms_eps; g.K = d_model; };
         ax::launch_embed_norm(m->tok_emb, sv.row_tok, m->norm_attn[0], x, h, ssq, nparts, R, d_model, stream);
         for (int l = 0; l < c.n_layers; ++l) {

@@ -130,6 +130,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_tile_kernel(GemmArgs g) {
     const int wm = wave >> 1, wn = wave & 1;
     const int lrow = lane & 31, lg = lane >> 5;
     const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+    const int kspan = g.ksplit > 1 ? K / g.ksplit : K, kbase = blockIdx.z * kspan;   // this block's K slice
 
     f32x16 acc[NB][TM][TN];
 #pragma unroll
@@ -151,12 +152,12 @@ __global__ __launch_bounds__(256) void gemm_bf16_tile_kernel(GemmArgs g) {
     for (int i = 0; i < A_CH; ++i) {
         const int c = tid + 256 * i, row = c >> 3, cc = c & 7;
         const int gm = min(m0 + row, M - 1);
-        a_off[i] = (long long)(g.a_rows ? g.a_rows[gm] : gm) * K + cc * 8;
+        a_off[i] = (long long)(g.a_rows ? g.a_rows[gm] : gm) * K + kbase + cc * 8;
     }
 #pragma unroll
     for (int i = 0; i < B_CH; ++i) {
         const int c = tid + 256 * i, row = c >> 3, cc = c & 7;
-        b_off[i] = (long long)min(n0 + row, N - 1) * K + cc * 8;
+        b_off[i] = (long long)min(n0 + row, N - 1) * K + kbase + cc * 8;
     }
     auto load_global = [&](int slot, int k0) {
 #pragma unroll
@@ -202,7 +203,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_tile_kernel(GemmArgs g) {
         }
     };
 
-    const int nsteps = K / BK;
+    const int nsteps = kspan / BK;
 #pragma unroll
     for (int s = 0; s < D; ++s)
         if (s < nsteps) load_global(s, s * BK);
@@ -270,6 +271,19 @@ __global__ __launch_bounds__(256) void gemm_bf16_tile_kernel(GemmArgs g) {
                             (f16)(silu_f(acc[0][i][j][r] * inv[i][r]) * (acc[NB - 1][i][j][r] * inv[i][r]));
                 }
     } else if constexpr (EPI == EPI_RESIDUAL) {
+        if (g.ksplit > 1) {          // K slice: raw partial products, finished by residual_reduce_kernel
+            float* part = g.split_ws + (long long)blockIdx.z * M * N;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) {
+                        const int m = m0 + row_of(i, r), n = col_of(j);
+                        if (m < M && n < N) part[(long long)m * N + n] = acc[0][i][j][r];
+                    }
+            return;
+        }
         float gain[TN];
 #pragma unroll
         for (int j = 0; j < TN; ++j) gain[j] = g.gain_next ? (float)((const bf16*)g.gain_next)[min(col_of(j), N - 1)] : 0.f;
@@ -366,6 +380,33 @@ __global__ __launch_bounds__(256) void gemm_bf16_tile_kernel(GemmArgs g) {
                     for (int j = 0; j < TN; ++j) dst[(long long)(j * 32 + lrow) * 16] = (f16)(acc[0][i][j][r] * inv[i][r]);
                 }
         }
+    }
+}
+
+// Second half of a K-split residual GEMM: x += sum of the K-slice partials (in slice order),
+// a = fp16(x * gain_next), per-row partial sums of x^2 over blocks of 64 columns (the layout the
+// unsplit tile kernel writes).  One wavefront per (row, 64 columns); N % 64 == 0.
+__global__ __launch_bounds__(256) void residual_reduce_kernel(GemmArgs g) {
+    const int lane = threadIdx.x & 63;
+    const long long item = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int nb = g.N / 64;
+    if (item >= (long long)g.M * nb) return;
+    const int m = (int)(item / nb), n = (int)(item % nb) * 64 + lane;
+    const long long o = (long long)m * g.N + n, slab = (long long)g.M * g.N;
+    float part[SPLITK_MAX];
+#pragma unroll
+    for (int ks = 0; ks < SPLITK_MAX; ++ks) part[ks] = ks < g.ksplit ? g.split_ws[ks * slab + o] : 0.f;
+    float xn = g.Cf[o];
+    const float gain = g.gain_next ? (float)((const bf16*)g.gain_next)[n] : 0.f;
+#pragma unroll
+    for (int ks = 0; ks < SPLITK_MAX; ++ks) xn += part[ks];
+    g.Cf[o] = xn;
+    if (g.gain_next) {
+        ((f16*)g.C16)[o] = (f16)(xn * gain);
+        float ss = xn * xn;
+#pragma unroll
+        for (int w = 32; w > 0; w >>= 1) ss += __shfl_xor(ss, w, 64);
+        if (lane == 0) g.ssq_out[(long long)m * nb + n / 64] = ss;
     }
 }
 
@@ -623,6 +664,22 @@ static void launch_bf16(const GemmArgs& g, hipStream_t s) {
         gemm_bf16_tile_kernel<EPI, 2, 2><<<grid, 256, 0, s>>>(g);
     } else {
         dim3 grid((N + 127) / 128, (M + 63) / 64);
+        if (EPI == EPI_RESIDUAL && g.split_ws && N % 64 == 0) {
+            // few output tiles (M = 256 against N = 2048 is 64 tiles for 256 CUs): cut K until
+            // there are ~256 blocks, each still with 8 or more k-steps
+            GemmArgs gs = g;
+            int ks = 1;
+            while (ks < SPLITK_MAX && (long long)grid.x * grid.y * ks < 256 && K % (ks * 2 * 64) == 0 &&
+                   K / (ks * 2 * 64) >= 8 && (size_t)ks * 2 * M * N * sizeof(float) <= g.split_ws_bytes)
+                ks *= 2;
+            if (ks > 1) {
+                gs.ksplit = ks;
+                grid.z = ks;
+                gemm_bf16_tile_kernel<EPI, 1, 2><<<grid, 256, 0, s>>>(gs);
+                residual_reduce_kernel<<<(unsigned)(((long long)M * (N / 64) + 3) / 4), 256, 0, s>>>(gs);
+                return;
+            }
+        }
         gemm_bf16_tile_kernel<EPI, 1, 2><<<grid, 256, 0, s>>>(g);
     }
 }

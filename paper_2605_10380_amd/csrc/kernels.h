@@ -69,7 +69,14 @@ struct GemmArgs {
     const void* gain_next;            // EPI_RESIDUAL: bf16 [N] gain of the next norm, NULL = plain residual add
     float* ssq_out;                   // EPI_RESIDUAL: [M][gemm_ssq_parts(M, N)] partial sums of x^2
     RopeArgs rope;                    // EPI_QKV
+    // EPI_RESIDUAL with M > 64 and few output tiles: K may be cut into ksplit slices (chosen by
+    // the launcher) whose fp32 partial products go to split_ws [ksplit][M][N]; a second kernel
+    // adds them up and runs the residual epilogue.  split_ws == NULL: never split.
+    float* split_ws;
+    size_t split_ws_bytes;
+    int ksplit;
 };
+constexpr int SPLITK_MAX = 8;
 void launch_gemm_bf16(Epilogue epi, const GemmArgs& g, hipStream_t s);
 // Number of sum-of-squares partials per row that an EPI_RESIDUAL launch with this M, N writes.
 int gemm_ssq_parts(int M, int N);
