@@ -238,7 +238,7 @@ ax_status prepare_call(ax_model* m, int n, ax_kv* const* kvs, const int32_t* tok
     // extend of 256 rows at 1, 2, 4 tiles per wavefront).
     cp.tile_nq = 2;
     for (int s = 0; s < n; ++s)
-        if (T_each[s] * G > 64) cp.tile_nq = 1;
+        if (T_each[s] * G > 64) cp.tile_nq = 4;
     cp.n_tiles = cp.bt_total = 0;
     for (int s = 0; s < n; ++s) {
         cp.n_tiles += (T_each[s] * G + 32 * cp.tile_nq - 1) / (32 * cp.tile_nq);

@@ -20,6 +20,7 @@ typedef _Float16 f16;      // activation and KV-cache type of bf16-weight models
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ float ld_f32(const float* p) { return *p; }
 __device__ __forceinline__ float ld_f32(const f16* p) { return (float)*p; }
@@ -282,6 +283,181 @@ __global__ __launch_bounds__(64) void attn_split_kernel(AttnArgs a) {
     }
 }
 
+// ------------------------------------------------------------------------------ MFMA block kernel
+// Long extends (many q tiles per KV head): a block of 4 wavefronts owns 4 consecutive q tiles
+// (128 stacked rows) of one KV head and one key slice.  The K/V operands of a 32-key step are
+// fetched once per block (one 16-byte chunk of K and one of V per thread and 64 channels of
+// head_dim), staged through LDS and shared by the four tiles; global loads run D steps ahead in
+// a register ring, LDS is double buffered, one barrier per step.  Everything after the operand
+// fetch is the per-wavefront online softmax of attn_split_kernel; the partial records are those
+// of a group of NQ = 4 tiles, merged by attn_combine_kernel<HD, 4>.
+//
+// LDS layout of a stage: K rows [32 keys][HD + 8] (padded, 16-byte operand reads are conflict
+// free); V rows [2 blocks * HD channels][16 tokens in operand order + 8 pad], where operand order
+// puts tokens {0-3, 8-11, 4-7, 12-15} so that a lane's PV operand (tokens 4g..4g+3 and
+// 8+4g..8+4g+3 of its channel) is one 16-byte read.
+template <int HD>
+__global__ __launch_bounds__(256) void attn_block_kernel(AttnArgs a) {
+    constexpr int KQ = HD / 16, DT = HD / 32, PS = HD * 32 + 64, NQ = 4;
+    constexpr int D = 4;                              // prefetch distance in key steps (even)
+    constexpr int KLS = HD + 8, VLS = 24;             // padded LDS row lengths (fp16 elements)
+    constexpr int CH = HD / 64;                       // 16-byte chunks of K (and of V) per thread and step
+    __shared__ __attribute__((aligned(16))) f16 sK[2][32 * KLS];
+    __shared__ __attribute__((aligned(16))) f16 sV[2][2 * HD * VLS];
+
+    const int tile = blockIdx.x, hk = blockIdx.y, split = blockIdx.z;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, ql = lane & 31, g = lane >> 5;
+    const int Hq = a.Hq, Hkv = a.kv.n_kv_heads, G = Hq / Hkv;
+    const int4 ti0 = *(const int4*)(a.tile_info + tile * 8), ti1 = *(const int4*)(a.tile_info + tile * 8 + 4);
+    const int r0 = ti0.y, P = ti0.z, T = ti0.w, row0 = ti1.x;
+    const int n_stacked = T * G;
+    const int* tab = a.bt + ti1.y;
+    const int kv_len = P + T, last_blk = (kv_len - 1) >> 4;
+
+    const int r_last = min(r0 + NQ * 32 - 1, n_stacked - 1);
+    const int kv_end = P + r_last / G + 1;
+    const int steps = (kv_end + 31) / 32;
+    const int per = (steps + a.n_splits - 1) / a.n_splits;
+    const int s_lo = split * per, s_hi = min(steps, s_lo + per);
+
+    // this wavefront's q tile
+    const int rq = min(r0 + wave * 32 + ql, n_stacked - 1);
+    const int tq = rq / G, gq = rq % G;
+    const int pos_q = P + tq;
+    const f16* qrow = a.q + ((long long)(row0 + tq) * Hq + hk * G + gq) * HD;
+    f16x8 qf[KQ];
+#pragma unroll
+    for (int kk = 0; kk < KQ; ++kk) qf[kk] = *(const f16x8*)(qrow + kk * 16 + g * 8);
+
+    const f16* Kp = (const f16*)a.kv.base + a.kv.plane(a.layer, 0, hk);
+    const f16* Vp = (const f16*)a.kv.base + a.kv.plane(a.layer, 1, hk);
+    const float c = 1.4426950408889634f / sqrtf((float)HD);
+    float m = -INFINITY, l = 0.f;
+    f32x16 o[DT];
+#pragma unroll
+    for (int d = 0; d < DT; ++d)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[d][r] = 0.f;
+
+    // operand chunks of this thread: K chunk i covers key (cidx / (HD/8)), columns 8*(cidx % (HD/8));
+    // V chunk i covers block (cidx / (2*HD)), channel ((cidx / 2) % HD), tokens 8*(cidx % 2)..+7
+    u32x4 rk[D][CH], rv[D][CH];
+    auto gload = [&](int slot, int st, int tabv, int chunk) {
+        const int kv0 = st * 32;
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            const int cidx = tid + 256 * i;
+            const int key = min(kv0 + cidx / (HD / 8), kv_len - 1);
+            const int kblk = __shfl(tabv, (key >> 4) - 2 * chunk, 64);
+            rk[slot][i] = *(const u32x4*)(Kp + ((long long)kblk * 16 + (key & 15)) * HD + (cidx % (HD / 8)) * 8);
+            const int vb = min((kv0 >> 4) + cidx / (2 * HD), last_blk);
+            const int vblk = __shfl(tabv, vb - 2 * chunk, 64);
+            rv[slot][i] = *(const u32x4*)(Vp + ((long long)vblk * HD + (cidx / 2) % HD) * 16 + (cidx % 2) * 8);
+        }
+    };
+    auto lstore = [&](int slot, int buf) {
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            const int cidx = tid + 256 * i;
+            *(u32x4*)(sK[buf] + (cidx / (HD / 8)) * KLS + (cidx % (HD / 8)) * 8) = rk[slot][i];
+            // tokens 8h..8h+3 -> operand position 4h, tokens 8h+4..8h+7 -> operand position 8 + 4h
+            const int vrow = (cidx / (2 * HD)) * HD + (cidx / 2) % HD, h = cidx % 2;
+            uint2* dst = (uint2*)(sV[buf] + vrow * VLS);
+            dst[h] = make_uint2(rv[slot][i][0], rv[slot][i][1]);
+            dst[2 + h] = make_uint2(rv[slot][i][2], rv[slot][i][3]);
+        }
+    };
+    auto process = [&](int buf, int st) {
+        const int kv0 = st * 32;
+        f32x16 s;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s[r] = 0.f;
+#pragma unroll
+        for (int kk = 0; kk < KQ; ++kk) {
+            const f16x8 kf = *(const f16x8*)(sK[buf] + ql * KLS + kk * 16 + g * 8);
+            s = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf, qf[kk], s, 0, 0, 0);
+        }
+        float mx = -INFINITY;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int kj = kv0 + (r >> 2) * 8 + g * 4 + (r & 3);
+            s[r] = (kj <= pos_q) ? s[r] * c : -INFINITY;
+            mx = fmaxf(mx, s[r]);
+        }
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const float mn = fmaxf(m, mx);
+        const float mu = (mn == -INFINITY) ? 0.f : mn;
+        const float alpha = exp2f(m - mu);
+        float ps = 0.f;
+        f16x8 pb[2];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const float p = exp2f(s[r] - mu);
+            ps += p;
+            pb[r >> 3][r & 7] = (f16)p;
+        }
+        ps += __shfl_xor(ps, 32, 64);
+        l = l * alpha + ps;
+        m = mn;
+#pragma unroll
+        for (int d = 0; d < DT; ++d) {
+            const f16x8 va = *(const f16x8*)(sV[buf] + (d * 32 + ql) * VLS + g * 8);
+            const f16x8 vb = *(const f16x8*)(sV[buf] + (HD + d * 32 + ql) * VLS + g * 8);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) o[d][r] *= alpha;
+            o[d] = __builtin_amdgcn_mfma_f32_32x32x16_f16(va, pb[0], o[d], 0, 0, 0);
+            o[d] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vb, pb[1], o[d], 0, 0, 0);
+        }
+    };
+
+    for (int chunk = s_lo; chunk < s_hi; chunk += 32) {          // 32 steps = 64 blocks = one table load
+        const int tabv = tab[min(2 * chunk + lane, last_blk)];
+        const int c_hi = min(s_hi, chunk + 32), n = c_hi - chunk;
+#pragma unroll
+        for (int u = 0; u < D; ++u)
+            if (u < n) gload(u, chunk + u, tabv, chunk);
+        lstore(0, 0);
+        __syncthreads();
+        int b = 0;
+        for (; b + 2 * D <= n; b += D) {                         // steady state, branch free
+#pragma unroll
+            for (int u = 0; u < D; ++u) {
+                gload(u, chunk + b + u + D, tabv, chunk);
+                process(u & 1, chunk + b + u);
+                lstore((u + 1) % D, (u + 1) & 1);
+                __syncthreads();
+            }
+        }
+        for (; b < n; b += D) {                                  // drain
+#pragma unroll
+            for (int u = 0; u < D; ++u) {
+                const int i = b + u;
+                if (i < n) {
+                    if (i + D < n) gload(u, chunk + i + D, tabv, chunk);
+                    process(u & 1, chunk + i);
+                    if (i + 1 < n) lstore((u + 1) % D, (u + 1) & 1);
+                    __syncthreads();
+                }
+            }
+        }
+    }
+
+    if (r0 + wave * 32 + ql < n_stacked) {
+        float* part = a.partials + (((long long)(tile * Hkv + hk) * a.n_splits + split) * NQ + wave) * PS;
+#pragma unroll
+        for (int d = 0; d < DT; ++d)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int ch = d * 32 + (r >> 2) * 8 + g * 4 + (r & 3);
+                part[ch * 32 + ql] = o[d][r];
+            }
+        if (g == 0) {
+            part[HD * 32 + ql] = m;
+            part[HD * 32 + 32 + ql] = l;
+        }
+    }
+}
+
 // Merges the key slices of one q tile.  grid (n_groups * Hkv * NQ, HD / 4), 256 threads =
 // 32 query rows x 8 slice groups; a block produces 4 output channels.  A thread loads the
 // (m, l, 4 channels) of its slices s = sg, sg + 8, ... in one go (up to 16 slices in registers),
@@ -384,7 +560,16 @@ void launch_attention(DType dt, const void* q, void* out, KVGeom kv, int layer, 
     a.q = (const f16*)q; a.out = (f16*)out; a.kv = kv; a.layer = layer; a.Hq = n_q_heads; a.n_splits = n_splits;
     a.tile_info = sv.tile_info; a.bt = sv.bt; a.partials = partials;
     const int hd = kv.head_dim;
-    if (sv.tile_nq == 2) {
+    if (sv.tile_nq == 4) {                                     // long extends: 4 tiles per block, K/V through LDS
+        dim3 grid(sv.n_tiles, kv.n_kv_heads, n_splits), cgrid(sv.n_tiles * kv.n_kv_heads * 4, hd / 4);
+        if (hd == 64) {
+            attn_block_kernel<64><<<grid, 256, 0, s>>>(a);
+            attn_combine_kernel<64, 4><<<cgrid, 256, 0, s>>>(a);
+        } else {
+            attn_block_kernel<128><<<grid, 256, 0, s>>>(a);
+            attn_combine_kernel<128, 4><<<cgrid, 256, 0, s>>>(a);
+        }
+    } else if (sv.tile_nq == 2) {
         if (hd == 64) launch_attn_mfma<64, 2>(a, sv.n_tiles, s); else launch_attn_mfma<128, 2>(a, sv.n_tiles, s);
     } else {
         if (hd == 64) launch_attn_mfma<64, 1>(a, sv.n_tiles, s); else launch_attn_mfma<128, 1>(a, sv.n_tiles, s);
