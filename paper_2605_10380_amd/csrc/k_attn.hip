@@ -117,6 +117,41 @@ __global__ __launch_bounds__(64) void attn_simple_kernel(const T* __restrict__ q
 // {4g..4g+3, 8+4g..8+4g+3} of the first 16-key block, registers 8..15 the same of the second
 // block (g = l/32).  V pages are token-minor ([head_dim][16]), so the matching A operand of a
 // lane (channel d) is two 8-byte loads from its channel's 16-token row.
+// One 32-key step of the online softmax for the lane's query row.  s: raw scores q.k of the
+// lane's 16 keys (key of register r: kv0 + (r/4)*8 + g*4 + r%4); c = log2(e)/sqrt(hd).  Updates
+// the running maximum m (scaled, base-2 domain) and sum l, returns the rescale factor of the
+// output accumulators and the probabilities packed as the two PV operands.  The causal mask is
+// applied only on steps that reach past the tile's earliest row (`diagonal`, wavefront-uniform).
+// v_exp_f32 is used directly: its arguments are <= 0 and a result that underflows to 0 is exact
+// enough for a probability.
+__device__ __forceinline__ void online_softmax_step(f32x16& s, int kv0, int g, int pos_q, bool diagonal, float c,
+                                                    float& m, float& l, float& alpha, f16x8 (&pb)[2]) {
+    if (diagonal) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int kj = kv0 + (r >> 2) * 8 + g * 4 + (r & 3);
+            s[r] = (kj <= pos_q) ? s[r] : -INFINITY;
+        }
+    }
+    float mx = s[0];
+#pragma unroll
+    for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[r]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * c;                // c > 0: max commutes with the scaling
+    const float mn = fmaxf(m, mx);
+    const float mu = (mn == -INFINITY) ? 0.f : mn;             // row with nothing visible yet
+    alpha = __builtin_amdgcn_exp2f(m - mu);                    // m = -inf -> 0
+    float ps = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const float p = __builtin_amdgcn_exp2f(fmaf(s[r], c, -mu));   // masked: -inf -> 0
+        ps += p;
+        pb[r >> 3][r & 7] = (f16)p;
+    }
+    ps += __shfl_xor(ps, 32, 64);
+    l = l * alpha + ps;
+    m = mn;
+}
+
 struct AttnArgs {
     const f16* q;
     f16* out;
@@ -154,13 +189,14 @@ __global__ __launch_bounds__(64) void attn_split_kernel(AttnArgs a) {
     const int s_lo = split * per, s_hi = min(steps, s_lo + per);
 
     // this lane's query rows (clamped rows compute garbage that is never written)
-    int pos_q[NQ];
+    int pos_q[NQ], pos_min[NQ];          // pos_min: earliest position among the tile's rows (uniform)
     f16x8 qf[NQ][KQ];
 #pragma unroll
     for (int t = 0; t < NQ; ++t) {
         const int rq = min(r0 + t * 32 + ql, n_stacked - 1);
         const int tq = rq / G, gq = rq % G;
         pos_q[t] = P + tq;
+        pos_min[t] = P + min(r0 + t * 32, n_stacked - 1) / G;
         const f16* qrow = a.q + ((long long)(row0 + tq) * Hq + hk * G + gq) * HD;
 #pragma unroll
         for (int kk = 0; kk < KQ; ++kk) qf[t][kk] = *(const f16x8*)(qrow + kk * 16 + g * 8);
@@ -213,29 +249,9 @@ __global__ __launch_bounds__(64) void attn_split_kernel(AttnArgs a) {
             for (int r = 0; r < 16; ++r) s[r] = 0.f;
 #pragma unroll
             for (int kk = 0; kk < KQ; ++kk) s = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf[buf][kk], qf[t][kk], s, 0, 0, 0);
-            // causal mask + online softmax (base-2 exponentials)
-            float mx = -INFINITY;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int kj = kv0 + (r >> 2) * 8 + g * 4 + (r & 3);
-                s[r] = (kj <= pos_q[t]) ? s[r] * c : -INFINITY;
-                mx = fmaxf(mx, s[r]);
-            }
-            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-            const float mn = fmaxf(m[t], mx);
-            const float mu = (mn == -INFINITY) ? 0.f : mn;        // row with nothing visible yet
-            const float alpha = exp2f(m[t] - mu);                 // m = -inf -> 0
-            float ps = 0.f;
+            float alpha;
             f16x8 pb[2];
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const float p = exp2f(s[r] - mu);                 // masked -> 0
-                ps += p;
-                pb[r >> 3][r & 7] = (f16)p;
-            }
-            ps += __shfl_xor(ps, 32, 64);
-            l[t] = l[t] * alpha + ps;
-            m[t] = mn;
+            online_softmax_step(s, kv0, g, pos_q[t], kv0 + 31 > pos_min[t], c, m[t], l[t], alpha, pb);
 #pragma unroll
             for (int d = 0; d < DT; ++d) {
                 const f16x4 *v = vq[buf][d];
@@ -332,7 +348,9 @@ __global__ __launch_bounds__(256) void attn_block_kernel(AttnArgs a) {
     const f16* Kp = (const f16*)a.kv.base + a.kv.plane(a.layer, 0, hk);
     const f16* Vp = (const f16*)a.kv.base + a.kv.plane(a.layer, 1, hk);
     const float c = 1.4426950408889634f / sqrtf((float)HD);
-    float m = -INFINITY, l = 0.f;
+    const int pos_tile_min = P + (r0 + wave * 32) / G;         // earliest position among this tile's rows
+    float m = -INFINITY, l = 0.f, alpha_out = 1.f;
+    f16x8 pb_out[2];
     f32x16 o[DT];
 #pragma unroll
     for (int d = 0; d < DT; ++d)
@@ -377,28 +395,9 @@ __global__ __launch_bounds__(256) void attn_block_kernel(AttnArgs a) {
             const f16x8 kf = *(const f16x8*)(sK[buf] + ql * KLS + kk * 16 + g * 8);
             s = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf, qf[kk], s, 0, 0, 0);
         }
-        float mx = -INFINITY;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int kj = kv0 + (r >> 2) * 8 + g * 4 + (r & 3);
-            s[r] = (kj <= pos_q) ? s[r] * c : -INFINITY;
-            mx = fmaxf(mx, s[r]);
-        }
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float mn = fmaxf(m, mx);
-        const float mu = (mn == -INFINITY) ? 0.f : mn;
-        const float alpha = exp2f(m - mu);
-        float ps = 0.f;
-        f16x8 pb[2];
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const float p = exp2f(s[r] - mu);
-            ps += p;
-            pb[r >> 3][r & 7] = (f16)p;
-        }
-        ps += __shfl_xor(ps, 32, 64);
-        l = l * alpha + ps;
-        m = mn;
+        online_softmax_step(s, kv0, g, pos_q, kv0 + 31 > pos_tile_min, c, m, l, alpha_out, pb_out);
+        const float alpha = alpha_out;
+        const f16x8* pb = pb_out;
 #pragma unroll
         for (int d = 0; d < DT; ++d) {
             const f16x8 va = *(const f16x8*)(sV[buf] + (d * 32 + ql) * VLS + g * 8);
