@@ -488,35 +488,77 @@ void gemm_bf16_skinny_kernel(GemmArgs g) {
         }
     }
 
-    // U MFMA k-steps (32 each) per trip: all U weight loads (and the matching activation loads)
-    // are issued before the first product, so a wavefront keeps U KB of weights in flight.
+    // One trip = U MFMA k-steps (32 each).  All weight and activation loads of trip i + 1 are issued
+    // before trip i is multiplied (two register sets), so a wavefront always has a trip's worth
+    // of loads (U KB of weights) in flight while its matrix pipe is busy.
     int k = kbeg;
-    auto trip = [&](auto u_tag) {
-        constexpr int U = decltype(u_tag)::value;
-        u32x4 rw[NB][U];
-        f16x8 fx[MT][U];
+    if constexpr (MT <= 2) {
+        constexpr int U = 4, S = 32 * U;
+        u32x4 rw[2][NB][U];
+        f16x8 fx[2][MT][U];
+        auto loads = [&](int set, int kk) {
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            rw[0][u] = *(const u32x4*)(wp + k + 32 * u);
-            if (NB == 2) rw[NB - 1][u] = *(const u32x4*)(wp2 + k + 32 * u);
-        }
-#pragma unroll
-        for (int t = 0; t < MT; ++t)
-#pragma unroll
-            for (int u = 0; u < U; ++u) fx[t][u] = *(const f16x8*)(xp[t] + k + 32 * u);
-#pragma unroll
-        for (int u = 0; u < U; ++u)
-#pragma unroll
-            for (int b = 0; b < NB; ++b) {
-                const f16x8 fw = bf16x8_to_f16x8(rw[b][u]);
-#pragma unroll
-                for (int t = 0; t < MT; ++t)
-                    acc[b][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fw, fx[t][u], acc[b][t], 0, 0, 0);
+            for (int u = 0; u < U; ++u) {
+                rw[set][0][u] = *(const u32x4*)(wp + kk + 32 * u);
+                if (NB == 2) rw[set][NB - 1][u] = *(const u32x4*)(wp2 + kk + 32 * u);
             }
-    };
-    if constexpr (MT <= 2 && NW <= 4)      // long K slices only: 8 KB of weights in flight per wavefront
-        for (; k + 256 <= kend; k += 256) trip(std::integral_constant<int, 8>{});
-    for (; k + 128 <= kend; k += 128) trip(std::integral_constant<int, 4>{});
+#pragma unroll
+            for (int t = 0; t < MT; ++t)
+#pragma unroll
+                for (int u = 0; u < U; ++u) fx[set][t][u] = *(const f16x8*)(xp[t] + kk + 32 * u);
+        };
+        auto compute = [&](int set) {
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int b = 0; b < NB; ++b) {
+                    const f16x8 fw = bf16x8_to_f16x8(rw[set][b][u]);
+#pragma unroll
+                    for (int t = 0; t < MT; ++t)
+                        acc[b][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fw, fx[set][t][u], acc[b][t], 0, 0, 0);
+                }
+        };
+        const int ntr = kslice / S;
+        if (ntr > 0) loads(0, kbeg);
+        int t = 0;
+        for (; t + 2 < ntr; t += 2) {                                // both loads unconditional
+            loads(1, kbeg + (t + 1) * S);
+            compute(0);
+            loads(0, kbeg + (t + 2) * S);
+            compute(1);
+        }
+        if (t + 1 < ntr) {
+            loads(1, kbeg + (t + 1) * S);
+            compute(0);
+            compute(1);
+        } else if (t < ntr) {
+            compute(0);
+        }
+        k = kbeg + ntr * S;
+    } else {
+        for (; k + 128 <= kend; k += 128) {
+            u32x4 rw[NB][4];
+            f16x8 fx[MT][4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                rw[0][u] = *(const u32x4*)(wp + k + 32 * u);
+                if (NB == 2) rw[NB - 1][u] = *(const u32x4*)(wp2 + k + 32 * u);
+            }
+#pragma unroll
+            for (int t = 0; t < MT; ++t)
+#pragma unroll
+                for (int u = 0; u < 4; ++u) fx[t][u] = *(const f16x8*)(xp[t] + k + 32 * u);
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int b = 0; b < NB; ++b) {
+                    const f16x8 fw = bf16x8_to_f16x8(rw[b][u]);
+#pragma unroll
+                    for (int t = 0; t < MT; ++t)
+                        acc[b][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fw, fx[t][u], acc[b][t], 0, 0, 0);
+                }
+        }
+    }
     for (; k < kend; k += 32) {
 #pragma unroll
         for (int b = 0; b < NB; ++b) {
