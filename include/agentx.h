@@ -177,6 +177,42 @@ ax_status ax_extend_batch(ax_model *model, int n, ax_kv *const *kvs, const int32
 ax_status ax_verify(ax_model *model, ax_kv *kv, int32_t pending, const int32_t *drafts, int k,
                     int *accepted, int32_t *next_token, void *hip_stream);
 
+/* ---- example-based drafter and decode loop (paper Sec. 4.3) -------------------------------------
+ * A per-query n-gram lookup table: a window of n tokens slides over `stream` (the few-shot
+ * examples followed by the user query; host memory) one token at a time; the first n-1 tokens
+ * are the key, the value is the next token seen most often with that key (ties: the one
+ * recorded first).  Host only, O(n_tokens).  n >= 1, vocab > 0, tokens in [0, vocab). */
+typedef struct ax_lut ax_lut;
+ax_status ax_lut_build(const int32_t *stream, int64_t n_tokens, int n, int vocab, ax_lut **out);
+void ax_lut_free(ax_lut *lut);
+/* Number of keys, or -1 for a bad handle. */
+int64_t ax_lut_size(const ax_lut *lut);
+/* Drafts after `context` (host, most recent token last): the table's answer to the last n-1
+ * tokens, appended to the context, k times.  selective != 0: if the first lookup misses, no draft
+ * is produced (the caller decodes one token normally).  A miss after a first hit - or any miss
+ * when selective == 0 - yields splitmix64(seed + stream_pos + i) % vocab for draft i: a guess that
+ * verification will reject.  Writes the drafts to drafts[0..k) and returns how many (0 or k),
+ * -1 on bad arguments; *hits (optional) = drafts that came from the table. */
+int ax_lut_draft(const ax_lut *lut, const int32_t *context, int64_t n_context, int k, int selective,
+                 uint64_t seed, int64_t stream_pos, int32_t *drafts, int *hits);
+
+typedef struct {
+    int64_t rounds;      /* verification forwards run                                   */
+    int64_t fallbacks;   /* rounds decoded without speculation (first lookup missed)    */
+    int64_t drafted;     /* draft tokens generated                                      */
+    int64_t accepted;    /* draft tokens accepted; accuracy = accepted / drafted        */
+} ax_exspec_stats;
+
+/* The decode loop: repeat { draft from the table (context = history, pending, everything emitted
+ * so far); ax_verify } until max_new tokens follow `pending`.  kv holds everything before
+ * `pending`; `history` (host, may be NULL) are the tokens before `pending` the drafter may use as
+ * context.  Never drafts past max_new.  out_tokens[0..max_new) (host) receives the tokens; they
+ * equal one-token-at-a-time greedy decoding whatever the table holds.  On return kv holds
+ * everything except the last emitted token (the next pending one).  Errors as ax_verify. */
+ax_status ax_exspec_generate(ax_model *model, ax_kv *kv, const ax_lut *lut, const int32_t *history,
+                             int64_t n_history, int32_t pending, int max_new, int k, int selective,
+                             uint64_t seed, int32_t *out_tokens, ax_exspec_stats *stats, void *hip_stream);
+
 /* Text for the last failing call on this thread (static storage, never NULL). */
 const char *ax_last_error(void);
 

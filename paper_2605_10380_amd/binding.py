@@ -25,6 +25,10 @@ class ax_model_config(C.Structure):
         ("max_tokens", C.c_int), ("max_seqs", C.c_int)]
 
 
+class ax_exspec_stats(C.Structure):
+    _fields_ = [(n, C.c_int64) for n in ("rounds", "fallbacks", "drafted", "accepted")]
+
+
 class ax_weights(C.Structure):
     _fields_ = [("tok_emb", C.c_void_p), ("lm_head", C.c_void_p), ("final_norm", C.c_void_p)] + [
         (n, C.POINTER(C.c_void_p)) for n in ("wqkv", "wo", "w_gate", "w_up", "w_down", "norm_attn", "norm_mlp")]
@@ -55,6 +59,12 @@ def _load():
         "ax_kv_reserve_host": (C.c_int, [vp, i64, i32p, i32p]),
         "ax_extend": (C.c_int, [vp, vp, i32p, C.c_int, C.c_int, vp, vp]),
         "ax_extend_batch": (C.c_int, [vp, C.c_int, C.POINTER(vp), i32p, C.POINTER(C.c_int), C.c_int, vp, vp]),
+        "ax_lut_build": (C.c_int, [i32p, i64, C.c_int, C.c_int, C.POINTER(vp)]),
+        "ax_lut_free": (None, [vp]),
+        "ax_lut_size": (i64, [vp]),
+        "ax_lut_draft": (C.c_int, [vp, i32p, i64, C.c_int, C.c_int, C.c_uint64, i64, i32p, C.POINTER(C.c_int)]),
+        "ax_exspec_generate": (C.c_int, [vp, vp, vp, i32p, i64, C.c_int32, C.c_int, C.c_int, C.c_int, C.c_uint64, i32p,
+                                         C.POINTER(ax_exspec_stats), vp]),
         "ax_dbg_gemm": (C.c_int, [C.c_int, C.c_int, vp, vp, vp, vp, C.c_int, C.c_int, C.c_int, vp]),
         "ax_dbg_gemm_time": (C.c_int, [C.c_int, C.c_int, vp, vp, vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_size_t,
                                        C.c_int, C.POINTER(C.c_float), vp]),
@@ -204,6 +214,44 @@ def ax_verify(model: int, kv: int, pending: int, drafts, stream: int = 0):
     _check(lib.ax_verify(model, kv, int(pending), dp if len(d) else None, len(d), C.byref(a), C.byref(nxt),
                          C.c_void_p(stream)))
     return a.value, nxt.value
+
+
+# ------------------------------------------------------------------ example-based drafter (host) and decode loop
+
+def ax_lut_build(stream, n: int, vocab: int) -> int:
+    t, tp = _i32(stream)
+    out = C.c_void_p()
+    _check(lib.ax_lut_build(tp if len(t) else None, len(t), n, vocab, C.byref(out)))
+    return out.value
+
+
+def ax_lut_free(lut: int):
+    lib.ax_lut_free(lut)
+
+
+def ax_lut_size(lut: int) -> int:
+    return lib.ax_lut_size(lut)
+
+
+def ax_lut_draft(lut: int, context, k: int, selective: bool = True, seed: int = 0, stream_pos: int = 0):
+    c, cp = _i32(context)
+    d = np.zeros(max(k, 1), dtype=np.int32)
+    hits = C.c_int()
+    n = lib.ax_lut_draft(lut, cp if len(c) else None, len(c), k, int(selective), seed, stream_pos,
+                         d.ctypes.data_as(C.POINTER(C.c_int32)), C.byref(hits))
+    if n < 0:
+        raise AxError(AX_ERR_INVALID)
+    return d[:n].tolist(), hits.value
+
+
+def ax_exspec_generate(model: int, kv: int, lut: int, history, pending: int, max_new: int, k: int,
+                       selective: bool = True, seed: int = 0, stream: int = 0):
+    h, hp = _i32(history)
+    out = np.zeros(max(max_new, 1), dtype=np.int32)
+    st = ax_exspec_stats()
+    _check(lib.ax_exspec_generate(model, kv, lut, hp if len(h) else None, len(h), int(pending), max_new, k, int(selective),
+                                  seed, out.ctypes.data_as(C.POINTER(C.c_int32)), C.byref(st), C.c_void_p(stream)))
+    return out[:max_new].tolist(), dict(rounds=st.rounds, fallbacks=st.fallbacks, drafted=st.drafted, accepted=st.accepted)
 
 
 # ------------------------------------------------------------------ test-only entry points

@@ -16,6 +16,7 @@
 
 #include "block_manager.h"
 #include "kernels.h"
+#include "ngram_lut.h"
 
 namespace {
 
@@ -35,7 +36,7 @@ ax_status fail(ax_status st, const char* fmt, ...) {
         if (e_ != hipSuccess) return fail(AX_ERR_DEVICE, "%s: %s", #expr, hipGetErrorString(e_)); \
     } while (0)
 
-constexpr uint32_t MAGIC_MODEL = 0x41584d44, MAGIC_POOL = 0x4158504c, MAGIC_KV = 0x41584b56;
+constexpr uint32_t MAGIC_MODEL = 0x41584d44, MAGIC_POOL = 0x4158504c, MAGIC_KV = 0x41584b56, MAGIC_LUT = 0x41584c54;
 constexpr int N_SLOTS = 4;            // staging ring for per-call descriptors
 constexpr int LOGIT_ROWS = 256;       // rows per LM-head pass when only the argmax is wanted
 constexpr int SPLIT_ITEMS = 2048;     // wavefronts the split attention aims for
@@ -132,6 +133,11 @@ struct ax_pool {
     ax::BlockPool blocks;
 };
 
+struct ax_lut {
+    uint32_t magic;
+    ax::NgramLut lut;
+};
+
 struct ax_kv {
     uint32_t magic;
     ax_pool* pool;
@@ -143,6 +149,7 @@ namespace {
 bool ok(const ax_model* m) { return m && m->magic == MAGIC_MODEL; }
 bool ok(const ax_pool* p) { return p && p->magic == MAGIC_POOL; }
 bool ok(const ax_kv* k) { return k && k->magic == MAGIC_KV && ok(k->pool); }
+bool ok(const ax_lut* l) { return l && l->magic == MAGIC_LUT; }
 
 struct ProfScope {                     // records a pair of events around one launch when profiling
     ax_model* m; hipStream_t st; hipEvent_t b = nullptr;
@@ -766,6 +773,75 @@ ax_status ax_verify(ax_model* model, ax_kv* kv, int32_t pending, const int32_t* 
     *accepted = a;
     *next_token = host_res[1];
     ax::truncate(kv->pool->blocks, kv->seq, P + 1 + a);                    // rollback of rejected drafts
+    return AX_OK;
+}
+
+ax_status ax_lut_build(const int32_t* stream, int64_t n_tokens, int n, int vocab, ax_lut** out) {
+    if (!out) return fail(AX_ERR_INVALID, "out is NULL");
+    *out = nullptr;
+    if (n < 1 || vocab <= 0 || n_tokens < 0 || (n_tokens > 0 && !stream)) return fail(AX_ERR_INVALID, "bad argument");
+    for (int64_t i = 0; i < n_tokens; ++i)
+        if (stream[i] < 0 || stream[i] >= vocab) return fail(AX_ERR_INVALID, "token %d outside the vocabulary", stream[i]);
+    ax_lut* l = new ax_lut();
+    l->lut.build(stream, n_tokens, n, vocab);
+    l->magic = MAGIC_LUT;
+    *out = l;
+    return AX_OK;
+}
+
+void ax_lut_free(ax_lut* lut) {
+    if (!ok(lut)) return;
+    lut->magic = 0;
+    delete lut;
+}
+
+int64_t ax_lut_size(const ax_lut* lut) { return ok(lut) ? (int64_t)lut->lut.table.size() : -1; }
+
+int ax_lut_draft(const ax_lut* lut, const int32_t* context, int64_t n_context, int k, int selective, uint64_t seed,
+                 int64_t stream_pos, int32_t* drafts, int* hits) {
+    if (!ok(lut) || k < 0 || n_context < 0 || (n_context > 0 && !context) || (k > 0 && !drafts)) return -1;
+    std::vector<int32_t> ctx(context, context + n_context);
+    int h = 0;
+    const int n = lut->lut.draft(ctx, k, selective != 0, seed, stream_pos, drafts, &h);
+    if (hits) *hits = h;
+    return n;
+}
+
+ax_status ax_exspec_generate(ax_model* model, ax_kv* kv, const ax_lut* lut, const int32_t* history, int64_t n_history,
+                             int32_t pending, int max_new, int k, int selective, uint64_t seed, int32_t* out_tokens,
+                             ax_exspec_stats* stats, void* hip_stream) {
+    if (!ok(model)) return fail(AX_ERR_INVALID, "bad model handle");
+    if (!ok(kv)) return fail(AX_ERR_INVALID, "bad KV handle");
+    if (!ok(lut)) return fail(AX_ERR_INVALID, "bad table handle");
+    if (max_new < 0 || k < 0 || n_history < 0 || (n_history > 0 && !history) || (max_new > 0 && !out_tokens))
+        return fail(AX_ERR_INVALID, "bad argument");
+    if (lut->lut.vocab != model->cfg.vocab) return fail(AX_ERR_INVALID, "table and model vocabularies differ");
+    ax_exspec_stats st{0, 0, 0, 0};
+    std::vector<int32_t> ctx(history, history + n_history);
+    ctx.push_back(pending);
+    std::vector<int32_t> drafts((size_t)std::max(k, 1));
+    int emitted = 0;
+    while (emitted < max_new) {
+        const int kk = std::min(k, max_new - emitted - 1);           // never draft past the requested length
+        int hits = 0;
+        const int nd = kk > 0 ? lut->lut.draft(ctx, kk, selective != 0, seed, emitted, drafts.data(), &hits) : 0;
+        if (nd == 0) ++st.fallbacks;
+        int a = 0;
+        int32_t nxt = 0;
+        const ax_status rc = ax_verify(model, kv, pending, drafts.data(), nd, &a, &nxt, hip_stream);
+        if (rc != AX_OK) {
+            if (stats) *stats = st;
+            return rc;
+        }
+        ++st.rounds;
+        st.drafted += nd;
+        st.accepted += a;
+        for (int i = 0; i < a; ++i) { out_tokens[emitted++] = drafts[(size_t)i]; ctx.push_back(drafts[(size_t)i]); }
+        out_tokens[emitted++] = nxt;
+        ctx.push_back(nxt);
+        pending = nxt;
+    }
+    if (stats) *stats = st;
     return AX_OK;
 }
 

@@ -360,3 +360,77 @@ def test_graph_replays_match_eager_verify(B, monkeypatch):
     for dm, kv in ((eager, ke), (graph, kg)):
         B.ax_kv_free(kv)
         dm.close()
+
+
+# ------------------------------------------------------------------ example-based drafter + decode loop
+
+@pytest.mark.parametrize("which", ["bf16-hd64-g4", "f32-hd32"])
+@pytest.mark.parametrize("selective", [True, False])
+def test_exspec_loop_equals_oracle_loop(B, which, selective):
+    """The library's draft-verify-rollback loop against the oracle's loop: same tokens, same
+    round / fallback / drafted / accepted counts.  The table is built from the prompt plus a
+    partly corrupted copy of the model's own greedy continuation, so rounds hit, miss and are
+    partially accepted.  Compared up to the first token whose oracle top-2 margin is <= MARGIN."""
+    from oracle import exspec as X
+    sh = SMALL[which]
+    w = I.make_weights(sh, 21)
+    prompt = I.templated_prompt(sh.vocab, 21, 75)
+    n, k, max_new = 3, 6, 48
+    dm = B.DeviceModel(sh, w, max_pos=512, max_tokens=128, pool_tokens=1024)
+    kv, ref_kv = dm.new_kv(), okv(sh)
+    dm.extend(kv, prompt)
+    pending = O.argmax_lowest(O.forward(sh, w, prompt, ref_kv)[-1])
+    # greedy continuation with margins
+    gkv = ref_kv.fork()
+    greedy, margins, tok = [], [], pending
+    for _ in range(max_new):
+        lg = O.forward(sh, w, [tok], gkv)[-1]
+        tok = O.argmax_lowest(lg)
+        greedy.append(tok)
+        margins.append(O.top2_margin(lg))
+    safe = next((i for i, m in enumerate(margins) if m <= MARGIN), max_new)
+    rng = np.random.default_rng(21)
+    example = np.array([pending] + greedy[:40])
+    bad = rng.random(len(example)) < 0.15
+    example = np.where(bad, rng.integers(0, sh.vocab, len(example)), example)
+    stream = np.concatenate([prompt, example]).astype(np.int32)
+    ref_lut = X.build_lut(stream, n)
+    lut = B.ax_lut_build(stream, n, sh.vocab)
+    assert B.ax_lut_size(lut) == len(ref_lut)
+    want, wst = X.generate(sh, w, ref_kv, ref_lut, n, prompt, pending, max_new, k, selective, seed=3, stream=dm.stream)
+    assert want == greedy                                     # the oracle loop itself is lossless
+    got, gst = B.ax_exspec_generate(dm.model, kv, lut, prompt, pending, max_new, k, selective, seed=3, stream=dm.stream)
+    print(which, "selective", selective, "stats", gst, "oracle", wst, "safe prefix", safe)
+    assert got[:safe] == want[:safe]
+    if safe == max_new:
+        assert got == want and gst == wst
+        assert B.ax_kv_len(kv) == len(prompt) + max_new
+        assert 0 < gst["accepted"] < gst["drafted"] and gst["rounds"] < max_new
+    B.ax_lut_free(lut)
+    B.ax_kv_free(kv)
+    dm.close()
+
+
+def test_exspec_loop_is_lossless_on_the_gpu(B):
+    """Whatever the table holds (here: built from unrelated text, non-selective, so mostly wrong
+    drafts), the loop emits the GPU's own one-token-at-a-time greedy stream."""
+    sh = SMALL["f32-hd32"]
+    w = I.make_weights(sh, 22)
+    prompt = I.templated_prompt(sh.vocab, 22, 60)
+    dm = B.DeviceModel(sh, w, max_pos=512, max_tokens=128, pool_tokens=1024)
+    kv = dm.new_kv()
+    pending = int(dm.extend(kv, prompt, B.AX_OUT_LAST_ARGMAX).cpu().numpy()[0])
+    base = B.ax_kv_fork(kv)
+    plain, tok = [], pending
+    for _ in range(30):
+        _, tok = dm.verify(base, tok, [])
+        plain.append(tok)
+    lut = B.ax_lut_build(I.zipf_tokens(sh.vocab, 5, "other", 500), 2, sh.vocab)
+    got, st = B.ax_exspec_generate(dm.model, kv, lut, prompt, pending, 30, 5, False, seed=1, stream=dm.stream)
+    print("stats", st)
+    assert got == plain and st["drafted"] > 0
+    assert B.ax_exspec_generate(dm.model, kv, lut, prompt, got[-1], 0, 5, stream=dm.stream)[0] == []
+    B.ax_lut_free(lut)
+    B.ax_kv_free(base)
+    B.ax_kv_free(kv)
+    dm.close()

@@ -421,3 +421,62 @@ def test_pins_catch_planted_mistakes(mistake, monkeypatch):
         bad = O.forward(sh, w, I.zipf_tokens(sh.vocab, 51, "p", 12), new_kv(sh))
     ref = torch_forward(sh, w, I.zipf_tokens(sh.vocab, 51, "p", 12))
     assert np.abs(bad - ref).max() > 1e-8
+
+
+# ------------------------------------------------------------------ n-gram drafter (Sec. 4.3)
+
+def _lut_example():
+    ex = {"entry": []}
+    for line in open(os.path.join(GOLDEN, "ngram_lut_example.txt")):
+        if line.startswith("#") or ":" not in line:
+            continue
+        k, v = line.split(":")
+        vals = [int(t) for t in v.split()]
+        if k == "entry":
+            ex["entry"].append(vals)
+        else:
+            ex[k] = vals
+    return ex
+
+
+def test_ngram_lut_matches_hand_worked_example():
+    from oracle import exspec as X
+    ex = _lut_example()
+    lut = X.build_lut(ex["stream"], ex["n"][0])
+    assert lut == {tuple(e[:-1]): e[-1] for e in ex["entry"]}
+    d, hits = X.draft(lut, 3, ex["context"], 4, True, 100, 0, 0)
+    assert d == ex["drafts"] and hits == 4
+    assert X.draft(lut, 3, ex["miss_context"], 4, True, 100, 0, 0) == ([], 0)
+    # non-selective: a miss still produces k (random) drafts; a later hit is used again
+    d2, hits2 = X.draft(lut, 3, ex["miss_context"], 4, False, 100, 5, 0)
+    assert len(d2) == 4 and hits2 <= 3 and d2[0] == X.splitmix64(5) % 100
+    # too little context is a miss, n = 1 proposes the most frequent token of the stream
+    assert X.draft(lut, 3, [7], 2, True, 100, 0, 0) == ([], 0)
+    uni = X.build_lut(ex["stream"], 1)
+    assert uni == {(): 3}
+    assert X.splitmix64(0) == 0xE220A8397B1DCDAF          # published first output for seed 0
+
+
+@pytest.mark.parametrize("selective", [True, False])
+def test_exspec_stream_equals_greedy_and_counts_drafts(selective):
+    """The decode loop emits exactly the greedy stream (accuracy preservation); a table built
+    from the greedy continuation itself predicts most of it, a table built from unrelated text
+    predicts nothing; accuracy = accepted / drafted."""
+    from oracle import exspec as X
+    sh = small_shape(vocab=61)
+    w = I.make_weights(sh, 71)
+    prompt = I.templated_prompt(sh.vocab, 71, 40)
+    kv = new_kv(sh)
+    first = O.argmax_lowest(O.forward(sh, w, prompt, kv)[-1])
+    greedy = O.greedy_decode(sh, w, kv.fork(), first, 48)
+    good = X.build_lut(list(prompt) + [first] + greedy, 3)
+    out, st = X.generate(sh, w, kv.fork(), good, 3, prompt, first, 48, 4, selective, seed=9)
+    assert out == greedy
+    assert st["accepted"] > 0 and st["drafted"] >= st["accepted"] and st["rounds"] < 48
+    bad = X.build_lut(I.zipf_tokens(sh.vocab, 72, "other", 30) + 0, 3)
+    out2, st2 = X.generate(sh, w, kv.fork(), bad, 3, prompt, first, 20, 4, selective, seed=9)
+    assert out2 == greedy[:20]
+    if selective:
+        assert st2["fallbacks"] >= 1
+    else:
+        assert st2["fallbacks"] <= 1 and st2["drafted"] > 0     # only the last round (0 drafts left) falls back
