@@ -397,7 +397,7 @@ def test_exspec_loop_equals_oracle_loop(B, which, selective):
     ref_lut = X.build_lut(stream, n)
     lut = B.ax_lut_build(stream, n, sh.vocab)
     assert B.ax_lut_size(lut) == len(ref_lut)
-    want, wst = X.generate(sh, w, ref_kv, ref_lut, n, prompt, pending, max_new, k, selective, seed=3, stream=dm.stream)
+    want, wst = X.generate(sh, w, ref_kv, ref_lut, n, prompt, pending, max_new, k, selective, seed=3)
     assert want == greedy                                     # the oracle loop itself is lossless
     got, gst = B.ax_exspec_generate(dm.model, kv, lut, prompt, pending, max_new, k, selective, seed=3, stream=dm.stream)
     print(which, "selective", selective, "stats", gst, "oracle", wst, "safe prefix", safe)
