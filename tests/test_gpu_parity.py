@@ -370,7 +370,8 @@ def test_exspec_loop_equals_oracle_loop(B, which, selective):
     """The library's draft-verify-rollback loop against the oracle's loop: same tokens, same
     round / fallback / drafted / accepted counts.  The table is built from the prompt plus a
     partly corrupted copy of the model's own greedy continuation, so rounds hit, miss and are
-    partially accepted.  Compared up to the first token whose oracle top-2 margin is <= MARGIN."""
+    partially accepted.  A first differing token is tolerated only where the oracle's top-2
+    margin is <= MARGIN; otherwise tokens and counts are identical."""
     from oracle import exspec as X
     sh = SMALL[which]
     w = I.make_weights(sh, 21)
@@ -388,7 +389,6 @@ def test_exspec_loop_equals_oracle_loop(B, which, selective):
         tok = O.argmax_lowest(lg)
         greedy.append(tok)
         margins.append(O.top2_margin(lg))
-    safe = next((i for i, m in enumerate(margins) if m <= MARGIN), max_new)
     rng = np.random.default_rng(21)
     example = np.array([pending] + greedy[:40])
     bad = rng.random(len(example)) < 0.15
@@ -400,10 +400,12 @@ def test_exspec_loop_equals_oracle_loop(B, which, selective):
     want, wst = X.generate(sh, w, ref_kv, ref_lut, n, prompt, pending, max_new, k, selective, seed=3)
     assert want == greedy                                     # the oracle loop itself is lossless
     got, gst = B.ax_exspec_generate(dm.model, kv, lut, prompt, pending, max_new, k, selective, seed=3, stream=dm.stream)
-    print(which, "selective", selective, "stats", gst, "oracle", wst, "safe prefix", safe)
-    assert got[:safe] == want[:safe]
-    if safe == max_new:
-        assert got == want and gst == wst
+    diff = next((i for i in range(max_new) if got[i] != want[i]), None)
+    print(which, "selective", selective, "stats", gst, "oracle", wst, "first difference", diff)
+    if diff is not None:                                      # only a near-tie may decide differently
+        assert margins[diff] <= MARGIN, (diff, margins[diff])
+    else:
+        assert gst == wst
         assert B.ax_kv_len(kv) == len(prompt) + max_new
         assert 0 < gst["accepted"] < gst["drafted"] and gst["rounds"] < max_new
     B.ax_lut_free(lut)
