@@ -177,6 +177,15 @@ ax_status ax_extend_batch(ax_model *model, int n, ax_kv *const *kvs, const int32
 ax_status ax_verify(ax_model *model, ax_kv *kv, int32_t pending, const int32_t *drafts, int k,
                     int *accepted, int32_t *next_token, void *hip_stream);
 
+/* ax_verify over n sequences of one pool in a single forward (paper Sec. 3.2: several agent
+ * sessions decode concurrently; Sec. 4.3 for the round itself): sequence s contributes the rows
+ * [pending[s], its k_each[s] drafts] (drafts_concat holds the drafts back to back; host memory),
+ * the weights are streamed once for all sum(1 + k_s) rows, acceptance and rollback are per
+ * sequence.  accepted[s], next_token[s] (host) as in ax_verify.  All or nothing on errors. */
+ax_status ax_verify_batch(ax_model *model, int n, ax_kv *const *kvs, const int32_t *pending,
+                          const int32_t *drafts_concat, const int *k_each, int *accepted,
+                          int32_t *next_token, void *hip_stream);
+
 /* ---- example-based drafter and decode loop (paper Sec. 4.3) -------------------------------------
  * A per-query n-gram lookup table: a window of n tokens slides over `stream` (the few-shot
  * examples followed by the user query; host memory) one token at a time; the first n-1 tokens

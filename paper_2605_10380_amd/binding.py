@@ -73,6 +73,7 @@ def _load():
         "ax_dbg_profile": (C.c_int, [vp, C.c_int]),
         "ax_dbg_profile_read": (C.c_int, [vp, C.POINTER(C.c_double), C.POINTER(i64)]),
         "ax_verify": (C.c_int, [vp, vp, C.c_int32, i32p, C.c_int, C.POINTER(C.c_int), i32p, vp]),
+        "ax_verify_batch": (C.c_int, [vp, C.c_int, C.POINTER(vp), i32p, i32p, C.POINTER(C.c_int), C.POINTER(C.c_int), i32p, vp]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -214,6 +215,21 @@ def ax_verify(model: int, kv: int, pending: int, drafts, stream: int = 0):
     _check(lib.ax_verify(model, kv, int(pending), dp if len(d) else None, len(d), C.byref(a), C.byref(nxt),
                          C.c_void_p(stream)))
     return a.value, nxt.value
+
+
+def ax_verify_batch(model: int, kvs, pending, drafts_each, stream: int = 0):
+    """drafts_each: one list of drafts per sequence.  Returns ([accepted], [next token])."""
+    n = len(kvs)
+    p, pp = _i32(pending)
+    flat = [int(t) for d in drafts_each for t in d]
+    d, dp = _i32(flat)
+    ke = (C.c_int * n)(*[len(d_) for d_ in drafts_each])
+    ka = (C.c_void_p * n)(*kvs)
+    acc = (C.c_int * n)()
+    nxt = np.zeros(n, dtype=np.int32)
+    _check(lib.ax_verify_batch(model, n, ka, pp, dp if len(d) else None, ke, acc, nxt.ctypes.data_as(C.POINTER(C.c_int32)),
+                               C.c_void_p(stream)))
+    return list(acc), nxt.tolist()
 
 
 # ------------------------------------------------------------------ example-based drafter (host) and decode loop
@@ -371,6 +387,9 @@ class DeviceModel:
 
     def verify(self, kv: int, pending: int, drafts):
         return ax_verify(self.model, kv, pending, drafts, self.stream)
+
+    def verify_batch(self, kvs, pending, drafts_each):
+        return ax_verify_batch(self.model, list(kvs), pending, drafts_each, self.stream)
 
     def close(self):
         if self.model:

@@ -95,7 +95,7 @@ Layout make_layout(const ax_model_config& c) {
     L.logits = take(std::min<size_t>(T, LOGIT_ROWS) * (size_t)c.vocab * 4);
     L.amax_scratch = take(2 * std::min<size_t>(T, LOGIT_ROWS) * ax::ARGMAX_PARTS * 4);
     L.amax_out = take(T * 4);
-    L.result = take(64);
+    L.result = take(align_up(8 * S));
     L.total = o;
     return L;
 }
@@ -455,8 +455,8 @@ ax_status enqueue_call(ax_model* m, const CallPlan& cp, void* out, hipStream_t s
     }
     if (verify_k >= 0) {
         int* res = (int*)(ws + L.result);
-        ax::launch_accept((const int*)out, sv.row_tok, verify_k, res, stream);
-        HIP_TRY(hipMemcpyAsync(host_result, res, 2 * sizeof(int), hipMemcpyDeviceToHost, stream));
+        ax::launch_accept((const int*)out, sv, res, stream);
+        HIP_TRY(hipMemcpyAsync(host_result, res, 2 * sizeof(int) * (size_t)cp.n, hipMemcpyDeviceToHost, stream));
     }
     if (!capturing) {
         HIP_TRY(hipGetLastError());
@@ -569,7 +569,7 @@ ax_status ax_model_create(const ax_model_config* cfg, const ax_weights* w, void*
         if (m->stage) (void)hipHostFree(m->stage);
         delete m;
     };
-    hipError_t e = hipHostMalloc((void**)&m->stage, ((N_SLOTS + 1) * m->slot_ints + 16) * sizeof(int), hipHostMallocDefault);
+    hipError_t e = hipHostMalloc((void**)&m->stage, ((N_SLOTS + 1) * m->slot_ints + 2 * (size_t)cfg->max_seqs + 16) * sizeof(int), hipHostMallocDefault);
     if (e != hipSuccess) { m->stage = nullptr; cleanup(); return fail(AX_ERR_DEVICE, "hipHostMalloc: %s", hipGetErrorString(e)); }
     for (auto& ev : m->slot_done) {
         e = hipEventCreateWithFlags(&ev, hipEventDisableTiming);
@@ -773,6 +773,49 @@ ax_status ax_verify(ax_model* model, ax_kv* kv, int32_t pending, const int32_t* 
     *accepted = a;
     *next_token = host_res[1];
     ax::truncate(kv->pool->blocks, kv->seq, P + 1 + a);                    // rollback of rejected drafts
+    return AX_OK;
+}
+
+ax_status ax_verify_batch(ax_model* model, int n, ax_kv* const* kvs, const int32_t* pending, const int32_t* drafts_concat,
+                          const int* k_each, int* accepted, int32_t* next_token, void* hip_stream) {
+    if (!ok(model)) return fail(AX_ERR_INVALID, "bad model handle");
+    if (n <= 0 || n > model->cfg.max_seqs) return fail(AX_ERR_INVALID, "n_seq %d outside 1..%d", n, model->cfg.max_seqs);
+    if (!kvs || !pending || !k_each || !accepted || !next_token) return fail(AX_ERR_INVALID, "NULL argument");
+    std::vector<int32_t> toks;
+    std::vector<int> T((size_t)n);
+    std::vector<int64_t> P((size_t)n);
+    long long nd = 0;
+    for (int s = 0; s < n; ++s) {
+        if (!ok(kvs[s])) return fail(AX_ERR_INVALID, "bad KV handle (sequence %d)", s);
+        if (k_each[s] < 0) return fail(AX_ERR_INVALID, "k < 0 (sequence %d)", s);
+        nd += k_each[s];
+    }
+    if (nd > 0 && !drafts_concat) return fail(AX_ERR_INVALID, "drafts is NULL");
+    if (nd + n > model->cfg.max_tokens) return fail(AX_ERR_INVALID, "sum of 1 + k exceeds max_tokens");
+    const int32_t* dr = drafts_concat;
+    for (int s = 0; s < n; ++s) {
+        toks.push_back(pending[s]);
+        toks.insert(toks.end(), dr, dr + k_each[s]);
+        dr += k_each[s];
+        T[(size_t)s] = 1 + k_each[s];
+        P[(size_t)s] = kvs[s]->seq.len;
+    }
+    auto undo = [&]() {
+        for (int s = 0; s < n; ++s)
+            if (kvs[s]->seq.len != P[(size_t)s]) ax::truncate(kvs[s]->pool->blocks, kvs[s]->seq, P[(size_t)s]);
+    };
+    int* host_res = model->stage + (N_SLOTS + 1) * model->slot_ints;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    ax_status st = run_extend(model, n, kvs, toks.data(), T.data(), AX_OUT_ALL_ARGMAX, model->ws + model->lay.amax_out,
+                              stream, 0, host_res);
+    if (st != AX_OK) { undo(); return st; }
+    hipError_t e = hipStreamSynchronize(stream);
+    if (e != hipSuccess) { undo(); return fail(AX_ERR_DEVICE, "hipStreamSynchronize: %s", hipGetErrorString(e)); }
+    for (int s = 0; s < n; ++s) {
+        accepted[s] = host_res[2 * s];
+        next_token[s] = host_res[2 * s + 1];
+        ax::truncate(kvs[s]->pool->blocks, kvs[s]->seq, P[(size_t)s] + 1 + accepted[s]);
+    }
     return AX_OK;
 }
 

@@ -202,26 +202,29 @@ void launch_argmax(const float* logits, int rows, int V, int* out, int* scratch,
 }
 
 // ---------------------------------------------------------------- greedy draft acceptance
-// One wavefront: lane i < k votes drafts[i] == g[i]; the accepted length is the position of
-// the first lane whose vote is false (ballot + count trailing ones).
-__global__ void accept_kernel(const int* __restrict__ g, const int* __restrict__ row_tok, int k,
+// One wavefront per sequence: its rows are [pending, drafts...], g holds the greedy token after
+// each row.  Lane i < k votes drafts[i] == g[i]; the accepted length is the position of the
+// first lane whose vote is false (ballot + find-first-set).
+__global__ void accept_kernel(const int* __restrict__ g, const int* __restrict__ row_tok,
+                              const int* __restrict__ seq_row0, const int* __restrict__ seq_T,
                               int* __restrict__ result) {
-    const int lane = threadIdx.x;
+    const int lane = threadIdx.x, s = blockIdx.x;
+    const int row0 = seq_row0[s], k = seq_T[s] - 1;
     int a = 0;
     for (int base = 0; base < k; base += 64) {           // k > 64 only in principle
         const int i = base + lane;
-        const bool ok = (i < k) && (row_tok[1 + i] == g[i]);
+        const bool ok = (i < k) && (row_tok[row0 + 1 + i] == g[row0 + i]);
         const unsigned long long mism = ~__ballot(ok);
         const int first_bad = __ffsll((long long)mism) - 1;   // 0..63, or -1 if none
         if (first_bad >= 0) { a = base + first_bad; break; }
         a = base + 64;
     }
     if (a > k) a = k;
-    if (lane == 0) { result[0] = a; result[1] = g[a]; }
+    if (lane == 0) { result[2 * s] = a; result[2 * s + 1] = g[row0 + a]; }
 }
 
-void launch_accept(const int* g, const int* row_tok, int k, int* result, hipStream_t s) {
-    accept_kernel<<<1, 64, 0, s>>>(g, row_tok, k, result);
+void launch_accept(const int* g, const StepView& sv, int* result, hipStream_t s) {
+    accept_kernel<<<sv.n_seq, 64, 0, s>>>(g, sv.row_tok, sv.seq_row0, sv.seq_T, result);
 }
 
 // ---------------------------------------------------------------- copy-on-write block copy

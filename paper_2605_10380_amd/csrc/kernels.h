@@ -111,9 +111,10 @@ size_t attention_partial_floats(int n_tiles, int n_kv_heads, int head_dim, int n
 // out[r] = argmax of logits[r, 0..V), lowest index on ties.  scratch: 2*rows*ARGMAX_PARTS ints.
 constexpr int ARGMAX_PARTS = 64;
 void launch_argmax(const float* logits, int rows, int V, int* out, int* scratch, hipStream_t s);
-// Greedy acceptance: g[0..k] greedy tokens after each verify row, row_tok[1..k] the drafts.
-// result[0] = a (longest prefix with drafts[i] == g[i]), result[1] = g[a].
-void launch_accept(const int* g, const int* row_tok, int k, int* result, hipStream_t s);
+// Greedy acceptance per sequence of a verify call: the sequence's rows are [pending, drafts],
+// g[row] the greedy token after each row.  result[2s] = a (longest prefix of the drafts equal to
+// g), result[2s + 1] = g[row0 + a].
+void launch_accept(const int* g, const StepView& sv, int* result, hipStream_t s);
 // Plain copy of n16 16-byte words (calibration kernel for hardware counters).
 void launch_plain_copy(void* dst, const void* src, size_t n16, hipStream_t s);
 // Copy one KV block (all layers, K and V, all heads) src -> dst: copy on write.

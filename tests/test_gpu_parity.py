@@ -436,3 +436,149 @@ def test_exspec_loop_is_lossless_on_the_gpu(B):
     B.ax_kv_free(base)
     B.ax_kv_free(kv)
     dm.close()
+
+
+# ------------------------------------------------------------------ batched verify, two resident models
+
+def _batched_rounds(B, dm, sh, w, kvs, refs, pend, rounds, k_of, seed):
+    """`rounds` batched verify rounds over the sessions; drafts carry a seeded number of the
+    oracle's own greedy tokens.  Every session's (accepted, next) must equal the oracle's unless
+    the oracle's deciding row is a near-tie, in which case the session is re-synchronised."""
+    exempt = 0
+    accepted_total = 0
+    for r in range(rounds):
+        drafts, want = [], []
+        for s, ref in enumerate(refs):
+            k = k_of(r, s)
+            g = O.greedy_decode(sh, w, ref.fork(), pend[s], k) if k else []
+            d = I.seeded_accept_drafts(np.array(g), sh.vocab, seed, 100 * r + s, k)[0] if k else np.zeros(0, np.int32)
+            drafts.append([int(t) for t in d])
+        P = [len(ref) for ref in refs]
+        acc, nxt = dm.verify_batch(kvs, pend, drafts)
+        for s, ref in enumerate(refs):
+            a_ref, n_ref, logits = O.verify(sh, w, ref, pend[s], drafts[s])
+            assert B.ax_kv_len(kvs[s]) == P[s] + 1 + acc[s]
+            if (acc[s], nxt[s]) != (a_ref, n_ref):
+                assert O.top2_margin(logits[min(acc[s], a_ref)]) <= MARGIN, (r, s, acc[s], a_ref, nxt[s], n_ref)
+                exempt += 1
+                if acc[s] > a_ref:
+                    B.ax_kv_truncate(kvs[s], P[s] + 1 + a_ref)
+                elif acc[s] < a_ref:
+                    dm.extend(kvs[s], np.asarray(drafts[s][acc[s]:a_ref], dtype=np.int32))
+            pend[s] = n_ref
+            accepted_total += a_ref
+    return accepted_total, exempt
+
+
+@pytest.mark.parametrize("which", ["bf16-hd64-g4", "bf16-hd128-g3", "f32-hd32"])
+def test_batched_verify_mixed_k(B, which):
+    """Sessions with different cached lengths and draft counts (0 included) verified in one
+    forward: per-session acceptance and rollback equal the oracle's."""
+    sh = SMALL[which]
+    w = I.make_weights(sh, 31)
+    prefix = I.templated_prompt(sh.vocab, 31, 70)
+    dm = B.DeviceModel(sh, w, max_pos=512, max_tokens=128, pool_tokens=4096, max_seqs=5)
+    root = dm.new_kv()
+    dm.extend(root, prefix)
+    kvs, refs, pend = [], [], []
+    for s, hl in enumerate([0, 13, 37, 90, 1]):
+        kv, ref = B.ax_kv_fork(root, -1), okv(sh)
+        h = np.concatenate([prefix, I.zipf_tokens(sh.vocab, 31, f"h{s}", hl)]).astype(np.int32)
+        if hl:
+            dm.extend(kv, h[70:])
+        pend.append(O.argmax_lowest(O.forward(sh, w, h, ref)[-1]))
+        kvs.append(kv)
+        refs.append(ref)
+    ks = [[8, 0, 3, 16, 1], [0, 0, 0, 0, 0], [4, 4, 4, 4, 4], [1, 16, 0, 2, 9]]
+    total, exempt = _batched_rounds(B, dm, sh, w, kvs, refs, pend, 4, lambda r, s: ks[r][s], 31)
+    print(which, "accepted", total, "exempt", exempt)
+    assert total > 0 and exempt <= 4
+    # a batch of one equals the single-sequence call
+    f = B.ax_kv_fork(kvs[0], -1)
+    d = [int(t) for t in I.zipf_tokens(sh.vocab, 31, "d", 5)]
+    one = dm.verify(kvs[0], pend[0], d)
+    acc, nxt = dm.verify_batch([f], [pend[0]], [d])
+    assert (acc[0], nxt[0]) == one and B.ax_kv_len(f) == B.ax_kv_len(kvs[0])
+    # all or nothing: a bad draft token in the last session leaves every session as it was
+    lens = [B.ax_kv_len(kv) for kv in kvs]
+    with pytest.raises(B.AxError):
+        dm.verify_batch(kvs, pend, [[1], [2], [3], [4], [sh.vocab]])
+    assert [B.ax_kv_len(kv) for kv in kvs] == lens
+    for kv in kvs + [root, f]:
+        B.ax_kv_free(kv)
+    dm.close()
+
+
+def test_two_resident_models_forked_sessions(B):
+    """The plan-out agent's shape at a size the oracle can follow: two decoders with their own
+    weights and pools resident together; per model, sessions fork one shared prefix, build
+    private histories, then interleave batched mixed-length extends with batched verify rounds
+    at k = 8.  Forks must not disturb each other or the shared prefix (copy on write)."""
+    sh = SMALL["bf16-hd64-g4"]
+    models = []
+    for mi in range(2):
+        w = I.make_weights(sh, 500 + mi)
+        dm = B.DeviceModel(sh, w, max_pos=1024, max_tokens=512, pool_tokens=8192, max_seqs=6)
+        prefix = I.templated_prompt(sh.vocab, 500 + mi, 200)          # ends inside a block: forks copy on write
+        root, root_ref = dm.new_kv(), okv(sh)
+        dm.extend(root, prefix)
+        O.forward(sh, w, prefix, root_ref)
+        kvs, refs = [], []
+        for s in range(6):
+            kv, ref = B.ax_kv_fork(root, -1), root_ref.fork()
+            kvs.append(kv)
+            refs.append(ref)
+        models.append((dm, w, root, root_ref, kvs, refs, prefix))
+    rng = np.random.default_rng(5)
+    pend = [[0] * 6, [0] * 6]
+    for step in range(3):
+        for mi, (dm, w, root, root_ref, kvs, refs, prefix) in enumerate(models):      # interleave the two models
+            T_each = [int(rng.integers(2, 80)) for _ in kvs]
+            news = [I.zipf_tokens(sh.vocab, 500 + mi, f"s{step}-{s}", T_each[s]) for s in range(6)]
+            got = dm.extend_batch(kvs, news, B.AX_OUT_LAST_LOGITS).cpu().numpy()
+            for s in range(6):
+                ref = O.forward(sh, w, news[s], refs[s])
+                check_logits(sh, got[s], ref[-1], f"model {mi} step {step} session {s}")
+                pend[mi][s] = O.argmax_lowest(ref[-1])
+            total, exempt = _batched_rounds(B, dm, sh, w, kvs, refs, pend[mi], 2, lambda r, s: 8, 500 + mi)
+            assert exempt <= 3
+    for dm, w, root, root_ref, kvs, refs, prefix in models:
+        # the shared prefix is intact: extending a fresh fork of it reproduces the oracle
+        f, fr = B.ax_kv_fork(root, -1), root_ref.fork()
+        t = I.zipf_tokens(sh.vocab, 9, "probe", 20)
+        check_logits(sh, dm.extend(f, t, B.AX_OUT_ALL_LOGITS).cpu().numpy(), O.forward(sh, w, t, fr), "shared prefix probe")
+        for kv in kvs + [root, f]:
+            B.ax_kv_free(kv)
+        free, total_blocks, live = B.ax_pool_stats(dm.pool)
+        assert free == total_blocks and live == 0
+        dm.close()
+
+
+def test_full_width_3b_batched_sessions(B):
+    """The ~3B per-layer shape (two layers): four sessions over a shared 1024-token prefix with
+    private histories, one batched extend and batched verify rounds at k = 8 - the launch shapes
+    of the two-model workload at a depth the oracle finishes."""
+    sh = I.SHAPES["3b"].with_layers(2)
+    w = I.make_weights(sh, 5005)
+    prefix = I.templated_prompt(sh.vocab, 5005, 1024)
+    dm = B.DeviceModel(sh, w, max_pos=4096, max_tokens=1024, pool_tokens=8192, max_seqs=4)
+    root, root_ref = dm.new_kv(), okv(sh)
+    for at in range(0, 1024, 512):
+        dm.extend(root, prefix[at:at + 512])
+    O.forward(sh, w, prefix, root_ref)
+    kvs, refs, pend = [], [], [0] * 4
+    T_each = [300, 32, 150, 77]
+    news = [I.zipf_tokens(sh.vocab, 5005, f"n{s}", T_each[s]) for s in range(4)]
+    for s in range(4):
+        kvs.append(B.ax_kv_fork(root, -1))
+        refs.append(root_ref.fork())
+    got = dm.extend_batch(kvs, news, B.AX_OUT_LAST_LOGITS).cpu().numpy()
+    for s in range(4):
+        ref = O.forward(sh, w, news[s], refs[s])
+        check_logits(sh, got[s], ref[-1], f"3b session {s}")
+        pend[s] = O.argmax_lowest(ref[-1])
+    total, exempt = _batched_rounds(B, dm, sh, w, kvs, refs, pend, 2, lambda r, s: 8, 5005)
+    print("3b batched: accepted", total, "exempt", exempt)
+    for kv in kvs + [root]:
+        B.ax_kv_free(kv)
+    dm.close()
