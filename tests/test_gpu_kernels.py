@@ -20,9 +20,11 @@ def torch_cuda():
 
 
 # M values: skinny path (<= 64, MT 1/2/4, ragged) and tile path (> 64, ragged); K / N pick
-# different wavefront counts in the skinny kernel and both tile shapes
+# different wavefront counts in the skinny kernel and both tile shapes; M >= 384 takes the
+# streaming SwiGLU kernel (steady-state loop and drain, ragged rows and columns)
 GEMM_CASES = [(1, 64, 64), (9, 3072, 2048), (9, 2048, 8192), (17, 512, 256), (33, 128, 1024), (64, 2064, 192),
-              (65, 384, 128), (100, 200 * 16, 320), (256, 3072, 2048), (300, 1024, 512), (512, 33 * 128, 256)]
+              (65, 384, 128), (100, 200 * 16, 320), (256, 3072, 2048), (300, 1024, 512), (512, 33 * 128, 256),
+              (400, 1040, 1024), (384, 2048, 576)]
 
 
 @pytest.mark.parametrize("M,N,K", GEMM_CASES)
