@@ -582,3 +582,47 @@ def test_full_width_3b_batched_sessions(B):
     for kv in kvs + [root]:
         B.ax_kv_free(kv)
     dm.close()
+
+
+# ------------------------------------------------------------------ the benchmark workload at full depth
+
+@pytest.mark.timeout(1200)
+def test_config2_full_depth_extend_and_verify(B):
+    """The ~1B decoder with all 16 layers at the benchmark's sizes and launch configuration:
+    prefix P = 4096 built in chunks of 512, the extend of T = 256 compared on every logit of
+    every row, then verify rounds at k = 8 (prompt-copied drafts, then drafts carrying a seeded
+    number of the oracle's greedy tokens) compared on accepted length and next token."""
+    wl = I.WORKLOADS[2]
+    sh = wl.shape
+    w = I.make_weights(sh, 2000)
+    prompt = I.templated_prompt(sh.vocab, 2000, wl.P + wl.T)
+    dm = B.DeviceModel(sh, w, max_pos=wl.P + wl.T + 1024, max_tokens=512, pool_tokens=wl.P + wl.T + 1024)
+    kv, ref_kv = dm.new_kv(), okv(sh)
+    for at in range(0, wl.P, 512):
+        dm.extend(kv, prompt[at:at + 512])
+    for at in range(0, wl.P, 1024):                     # the oracle's prefix, in pieces to bound its memory
+        O.forward(sh, w, prompt[at:at + 1024], ref_kv, rows=[-1])
+        print(f"oracle prefix {at + 1024}/{wl.P}", flush=True)
+    got = dm.extend(kv, prompt[wl.P:], B.AX_OUT_ALL_LOGITS).cpu().numpy()
+    ref = O.forward(sh, w, prompt[wl.P:], ref_kv)
+    check_logits(sh, got, ref, f"config 2 full depth, extend T={wl.T} over P={wl.P}")
+    B.ax_kv_truncate(kv, wl.P)
+    am = dm.extend(kv, prompt[wl.P:], B.AX_OUT_ALL_ARGMAX).cpu().numpy()
+    assert_argmax_of(am, got)
+    pending = O.argmax_lowest(ref[-1])
+    hist, exempt, pending = run_verify_rounds(B, dm, sh, w, kv, ref_kv, pending, 3, wl.k,
+                                              lambda r, _kv, _p: I.prompt_copied_drafts(prompt, 2000, r, wl.k))
+    print("prompt-copied drafts: accepted", hist, "exempt", exempt, flush=True)
+    greedy = O.greedy_decode(sh, w, ref_kv.fork(), pending, 3 * (wl.k + 1) + wl.k)
+    base = len(ref_kv)
+
+    def drafts(r, kv_now, p):
+        at = len(kv_now) - base
+        return I.seeded_accept_drafts(np.array(greedy[at:at + wl.k]), sh.vocab, 2000, r, wl.k)[0]
+
+    hist2, exempt2, _ = run_verify_rounds(B, dm, sh, w, kv, ref_kv, pending, 3, wl.k, drafts)
+    print("seeded drafts: accepted", hist2, "exempt", exempt2, flush=True)
+    assert sum(hist2) > 0 and exempt + exempt2 <= 2
+    B.ax_kv_free(kv)
+    dm.close()
+    O.clear_widen_cache()
