@@ -186,6 +186,26 @@ ax_status ax_verify_batch(ax_model *model, int n, ax_kv *const *kvs, const int32
                           const int32_t *drafts_concat, const int *k_each, int *accepted,
                           int32_t *next_token, void *hip_stream);
 
+/* ---- KV images: precomputed prefixes kept outside the pool (paper Sec. 4.2, Sec. 5: the KV of
+ * the static prefix and of the selected cluster combinations is computed offline, kept on
+ * storage and loaded on demand).  An image is a 64-byte header (magic "AXKV", version, layers,
+ * KV heads, head_dim, dtype, block size, token count, payload size) followed by the sequence's
+ * blocks in logical order, each exactly as it lies in the pool; it depends on the cached values
+ * only (not on block ids; the unused slots of the last block are zero).  `image` must be memory
+ * the GPU can address - pinned host memory (hipHostMalloc, a pinned torch tensor: the staging
+ * buffer of a file read or write) or device memory - because a kernel gathers / scatters the
+ * blocks directly; other pointers are rejected with AX_ERR_INVALID.  The model lends its
+ * descriptor ring; pool and model geometry must match. */
+int64_t ax_kv_image_bytes(const ax_pool *p, int64_t n_tokens);          /* -1 on bad arguments */
+/* Writes the image of the first n_tokens (-1 = all) of kv; returns after the image is complete. */
+ax_status ax_kv_export(ax_model *model, const ax_kv *kv, int64_t n_tokens, void *image,
+                       int64_t image_bytes, void *hip_stream);
+/* Creates a sequence in `pool` holding the image's tokens.  Only enqueues: the image must stay
+ * valid and unchanged until the stream has passed the copy; later calls on the same stream see
+ * the imported values.  AX_ERR_OOM (nothing changed) if the pool lacks the blocks. */
+ax_status ax_kv_import(ax_model *model, ax_pool *pool, const void *image, int64_t image_bytes,
+                       ax_kv **out, void *hip_stream);
+
 /* ---- example-based drafter and decode loop (paper Sec. 4.3) -------------------------------------
  * A per-query n-gram lookup table: a window of n tokens slides over `stream` (the few-shot
  * examples followed by the user query; host memory) one token at a time; the first n-1 tokens

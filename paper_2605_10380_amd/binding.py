@@ -59,6 +59,9 @@ def _load():
         "ax_kv_reserve_host": (C.c_int, [vp, i64, i32p, i32p]),
         "ax_extend": (C.c_int, [vp, vp, i32p, C.c_int, C.c_int, vp, vp]),
         "ax_extend_batch": (C.c_int, [vp, C.c_int, C.POINTER(vp), i32p, C.POINTER(C.c_int), C.c_int, vp, vp]),
+        "ax_kv_image_bytes": (i64, [vp, i64]),
+        "ax_kv_export": (C.c_int, [vp, vp, i64, vp, i64, vp]),
+        "ax_kv_import": (C.c_int, [vp, vp, vp, i64, C.POINTER(vp), vp]),
         "ax_lut_build": (C.c_int, [i32p, i64, C.c_int, C.c_int, C.POINTER(vp)]),
         "ax_lut_free": (None, [vp]),
         "ax_lut_size": (i64, [vp]),
@@ -215,6 +218,20 @@ def ax_verify(model: int, kv: int, pending: int, drafts, stream: int = 0):
     _check(lib.ax_verify(model, kv, int(pending), dp if len(d) else None, len(d), C.byref(a), C.byref(nxt),
                          C.c_void_p(stream)))
     return a.value, nxt.value
+
+
+def ax_kv_image_bytes(pool: int, n_tokens: int) -> int:
+    return lib.ax_kv_image_bytes(pool, n_tokens)
+
+
+def ax_kv_export(model: int, kv: int, n_tokens: int, image_ptr: int, image_bytes: int, stream: int = 0):
+    _check(lib.ax_kv_export(model, kv, n_tokens, C.c_void_p(image_ptr), image_bytes, C.c_void_p(stream)))
+
+
+def ax_kv_import(model: int, pool: int, image_ptr: int, image_bytes: int, stream: int = 0) -> int:
+    out = C.c_void_p()
+    _check(lib.ax_kv_import(model, pool, C.c_void_p(image_ptr), image_bytes, C.byref(out), C.c_void_p(stream)))
+    return out.value
 
 
 def ax_verify_batch(model: int, kvs, pending, drafts_each, stream: int = 0):
@@ -387,6 +404,19 @@ class DeviceModel:
 
     def verify(self, kv: int, pending: int, drafts):
         return ax_verify(self.model, kv, pending, drafts, self.stream)
+
+    def export_kv(self, kv: int, n_tokens: int = -1, device: bool = False):
+        """Image of the first n_tokens of kv as a uint8 tensor (pinned host memory, or device)."""
+        import torch
+        n = ax_kv_len(kv) if n_tokens < 0 else n_tokens
+        nbytes = ax_kv_image_bytes(self.pool, n)
+        img = (torch.empty(nbytes, dtype=torch.uint8, device="cuda") if device
+               else torch.empty(nbytes, dtype=torch.uint8, pin_memory=True))
+        ax_kv_export(self.model, kv, n_tokens, img.data_ptr(), nbytes, self.stream)
+        return img
+
+    def import_kv(self, image) -> int:
+        return ax_kv_import(self.model, self.pool, image.data_ptr(), image.numel(), self.stream)
 
     def verify_batch(self, kvs, pending, drafts_each):
         return ax_verify_batch(self.model, list(kvs), pending, drafts_each, self.stream)

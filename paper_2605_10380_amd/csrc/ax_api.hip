@@ -776,6 +776,149 @@ ax_status ax_verify(ax_model* model, ax_kv* kv, int32_t pending, const int32_t* 
     return AX_OK;
 }
 
+// ---- KV images -------------------------------------------------------------------------------
+
+namespace {
+
+struct ImageHeader {                  // 64 bytes, little endian
+    uint32_t magic, version;
+    int32_t n_layers, n_kv_heads, head_dim, dtype, block_tokens, reserved;
+    int64_t n_tokens, payload_bytes;
+    int64_t pad[2];
+};
+static_assert(sizeof(ImageHeader) == 64, "image header is 64 bytes");
+constexpr uint32_t IMAGE_MAGIC = 0x564b5841;   // "AXKV"
+
+// The image is read or written by a kernel: only memory the GPU can address will do.
+ax_status device_view(const void* p, size_t bytes, char** dev) {
+    hipPointerAttribute_t at{};
+    hipError_t e = hipPointerGetAttributes(&at, p);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(AX_ERR_INVALID, "image buffer is neither pinned host memory nor device memory");
+    }
+    if (at.type != hipMemoryTypeHost && at.type != hipMemoryTypeDevice)
+        return fail(AX_ERR_INVALID, "image buffer is neither pinned host memory nor device memory");
+    char* d = (char*)(at.type == hipMemoryTypeHost ? at.devicePointer : p);
+    if (!d) return fail(AX_ERR_INVALID, "image buffer has no device address");
+    hipDeviceptr_t base = nullptr;
+    size_t size = 0;
+    if (hipMemGetAddressRange(&base, &size, (hipDeviceptr_t)d) == hipSuccess) {
+        if (d + bytes > (char*)base + size) return fail(AX_ERR_INVALID, "image buffer is smaller than the image");
+    } else {
+        (void)hipGetLastError();
+    }
+    *dev = d;
+    return AX_OK;
+}
+
+// Uploads a sequence's block ids through the descriptor ring; returns their device address.
+ax_status upload_ids(ax_model* m, const std::vector<int32_t>& ids, hipStream_t stream, int* slot_out, const int** dev_ids) {
+    if (ids.size() > m->slot_ints) return fail(AX_ERR_INVALID, "sequence has more blocks than a descriptor slot holds");
+    const int slot = m->next_slot;
+    m->next_slot = (slot + 1) % N_SLOTS;
+    HIP_TRY(hipEventSynchronize(m->slot_done[slot]));
+    int* d = m->stage + (size_t)slot * m->slot_ints;
+    std::memcpy(d, ids.data(), ids.size() * sizeof(int));
+    int* dev_d = (int*)(m->ws + m->lay.desc) + (size_t)slot * m->slot_ints;
+    HIP_TRY(hipMemcpyAsync(dev_d, d, ids.size() * sizeof(int), hipMemcpyHostToDevice, stream));
+    *slot_out = slot;
+    *dev_ids = dev_d;
+    return AX_OK;
+}
+
+}  // namespace
+
+int64_t ax_kv_image_bytes(const ax_pool* p, int64_t n_tokens) {
+    if (!ok(p) || n_tokens < 0) return -1;
+    return (int64_t)sizeof(ImageHeader) +
+           ax::blocks_for(n_tokens, 16) * (int64_t)ax_pool_block_bytes(&p->cfg, 16);
+}
+
+ax_status ax_kv_export(ax_model* model, const ax_kv* kv, int64_t n_tokens, void* image, int64_t image_bytes,
+                       void* hip_stream) {
+    if (!ok(model)) return fail(AX_ERR_INVALID, "bad model handle");
+    if (!ok(kv)) return fail(AX_ERR_INVALID, "bad KV handle");
+    if (n_tokens < 0) n_tokens = kv->seq.len;
+    if (n_tokens > kv->seq.len)
+        return fail(AX_ERR_INVALID, "export of %lld tokens from a sequence of %lld", (long long)n_tokens, (long long)kv->seq.len);
+    const ax_pool* pool = kv->pool;
+    if (!pool->geom.base) return fail(AX_ERR_INVALID, "pool has no device memory");
+    const int64_t need = ax_kv_image_bytes(pool, n_tokens);
+    if (!image || image_bytes < need) return fail(AX_ERR_INVALID, "image buffer of %lld bytes, %lld needed", (long long)image_bytes, (long long)need);
+    char* dev = nullptr;
+    ax_status st = device_view(image, (size_t)need, &dev);
+    if (st != AX_OK) return st;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    ImageHeader h{};
+    h.magic = IMAGE_MAGIC; h.version = 1;
+    h.n_layers = pool->cfg.n_layers; h.n_kv_heads = pool->cfg.n_kv_heads; h.head_dim = pool->cfg.head_dim;
+    h.dtype = pool->cfg.dtype; h.block_tokens = 16;
+    h.n_tokens = n_tokens; h.payload_bytes = need - (int64_t)sizeof(ImageHeader);
+    HIP_TRY(hipMemcpyAsync(image, &h, sizeof h, hipMemcpyDefault, stream));
+    const int64_t nb = ax::blocks_for(n_tokens, 16);
+    if (nb > 0) {
+        std::vector<int32_t> ids(kv->seq.blocks.begin(), kv->seq.blocks.begin() + nb);
+        int slot = 0;
+        const int* dev_ids = nullptr;
+        st = upload_ids(model, ids, stream, &slot, &dev_ids);
+        if (st != AX_OK) return st;
+        ax::launch_kv_image(true, pool->cfg.dtype == AX_F32 ? ax::F32 : ax::BF16, pool->geom, pool->cfg.n_layers, dev_ids,
+                            (int)nb, dev + sizeof(ImageHeader), (int)(n_tokens - (nb - 1) * 16), stream);
+        HIP_TRY(hipGetLastError());
+        HIP_TRY(hipEventRecord(model->slot_done[slot], stream));
+    }
+    HIP_TRY(hipStreamSynchronize(stream));
+    return AX_OK;
+}
+
+ax_status ax_kv_import(ax_model* model, ax_pool* pool, const void* image, int64_t image_bytes, ax_kv** out,
+                       void* hip_stream) {
+    if (!out) return fail(AX_ERR_INVALID, "out is NULL");
+    *out = nullptr;
+    if (!ok(model)) return fail(AX_ERR_INVALID, "bad model handle");
+    if (!ok(pool)) return fail(AX_ERR_INVALID, "bad pool handle");
+    if (!pool->geom.base) return fail(AX_ERR_INVALID, "pool has no device memory");
+    if (!image || image_bytes < (int64_t)sizeof(ImageHeader)) return fail(AX_ERR_INVALID, "image shorter than its header");
+    char* dev = nullptr;
+    ax_status st = device_view(image, (size_t)image_bytes, &dev);
+    if (st != AX_OK) return st;
+    ImageHeader h{};
+    HIP_TRY(hipMemcpy(&h, image, sizeof h, hipMemcpyDefault));
+    const ax_model_config& pc = pool->cfg;
+    if (h.magic != IMAGE_MAGIC || h.version != 1) return fail(AX_ERR_INVALID, "not a KV image");
+    if (h.n_layers != pc.n_layers || h.n_kv_heads != pc.n_kv_heads || h.head_dim != pc.head_dim || h.dtype != pc.dtype ||
+        h.block_tokens != 16)
+        return fail(AX_ERR_INVALID, "image geometry does not match the pool");
+    if (h.n_tokens < 0 || h.n_tokens > model->cfg.max_pos) return fail(AX_ERR_INVALID, "image of %lld tokens exceeds max_pos", (long long)h.n_tokens);
+    const int64_t need = ax_kv_image_bytes(pool, h.n_tokens);
+    if (h.payload_bytes != need - (int64_t)sizeof(ImageHeader) || image_bytes < need) return fail(AX_ERR_INVALID, "image is truncated");
+    const int64_t nb = ax::blocks_for(h.n_tokens, 16);
+    if (nb > pool->blocks.n_free()) return fail(AX_ERR_OOM, "need %lld KV blocks, %lld free", (long long)nb, (long long)pool->blocks.n_free());
+    ax_kv* k = nullptr;
+    st = ax_kv_alloc(pool, &k);
+    if (st != AX_OK) return st;
+    if (nb > 0) {
+        const ax::AppendPlan plan = ax::plan_append(pool->blocks, k->seq, h.n_tokens);
+        int32_t cs, cd;
+        ax::apply_append(pool->blocks, k->seq, h.n_tokens, plan, &cs, &cd);
+        hipStream_t stream = (hipStream_t)hip_stream;
+        int slot = 0;
+        const int* dev_ids = nullptr;
+        st = upload_ids(model, k->seq.blocks, stream, &slot, &dev_ids);
+        if (st == AX_OK) {
+            ax::launch_kv_image(false, pc.dtype == AX_F32 ? ax::F32 : ax::BF16, pool->geom, pc.n_layers, dev_ids, (int)nb,
+                                dev + sizeof(ImageHeader), 16, stream);
+            hipError_t e = hipGetLastError();
+            if (e == hipSuccess) e = hipEventRecord(model->slot_done[slot], stream);
+            if (e != hipSuccess) st = fail(AX_ERR_DEVICE, "KV import: %s", hipGetErrorString(e));
+        }
+        if (st != AX_OK) { ax_kv_free(k); return st; }
+    }
+    *out = k;
+    return AX_OK;
+}
+
 ax_status ax_verify_batch(ax_model* model, int n, ax_kv* const* kvs, const int32_t* pending, const int32_t* drafts_concat,
                           const int* k_each, int* accepted, int32_t* next_token, void* hip_stream) {
     if (!ok(model)) return fail(AX_ERR_INVALID, "bad model handle");

@@ -237,6 +237,48 @@ __global__ void block_copy_kernel(char* __restrict__ base, long long plane_bytes
     for (int i = threadIdx.x; i < block_bytes / 16; i += blockDim.x) d[i] = s[i];
 }
 
+// ---------------------------------------------------------------- KV image <-> pages
+// An image holds a sequence's blocks in logical order; block record b is
+// [plane (layer, K|V, kv head)][block_tokens * hd elements] exactly as a block lies in the pool.
+// grid = (planes, blocks of the sequence); 16-byte words.  On export the slots of the last
+// block at or beyond `last_fill` are written as zero, so an image is a function of the cached
+// values only.
+template <bool TO_IMAGE>
+__global__ void kv_image_kernel(char* __restrict__ pool, long long plane_bytes, int block_bytes,
+                                const int* __restrict__ ids, char* __restrict__ image, int n_kv_heads,
+                                int hd, int isz, int last_fill) {
+    const int p = blockIdx.x, b = blockIdx.y, n_planes = gridDim.x;
+    char* pg = pool + p * plane_bytes + (long long)ids[b] * block_bytes;
+    char* im = image + ((long long)b * n_planes + p) * block_bytes;
+    if (TO_IMAGE && b == (int)gridDim.y - 1 && last_fill < 16) {
+        const bool is_v = (p / n_kv_heads) & 1;             // V pages are [hd][slot], K pages [slot][hd]
+        const int n_el = block_bytes / isz;
+        for (int e = threadIdx.x; e < n_el; e += blockDim.x) {
+            const int slot = is_v ? (e & 15) : e / hd;
+            if (isz == 2) ((unsigned short*)im)[e] = slot < last_fill ? ((const unsigned short*)pg)[e] : (unsigned short)0;
+            else ((unsigned*)im)[e] = slot < last_fill ? ((const unsigned*)pg)[e] : 0u;
+        }
+        return;
+    }
+    const uint4* src = (const uint4*)(TO_IMAGE ? pg : im);
+    uint4* dst = (uint4*)(TO_IMAGE ? im : pg);
+    for (int i = threadIdx.x; i < block_bytes / 16; i += blockDim.x) dst[i] = src[i];
+}
+
+void launch_kv_image(bool to_image, DType dt, KVGeom kv, int n_layers, const int* ids, int n_seq_blocks,
+                     void* image, int last_fill, hipStream_t s) {
+    const int isz = dt == F32 ? 4 : 2;
+    const int block_bytes = kv.block_tokens * kv.head_dim * isz;
+    const long long plane_bytes = kv.n_blocks * (long long)block_bytes;
+    dim3 grid((unsigned)(2 * n_layers * kv.n_kv_heads), (unsigned)n_seq_blocks);
+    if (to_image)
+        kv_image_kernel<true><<<grid, 128, 0, s>>>((char*)kv.base, plane_bytes, block_bytes, ids, (char*)image,
+                                                   kv.n_kv_heads, kv.head_dim, isz, last_fill);
+    else
+        kv_image_kernel<false><<<grid, 128, 0, s>>>((char*)kv.base, plane_bytes, block_bytes, ids, (char*)image,
+                                                    kv.n_kv_heads, kv.head_dim, isz, last_fill);
+}
+
 __global__ void plain_copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n16) {
     const size_t stride = (size_t)gridDim.x * blockDim.x;
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];

@@ -120,4 +120,10 @@ void launch_plain_copy(void* dst, const void* src, size_t n16, hipStream_t s);
 // Copy one KV block (all layers, K and V, all heads) src -> dst: copy on write.
 void launch_block_copy(DType dt, KVGeom kv, int n_layers, int src, int dst, hipStream_t s);
 
+// Gather (to_image) or scatter the blocks `ids[0..n_seq_blocks)` of a sequence between the pool and
+// an image buffer (device-accessible memory) that holds them back to back in logical order.
+// last_fill: tokens in the last block (export zero-fills the slots beyond).
+void launch_kv_image(bool to_image, DType dt, KVGeom kv, int n_layers, const int* ids, int n_seq_blocks,
+                     void* image, int last_fill, hipStream_t s);
+
 }  // namespace ax
