@@ -206,6 +206,41 @@ ax_status ax_kv_export(ax_model *model, const ax_kv *kv, int64_t n_tokens, void 
 ax_status ax_kv_import(ax_model *model, ax_pool *pool, const void *image, int64_t image_bytes,
                        ax_kv **out, void *hip_stream);
 
+/* ---- automatic prefix reuse (paper Sec. 3.1: KV is reused for all tokens before the first one
+ * that differs; Sec. 4.2: a cached "1-3-2" serves a prompt that activates "1-3" by cutting the
+ * tail).  An index remembers which token sequence each registered KV holds.  Host only.
+ * The index keeps its own reference (a fork) to every registered sequence, so the blocks stay
+ * alive after the caller frees its handle; destroy the index before its pool. */
+typedef struct ax_index ax_index;
+ax_status ax_index_create(ax_pool *pool, ax_index **out);
+void ax_index_destroy(ax_index *index);
+int64_t ax_index_entries(const ax_index *index);                        /* -1 for a bad handle */
+/* Registers that the first n positions of kv cache `tokens` (host).  n <= length of kv. */
+ax_status ax_index_insert(ax_index *index, const ax_kv *kv, const int32_t *tokens, int64_t n);
+/* New sequence sharing the blocks of the registered sequence with the longest common prefix with
+ * `prompt` (token granular; the first registered among equals), cut to that prefix and to at most
+ * max_reuse tokens (-1 = no limit; pass n - 1 to keep one token to run).  *matched = reused
+ * tokens; with no match *out is an empty sequence.  The caller extends *out with
+ * prompt[matched..n) - a shared, partly filled last block is copied on that write - and frees it. */
+ax_status ax_index_match(ax_index *index, const int32_t *prompt, int64_t n, int64_t max_reuse,
+                         ax_kv **out, int64_t *matched);
+
+/* ---- offline selection of the cluster combinations to precompute (paper Sec. 4.2, Algorithm 1).
+ * A sample is the ordered list of clusters it activates (sample i has sample_len[i] ids, all
+ * samples back to back in samples_concat).  `budget` rounds; each adds the prefix - a single
+ * cluster, or a chosen prefix extended by one cluster - whose addition raises the coverage (sum
+ * over samples of the number of leading clusters found in the chosen set) most; equal gains go to
+ * the smallest prefix in lexicographic order of cluster ids.  Stops early when no candidate is
+ * left.  Outputs: the chosen prefixes back to back in chosen_concat (capacity chosen_cap ids),
+ * their lengths, the coverage after each round (optional), and their number.  Host only. */
+ax_status ax_select_combinations(const int32_t *samples_concat, const int32_t *sample_len,
+                                 int64_t n_samples, int budget, int32_t *chosen_concat,
+                                 int64_t chosen_cap, int32_t *chosen_len, int64_t *coverage_after,
+                                 int *n_chosen);
+/* Coverage of a cached set as defined above; -1 on bad arguments. */
+int64_t ax_coverage(const int32_t *samples_concat, const int32_t *sample_len, int64_t n_samples,
+                    const int32_t *cached_concat, const int32_t *cached_len, int64_t n_cached);
+
 /* ---- example-based drafter and decode loop (paper Sec. 4.3) -------------------------------------
  * A per-query n-gram lookup table: a window of n tokens slides over `stream` (the few-shot
  * examples followed by the user query; host memory) one token at a time; the first n-1 tokens

@@ -62,6 +62,13 @@ def _load():
         "ax_kv_image_bytes": (i64, [vp, i64]),
         "ax_kv_export": (C.c_int, [vp, vp, i64, vp, i64, vp]),
         "ax_kv_import": (C.c_int, [vp, vp, vp, i64, C.POINTER(vp), vp]),
+        "ax_index_create": (C.c_int, [vp, C.POINTER(vp)]),
+        "ax_index_destroy": (None, [vp]),
+        "ax_index_entries": (i64, [vp]),
+        "ax_index_insert": (C.c_int, [vp, vp, i32p, i64]),
+        "ax_index_match": (C.c_int, [vp, i32p, i64, i64, C.POINTER(vp), C.POINTER(i64)]),
+        "ax_select_combinations": (C.c_int, [i32p, i32p, i64, C.c_int, i32p, i64, i32p, C.POINTER(i64), C.POINTER(C.c_int)]),
+        "ax_coverage": (i64, [i32p, i32p, i64, i32p, i32p, i64]),
         "ax_lut_build": (C.c_int, [i32p, i64, C.c_int, C.c_int, C.POINTER(vp)]),
         "ax_lut_free": (None, [vp]),
         "ax_lut_size": (i64, [vp]),
@@ -247,6 +254,66 @@ def ax_verify_batch(model: int, kvs, pending, drafts_each, stream: int = 0):
     _check(lib.ax_verify_batch(model, n, ka, pp, dp if len(d) else None, ke, acc, nxt.ctypes.data_as(C.POINTER(C.c_int32)),
                                C.c_void_p(stream)))
     return list(acc), nxt.tolist()
+
+
+# ------------------------------------------------------------------ prefix index and offline selection (host)
+
+def ax_index_create(pool: int) -> int:
+    out = C.c_void_p()
+    _check(lib.ax_index_create(pool, C.byref(out)))
+    return out.value
+
+
+def ax_index_destroy(index: int):
+    lib.ax_index_destroy(index)
+
+
+def ax_index_entries(index: int) -> int:
+    return lib.ax_index_entries(index)
+
+
+def ax_index_insert(index: int, kv: int, tokens):
+    t, tp = _i32(tokens)
+    _check(lib.ax_index_insert(index, kv, tp, len(t)))
+
+
+def ax_index_match(index: int, prompt, max_reuse: int = -1):
+    """(new sequence handle, reused tokens)."""
+    t, tp = _i32(prompt)
+    out, m = C.c_void_p(), C.c_int64()
+    _check(lib.ax_index_match(index, tp if len(t) else None, len(t), max_reuse, C.byref(out), C.byref(m)))
+    return out.value, m.value
+
+
+def _pack_seqs(seqs):
+    flat = np.asarray([int(c) for s in seqs for c in s], dtype=np.int32)
+    lens = np.asarray([len(s) for s in seqs], dtype=np.int32)
+    p32 = C.POINTER(C.c_int32)
+    return flat, lens, (flat.ctypes.data_as(p32) if len(flat) else None), (lens.ctypes.data_as(p32) if len(lens) else None)
+
+
+def ax_select_combinations(samples, budget: int):
+    """([chosen prefixes as tuples, in the order chosen], [coverage after each])."""
+    flat, lens, fp, lp = _pack_seqs(samples)
+    cap = max(1, budget * (int(lens.max()) if len(lens) else 1))
+    out = np.zeros(cap, dtype=np.int32)
+    out_len = np.zeros(max(budget, 1), dtype=np.int32)
+    cov = np.zeros(max(budget, 1), dtype=np.int64)
+    n = C.c_int()
+    p32 = C.POINTER(C.c_int32)
+    _check(lib.ax_select_combinations(fp, lp, len(lens), budget, out.ctypes.data_as(p32), cap, out_len.ctypes.data_as(p32),
+                                      cov.ctypes.data_as(C.POINTER(C.c_int64)), C.byref(n)))
+    chosen, at = [], 0
+    for i in range(n.value):
+        chosen.append(tuple(int(c) for c in out[at:at + out_len[i]]))
+        at += out_len[i]
+    return chosen, cov[:n.value].tolist()
+
+
+def ax_coverage(samples, cached) -> int:
+    _f, sl, fp, lp = _pack_seqs(samples)
+    _g, cl, cp, clp = _pack_seqs(cached)
+    return lib.ax_coverage(fp, lp, len(sl), cp, clp, len(cl))
 
 
 # ------------------------------------------------------------------ example-based drafter (host) and decode loop

@@ -16,7 +16,9 @@
 
 #include "block_manager.h"
 #include "kernels.h"
+#include "cluster_select.h"
 #include "ngram_lut.h"
+#include "prefix_index.h"
 
 namespace {
 
@@ -36,7 +38,7 @@ ax_status fail(ax_status st, const char* fmt, ...) {
         if (e_ != hipSuccess) return fail(AX_ERR_DEVICE, "%s: %s", #expr, hipGetErrorString(e_)); \
     } while (0)
 
-constexpr uint32_t MAGIC_MODEL = 0x41584d44, MAGIC_POOL = 0x4158504c, MAGIC_KV = 0x41584b56, MAGIC_LUT = 0x41584c54;
+constexpr uint32_t MAGIC_MODEL = 0x41584d44, MAGIC_POOL = 0x4158504c, MAGIC_KV = 0x41584b56, MAGIC_LUT = 0x41584c54, MAGIC_INDEX = 0x41584958;
 constexpr int N_SLOTS = 4;            // staging ring for per-call descriptors
 constexpr int LOGIT_ROWS = 256;       // rows per LM-head pass when only the argmax is wanted
 constexpr int SPLIT_ITEMS = 2048;     // wavefronts the split attention aims for
@@ -138,6 +140,12 @@ struct ax_lut {
     ax::NgramLut lut;
 };
 
+struct ax_index {
+    uint32_t magic;
+    ax_pool* pool;
+    ax::PrefixIndex idx;
+};
+
 struct ax_kv {
     uint32_t magic;
     ax_pool* pool;
@@ -150,6 +158,7 @@ bool ok(const ax_model* m) { return m && m->magic == MAGIC_MODEL; }
 bool ok(const ax_pool* p) { return p && p->magic == MAGIC_POOL; }
 bool ok(const ax_kv* k) { return k && k->magic == MAGIC_KV && ok(k->pool); }
 bool ok(const ax_lut* l) { return l && l->magic == MAGIC_LUT; }
+bool ok(const ax_index* x) { return x && x->magic == MAGIC_INDEX && ok(x->pool); }
 
 struct ProfScope {                     // records a pair of events around one launch when profiling
     ax_model* m; hipStream_t st; hipEvent_t b = nullptr;
@@ -960,6 +969,105 @@ ax_status ax_verify_batch(ax_model* model, int n, ax_kv* const* kvs, const int32
         ax::truncate(kvs[s]->pool->blocks, kvs[s]->seq, P[(size_t)s] + 1 + accepted[s]);
     }
     return AX_OK;
+}
+
+// ---- automatic prefix reuse and offline combination selection (host only) --------------------
+
+ax_status ax_index_create(ax_pool* pool, ax_index** out) {
+    if (!out) return fail(AX_ERR_INVALID, "out is NULL");
+    *out = nullptr;
+    if (!ok(pool)) return fail(AX_ERR_INVALID, "bad pool handle");
+    ax_index* x = new ax_index();
+    x->pool = pool;
+    x->magic = MAGIC_INDEX;
+    *out = x;
+    return AX_OK;
+}
+
+void ax_index_destroy(ax_index* x) {
+    if (!ok(x)) return;
+    for (auto& e : x->idx.entries)
+        if (e.live) ax_kv_free((ax_kv*)e.owner);
+    x->magic = 0;
+    delete x;
+}
+
+int64_t ax_index_entries(const ax_index* x) {
+    if (!ok(x)) return -1;
+    int64_t n = 0;
+    for (auto& e : x->idx.entries) n += e.live ? 1 : 0;
+    return n;
+}
+
+ax_status ax_index_insert(ax_index* x, const ax_kv* kv, const int32_t* tokens, int64_t n) {
+    if (!ok(x)) return fail(AX_ERR_INVALID, "bad index handle");
+    if (!ok(kv)) return fail(AX_ERR_INVALID, "bad KV handle");
+    if (kv->pool != x->pool) return fail(AX_ERR_INVALID, "sequence lives in another pool");
+    if (n <= 0 || !tokens) return fail(AX_ERR_INVALID, "bad argument");
+    if (n > kv->seq.len) return fail(AX_ERR_INVALID, "%lld tokens given, the sequence holds %lld", (long long)n, (long long)kv->seq.len);
+    ax_kv* held = nullptr;
+    ax_status st = ax_kv_fork(kv, n, &held);
+    if (st != AX_OK) return st;
+    x->idx.insert(tokens, n, held);
+    return AX_OK;
+}
+
+ax_status ax_index_match(ax_index* x, const int32_t* prompt, int64_t n, int64_t max_reuse, ax_kv** out, int64_t* matched) {
+    if (!out || !matched) return fail(AX_ERR_INVALID, "NULL argument");
+    *out = nullptr;
+    *matched = 0;
+    if (!ok(x)) return fail(AX_ERR_INVALID, "bad index handle");
+    if (n < 0 || (n > 0 && !prompt)) return fail(AX_ERR_INVALID, "bad argument");
+    int64_t m = 0;
+    const int id = x->idx.match(prompt, n, &m);
+    if (max_reuse >= 0 && m > max_reuse) m = max_reuse;
+    if (id < 0 || m == 0) return ax_kv_alloc(x->pool, out);
+    ax_status st = ax_kv_fork((const ax_kv*)x->idx.entries[(size_t)id].owner, m, out);
+    if (st == AX_OK) *matched = m;
+    return st;
+}
+
+namespace {
+bool unpack_seqs(const int32_t* concat, const int32_t* len, int64_t n, std::vector<ax::ClusterSeq>& out) {
+    if (n < 0 || (n > 0 && (!concat || !len))) return false;
+    const int32_t* at = concat;
+    for (int64_t i = 0; i < n; ++i) {
+        if (len[i] < 0) return false;
+        out.emplace_back(at, at + len[i]);
+        at += len[i];
+    }
+    return true;
+}
+}  // namespace
+
+ax_status ax_select_combinations(const int32_t* samples_concat, const int32_t* sample_len, int64_t n_samples, int budget,
+                                 int32_t* chosen_concat, int64_t chosen_cap, int32_t* chosen_len,
+                                 int64_t* coverage_after, int* n_chosen) {
+    if (!n_chosen || budget < 0) return fail(AX_ERR_INVALID, "bad argument");
+    *n_chosen = 0;
+    std::vector<ax::ClusterSeq> samples;
+    if (!unpack_seqs(samples_concat, sample_len, n_samples, samples)) return fail(AX_ERR_INVALID, "bad sample list");
+    const ax::SelectionResult r = ax::select_combinations(samples, budget);
+    int64_t total = 0;
+    for (auto& c : r.chosen) total += (int64_t)c.size();
+    if (!r.chosen.empty() && (!chosen_concat || !chosen_len || total > chosen_cap))
+        return fail(AX_ERR_INVALID, "output holds %lld cluster ids, %lld needed", (long long)chosen_cap, (long long)total);
+    int32_t* at = chosen_concat;
+    for (size_t i = 0; i < r.chosen.size(); ++i) {
+        chosen_len[i] = (int32_t)r.chosen[i].size();
+        for (int32_t c : r.chosen[i]) *at++ = c;
+        if (coverage_after) coverage_after[i] = r.coverage[i];
+    }
+    *n_chosen = (int)r.chosen.size();
+    return AX_OK;
+}
+
+int64_t ax_coverage(const int32_t* samples_concat, const int32_t* sample_len, int64_t n_samples,
+                    const int32_t* cached_concat, const int32_t* cached_len, int64_t n_cached) {
+    std::vector<ax::ClusterSeq> samples, cached;
+    if (!unpack_seqs(samples_concat, sample_len, n_samples, samples) || !unpack_seqs(cached_concat, cached_len, n_cached, cached))
+        return -1;
+    return ax::coverage(samples, cached);
 }
 
 ax_status ax_lut_build(const int32_t* stream, int64_t n_tokens, int n, int vocab, ax_lut** out) {

@@ -213,3 +213,30 @@ def seeded_accept_drafts(greedy: np.ndarray, vocab: int, seed: int, round_idx: i
     if j < k:
         d[j] = (int(greedy[j]) + 1 + int(g.integers(0, vocab - 1))) % vocab
     return np.ascontiguousarray(d, dtype=np.int32), j
+
+
+def cluster_activation_samples(seed: int, n_samples: int, n_clusters: int = 8):
+    """Synthetic stand-in for the cluster sequences a tool-retrieval step activates per query
+    (the paper clusters 16 tools into 8 ordered clusters; a query activates the clusters that
+    hold its retrieved tools).  Clusters come in adjacent pairs of one theme; a sample picks a
+    theme with Zipf-like popularity, activates each cluster of the pair with its own probability
+    and sometimes one cluster of another theme.  Returns a list of ascending tuples (the fixed
+    order), none empty."""
+    g = _rng(seed, "clusters")
+    n_themes = max(1, n_clusters // 2)
+    pop = 1.0 / np.arange(1, n_themes + 1) ** 1.2
+    pop /= pop.sum()
+    out = []
+    for _ in range(n_samples):
+        t = int(g.choice(n_themes, p=pop))
+        act = set()
+        if g.random() < 0.8:
+            act.add(2 * t)
+        if 2 * t + 1 < n_clusters and g.random() < 0.55:
+            act.add(2 * t + 1)
+        if g.random() < 0.3:
+            act.add(int(g.integers(0, n_clusters)))
+        if not act:
+            act.add(2 * t)
+        out.append(tuple(sorted(act)))
+    return out

@@ -626,3 +626,44 @@ def test_config2_full_depth_extend_and_verify(B):
     B.ax_kv_free(kv)
     dm.close()
     O.clear_widen_cache()
+
+
+# ------------------------------------------------------------------ automatic prefix reuse
+
+@pytest.mark.parametrize("which", ["bf16-hd64-g4", "f32-hd32"])
+def test_prefix_index_reuses_cached_combination(B, which):
+    """A cached prompt "static part, cluster 1, cluster 3, cluster 2" serves a prompt that
+    activates only clusters 1 and 3: the index finds the common prefix (token granular, here
+    inside a block), the tail is cut, only the rest is computed - and the logits equal the
+    oracle's full recomputation.  The cached entry itself stays intact."""
+    sh = SMALL[which]
+    w = I.make_weights(sh, 61)
+    static = I.templated_prompt(sh.vocab, 61, 70)
+    c1, c3, c2 = (I.zipf_tokens(sh.vocab, 61, f"cluster{i}", n) for i, n in ((1, 23), (3, 31), (2, 18)))
+    cached = np.concatenate([static, c1, c3, c2]).astype(np.int32)
+    dm = B.DeviceModel(sh, w, max_pos=512, max_tokens=256, pool_tokens=2048)
+    idx = B.ax_index_create(dm.pool)
+    kv = dm.new_kv()
+    dm.extend(kv, cached)
+    B.ax_index_insert(idx, kv, cached)
+    B.ax_kv_free(kv)
+    dynamic = I.zipf_tokens(sh.vocab, 61, "query", 27)
+    prompts = {"1-3": np.concatenate([static, c1, c3, dynamic]), "1-3-2": np.concatenate([cached, dynamic]),
+               "1 only": np.concatenate([static, c1, dynamic]), "other": np.concatenate([dynamic, static])}
+    expect = {"1-3": 70 + 23 + 31, "1-3-2": len(cached), "1 only": 70 + 23, "other": 0}
+    for name, p in prompts.items():
+        p = p.astype(np.int32)
+        got_kv, m = B.ax_index_match(idx, p, max_reuse=len(p) - 1)
+        assert m == expect[name], name
+        got = dm.extend(got_kv, p[m:], B.AX_OUT_ALL_LOGITS).cpu().numpy()
+        ref = O.forward(sh, w, p, okv(sh))[m:]
+        check_logits(sh, got, ref, f"prompt '{name}' reusing {m} of {len(p)} tokens")
+        B.ax_kv_free(got_kv)
+    # a prompt that IS a cached sequence keeps one token to run
+    got_kv, m = B.ax_index_match(idx, cached, max_reuse=len(cached) - 1)
+    assert m == len(cached) - 1
+    B.ax_kv_free(got_kv)
+    B.ax_index_destroy(idx)
+    free, total, live = B.ax_pool_stats(dm.pool)
+    assert free == total and live == 0
+    dm.close()

@@ -1,0 +1,181 @@
+"""No GPU: the offline cluster-combination selection and the prefix index - the oracle against a
+hand-worked example, brute force and closed-form cases; the library against the oracle."""
+import itertools
+import os
+
+import numpy as np
+import pytest
+
+from oracle import selection as S
+from paper_2605_10380_amd import binding as B
+from paper_2605_10380_amd import inputs as I
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "cluster_selection_example.txt")
+
+
+def read_golden():
+    samples, picks = [], []
+    for line in open(GOLDEN):
+        w = line.split()
+        if not w or w[0] == "#":
+            continue
+        if w[0] == "sample":
+            samples.append(tuple(int(c) for c in w[1:]))
+        elif w[0] == "pick":
+            bar = w.index("|")
+            picks.append((tuple(int(c) for c in w[1:bar]), int(w[bar + 1])))
+    return samples, picks
+
+
+# ------------------------------------------------------------------ oracle pins
+
+def test_oracle_matches_hand_worked_example():
+    samples, picks = read_golden()
+    chosen, trace = S.select_combinations(samples, 7)
+    assert list(zip(chosen, trace)) == picks
+    assert S.select_combinations(samples, 3)[0] == [p for p, _ in picks[:3]]      # a smaller budget is a prefix
+    assert S.select_combinations(samples, 50)[0] == [p for p, _ in picks]         # stops when nothing is left
+
+
+def test_coverage_definition_cases():
+    samples = [(0, 1, 2), (0, 1), (3,)]
+    assert S.coverage(samples, []) == 0
+    assert S.coverage(samples, [(0,)]) == 2
+    assert S.coverage(samples, [(0, 1)]) == 4                 # the longest cached prefix counts, here 2 + 2
+    assert S.coverage(samples, [(0,), (0, 1), (0, 1, 2), (3,)]) == 6 == sum(len(s) for s in samples)
+    assert S.coverage(samples, [(1,), (1, 2), (2,)]) == 0     # cached sequences that are no prefix of any sample
+
+
+def test_identical_samples_walk_down_the_chain():
+    chosen, trace = S.select_combinations([(4, 5, 6)] * 9, 3)
+    assert chosen == [(4,), (4, 5), (4, 5, 6)] and trace == [9, 18, 27]
+
+
+def brute_force_best(samples, budget):
+    """Best coverage over every admissible cached set of `budget` prefixes: sets in which each
+    member is a single cluster or extends another member by one cluster (what the rounds can
+    build, in any order).  Down a chain of prefixes the number of samples sharing them can only
+    fall, so taking the largest gains first reaches this optimum: the greedy result must EQUAL it."""
+    prefixes = sorted({s[:n] for s in samples for n in range(1, len(s) + 1)})
+    best = 0
+    for combo in itertools.combinations(prefixes, min(budget, len(prefixes))):
+        have = set(combo)
+        if all(len(p) == 1 or p[:-1] in have for p in combo):
+            best = max(best, S.coverage(samples, combo))
+    return best
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_greedy_against_exhaustive_search(seed):
+    samples = I.cluster_activation_samples(seed, 14, n_clusters=4)
+    for budget in (1, 2, 3, 4):
+        chosen, trace = S.select_combinations(samples, budget)
+        assert trace[-1] == S.coverage(samples, chosen) == brute_force_best(samples, budget)
+        have = set(chosen)
+        assert all(len(p) == 1 or p[:-1] in have for p in chosen)           # every member is reachable by cutting tails
+        assert trace == sorted(trace)
+    # one round: the greedy choice IS the optimum (the most frequent first cluster)
+    first = max(sorted({s[:1] for s in samples}), key=lambda p: sum(s[:1] == p for s in samples))
+    assert S.select_combinations(samples, 1)[0] == [first]
+    assert S.select_combinations(samples, 1)[1][0] == brute_force_best(samples, 1)
+    # enough rounds: everything is covered
+    full = S.select_combinations(samples, 1000)
+    assert full[1][-1] == sum(len(s) for s in samples)
+
+
+def test_planted_mistakes_are_caught():
+    samples, picks = read_golden()
+    # a selection that drops the "single cluster or extension of a chosen prefix" rule takes (0, 1)
+    # first: alone it already gives two hits to each of three samples (+6 against +4 for (0,))
+    prefixes = sorted({s[:n] for s in samples for n in range(1, len(s) + 1)})
+    unconstrained_first = max(prefixes, key=lambda p: S.coverage(samples, [p]))
+    assert unconstrained_first == (0, 1) != picks[0][0]
+    # coverage that counted any cached member instead of the longest prefix would differ
+    assert S.coverage([(0, 1)], [(0,), (0, 1)]) == 2
+
+
+# ------------------------------------------------------------------ library against the oracle
+
+def test_library_matches_hand_worked_example():
+    samples, picks = read_golden()
+    chosen, cov = B.ax_select_combinations(samples, 7)
+    assert list(zip(chosen, cov)) == picks
+
+
+@pytest.mark.parametrize("seed", range(5))
+@pytest.mark.parametrize("budget", [0, 1, 5, 15, 40])
+def test_library_selection_matches_oracle(seed, budget):
+    samples = I.cluster_activation_samples(100 + seed, 300, n_clusters=8)
+    want = S.select_combinations(samples, budget)
+    got = B.ax_select_combinations(samples, budget)
+    assert got == (want[0], want[1])
+    assert B.ax_coverage(samples, got[0]) == (want[1][-1] if want[1] else 0)
+    rng = np.random.default_rng(seed)
+    some = [samples[i][:int(rng.integers(1, len(samples[i]) + 1))] for i in rng.integers(0, len(samples), 6)]
+    assert B.ax_coverage(samples, some) == S.coverage(samples, some)
+
+
+def test_selection_bad_arguments():
+    assert B.ax_select_combinations([], 5) == ([], [])
+    with pytest.raises(B.AxError):
+        B.ax_select_combinations([(1, 2)], -1)
+
+
+# ------------------------------------------------------------------ prefix index (host bookkeeping only)
+
+@pytest.fixture
+def pool():
+    cfg = B.make_config(I.SHAPES["tiny"], 4096, 64)
+    p = B.ax_pool_create(cfg, 0, B.ax_pool_block_bytes(cfg) * 256)
+    yield p
+    free, total, live = B.ax_pool_stats(p)
+    assert (free, live) == (total, 0)
+    B.ax_pool_destroy(p)
+
+
+def test_index_finds_longest_common_prefix(pool):
+    rng = np.random.default_rng(3)
+    base = I.templated_prompt(4096, 3, 200)
+    cached = []
+    idx = B.ax_index_create(pool)
+    for i, (cut, extra) in enumerate([(200, 0), (90, 40), (90, 25), (16, 3), (33, 0)]):
+        toks = np.concatenate([base[:cut], rng.integers(0, 4096, extra)]).astype(np.int32)
+        kv = B.ax_kv_alloc(pool)
+        B.ax_kv_reserve_host(kv, len(toks))
+        B.ax_index_insert(idx, kv, toks)
+        B.ax_kv_free(kv)                                      # the index keeps the blocks alive
+        cached.append(toks)
+    assert B.ax_index_entries(idx) == 5
+    prompts = [base[:150], base[:95], cached[1][:120], np.concatenate([cached[2][:100], base[:7]]),
+               np.concatenate([base[:16], cached[3][16:18], base[:3]]), rng.integers(0, 4096, 50), base[:1], base[:0],
+               np.concatenate([base[:40], [base[40] ^ 1], base[41:80]])]
+    for p in prompts:
+        p = np.asarray(p, dtype=np.int32)
+        want_i, want_n = S.longest_cached_prefix(cached, p)
+        kv, m = B.ax_index_match(idx, p)
+        assert m == want_n, (len(p), m, want_n)
+        assert B.ax_kv_len(kv) == m
+        if m:
+            owner_blocks = None
+            # the new sequence shares the blocks of an entry with that common prefix
+            assert len(B.ax_kv_blocks(kv)) == (m + 15) // 16
+            assert all(B.ax_pool_refcount(pool, int(b)) >= 2 for b in B.ax_kv_blocks(kv))
+        kv2, m2 = B.ax_index_match(idx, p, max_reuse=max(len(p) - 1, 0))
+        assert m2 == min(want_n, max(len(p) - 1, 0)) and B.ax_kv_len(kv2) == m2
+        B.ax_kv_free(kv)
+        B.ax_kv_free(kv2)
+    B.ax_index_destroy(idx)
+    assert B.ax_index_entries(idx) == -1
+
+
+def test_index_errors(pool):
+    idx = B.ax_index_create(pool)
+    kv = B.ax_kv_alloc(pool)
+    B.ax_kv_reserve_host(kv, 10)
+    with pytest.raises(B.AxError):
+        B.ax_index_insert(idx, kv, np.arange(11))             # more tokens than the sequence holds
+    with pytest.raises(B.AxError):
+        B.ax_index_insert(idx, kv, [])
+    B.ax_index_insert(idx, kv, np.arange(10))
+    B.ax_kv_free(kv)
+    B.ax_index_destroy(idx)
