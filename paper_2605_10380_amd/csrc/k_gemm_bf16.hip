@@ -109,15 +109,16 @@ __device__ __forceinline__ void block_inv_rms(const GemmArgs& g, int first_row, 
 // ------------------------------------------------------------------------------ tile kernel
 // MFMA 32x32x16 operand layout (wave64): lane l supplies row/col (l % 32) and the 8 k values
 // 8*(l/32) .. +7; result register r of lane l is C[(r/4)*8 + (l/32)*4 + r%4][l % 32].
-// Block = 2 x 2 wavefronts, wavefront tile = (TM*32) x (TN*32).  For EPI_QKV the wavefront's
+// Block = WM x WN wavefronts, wavefront tile = (TM*32) x (TN*32).  For EPI_QKV the wavefront's
 // TN*32 columns are exactly one head, so a rotary pair (c, c + hd/2) sits in the same lane and
 // register of tiles j and j + TN/2.
-template <int EPI, int TM, int TN>
-__global__ __launch_bounds__(256) void gemm_bf16_tile_kernel(GemmArgs g) {
-    constexpr int BM = 2 * TM * 32, BN = 2 * TN * 32, BK = 64, LS = BK + 8;  // LS: padded row
+template <int EPI, int TM, int TN, int WM = 2, int WN = 2>
+__global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_tile_kernel(GemmArgs g) {
+    constexpr int NT = 64 * WM * WN;                                         // threads per block
+    constexpr int BM = WM * TM * 32, BN = WN * TN * 32, BK = 64, LS = BK + 8;  // LS: padded row
     constexpr int NB = EPI == EPI_SWIGLU ? 2 : 1;
-    constexpr int A_CH = BM * 8 / 256, B_CH = BN * 8 / 256;                  // 16-byte chunks per thread
-    constexpr int D = NB == 2 ? 2 : 4;                                       // prefetch distance (even)
+    constexpr int A_CH = BM * 8 / NT, B_CH = BN * 8 / NT;                  // 16-byte chunks per thread
+    constexpr int D = (NB == 2 && B_CH > 2) ? 2 : 4;                         // prefetch distance (even)
     __shared__ __attribute__((aligned(16))) f16 sA[2][BM * LS];
     __shared__ __attribute__((aligned(16))) f16 sB[2][NB][BN * LS];
     __shared__ float s_inv[BM];
@@ -127,7 +128,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_tile_kernel(GemmArgs g) {
     const bf16* __restrict__ W2 = (const bf16*)g.W2;
     const int M = g.M, N = g.N, K = g.K;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave / WN, wn = wave % WN;
     const int lrow = lane & 31, lg = lane >> 5;
     const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
     const int kspan = g.ksplit > 1 ? K / g.ksplit : K, kbase = blockIdx.z * kspan;   // this block's K slice
@@ -150,13 +151,13 @@ __global__ __launch_bounds__(256) void gemm_bf16_tile_kernel(GemmArgs g) {
     long long a_off[A_CH], b_off[B_CH];
 #pragma unroll
     for (int i = 0; i < A_CH; ++i) {
-        const int c = tid + 256 * i, row = c >> 3, cc = c & 7;
+        const int c = tid + NT * i, row = c >> 3, cc = c & 7;
         const int gm = min(m0 + row, M - 1);
         a_off[i] = (long long)(g.a_rows ? g.a_rows[gm] : gm) * K + kbase + cc * 8;
     }
 #pragma unroll
     for (int i = 0; i < B_CH; ++i) {
-        const int c = tid + 256 * i, row = c >> 3, cc = c & 7;
+        const int c = tid + NT * i, row = c >> 3, cc = c & 7;
         b_off[i] = (long long)min(n0 + row, N - 1) * K + kbase + cc * 8;
     }
     auto load_global = [&](int slot, int k0) {
@@ -171,12 +172,12 @@ __global__ __launch_bounds__(256) void gemm_bf16_tile_kernel(GemmArgs g) {
     auto store_lds = [&](int slot, int buf) {
 #pragma unroll
         for (int i = 0; i < A_CH; ++i) {
-            const int c = tid + 256 * i, row = c >> 3, cc = c & 7;
+            const int c = tid + NT * i, row = c >> 3, cc = c & 7;
             *(f16x8*)(sA[buf] + row * LS + cc * 8) = ra[slot][i];
         }
 #pragma unroll
         for (int i = 0; i < B_CH; ++i) {
-            const int c = tid + 256 * i, row = c >> 3, cc = c & 7;
+            const int c = tid + NT * i, row = c >> 3, cc = c & 7;
 #pragma unroll
             for (int b = 0; b < NB; ++b) *(f16x8*)(sB[buf][b] + row * LS + cc * 8) = bf16x8_to_f16x8(rb[slot][b][i]);
         }
@@ -320,7 +321,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_tile_kernel(GemmArgs g) {
                 if (g.gain_next) {   // partial sum of squares over this wavefront's TN*32 columns
 #pragma unroll
                     for (int o = 16; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
-                    if (lrow == 0 && m < M) g.ssq_out[(long long)m * (N / (TN * 32)) + (n0 / (TN * 32)) + wn] = ss;
+                    const int part = n0 / (TN * 32) + wn;                 // this wavefront's block of columns
+                    if (lrow == 0 && m < M && part < N / (TN * 32)) g.ssq_out[(long long)m * (N / (TN * 32)) + part] = ss;
                 }
             }
     } else {                         // EPI_QKV: one head per wavefront, rotary pairs (j, j + TN/2)
@@ -384,7 +386,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_tile_kernel(GemmArgs g) {
 }
 
 // Second half of a K-split residual GEMM: x += sum of the K-slice partials (in slice order),
-// a = fp16(x * gain_next), per-row partial sums of x^2 over blocks of 64 columns (the layout the
+// a = fp16(x * gain_next), per-row partial sums of x^2 over blocks of 32 columns (the layout the
 // unsplit tile kernel writes).  One wavefront per (row, 64 columns); N % 64 == 0.
 __global__ __launch_bounds__(256) void residual_reduce_kernel(GemmArgs g) {
     const int lane = threadIdx.x & 63;
@@ -405,8 +407,8 @@ __global__ __launch_bounds__(256) void residual_reduce_kernel(GemmArgs g) {
         ((f16*)g.C16)[o] = (f16)(xn * gain);
         float ss = xn * xn;
 #pragma unroll
-        for (int w = 32; w > 0; w >>= 1) ss += __shfl_xor(ss, w, 64);
-        if (lane == 0) g.ssq_out[(long long)m * nb + n / 64] = ss;
+        for (int w = 16; w > 0; w >>= 1) ss += __shfl_xor(ss, w, 64);
+        if ((lane & 31) == 0) g.ssq_out[(long long)m * (g.N / 32) + n / 32] = ss;
     }
 }
 
@@ -816,8 +818,12 @@ static void launch_lds_tile(const GemmArgs& g, hipStream_t s) {
         else gemm_bf16_tile_kernel<EPI_QKV, 1, 4><<<grid, 256, 0, s>>>(g);
         return;
     }
+    // 64 x 128 tiles, 2 x 4 wavefronts of 32 x 32 each: two wavefronts per SIMD cover each
+    // other's LDS and barrier waits (measured 10-20 % faster than 2 x 2 wavefronts of 32 x 64)
     dim3 grid((N + 127) / 128, (M + 63) / 64);
     if (EPI == EPI_RESIDUAL && g.split_ws && N % 64 == 0) {
+        // few output tiles (M = 256 against N = 2048 is 64 tiles for 256 CUs): cut K until
+        // there are ~256 blocks, each still with 8 or more k-steps
         GemmArgs gs = g;
         int ks = 1;
         while (ks < SPLITK_MAX && (long long)grid.x * grid.y * ks < 256 && K % (ks * 2 * 64) == 0 &&
@@ -826,12 +832,12 @@ static void launch_lds_tile(const GemmArgs& g, hipStream_t s) {
         if (ks > 1) {
             gs.ksplit = ks;
             grid.z = ks;
-            gemm_bf16_tile_kernel<EPI, 1, 2><<<grid, 256, 0, s>>>(gs);
+            gemm_bf16_tile_kernel<EPI, 1, 1, 2, 4><<<grid, 512, 0, s>>>(gs);
             residual_reduce_kernel<<<(unsigned)(((long long)M * (N / 64) + 3) / 4), 256, 0, s>>>(gs);
             return;
         }
     }
-    gemm_bf16_tile_kernel<EPI, 1, 2><<<grid, 256, 0, s>>>(g);
+    gemm_bf16_tile_kernel<EPI, 1, 1, 2, 4><<<grid, 512, 0, s>>>(g);
 }
 
 template <int EPI>
@@ -858,7 +864,7 @@ static void launch_bf16(const GemmArgs& g, hipStream_t s) {
     launch_lds_tile<EPI>(g, s);
 }
 
-int gemm_ssq_parts(int M, int N) { return M <= 64 ? N / 16 : N / 64; }
+int gemm_ssq_parts(int M, int N) { return M <= 64 ? N / 16 : N / 32; }
 
 void launch_gemm_bf16(Epilogue epi, const GemmArgs& g, hipStream_t s) {
     if (epi == EPI_STORE_F32) launch_bf16<EPI_STORE_F32>(g, s);
