@@ -22,6 +22,13 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-u
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 
+# Per-file extras.  Attention: keep the MFMA accumulators in ordinary vector registers; the score
+# tile and the output accumulators are read and rescaled by vector instructions on every key
+# step, and with accumulation registers each such access costs an extra move (about a third of
+# the instructions of the key-step loop).
+EXTRA_FLAGS = {"k_attn.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
+
+
 def sources():
     return sorted(f for f in os.listdir(CSRC) if f.endswith(".hip"))
 
@@ -38,7 +45,7 @@ def _compile(src: str, force: bool) -> str:
     if (not force and os.path.exists(obj)
             and os.path.getmtime(obj) > max(os.path.getmtime(spath), _newest_header())):
         return obj
-    cmd = [HIPCC, *FLAGS, "-c", spath, "-o", obj]
+    cmd = [HIPCC, *FLAGS, *EXTRA_FLAGS.get(src, []), "-c", spath, "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
     if r.returncode != 0:

@@ -247,12 +247,11 @@ ax_status prepare_call(ax_model* m, int n, ax_kv* const* kvs, const int32_t* tok
     cp.n_rows = (int)n_rows;
     cp.out_mode = out_mode;
     cp.pool = pool;
-    // attention q tiles (32 stacked rows): a verify step's rows (<= 64 stacked rows per sequence)
-    // form one pair handled by one wavefront, which loads each K/V operand once for both tiles.
-    // Long extends keep one tile per wavefront: measured, larger groups lengthen the serial
-    // softmax chain per key step more than they save in K/V loads (0.87 / 0.91 / 1.25 ms per
-    // extend of 256 rows at 1, 2, 4 tiles per wavefront).
-    cp.tile_nq = 2;
+    // attention q tiles (32 stacked rows).  Verify steps and short extends (<= 64 stacked rows
+    // per sequence): one tile per wavefront - measured, a wavefront that carries two tiles
+    // (sharing the K/V loads) is no faster, its serial softmax chain per key step is twice as
+    // long.  Longer extends: blocks of 4 tiles that share LDS-staged K/V.
+    cp.tile_nq = 1;
     for (int s = 0; s < n; ++s)
         if (T_each[s] * G > 64) cp.tile_nq = 4;
     cp.n_tiles = cp.bt_total = 0;

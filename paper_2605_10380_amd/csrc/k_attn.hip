@@ -18,6 +18,7 @@ namespace ax {
 
 typedef _Float16 f16;      // activation and KV-cache type of bf16-weight models
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
@@ -118,13 +119,22 @@ __global__ __launch_bounds__(64) void attn_simple_kernel(const T* __restrict__ q
 // block (g = l/32).  V pages are token-minor ([head_dim][16]), so the matching A operand of a
 // lane (channel d) is two 8-byte loads from its channel's 16-token row.
 // One 32-key step of the online softmax for the lane's query row.  s: raw scores q.k of the
-// lane's 16 keys (key of register r: kv0 + (r/4)*8 + g*4 + r%4); c = log2(e)/sqrt(hd).  Updates
-// the running maximum m (scaled, base-2 domain) and sum l, returns the rescale factor of the
-// output accumulators and the probabilities packed as the two PV operands.  The causal mask is
-// applied only on steps that reach past the tile's earliest row (`diagonal`, wavefront-uniform).
-// v_exp_f32 is used directly: its arguments are <= 0 and a result that underflows to 0 is exact
-// enough for a probability.
-__device__ __forceinline__ void online_softmax_step(f32x16& s, int kv0, int g, int pos_q, bool diagonal, float c,
+// lane's 16 keys (key of register r: kv0 + (r/4)*8 + g*4 + r%4); c = log2(e)/sqrt(hd).  m is the
+// reference exponent of the row (scaled, base-2 domain), l the running sum of 2^(s*c - m).  The
+// reference is NOT kept equal to the running maximum: it is only raised when some row of the
+// wavefront has a score more than SOFTMAX_SLACK above it (then every row moves to its current
+// maximum, the function returns true and the caller multiplies its output accumulators by
+// alpha).  In between, probabilities may exceed 1 by at most 2^SOFTMAX_SLACK, far inside the
+// range of fp16 operands and fp32 sums, and the per-step rescale of the accumulators - as much
+// vector work as the exponentials themselves - runs a handful of times per row instead of on
+// every step.  (m, l, o) stay mutually consistent, which is all the slice merge needs.
+// The probabilities are packed to fp16 (round toward zero, one instruction per pair) as the two
+// PV operands, and l sums exactly those packed values (dot product with ones), so the
+// normalisation matches the weights the PV product really uses.  The causal mask is applied only
+// on steps that reach past the tile's earliest row (`diagonal`, wavefront-uniform).  v_exp_f32
+// is used directly: a result that underflows to 0 is exact enough for a probability.
+constexpr float SOFTMAX_SLACK = 8.0f;
+__device__ __forceinline__ bool online_softmax_step(f32x16& s, int kv0, int g, int pos_q, bool diagonal, float c,
                                                     float& m, float& l, float& alpha, f16x8 (&pb)[2]) {
     if (diagonal) {
 #pragma unroll
@@ -137,19 +147,31 @@ __device__ __forceinline__ void online_softmax_step(f32x16& s, int kv0, int g, i
 #pragma unroll
     for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[r]);
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * c;                // c > 0: max commutes with the scaling
-    const float mn = fmaxf(m, mx);
-    const float mu = (mn == -INFINITY) ? 0.f : mn;             // row with nothing visible yet
-    alpha = __builtin_amdgcn_exp2f(m - mu);                    // m = -inf -> 0
-    float ps = 0.f;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        const float p = __builtin_amdgcn_exp2f(fmaf(s[r], c, -mu));   // masked: -inf -> 0
-        ps += p;
-        pb[r >> 3][r & 7] = (f16)p;
+    const bool raise = __any(mx > m + SOFTMAX_SLACK);           // m = -inf: any visible key raises it
+    alpha = 1.0f;
+    if (raise) {
+        const float mn = fmaxf(m, mx);
+        alpha = (mn == -INFINITY) ? 1.0f : __builtin_amdgcn_exp2f(m - mn);   // m = -inf -> 0
+        l *= alpha;
+        m = mn;
     }
+    const float mu = (m == -INFINITY) ? 0.f : m;               // row with nothing visible yet
+    const f16x2 ones = {(f16)1.0f, (f16)1.0f};
+    float ps = 0.f;
+    u32x4 pw[2];
+#pragma unroll
+    for (int r = 0; r < 16; r += 2) {
+        const float p0 = __builtin_amdgcn_exp2f(fmaf(s[r], c, -mu));       // masked: -inf -> 0
+        const float p1 = __builtin_amdgcn_exp2f(fmaf(s[r + 1], c, -mu));
+        const auto h = __builtin_amdgcn_cvt_pkrtz(p0, p1);
+        ps = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, h), ones, ps, false);
+        pw[r >> 3][(r & 7) >> 1] = __builtin_bit_cast(unsigned, h);
+    }
+    pb[0] = __builtin_bit_cast(f16x8, pw[0]);
+    pb[1] = __builtin_bit_cast(f16x8, pw[1]);
     ps += __shfl_xor(ps, 32, 64);
-    l = l * alpha + ps;
-    m = mn;
+    l += ps;
+    return raise;
 }
 
 struct AttnArgs {
@@ -251,14 +273,17 @@ __global__ __launch_bounds__(64) void attn_split_kernel(AttnArgs a) {
             for (int kk = 0; kk < KQ; ++kk) s = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf[buf][kk], qf[t][kk], s, 0, 0, 0);
             float alpha;
             f16x8 pb[2];
-            online_softmax_step(s, kv0, g, pos_q[t], kv0 + 31 > pos_min[t], c, m[t], l[t], alpha, pb);
+            if (online_softmax_step(s, kv0, g, pos_q[t], kv0 + 31 > pos_min[t], c, m[t], l[t], alpha, pb)) {
+#pragma unroll
+                for (int d = 0; d < DT; ++d)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) o[t][d][r] *= alpha;
+            }
 #pragma unroll
             for (int d = 0; d < DT; ++d) {
                 const f16x4 *v = vq[buf][d];
                 const f16x8 va = {v[0][0], v[0][1], v[0][2], v[0][3], v[1][0], v[1][1], v[1][2], v[1][3]};
                 const f16x8 vb = {v[2][0], v[2][1], v[2][2], v[2][3], v[3][0], v[3][1], v[3][2], v[3][3]};
-#pragma unroll
-                for (int r = 0; r < 16; ++r) o[t][d][r] *= alpha;
                 o[t][d] = __builtin_amdgcn_mfma_f32_32x32x16_f16(va, pb[0], o[t][d], 0, 0, 0);
                 o[t][d] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vb, pb[1], o[t][d], 0, 0, 0);
             }
@@ -395,15 +420,18 @@ __global__ __launch_bounds__(256) void attn_block_kernel(AttnArgs a) {
             const f16x8 kf = *(const f16x8*)(sK[buf] + ql * KLS + kk * 16 + g * 8);
             s = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf, qf[kk], s, 0, 0, 0);
         }
-        online_softmax_step(s, kv0, g, pos_q, kv0 + 31 > pos_tile_min, c, m, l, alpha_out, pb_out);
-        const float alpha = alpha_out;
+        if (online_softmax_step(s, kv0, g, pos_q, kv0 + 31 > pos_tile_min, c, m, l, alpha_out, pb_out)) {
+            const float alpha = alpha_out;
+#pragma unroll
+            for (int d = 0; d < DT; ++d)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) o[d][r] *= alpha;
+        }
         const f16x8* pb = pb_out;
 #pragma unroll
         for (int d = 0; d < DT; ++d) {
             const f16x8 va = *(const f16x8*)(sV[buf] + (d * 32 + ql) * VLS + g * 8);
             const f16x8 vb = *(const f16x8*)(sV[buf] + (HD + d * 32 + ql) * VLS + g * 8);
-#pragma unroll
-            for (int r = 0; r < 16; ++r) o[d][r] *= alpha;
             o[d] = __builtin_amdgcn_mfma_f32_32x32x16_f16(va, pb[0], o[d], 0, 0, 0);
             o[d] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vb, pb[1], o[d], 0, 0, 0);
         }
@@ -568,8 +596,6 @@ void launch_attention(DType dt, const void* q, void* out, KVGeom kv, int layer, 
             attn_block_kernel<128><<<grid, 256, 0, s>>>(a);
             attn_combine_kernel<128, 4><<<cgrid, 256, 0, s>>>(a);
         }
-    } else if (sv.tile_nq == 2) {
-        if (hd == 64) launch_attn_mfma<64, 2>(a, sv.n_tiles, s); else launch_attn_mfma<128, 2>(a, sv.n_tiles, s);
     } else {
         if (hd == 64) launch_attn_mfma<64, 1>(a, sv.n_tiles, s); else launch_attn_mfma<128, 1>(a, sv.n_tiles, s);
     }
