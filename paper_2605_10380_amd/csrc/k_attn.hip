@@ -563,6 +563,66 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(AttnArgs a) {
     a.out[((long long)(row0 + r / G) * a.Hq + hk * G + r % G) * HD + ch0 + sg] = (f16)(o / L);
 }
 
+// Slice merge for the block kernel (groups of 4 tiles, long extends: many tiles, few slices).
+// One block per (group, KV head, tile): 256 threads = 32 query rows x 8 channel groups, a thread
+// owns HD/8 consecutive channels of its row and walks the slices itself, so nothing meets in
+// LDS and every load of a pass is independent.  Pass 1: the row's reference exponents of all
+// slices -> maximum.  Pass 2: weights 2^(m_s - M), weighted sums, one 16-byte (HD = 64) or
+// 32-byte store of the normalised fp16 outputs.
+template <int HD>
+__global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a) {
+    constexpr int PS = HD * 32 + 64, NQ = 4, CPT = HD / 8, SU = 4;
+    const int Hkv = a.kv.n_kv_heads, G = a.Hq / Hkv;
+    const int t = blockIdx.x % NQ, hk = (blockIdx.x / NQ) % Hkv, tile = blockIdx.x / (NQ * Hkv);
+    const int ql = threadIdx.x & 31, cg = threadIdx.x >> 5;
+    const int4 ti0 = *(const int4*)(a.tile_info + tile * 8);
+    const int row0 = a.tile_info[tile * 8 + 4];
+    const int r = ti0.y + t * 32 + ql, n_stacked = ti0.w * G;
+    if (r >= n_stacked) return;
+    const int n_splits = a.n_splits;
+    const float* base = a.partials + ((long long)(tile * Hkv + hk) * n_splits * NQ + t) * PS;
+    const long long stride = (long long)NQ * PS;               // between slices
+
+    float M = -INFINITY;
+    for (int s0 = 0; s0 < n_splits; s0 += 8) {
+        float mv[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) mv[i] = s0 + i < n_splits ? base[(s0 + i) * stride + HD * 32 + ql] : -INFINITY;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) M = fmaxf(M, mv[i]);
+    }                                                          // finite: slice 0 always sees key 0
+    float L = 0.f, acc[CPT];
+#pragma unroll
+    for (int c = 0; c < CPT; ++c) acc[c] = 0.f;
+    for (int s0 = 0; s0 < n_splits; s0 += SU) {
+        float mv[SU], lv[SU], ov[SU][CPT];
+#pragma unroll
+        for (int i = 0; i < SU; ++i) {
+            const float* p = base + (long long)min(s0 + i, n_splits - 1) * stride;
+            mv[i] = s0 + i < n_splits ? p[HD * 32 + ql] : -INFINITY;       // absent slice: weight 0
+            lv[i] = p[HD * 32 + 32 + ql];
+#pragma unroll
+            for (int c = 0; c < CPT; ++c) ov[i][c] = p[(cg * CPT + c) * 32 + ql];
+        }
+#pragma unroll
+        for (int i = 0; i < SU; ++i) {
+            const float w = exp2f(mv[i] - M);
+            L += w * lv[i];
+#pragma unroll
+            for (int c = 0; c < CPT; ++c) acc[c] += w * ov[i][c];
+        }
+    }
+    const float inv = 1.0f / L;
+    f16* dst = a.out + ((long long)(row0 + r / G) * a.Hq + hk * G + r % G) * HD + cg * CPT;
+#pragma unroll
+    for (int c0 = 0; c0 < CPT; c0 += 8) {
+        f16x8 v;
+#pragma unroll
+        for (int c = 0; c < 8; ++c) v[c] = (f16)(acc[c0 + c] * inv);
+        *(f16x8*)(dst + c0) = v;
+    }
+}
+
 size_t attention_partial_floats(int n_tiles, int n_kv_heads, int head_dim, int n_splits) {
     return (size_t)n_tiles * n_kv_heads * n_splits * ((size_t)head_dim * 32 + 64);
 }
@@ -588,13 +648,14 @@ void launch_attention(DType dt, const void* q, void* out, KVGeom kv, int layer, 
     a.tile_info = sv.tile_info; a.bt = sv.bt; a.partials = partials;
     const int hd = kv.head_dim;
     if (sv.tile_nq == 4) {                                     // long extends: 4 tiles per block, K/V through LDS
-        dim3 grid(sv.n_tiles, kv.n_kv_heads, n_splits), cgrid(sv.n_tiles * kv.n_kv_heads * 4, hd / 4);
+        dim3 grid(sv.n_tiles, kv.n_kv_heads, n_splits);
+        const unsigned mgrid = (unsigned)(sv.n_tiles * kv.n_kv_heads * 4);
         if (hd == 64) {
             attn_block_kernel<64><<<grid, 256, 0, s>>>(a);
-            attn_combine_kernel<64, 4><<<cgrid, 256, 0, s>>>(a);
+            attn_merge_kernel<64><<<mgrid, 256, 0, s>>>(a);
         } else {
             attn_block_kernel<128><<<grid, 256, 0, s>>>(a);
-            attn_combine_kernel<128, 4><<<cgrid, 256, 0, s>>>(a);
+            attn_merge_kernel<128><<<mgrid, 256, 0, s>>>(a);
         }
     } else {
         if (hd == 64) launch_attn_mfma<64, 1>(a, sv.n_tiles, s); else launch_attn_mfma<128, 1>(a, sv.n_tiles, s);
