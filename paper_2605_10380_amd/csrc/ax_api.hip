@@ -41,7 +41,7 @@ ax_status fail(ax_status st, const char* fmt, ...) {
 constexpr uint32_t MAGIC_MODEL = 0x41584d44, MAGIC_POOL = 0x4158504c, MAGIC_KV = 0x41584b56, MAGIC_LUT = 0x41584c54, MAGIC_INDEX = 0x41584958;
 constexpr int N_SLOTS = 4;            // staging ring for per-call descriptors
 constexpr int LOGIT_ROWS = 256;       // rows per LM-head pass when only the argmax is wanted
-constexpr int SPLIT_ITEMS = 2048;     // wavefronts the split attention aims for
+constexpr int SPLIT_ITEMS = 2048;     // partial records the split attention may use (workspace size)
 
 size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 int isz(int dtype) { return dtype == AX_F32 ? 4 : 2; }
@@ -177,11 +177,15 @@ struct ProfScope {                     // records a pair of events around one la
     ~ProfScope() { if (b) (void)hipEventRecord(b, st); }
 };
 
-// Key slices of the split attention: enough wavefronts to fill the chip (~SPLIT_ITEMS), each
-// with at least two 32-key steps, rounded down to a power of two so that the choice (a launch
-// dimension, hence part of a captured graph) changes only when the cache length doubles.
+// Key slices of the split attention, from measurements on the ~1B and ~8B shapes: blocks of 4 q
+// tiles (long extends) run best at about two blocks per CU (2048 wavefronts); single-tile
+// wavefronts (verify steps, short extends) at about 512 wavefronts - beyond that the merge of the
+// slices costs more than the shorter key loops save.  At least two 32-key steps per slice,
+// rounded down to a power of two so that the choice (a launch dimension, hence part of a captured
+// graph) changes only when the cache length doubles.
 int choose_splits(const ax_model* m, int items, int nq, int max_steps) {
-    int want = std::max(1, (SPLIT_ITEMS + items - 1) / items);
+    const int target = nq == 1 ? 512 : 2048;
+    int want = std::max(1, target / std::max(1, items * nq));
     want = std::min(want, std::max(1, max_steps / 2));
     const size_t cap = std::max<size_t>(SPLIT_ITEMS, (size_t)m->lay.max_tiles * m->cfg.n_kv_heads) / ((size_t)items * nq);
     want = std::min(want, std::max(1, (int)cap));
