@@ -38,6 +38,10 @@ def _load():
     if not os.path.exists(LIB_PATH):
         raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2605_10380_amd.build` "
                           "(there is no fallback path)")
+    # PyTorch ships its own HIP runtime (same soname as the system one the library is linked
+    # against).  Whichever is loaded first serves the whole process, and PyTorch only works with
+    # its own: load it before the library so that both use that copy.
+    import torch  # noqa: F401
     lib = C.CDLL(LIB_PATH)
     vp, i32p, i64 = C.c_void_p, C.POINTER(C.c_int32), C.c_int64
     sig = {

@@ -109,9 +109,8 @@ __device__ __forceinline__ void block_inv_rms(const GemmArgs& g, int first_row, 
 // ------------------------------------------------------------------------------ tile kernel
 // MFMA 32x32x16 operand layout (wave64): lane l supplies row/col (l % 32) and the 8 k values
 // 8*(l/32) .. +7; result register r of lane l is C[(r/4)*8 + (l/32)*4 + r%4][l % 32].
-// Block = WM x WN wavefronts, wavefront tile = (TM*32) x (TN*32).  For EPI_QKV the wavefront's
-// TN*32 columns are exactly one head, so a rotary pair (c, c + hd/2) sits in the same lane and
-// register of tiles j and j + TN/2.
+// Block = WM x WN wavefronts, wavefront tile = (TM*32) x (TN*32).  (The QKV projection runs
+// as a plain store GEMM followed by qkv_reduce_rope_kernel.)
 template <int EPI, int TM, int TN, int WM = 2, int WN = 2>
 __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_tile_kernel(GemmArgs g) {
     constexpr int NT = 64 * WM * WN;                                         // threads per block
@@ -249,6 +248,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_tile_kernel(GemmArgs g
         for (int r = 0; r < 16; ++r) inv[i][r] = g.ssq ? s_inv[row_of(i, r)] : 1.0f;
 
     if constexpr (EPI == EPI_STORE_F32) {
+        float* __restrict__ C = g.Cf + (g.ksplit > 1 ? (long long)blockIdx.z * M * N : 0);   // K slice: its own slab
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -256,7 +256,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_tile_kernel(GemmArgs g
 #pragma unroll
                 for (int j = 0; j < TN; ++j) {
                     const int m = m0 + row_of(i, r), n = col_of(j);
-                    if (m < M && n < N) g.Cf[(long long)m * N + n] = acc[0][i][j][r] * inv[i][r];
+                    if (m < M && n < N) C[(long long)m * N + n] = acc[0][i][j][r] * inv[i][r];
                 }
     } else if constexpr (EPI == EPI_SWIGLU) {
         f16* __restrict__ out = (f16*)g.C16;
@@ -325,63 +325,6 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_tile_kernel(GemmArgs g
                     if (lrow == 0 && m < M && part < N / (TN * 32)) g.ssq_out[(long long)m * (N / (TN * 32)) + part] = ss;
                 }
             }
-    } else {                         // EPI_QKV: one head per wavefront, rotary pairs (j, j + TN/2)
-        const int head = n0 / (TN * 32) + wn;
-        const RopeArgs& ro = g.rope;
-        const int Hq = ro.n_q_heads, Hkv = ro.kv.n_kv_heads;
-        constexpr int hd = TN * 32;
-        if (head >= Hq + 2 * Hkv) return;
-        f16* pool = (f16*)ro.kv.base;
-        int pos[TM][16], slot[TM][16];
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int m = min(m0 + row_of(i, r), M - 1);
-                pos[i][r] = ro.row_pos[m];
-                slot[i][r] = ro.row_slot[m];
-            }
-        if (head < Hq + Hkv) {
-            float cs[TM][16][TN / 2], sn[TM][16][TN / 2];
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int r = 0; r < 16; ++r)
-#pragma unroll
-                    for (int j = 0; j < TN / 2; ++j) {
-                        const long long ao = (long long)pos[i][r] * (hd / 2) + j * 32 + lrow;
-                        cs[i][r][j] = ro.cos[ao];
-                        sn[i][r][j] = ro.sin[ao];
-                    }
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int m = m0 + row_of(i, r);
-                    if (m >= M) continue;
-                    f16* dst = head < Hq ? (f16*)ro.q_out + ((long long)m * Hq + head) * hd
-                                         : pool + ro.kv.plane(ro.layer, 0, head - Hq) + (long long)slot[i][r] * hd;
-#pragma unroll
-                    for (int j = 0; j < TN / 2; ++j) {
-                        const int c = j * 32 + lrow;
-                        const float a = acc[0][i][j][r] * inv[i][r], b = acc[0][i][j + TN / 2][r] * inv[i][r];
-                        dst[c] = (f16)(a * cs[i][r][j] - b * sn[i][r][j]);
-                        dst[c + hd / 2] = (f16)(b * cs[i][r][j] + a * sn[i][r][j]);
-                    }
-                }
-        } else {
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int m = m0 + row_of(i, r);
-                    if (m >= M) continue;
-                    f16* dst = pool + ro.kv.plane(ro.layer, 1, head - Hq - Hkv) +
-                               (long long)(slot[i][r] >> 4) * 16 * hd + (slot[i][r] & 15);
-#pragma unroll
-                    for (int j = 0; j < TN; ++j) dst[(long long)(j * 32 + lrow) * 16] = (f16)(acc[0][i][j][r] * inv[i][r]);
-                }
-        }
     }
 }
 
@@ -409,6 +352,54 @@ __global__ __launch_bounds__(256) void residual_reduce_kernel(GemmArgs g) {
 #pragma unroll
         for (int w = 16; w > 0; w >>= 1) ss += __shfl_xor(ss, w, 64);
         if ((lane & 31) == 0) g.ssq_out[(long long)m * (g.N / 32) + n / 32] = ss;
+    }
+}
+
+// Second half of a K-split QKV GEMM: sums the K-slice partials, applies 1 / rms of the row,
+// rotates q and k heads by the row's position and writes q to the activation buffer, k and v
+// into the row's KV slot.  grid (rows, ceil(items / 256)): a thread owns one (head, channel pair)
+// item of its row, so all its operands are requested in one go while wavefront 0 works out the
+// row's 1 / rms.
+__global__ __launch_bounds__(256) void qkv_reduce_rope_kernel(GemmArgs g) {
+    __shared__ float s_inv;
+    const int m = blockIdx.x, N = g.N;
+    const RopeArgs& ro = g.rope;
+    const int Hq = ro.n_q_heads, Hkv = ro.kv.n_kv_heads, hd = ro.kv.head_dim, half = hd >> 1;
+    const int n_items = (Hq + 2 * Hkv) * half;
+    const int it = min((int)(blockIdx.y * 256 + threadIdx.x), n_items - 1);
+    const bool live = blockIdx.y * 256 + threadIdx.x < n_items;
+    const int head = it / half, j = it - head * half;
+    const int pos = ro.row_pos[m], slot = ro.row_slot[m];
+    const long long slab = (long long)g.M * N;
+    const float* p = g.split_ws + (long long)m * N + head * hd + j;
+    float pa[SPLITK_MAX], pb[SPLITK_MAX];
+#pragma unroll
+    for (int ks = 0; ks < SPLITK_MAX; ++ks) {
+        pa[ks] = ks < g.ksplit ? p[ks * slab] : 0.f;
+        pb[ks] = ks < g.ksplit ? p[ks * slab + half] : 0.f;
+    }
+    const float c = ro.cos[(long long)pos * half + j], sg = ro.sin[(long long)pos * half + j];
+    if (threadIdx.x < 64) {
+        const float inv = g.ssq ? wave_inv_rms(g.ssq, m, g.nparts, g.d_norm, g.eps, threadIdx.x) : 1.0f;
+        if (threadIdx.x == 0) s_inv = inv;
+    }
+    __syncthreads();
+    if (!live) return;
+    float a = 0.f, b = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < SPLITK_MAX; ++ks) { a += pa[ks]; b += pb[ks]; }
+    a *= s_inv;
+    b *= s_inv;
+    f16* pool = (f16*)ro.kv.base;
+    if (head < Hq + Hkv) {
+        f16* dst = head < Hq ? (f16*)ro.q_out + ((long long)m * Hq + head) * hd
+                             : pool + ro.kv.plane(ro.layer, 0, head - Hq) + (long long)slot * hd;
+        dst[j] = (f16)(a * c - b * sg);
+        dst[j + half] = (f16)(b * c + a * sg);
+    } else {
+        f16* dst = pool + ro.kv.plane(ro.layer, 1, head - Hq - Hkv) + (long long)(slot >> 4) * 16 * hd + (slot & 15);
+        dst[(long long)j * 16] = (f16)a;
+        dst[(long long)(j + half) * 16] = (f16)b;
     }
 }
 
@@ -808,16 +799,31 @@ static int env_int(const char* name, int dflt) {
 static const int kForceNW = env_int("AX_SKINNY_NW", 0);   // experiment knob: wavefronts per block, 0 = automatic
 
 // M > 64: LDS-staged tiles.
+static const int kQkvKs = env_int("AX_QKV_KS", 0);   // experiment knob: K slices of the QKV GEMM (1 = never split)
 template <int EPI>
 static void launch_lds_tile(const GemmArgs& g, hipStream_t s) {
     const int M = g.M, N = g.N, K = g.K;
-    if (EPI == EPI_QKV) {                                 // one head per wavefront: BN = 2 heads
-        const int hd = g.rope.kv.head_dim;
-        dim3 grid((N + 2 * hd - 1) / (2 * hd), (M + 63) / 64);
-        if (hd == 64) gemm_bf16_tile_kernel<EPI_QKV, 1, 2><<<grid, 256, 0, s>>>(g);
-        else gemm_bf16_tile_kernel<EPI_QKV, 1, 4><<<grid, 256, 0, s>>>(g);
+    if constexpr (EPI == EPI_QKV) {
+        // Plain 64 x 128 tiles (8 wavefronts) write fp32 products, a second kernel does the rms
+        // scaling, rotary embedding and KV append: measured faster than a fused epilogue (one
+        // head per wavefront) at every size tried (M = 256 / 512, all three model shapes).  With fewer than 1024
+        // tiles K is cut in two slices that the second kernel adds up.
+        // (The workspace always holds at least one [M, N] fp32 slab: it is sized for 8 slabs of
+        // [max_tokens, d_model] and N <= 3 d_model.)
+        const long long tiles = (long long)((N + 127) / 128) * ((M + 63) / 64);
+        int ks = (tiles < 1024 && K % 128 == 0) ? 2 : 1;
+        if (kQkvKs > 0 && K % (kQkvKs * 64) == 0) ks = kQkvKs;
+        while (ks > 1 && (size_t)ks * M * N * sizeof(float) > g.split_ws_bytes) ks >>= 1;
+        GemmArgs gs = g;
+        gs.ksplit = ks;
+        GemmArgs gp = gs;                                 // the products: no scaling, no epilogue work
+        gp.ssq = nullptr;
+        gp.Cf = g.split_ws;
+        dim3 grid((N + 127) / 128, (M + 63) / 64, ks);
+        gemm_bf16_tile_kernel<EPI_STORE_F32, 1, 1, 2, 4><<<grid, 512, 0, s>>>(gp);
+        qkv_reduce_rope_kernel<<<dim3((unsigned)M, (unsigned)((N / 2 + 255) / 256)), 256, 0, s>>>(gs);
         return;
-    }
+    } else {
     // 64 x 128 tiles, 2 x 4 wavefronts of 32 x 32 each: two wavefronts per SIMD cover each
     // other's LDS and barrier waits (measured 10-20 % faster than 2 x 2 wavefronts of 32 x 64)
     dim3 grid((N + 127) / 128, (M + 63) / 64);
@@ -838,6 +844,7 @@ static void launch_lds_tile(const GemmArgs& g, hipStream_t s) {
         }
     }
     gemm_bf16_tile_kernel<EPI, 1, 1, 2, 4><<<grid, 512, 0, s>>>(g);
+    }
 }
 
 template <int EPI>
