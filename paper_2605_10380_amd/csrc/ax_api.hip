@@ -86,7 +86,7 @@ Layout make_layout(const ax_model_config& c) {
     L.desc = take((N_SLOTS + 1) * align_up(L.desc_ints * 4));   // ring + the slot of captured graphs
     L.x = take(T * c.d_model * 4);
     L.h = take(T * c.d_model * a);
-    L.ssq = take(T * (size_t)(c.d_model / 16 + 1) * 4);       // sum-of-squares partials per row
+    L.ssq = take(T * (size_t)(c.d_model / 8 + 1) * 4);        // sum-of-squares partials per row
     L.qkv = take(T * (size_t)(c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim * 4);
     L.q = take(T * (size_t)c.n_q_heads * c.head_dim * a);
     L.attn = take(T * (size_t)c.n_q_heads * c.head_dim * a);

@@ -539,10 +539,13 @@ __global__ __launch_bounds__(256) void gemm_bf16_stream_swiglu_kernel(GemmArgs g
 // D rows are output columns n, D columns are activation rows m, so a lane ends up with four
 // consecutive n of one row m (one 16-byte store).
 //
+// COLS < 16 (residual GEMMs): a block owns fewer columns so that every CU gets a block; the
+// unused MFMA rows are zero and their lanes issue no loads.
+//
 // For EPI_QKV the 16 columns of a block are 8 + 8 rotary partners of one head: local columns
 // 0..7 are channels j0..j0+7, local columns 8..15 are channels hd/2 + j0 .. +7, so the partner
 // of a lane's value lives in lane ^ 32.
-template <int EPI, int MT, int NW>
+template <int EPI, int MT, int NW, int COLS = 16>
 __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(1, NW >= 8 ? 4 : 8)))
 void gemm_bf16_skinny_kernel(GemmArgs g) {
     constexpr int NB = EPI == EPI_SWIGLU ? 2 : 1;
@@ -555,7 +558,7 @@ void gemm_bf16_skinny_kernel(GemmArgs g) {
     const int M = g.M, N = g.N, K = g.K;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int lr = lane & 15, lg = lane >> 4;
-    const int n0 = blockIdx.x * 16;
+    const int n0 = blockIdx.x * COLS;
     const int kslice = K / NW, kbeg = wave * kslice, kend = kbeg + kslice;
 
     int wrow;                            // weight row this lane streams
@@ -566,8 +569,9 @@ void gemm_bf16_skinny_kernel(GemmArgs g) {
         q_j0 = (blockIdx.x % per) * 8;
         wrow = q_head * hd + (lr < 8 ? q_j0 + lr : hd / 2 + q_j0 + lr - 8);
     } else {
-        wrow = min(n0 + lr, N - 1);
+        wrow = min(n0 + min(lr, COLS - 1), N - 1);
     }
+    const bool wlane = lr < COLS;      // COLS < 16: the other MFMA rows are zero, their lanes request nothing
     const bf16* wp = W + (long long)wrow * K + lg * 8;
     const bf16* wp2 = NB == 2 ? W2 + (long long)wrow * K + lg * 8 : nullptr;
     const f16* xp[MT];
@@ -622,7 +626,7 @@ void gemm_bf16_skinny_kernel(GemmArgs g) {
         auto loads = [&](int set, int kk) {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                rw[set][0][u] = *(const u32x4*)(wp + kk + 32 * u);
+                rw[set][0][u] = (COLS == 16 || wlane) ? *(const u32x4*)(wp + kk + 32 * u) : (u32x4){0u, 0u, 0u, 0u};
                 if (NB == 2) rw[set][NB - 1][u] = *(const u32x4*)(wp2 + kk + 32 * u);
             }
 #pragma unroll
@@ -664,7 +668,7 @@ void gemm_bf16_skinny_kernel(GemmArgs g) {
             f16x8 fx[MT][4];
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                rw[0][u] = *(const u32x4*)(wp + k + 32 * u);
+                rw[0][u] = (COLS == 16 || wlane) ? *(const u32x4*)(wp + k + 32 * u) : (u32x4){0u, 0u, 0u, 0u};
                 if (NB == 2) rw[NB - 1][u] = *(const u32x4*)(wp2 + k + 32 * u);
             }
 #pragma unroll
@@ -718,7 +722,7 @@ void gemm_bf16_skinny_kernel(GemmArgs g) {
             for (int w = 1; w < NW; ++w) sum[b] += red[w][b][t][lane];
         }
         const int m = t * 16 + lr, n = n0 + lg * 4;
-        const bool mok = m < M;
+        const bool mok = m < M && lg * 4 < COLS;
         const float inv = g.ssq ? s_inv[t * 16 + lr] : 1.0f;
         const long long o = (long long)m * N + n;
         if (EPI == EPI_STORE_F32) {
@@ -745,10 +749,10 @@ void gemm_bf16_skinny_kernel(GemmArgs g) {
                     *(f16x4*)((f16*)g.C16 + o) = h;
                 }
             }
-            if (g.gain_next) {           // sum of squares over the block's 16 columns, per row
+            if (g.gain_next) {           // sum of squares over the block's COLS columns, per row
                 ss += __shfl_xor(ss, 16, 64);
                 ss += __shfl_xor(ss, 32, 64);
-                if (lg == 0 && mok) g.ssq_out[(long long)m * (N / 16) + blockIdx.x] = ss;
+                if (lg == 0 && mok) g.ssq_out[(long long)m * (N / COLS) + blockIdx.x] = ss;
             }
         } else {                         // EPI_QKV
             const RopeArgs& ro = g.rope;
@@ -782,14 +786,39 @@ void gemm_bf16_skinny_kernel(GemmArgs g) {
     }
 }
 
+// Columns per block of the skinny kernel.  A CU pulls only ~26 GB/s of weights however many
+// wavefronts it runs (measured), so a launch streams at the chip's rate only if every CU has a
+// block: residual GEMMs (N = d_model, too few blocks of 16 columns) use 12 or 8 columns per
+// block when that shortens rounds-of-256-blocks x columns.
+static int skinny_cols(int epi, int N) {
+    if (epi != EPI_RESIDUAL) return 16;
+    int best = 16, best_cost = ((N / 16 + 255) / 256) * 16;
+    for (int c : {12, 8}) {
+        if (N % c) continue;
+        const int cost = ((N / c + 255) / 256) * c;
+        if (cost < best_cost) { best = c; best_cost = cost; }
+    }
+    return best;
+}
+
+template <int EPI, int MT, int COLS>
+static void launch_skinny_cols(const GemmArgs& g, int nw, hipStream_t s) {
+    const int grid = (g.N + COLS - 1) / COLS;
+    if (nw == 16) gemm_bf16_skinny_kernel<EPI, MT, 16, COLS><<<grid, 1024, 0, s>>>(g);
+    else if (nw == 1) gemm_bf16_skinny_kernel<EPI, MT, 1, COLS><<<grid, 64, 0, s>>>(g);
+    else if (nw == 2) gemm_bf16_skinny_kernel<EPI, MT, 2, COLS><<<grid, 128, 0, s>>>(g);
+    else if (nw == 8) gemm_bf16_skinny_kernel<EPI, MT, 8, COLS><<<grid, 512, 0, s>>>(g);
+    else gemm_bf16_skinny_kernel<EPI, MT, 4, COLS><<<grid, 256, 0, s>>>(g);
+}
+
 template <int EPI, int MT>
 static void launch_skinny_nw(const GemmArgs& g, int nw, hipStream_t s) {
-    const int grid = (g.N + 15) / 16;
-    if (nw == 16) gemm_bf16_skinny_kernel<EPI, MT, 16><<<grid, 1024, 0, s>>>(g);
-    else if (nw == 1) gemm_bf16_skinny_kernel<EPI, MT, 1><<<grid, 64, 0, s>>>(g);
-    else if (nw == 2) gemm_bf16_skinny_kernel<EPI, MT, 2><<<grid, 128, 0, s>>>(g);
-    else if (nw == 8) gemm_bf16_skinny_kernel<EPI, MT, 8><<<grid, 512, 0, s>>>(g);
-    else gemm_bf16_skinny_kernel<EPI, MT, 4><<<grid, 256, 0, s>>>(g);
+    if constexpr (EPI == EPI_RESIDUAL) {
+        const int c = skinny_cols(EPI, g.N);
+        if (c == 8) { launch_skinny_cols<EPI, MT, 8>(g, nw, s); return; }
+        if (c == 12) { launch_skinny_cols<EPI, MT, 12>(g, nw, s); return; }
+    }
+    launch_skinny_cols<EPI, MT, 16>(g, nw, s);
 }
 
 static int env_int(const char* name, int dflt) {
@@ -853,7 +882,8 @@ static void launch_bf16(const GemmArgs& g, hipStream_t s) {
     if (M <= 64) {
         // wavefronts per block (= K slices): enough to keep ~2k wavefronts in flight, each with
         // at least 128 of K; K / nw must stay a multiple of the MFMA k (32)
-        const long long tiles = (N + 15) / 16;
+        const int cols = skinny_cols(EPI, N);
+        const long long tiles = (N + cols - 1) / cols;
         int nw = 1;
         while (nw < 16 && tiles * nw < 2048 && K % (nw * 2 * 32) == 0 && K / (nw * 2) >= 128) nw *= 2;
         if (kForceNW && K % (kForceNW * 32) == 0) nw = kForceNW;
@@ -871,7 +901,7 @@ static void launch_bf16(const GemmArgs& g, hipStream_t s) {
     launch_lds_tile<EPI>(g, s);
 }
 
-int gemm_ssq_parts(int M, int N) { return M <= 64 ? N / 16 : N / 32; }
+int gemm_ssq_parts(int M, int N) { return M <= 64 ? N / skinny_cols(EPI_RESIDUAL, N) : N / 32; }
 
 void launch_gemm_bf16(Epilogue epi, const GemmArgs& g, hipStream_t s) {
     if (epi == EPI_STORE_F32) launch_bf16<EPI_STORE_F32>(g, s);
