@@ -257,10 +257,12 @@ ax_status prepare_call(ax_model* m, int n, ax_kv* const* kvs, const int32_t* tok
     // attention q tiles (32 stacked rows).  Verify steps and short extends (<= 64 stacked rows
     // per sequence): one tile per wavefront - measured, a wavefront that carries two tiles
     // (sharing the K/V loads) is no faster, its serial softmax chain per key step is twice as
-    // long.  Longer extends: blocks of 4 tiles that share LDS-staged K/V.
+    // long.  Longer extends: blocks of 4 or 8 tiles that share LDS-staged K/V.
     cp.tile_nq = 1;
-    for (int s = 0; s < n; ++s)
-        if (T_each[s] * G > 64) cp.tile_nq = 4;
+    for (int s = 0; s < n; ++s) {
+        if (T_each[s] * G > 64 && cp.tile_nq < 4) cp.tile_nq = 4;
+        if (T_each[s] * G >= 2048) cp.tile_nq = 8;    // 8 tiles per block: ~10 % on the ~8B shape at T = 512, none below
+    }
     cp.n_tiles = cp.bt_total = 0;
     for (int s = 0; s < n; ++s) {
         cp.n_tiles += (T_each[s] * G + 32 * cp.tile_nq - 1) / (32 * cp.tile_nq);

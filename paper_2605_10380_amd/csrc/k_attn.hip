@@ -337,12 +337,13 @@ __global__ __launch_bounds__(64) void attn_split_kernel(AttnArgs a) {
 // free); V rows [2 blocks * HD channels][16 tokens in operand order + 8 pad], where operand order
 // puts tokens {0-3, 8-11, 4-7, 12-15} so that a lane's PV operand (tokens 4g..4g+3 and
 // 8+4g..8+4g+3 of its channel) is one 16-byte read.
-template <int HD>
-__global__ __launch_bounds__(256) void attn_block_kernel(AttnArgs a) {
-    constexpr int KQ = HD / 16, DT = HD / 32, PS = HD * 32 + 64, NQ = 4;
+template <int HD, int NQ>
+__global__ __launch_bounds__(64 * NQ) void attn_block_kernel(AttnArgs a) {
+    constexpr int KQ = HD / 16, DT = HD / 32, PS = HD * 32 + 64, NT = 64 * NQ;
     constexpr int D = 4;                              // prefetch distance in key steps (even)
     constexpr int KLS = HD + 8, VLS = 24;             // padded LDS row lengths (fp16 elements)
-    constexpr int CH = HD / 64;                       // 16-byte chunks of K (and of V) per thread and step
+    constexpr int TCH = 32 * HD / 8;                  // 16-byte chunks of K (and of V) per step
+    constexpr int CH = (TCH + NT - 1) / NT;           // ... per thread (threads past TCH idle)
     __shared__ __attribute__((aligned(16))) f16 sK[2][32 * KLS];
     __shared__ __attribute__((aligned(16))) f16 sV[2][2 * HD * VLS];
 
@@ -389,7 +390,8 @@ __global__ __launch_bounds__(256) void attn_block_kernel(AttnArgs a) {
         const int kv0 = st * 32;
 #pragma unroll
         for (int i = 0; i < CH; ++i) {
-            const int cidx = tid + 256 * i;
+            const int cidx = min(tid + NT * i, TCH - 1);
+            if (TCH % NT != 0 && tid + NT * i >= TCH) continue;            // more threads than chunks: the rest load nothing
             const int key = min(kv0 + cidx / (HD / 8), kv_len - 1);
             const int kblk = __shfl(tabv, (key >> 4) - 2 * chunk, 64);
             rk[slot][i] = *(const u32x4*)(Kp + ((long long)kblk * 16 + (key & 15)) * HD + (cidx % (HD / 8)) * 8);
@@ -401,7 +403,8 @@ __global__ __launch_bounds__(256) void attn_block_kernel(AttnArgs a) {
     auto lstore = [&](int slot, int buf) {
 #pragma unroll
         for (int i = 0; i < CH; ++i) {
-            const int cidx = tid + 256 * i;
+            const int cidx = tid + NT * i;
+            if (TCH % NT != 0 && cidx >= TCH) continue;
             *(u32x4*)(sK[buf] + (cidx / (HD / 8)) * KLS + (cidx % (HD / 8)) * 8) = rk[slot][i];
             // tokens 8h..8h+3 -> operand position 4h, tokens 8h+4..8h+7 -> operand position 8 + 4h
             const int vrow = (cidx / (2 * HD)) * HD + (cidx / 2) % HD, h = cidx % 2;
@@ -569,9 +572,9 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(AttnArgs a) {
 // LDS and every load of a pass is independent.  Pass 1: the row's reference exponents of all
 // slices -> maximum.  Pass 2: weights 2^(m_s - M), weighted sums, one 16-byte (HD = 64) or
 // 32-byte store of the normalised fp16 outputs.
-template <int HD>
+template <int HD, int NQ>
 __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a) {
-    constexpr int PS = HD * 32 + 64, NQ = 4, CPT = HD / 8, SU = 4;
+    constexpr int PS = HD * 32 + 64, CPT = HD / 8, SU = 4;
     const int Hkv = a.kv.n_kv_heads, G = a.Hq / Hkv;
     const int t = blockIdx.x % NQ, hk = (blockIdx.x / NQ) % Hkv, tile = blockIdx.x / (NQ * Hkv);
     const int ql = threadIdx.x & 31, cg = threadIdx.x >> 5;
@@ -647,15 +650,25 @@ void launch_attention(DType dt, const void* q, void* out, KVGeom kv, int layer, 
     a.q = (const f16*)q; a.out = (f16*)out; a.kv = kv; a.layer = layer; a.Hq = n_q_heads; a.n_splits = n_splits;
     a.tile_info = sv.tile_info; a.bt = sv.bt; a.partials = partials;
     const int hd = kv.head_dim;
-    if (sv.tile_nq == 4) {                                     // long extends: 4 tiles per block, K/V through LDS
+    if (sv.tile_nq >= 4) {                                     // long extends: 4 or 8 tiles per block, K/V through LDS
         dim3 grid(sv.n_tiles, kv.n_kv_heads, n_splits);
-        const unsigned mgrid = (unsigned)(sv.n_tiles * kv.n_kv_heads * 4);
-        if (hd == 64) {
-            attn_block_kernel<64><<<grid, 256, 0, s>>>(a);
-            attn_merge_kernel<64><<<mgrid, 256, 0, s>>>(a);
+        const unsigned mgrid = (unsigned)(sv.n_tiles * kv.n_kv_heads * sv.tile_nq);
+        if (sv.tile_nq == 4) {
+            if (hd == 64) {
+                attn_block_kernel<64, 4><<<grid, 256, 0, s>>>(a);
+                attn_merge_kernel<64, 4><<<mgrid, 256, 0, s>>>(a);
+            } else {
+                attn_block_kernel<128, 4><<<grid, 256, 0, s>>>(a);
+                attn_merge_kernel<128, 4><<<mgrid, 256, 0, s>>>(a);
+            }
         } else {
-            attn_block_kernel<128><<<grid, 256, 0, s>>>(a);
-            attn_merge_kernel<128><<<mgrid, 256, 0, s>>>(a);
+            if (hd == 64) {
+                attn_block_kernel<64, 8><<<grid, 512, 0, s>>>(a);
+                attn_merge_kernel<64, 8><<<mgrid, 256, 0, s>>>(a);
+            } else {
+                attn_block_kernel<128, 8><<<grid, 512, 0, s>>>(a);
+                attn_merge_kernel<128, 8><<<mgrid, 256, 0, s>>>(a);
+            }
         }
     } else {
         if (hd == 64) launch_attn_mfma<64, 1>(a, sv.n_tiles, s); else launch_attn_mfma<128, 1>(a, sv.n_tiles, s);

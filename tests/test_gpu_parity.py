@@ -143,6 +143,22 @@ def test_extend_logits_small(B, which, P, T):
     dm.close()
 
 
+@pytest.mark.parametrize("which,P,T", [("bf16-hd64-g4", 40, 520), ("bf16-hd128-g3", 10, 700)])
+def test_very_long_extend_uses_eight_tile_blocks(B, which, P, T):
+    """T * G >= 2048 stacked rows: the attention launches blocks of 8 q tiles."""
+    sh = SMALL[which]
+    w = I.make_weights(sh, 8)
+    toks = I.templated_prompt(sh.vocab, 8, P + T)
+    dm = B.DeviceModel(sh, w, max_pos=1024, max_tokens=768, pool_tokens=2048)
+    kv, ref_kv = dm.new_kv(), okv(sh)
+    dm.extend(kv, toks[:P])
+    O.forward(sh, w, toks[:P], ref_kv)
+    got = dm.extend(kv, toks[P:], B.AX_OUT_ALL_LOGITS).cpu().numpy()
+    check_logits(sh, got, O.forward(sh, w, toks[P:], ref_kv), f"{which} P={P} T={T}")
+    B.ax_kv_free(kv)
+    dm.close()
+
+
 @pytest.mark.parametrize("which", ["bf16-hd64-g4", "bf16-hd128-g3", "f32-hd32"])
 @pytest.mark.parametrize("k", [0, 1, 4, 8, 16])
 def test_verify_rounds_seeded_acceptance(B, which, k):
