@@ -307,6 +307,55 @@ def test_errors_leave_kv_untouched(B):
     dm.close()
 
 
+@pytest.mark.parametrize("which", ["bf16-hd64-g4", "f32-hd32"])
+def test_limits_are_reachable(B, which):
+    """Exactly max_tokens rows in one call, a sequence filled to exactly max_pos, a verify round
+    with the most drafts a call can carry, max_seqs sequences in one batch, one token on an empty
+    sequence - each against the oracle; one past each limit is refused."""
+    sh = SMALL[which]
+    w = I.make_weights(sh, 71)
+    MT, MP, MS = 96, 208, 3
+    dm = B.DeviceModel(sh, w, max_pos=MP, max_tokens=MT, pool_tokens=1024, max_seqs=MS)
+    toks = I.templated_prompt(sh.vocab, 71, MP)
+    kv, ref = dm.new_kv(), okv(sh)
+    got = dm.extend(kv, toks[:1], B.AX_OUT_ALL_LOGITS).cpu().numpy()             # one token, empty cache
+    check_logits(sh, got, O.forward(sh, w, toks[:1], ref), "T=1 on an empty sequence")
+    got = dm.extend(kv, toks[1:1 + MT], B.AX_OUT_LAST_LOGITS).cpu().numpy()      # max_tokens rows
+    check_logits(sh, got[0], O.forward(sh, w, toks[1:1 + MT], ref)[-1], "T = max_tokens")
+    with pytest.raises(B.AxError):
+        dm.extend(kv, toks[:MT + 1])
+    got = dm.extend(kv, toks[1 + MT:MP - 16], B.AX_OUT_LAST_LOGITS).cpu().numpy()
+    O.forward(sh, w, toks[1 + MT:MP - 16], ref)
+    got = dm.extend(kv, toks[MP - 16:MP], B.AX_OUT_LAST_LOGITS).cpu().numpy()     # ends exactly at max_pos
+    check_logits(sh, got[0], O.forward(sh, w, toks[MP - 16:MP], ref)[-1], "P + T = max_pos")
+    assert B.ax_kv_len(kv) == MP
+    with pytest.raises(B.AxError):
+        dm.extend(kv, toks[:1])
+    with pytest.raises(B.AxError):
+        dm.verify(kv, int(toks[0]), [])                                           # no room for the pending token
+    B.ax_kv_truncate(kv, 100)
+    ref.truncate(100)
+    drafts = I.zipf_tokens(sh.vocab, 71, "d", MT - 1)                             # 1 + k = max_tokens rows
+    a_ref, n_ref, lg = O.verify(sh, w, ref, int(toks[100]), drafts)
+    a, nxt = dm.verify(kv, int(toks[100]), drafts)
+    if O.top2_margin(lg[min(a, a_ref)]) > MARGIN:
+        assert (a, nxt) == (a_ref, n_ref)
+    with pytest.raises(B.AxError):
+        dm.verify(kv, int(toks[100]), I.zipf_tokens(sh.vocab, 71, "d", MT))
+    # max_seqs sequences in one call; one more is refused
+    kvs = [dm.new_kv() for _ in range(MS + 1)]
+    news = [toks[10 * s:10 * s + 7 + s] for s in range(MS + 1)]
+    got = dm.extend_batch(kvs[:MS], news[:MS], B.AX_OUT_LAST_LOGITS).cpu().numpy()
+    for s in range(MS):
+        check_logits(sh, got[s], O.forward(sh, w, news[s], okv(sh))[-1], f"batch of max_seqs, sequence {s}")
+    with pytest.raises(B.AxError):
+        dm.extend_batch(kvs, news)
+    assert B.ax_kv_len(kvs[MS]) == 0
+    for k_ in kvs + [kv]:
+        B.ax_kv_free(k_)
+    dm.close()
+
+
 # ------------------------------------------------------------------ full-size shapes
 
 @pytest.mark.parametrize("name,P,T,k", [("1b", 4096, 256, 8), ("8b", 2048, 128, 8)])
