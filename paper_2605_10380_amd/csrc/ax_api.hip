@@ -67,10 +67,16 @@ bool config_ok(const ax_model_config* c, ax_status* why) {
 
 struct Layout {                       // byte offsets into the workspace
     size_t rope_cos, rope_sin, desc, x, h, ssq, qkv, q, attn, ffn, partials, splitk, logits, amax_scratch,
-        amax_out, result, total;
+        amax_out, result, packed, total;
     size_t desc_ints;                 // capacity of one descriptor slot
     int max_tiles, max_bt;
 };
+
+size_t packed_weight_bytes(const ax_model_config& c) {
+    const size_t qkv = (size_t)(c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim, qd = (size_t)c.n_q_heads * c.head_dim;
+    const size_t per_layer = qkv * c.d_model + (size_t)c.d_model * qd + 3 * (size_t)c.d_ff * c.d_model;
+    return align_up(((size_t)c.n_layers * per_layer + (size_t)c.vocab * c.d_model) * 2 + 256 * (5 * (size_t)c.n_layers + 1));
+}
 
 Layout make_layout(const ax_model_config& c) {
     Layout L{};
@@ -98,6 +104,8 @@ Layout make_layout(const ax_model_config& c) {
     L.amax_scratch = take(2 * std::min<size_t>(T, LOGIT_ROWS) * ax::ARGMAX_PARTS * 4);
     L.amax_out = take(T * 4);
     L.result = take(align_up(8 * S));
+    // bf16 models: the library's own copy of every weight matrix in the kernels' packed layout
+    L.packed = take(c.dtype == AX_BF16 ? packed_weight_bytes(c) : 0);
     L.total = o;
     return L;
 }
@@ -609,6 +617,27 @@ ax_status ax_model_create(const ax_model_config* cfg, const ax_weights* w, void*
     e = hipMemcpy(m->ws + L.rope_cos, cs.data(), cs.size() * 4, hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemcpy(m->ws + L.rope_sin, sn.data(), sn.size() * 4, hipMemcpyHostToDevice);
     if (e != hipSuccess) { cleanup(); return fail(AX_ERR_DEVICE, "rotary table upload: %s", hipGetErrorString(e)); }
+    if (cfg->dtype == AX_BF16) {
+        // the kernels read their own packed copies of the matrices (token embedding and gains stay as given)
+        char* at = m->ws + L.packed;
+        const int d = cfg->d_model, qkv = (cfg->n_q_heads + 2 * cfg->n_kv_heads) * cfg->head_dim, qd = cfg->n_q_heads * cfg->head_dim;
+        auto pack = [&](const void*& w_ptr, int N, int K) {
+            ax::launch_pack_weights(w_ptr, at, N, K, nullptr);
+            w_ptr = at;
+            at += align_up((size_t)N * K * 2);
+        };
+        for (size_t l = 0; l < nl; ++l) {
+            pack(m->wqkv[l], qkv, d);
+            pack(m->wo[l], d, qd);
+            pack(m->w_gate[l], cfg->d_ff, d);
+            pack(m->w_up[l], cfg->d_ff, d);
+            pack(m->w_down[l], d, cfg->d_ff);
+        }
+        pack(m->lm_head, cfg->vocab, d);
+        e = hipGetLastError();
+        if (e == hipSuccess) e = hipDeviceSynchronize();
+        if (e != hipSuccess) { cleanup(); return fail(AX_ERR_DEVICE, "weight repack: %s", hipGetErrorString(e)); }
+    }
     m->magic = MAGIC_MODEL;
     *out = m;
     return AX_OK;
@@ -1154,9 +1183,25 @@ ax_status ax_dbg_gemm(int dtype, int epilogue, const void* A, const void* W, con
         return fail(AX_ERR_INVALID, "bad argument");
     if (dtype == AX_BF16 && (K % 64 != 0 || N % 16 != 0)) return fail(AX_ERR_UNSUPPORTED, "bf16 needs K %% 64 == 0, N %% 16 == 0");
     hipStream_t s = (hipStream_t)hip_stream;
-    ax::launch_gemm(dtype == AX_F32 ? ax::F32 : ax::BF16, (ax::Epilogue)epilogue, A, W, W2, C, M, N, K, s);
-    HIP_TRY(hipGetLastError());
-    HIP_TRY(hipStreamSynchronize(s));
+    // test-only entry: the kernels read packed weights, the caller passes row-major ones - repack
+    // into temporary device memory (the only place the library allocates device memory)
+    void *pw = nullptr, *pw2 = nullptr;
+    if (dtype == AX_BF16) {
+        const size_t bytes = (size_t)N * K * 2;
+        HIP_TRY(hipMalloc(&pw, bytes));
+        ax::launch_pack_weights(W, pw, N, K, s);
+        if (W2) {
+            hipError_t e2 = hipMalloc(&pw2, bytes);
+            if (e2 != hipSuccess) { (void)hipFree(pw); return fail(AX_ERR_DEVICE, "hipMalloc: %s", hipGetErrorString(e2)); }
+            ax::launch_pack_weights(W2, pw2, N, K, s);
+        }
+    }
+    ax::launch_gemm(dtype == AX_F32 ? ax::F32 : ax::BF16, (ax::Epilogue)epilogue, A, pw ? pw : W, pw2 ? pw2 : W2, C, M, N, K, s);
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    if (pw) (void)hipFree(pw);
+    if (pw2) (void)hipFree(pw2);
+    if (e != hipSuccess) return fail(AX_ERR_DEVICE, "debug GEMM: %s", hipGetErrorString(e));
     return AX_OK;
 }
 
@@ -1172,6 +1217,18 @@ ax_status ax_dbg_gemm_time(int dtype, int epilogue, const void* A, const void* W
     HIP_TRY(hipEventCreate(&e0));
     HIP_TRY(hipEventCreate(&e1));
     const ax::DType dt = dtype == AX_F32 ? ax::F32 : ax::BF16;
+    void *pw = nullptr, *pw2 = nullptr;                     // packed copies of all the weight sets (test-only allocation)
+    if (dtype == AX_BF16) {
+        if (hipMalloc(&pw, (size_t)w_count * w_stride_bytes) != hipSuccess) return fail(AX_ERR_DEVICE, "hipMalloc failed");
+        if (W2 && hipMalloc(&pw2, (size_t)w_count * w_stride_bytes) != hipSuccess) { (void)hipFree(pw); return fail(AX_ERR_DEVICE, "hipMalloc failed"); }
+        for (int i = 0; i < w_count; ++i) {
+            const size_t off = (size_t)i * w_stride_bytes;
+            ax::launch_pack_weights((const char*)W + off, (char*)pw + off, N, K, s);
+            if (W2) ax::launch_pack_weights((const char*)W2 + off, (char*)pw2 + off, N, K, s);
+        }
+        W = pw;
+        if (W2) W2 = pw2;
+    }
     auto run = [&](int i) {
         const size_t off = (size_t)(i % w_count) * w_stride_bytes;
         ax::launch_gemm(dt, (ax::Epilogue)epilogue, A, (const char*)W + off, W2 ? (const char*)W2 + off : nullptr, C,
@@ -1186,6 +1243,8 @@ ax_status ax_dbg_gemm_time(int dtype, int epilogue, const void* A, const void* W
     if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
     (void)hipEventDestroy(e0);
     (void)hipEventDestroy(e1);
+    if (pw) (void)hipFree(pw);
+    if (pw2) (void)hipFree(pw2);
     if (e != hipSuccess) return fail(AX_ERR_DEVICE, "timing: %s", hipGetErrorString(e));
     *avg_us = ms * 1000.f / (float)iters;
     return AX_OK;
