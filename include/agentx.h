@@ -73,8 +73,12 @@ typedef struct {
     int max_seqs;     /* most sequences one ax_extend_batch call may carry (>= 1)                   */
 } ax_model_config;
 
-/* Device pointers, borrowed for the life of the model.  Element type = config.dtype.
- * Per-layer members are HOST arrays of n_layers device pointers (copied at create time). */
+/* Device pointers, row-major [out, in] (y = x W^T).  Element type = config.dtype.
+ * Per-layer members are HOST arrays of n_layers device pointers (copied at create time).
+ * AX_F32: all tensors are borrowed for the life of the model.  AX_BF16: ax_model_create copies
+ * the seven kinds of matrices (wqkv, wo, w_gate, w_up, w_down, lm_head) into the workspace in
+ * the kernels' own layout and never reads the caller's copies again - they may be released
+ * after the call; tok_emb and the three kinds of gain vectors stay borrowed. */
 typedef struct {
     const void *tok_emb;            /* [vocab, d_model]                                             */
     const void *lm_head;            /* [vocab, d_model]                                             */
@@ -93,10 +97,11 @@ size_t ax_workspace_bytes(const ax_model_config *cfg);
 
 /* Build a model over borrowed weights.  `workspace` is device memory of at least
  * ax_workspace_bytes(cfg) bytes, 256-byte aligned, owned by the caller and used by every call
- * on this model (activations, rotary table, per-call descriptors, split-attention partials).
+ * on this model (activations, rotary table, per-call descriptors, split-attention partials
+ * and, for AX_BF16, the repacked weight matrices: about as many bytes again as the weights).
  * AX_BF16 needs d_model, d_ff, head counts*head_dim and vocab to be multiples of 64 and
  * head_dim in {64, 128}; AX_F32 takes any sizes with an even head_dim <= 256.
- * Needs a GPU (uploads the rotary table).  Errors: INVALID, OOM (workspace too small),
+ * Needs a GPU (uploads the rotary table, repacks the weights; synchronises the device).  Errors: INVALID, OOM (workspace too small),
  * UNSUPPORTED, DEVICE. */
 ax_status ax_model_create(const ax_model_config *cfg, const ax_weights *weights,
                           void *workspace, size_t workspace_bytes, ax_model **out);
