@@ -227,7 +227,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (sessions would shard across GPUs with no "
-                 "collective; see DESIGN.md); run with --gpus 1")
+                 "collective); run with --gpus 1")
 
     import torch
     if not torch.cuda.is_available():
