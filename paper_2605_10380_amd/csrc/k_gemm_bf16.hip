@@ -1,17 +1,17 @@
 // GEMMs of bf16-weight models on the gfx950 matrix cores: C = A[M,K] * W[N,K]^T, fp32
-// accumulation.  Weights stay bf16 in HBM (that is what is streamed); activations are fp16.
-// A bf16 weight fragment is widened to fp16 in registers (exact for every |w| >= 2^-14, absolute
-// error below 2^-25 beneath that) and the product runs on the fp16 MFMA, which has the same
-// rate as the bf16 one.  Reason: bf16 activations (8 significant bits) put the logits of a
-// 16-layer decoder ~0.05 away from the exact result; fp16 activations (11 bits) keep them
-// within 0.01.  Both operands are K-contiguous, which is exactly what the MFMA operand layout
-// wants: a lane holds 8 consecutive k of one row (A) or one column (W), i.e. one 16-byte load.
+// accumulation.  The caller's weights are bf16; the kernels read the library's own 16-bit copy,
+// made once at model creation: each bf16 widened to fp16 (exact for every |w| >= 2^-14, absolute
+// error below 2^-25 beneath that) and laid out in MFMA operand order (see "weight layout" below).
+// Activations are fp16 and the product runs on the fp16 MFMA, which has the same rate as the
+// bf16 one.  Reason: bf16 activations (8 significant bits) put the logits of a 16-layer decoder
+// ~0.05 away from the exact result; fp16 activations (11 bits) keep them within 0.01.
 //
-//   * tile kernel   (M > 64, large-T extend: compute bound): 4 wavefronts, LDS-staged
-//     BM x BN x 64 tiles, v_mfma_f32_32x32x16_f16, global loads several K slices ahead.
 //   * skinny kernel (M <= 64, verify steps: pure weight streaming): one block owns 16 output
 //     columns, its wavefronts split K, W goes HBM -> registers -> v_mfma_f32_16x16x32_f16
 //     with no LDS in the streaming loop; the per-wavefront partial sums meet in LDS.
+//   * tile kernel   (M > 64): 8 wavefronts, LDS-staged 64 x 128 x 64 tiles,
+//     v_mfma_f32_32x32x16_f16, global loads several K slices ahead.
+//   * stream kernel (SwiGLU, M >= 384): activations through LDS, weights straight into MFMA operands.
 //
 // RMSNorm is folded into the GEMMs around it.  The GEMM that produces the residual stream x
 // also writes a = fp16(x * gain_next) and, per row and per block of columns, a partial sum of
@@ -56,11 +56,12 @@ __device__ __forceinline__ f16x8 bf16x8_to_f16x8(u32x4 raw) {
     }
     return out;
 }
-__device__ __forceinline__ f16x8 load_w(const bf16* p) { return bf16x8_to_f16x8(*(const u32x4*)p); }
+__device__ __forceinline__ f16x8 load_w(const bf16* p) { return *(const f16x8*)p; }     // packed weights are already fp16
 
 // ------------------------------------------------------------------------------ weight layout
-// bf16 weight matrices are not read row-major.  ax_model_create repacks every [N, K] matrix once
-// into panels of 16 rows; a panel is cut into chunks of 32 k, and a chunk (1 KB) is stored in
+// bf16 weight matrices are not read as given.  ax_model_create repacks every [N, K] matrix once,
+// widening each bf16 to fp16 on the way (the round-toward-zero pack above: exact in fp16's normal
+// range; the kernels multiply on the fp16 MFMA), into panels of 16 rows; a panel is cut into chunks of 32 k, and a chunk (1 KB) is stored in
 // the order the 16x16x32 MFMA takes it: 4 k-groups of 8, inside a group the 16 rows, each with
 // its 8 consecutive k (16 bytes).  A wavefront's weight load for one MFMA step is then 1 KB of
 // contiguous memory instead of 16 pieces of 64 bytes from 16 rows - measured 7-19 % faster
@@ -79,7 +80,7 @@ __global__ void pack_weights_kernel(const u32x4* __restrict__ src, u32x4* __rest
     for (long long u = (long long)blockIdx.x * blockDim.x + threadIdx.x; u < units; u += stride) {
         const int panel = (int)(u / upp), w = (int)(u % upp);
         const int c = w >> 6, kg = (w >> 4) & 3, r = w & 15;
-        dst[u] = src[((long long)(panel * 16 + r) * K + c * 32 + kg * 8) / 8];
+        dst[u] = __builtin_bit_cast(u32x4, bf16x8_to_f16x8(src[((long long)(panel * 16 + r) * K + c * 32 + kg * 8) / 8]));
     }
 }
 
@@ -210,7 +211,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_tile_kernel(GemmArgs g
             const int c = tid + NT * i, u = c & 127;
             const int row = (c >> 7) * 16 + (u & 15), col = (u >> 6) * 32 + ((u >> 4) & 3) * 8;
 #pragma unroll
-            for (int b = 0; b < NB; ++b) *(f16x8*)(sB[buf][b] + row * LS + col) = bf16x8_to_f16x8(rb[slot][b][i]);
+            for (int b = 0; b < NB; ++b) *(f16x8*)(sB[buf][b] + row * LS + col) = __builtin_bit_cast(f16x8, rb[slot][b][i]);
         }
     };
     auto multiply = [&](int buf) {
@@ -511,7 +512,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_stream_swiglu_kernel(GemmArgs g
 #pragma unroll
             for (int i = 0; i < TM; ++i) fa[i] = *(const f16x8*)(sA[buf] + (i * 32 + lrow) * LS + c * 16 + lg * 8);
 #pragma unroll
-            for (int t = 0; t < 2; ++t) fw[t] = bf16x8_to_f16x8(rw[slot][t][c]);
+            for (int t = 0; t < 2; ++t) fw[t] = __builtin_bit_cast(f16x8, rw[slot][t][c]);
 #pragma unroll
             for (int t = 0; t < 2; ++t)
 #pragma unroll
@@ -672,7 +673,7 @@ void gemm_bf16_skinny_kernel(GemmArgs g) {
             for (int u = 0; u < U; ++u)
 #pragma unroll
                 for (int b = 0; b < NB; ++b) {
-                    const f16x8 fw = bf16x8_to_f16x8(rw[set][b][u]);
+                    const f16x8 fw = __builtin_bit_cast(f16x8, rw[set][b][u]);
 #pragma unroll
                     for (int t = 0; t < MT; ++t)
                         acc[b][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fw, fx[set][t][u], acc[b][t], 0, 0, 0);
@@ -712,7 +713,7 @@ void gemm_bf16_skinny_kernel(GemmArgs g) {
             for (int u = 0; u < 4; ++u)
 #pragma unroll
                 for (int b = 0; b < NB; ++b) {
-                    const f16x8 fw = bf16x8_to_f16x8(rw[b][u]);
+                    const f16x8 fw = __builtin_bit_cast(f16x8, rw[b][u]);
 #pragma unroll
                     for (int t = 0; t < MT; ++t)
                         acc[b][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fw, fx[t][u], acc[b][t], 0, 0, 0);

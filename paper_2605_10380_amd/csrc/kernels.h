@@ -57,7 +57,7 @@ struct RopeArgs {
 struct GemmArgs {
     const void* A;                    // fp16 [rows, K]
     const int* a_rows;                // optional gather: A row of output row m is a_rows[m]
-    const void *W, *W2;               // bf16 [N, K] in the packed layout (launch_pack_weights); W2 only for EPI_SWIGLU
+    const void *W, *W2;               // [N, K] packed by launch_pack_weights (fp16, MFMA operand order); W2 only for EPI_SWIGLU
     int M, N, K;
     // deferred RMSNorm of the A rows: ssq[row][nparts] partial sums of x^2 over d_norm columns;
     // the accumulators are scaled by 1 / sqrt(sum / d_norm + eps).  NULL = no scaling.
@@ -78,8 +78,8 @@ struct GemmArgs {
 };
 constexpr int SPLITK_MAX = 8;
 void launch_gemm_bf16(Epilogue epi, const GemmArgs& g, hipStream_t s);
-// Repacks a row-major bf16 [N, K] matrix (N % 16 == 0, K % 32 == 0) into the layout every bf16 GEMM
-// kernel reads (16-row panels, 32-k chunks in MFMA operand order); src and dst must not overlap.
+// Repacks a row-major bf16 [N, K] matrix (N % 16 == 0, K % 32 == 0) into what every bf16-model GEMM
+// kernel reads: fp16 values in 16-row panels, 32-k chunks in MFMA operand order; src and dst must not overlap.
 void launch_pack_weights(const void* src, void* dst, int N, int K, hipStream_t s);
 // Number of sum-of-squares partials per row that an EPI_RESIDUAL launch with this M, N writes.
 int gemm_ssq_parts(int M, int N);
