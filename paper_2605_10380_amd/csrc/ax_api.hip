@@ -41,6 +41,7 @@ ax_status fail(ax_status st, const char* fmt, ...) {
 constexpr uint32_t MAGIC_MODEL = 0x41584d44, MAGIC_POOL = 0x4158504c, MAGIC_KV = 0x41584b56, MAGIC_LUT = 0x41584c54, MAGIC_INDEX = 0x41584958;
 constexpr int N_SLOTS = 4;            // staging ring for per-call descriptors
 constexpr int LOGIT_ROWS = 256;       // rows per LM-head pass when only the argmax is wanted
+const long long kSharedMinKeys = std::getenv("AX_SHARED_MIN_KEYS") ? std::atoll(std::getenv("AX_SHARED_MIN_KEYS")) : 2048;   // (sequences - 1) x shared keys that justify a shared-prefix pass
 constexpr int SPLIT_ITEMS = 2048;     // partial records the split attention may use (workspace size)
 
 size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
@@ -82,7 +83,7 @@ Layout make_layout(const ax_model_config& c) {
     Layout L{};
     const size_t T = (size_t)c.max_tokens, S = (size_t)c.max_seqs, a = (size_t)isz(c.dtype);
     const int G = c.n_q_heads / c.n_kv_heads;
-    L.max_tiles = (int)((T * G + 31) / 32 + S);
+    L.max_tiles = (int)((T * G + 31) / 32 + S + (T * G) / 128 + 2);     // per-sequence tiles + groups of a shared-prefix pass
     L.max_bt = (c.max_pos + 15) / 16;
     L.desc_ints = 5 * T + 4 * S + S * (size_t)L.max_bt + 8 * (size_t)L.max_tiles + 32;
     size_t o = 0;
@@ -98,7 +99,7 @@ Layout make_layout(const ax_model_config& c) {
     L.attn = take(T * (size_t)c.n_q_heads * c.head_dim * a);
     L.ffn = take(T * (size_t)c.d_ff * a);
     const size_t items = std::max<size_t>(SPLIT_ITEMS, (size_t)L.max_tiles * c.n_kv_heads);
-    L.partials = take(c.dtype == AX_BF16 ? items * ((size_t)c.head_dim * 32 + 64) * 4 : 0);
+    L.partials = take(c.dtype == AX_BF16 ? 2 * items * ((size_t)c.head_dim * 32 + 64) * 4 : 0);   // second half: shared-prefix pass
     L.splitk = take(c.dtype == AX_BF16 ? T * c.d_model * 4 * ax::SPLITK_MAX : 0);   // K-slice partials of residual GEMMs
     L.logits = take(std::min<size_t>(T, LOGIT_ROWS) * (size_t)c.vocab * 4);
     L.amax_scratch = take(2 * std::min<size_t>(T, LOGIT_ROWS) * ax::ARGMAX_PARTS * 4);
@@ -209,6 +210,7 @@ int choose_splits(const ax_model* m, int items, int nq, int max_steps) {
 // into a pinned staging slot.  Nothing is launched here.
 struct CallPlan {
     int n = 0, n_rows = 0, n_out = 0, n_tiles = 0, tile_nq = 1, bt_total = 0, max_steps = 1, out_mode = 0, slot = 0;
+    int n_tiles_shared = 0, shared_nq = 4, shared_len = 0, shared_splits = 1;   // shared-prefix attention pass (0 groups = none)
     size_t o_tok = 0, o_pos = 0, o_seq = 0, o_slot = 0, o_out = 0, o_P = 0, o_T = 0, o_row0 = 0, o_bt = 0, o_tinfo = 0,
            o_tab = 0, ints = 0;
     ax_pool* pool = nullptr;
@@ -276,6 +278,33 @@ ax_status prepare_call(ax_model* m, int n, ax_kv* const* kvs, const int32_t* tok
         cp.n_tiles += (T_each[s] * G + 32 * cp.tile_nq - 1) / (32 * cp.tile_nq);
         cp.bt_total += (int)ax::blocks_for(kvs[s]->seq.len + T_each[s], 16);
     }
+    // Several short sequences (verify rounds of many sessions) whose block tables begin with the
+    // same blocks - forks of one cached prefix: the keys of those blocks are applied to the rows
+    // of all sequences in one pass.  Only whole blocks below every sequence's length count (they
+    // cannot be copied on write by this call); worth a pass of its own from ~2k saved key reads.
+    cp.n_tiles_shared = 0;
+    if (c.dtype == AX_BF16 && cp.tile_nq == 1 && n >= 2) {
+        size_t common = (size_t)(kvs[0]->seq.len / 16);
+        for (int s = 1; s < n && common > 0; ++s) {
+            common = std::min(common, (size_t)(kvs[s]->seq.len / 16));
+            size_t i = 0;
+            while (i < common && kvs[s]->seq.blocks[i] == kvs[0]->seq.blocks[i]) ++i;
+            common = i;
+        }
+        const int shared = (int)(common * 16) & ~31;
+        if ((long long)(n - 1) * shared >= kSharedMinKeys) {
+            cp.shared_len = shared;
+            cp.shared_nq = n_rows * G > 128 ? 8 : 4;
+            cp.n_tiles_shared = (int)((n_rows * G + 32 * cp.shared_nq - 1) / (32 * cp.shared_nq));
+            int want = std::max(1, 2048 / (cp.n_tiles_shared * c.n_kv_heads * cp.shared_nq));
+            want = std::min(want, std::max(1, shared / 64));
+            const size_t cap = std::max<size_t>(SPLIT_ITEMS, (size_t)m->lay.max_tiles * c.n_kv_heads) /
+                               ((size_t)cp.n_tiles_shared * c.n_kv_heads * cp.shared_nq);
+            want = std::min(want, std::max(1, (int)cap));
+            cp.shared_splits = 1;
+            while (cp.shared_splits * 2 <= want) cp.shared_splits *= 2;
+        }
+    }
     cp.n_out = out_mode == AX_OUT_NONE ? 0
                : (out_mode == AX_OUT_LAST_LOGITS || out_mode == AX_OUT_LAST_ARGMAX) ? n : (int)n_rows;
     size_t at = 0;
@@ -285,7 +314,7 @@ ax_status prepare_call(ax_model* m, int n, ax_kv* const* kvs, const int32_t* tok
     cp.o_out = region((size_t)std::max(cp.n_out, 1)); cp.o_P = region((size_t)n); cp.o_T = region((size_t)n);
     cp.o_row0 = region((size_t)n); cp.o_bt = region((size_t)n);
     at = (at + 7) / 8 * 8;                                                   // 32-byte aligned tile records
-    cp.o_tinfo = region((size_t)cp.n_tiles * 8);
+    cp.o_tinfo = region((size_t)(cp.n_tiles + cp.n_tiles_shared) * 8);
     cp.o_tab = region((size_t)(graph_slot ? m->lay.max_bt : cp.bt_total));   // fixed extent inside a graph
     cp.ints = at;
     if (cp.ints > m->slot_ints || cp.bt_total > n * m->lay.max_bt)
@@ -320,7 +349,9 @@ ax_status prepare_call(ax_model* m, int n, ax_kv* const* kvs, const int32_t* tok
         for (int32_t b : kvs[s]->seq.blocks) d[cp.o_tab + tab++] = b;
         for (int r0 = 0; r0 < T * G; r0 += 32 * cp.tile_nq) {
             int* ti = d + cp.o_tinfo + (size_t)tile * 8;
-            ti[0] = s; ti[1] = r0; ti[2] = P[(size_t)s]; ti[3] = T; ti[4] = row; ti[5] = d[cp.o_bt + s]; ti[6] = ti[7] = 0;
+            ti[0] = s; ti[1] = r0; ti[2] = P[(size_t)s]; ti[3] = T; ti[4] = row; ti[5] = d[cp.o_bt + s];
+            ti[6] = 0;
+            ti[7] = cp.n_tiles_shared > 0 ? cp.shared_len : 0;      // keys before it are the shared pass's
             ++tile;
         }
         for (int t = 0; t < T; ++t, ++row) {
@@ -331,7 +362,12 @@ ax_status prepare_call(ax_model* m, int n, ax_kv* const* kvs, const int32_t* tok
             if (out_mode == AX_OUT_ALL_LOGITS || out_mode == AX_OUT_ALL_ARGMAX) d[cp.o_out + oi++] = row;
         }
         if (out_mode == AX_OUT_LAST_LOGITS || out_mode == AX_OUT_LAST_ARGMAX) d[cp.o_out + oi++] = row - 1;
-        cp.max_steps = std::max(cp.max_steps, (P[(size_t)s] + T + 31) / 32);
+        cp.max_steps = std::max(cp.max_steps, (P[(size_t)s] + T - (cp.n_tiles_shared > 0 ? cp.shared_len : 0) + 31) / 32);
+    }
+    for (int g = 0; g < cp.n_tiles_shared; ++g) {                   // the shared pass: one virtual sequence of all rows
+        int* ti = d + cp.o_tinfo + (size_t)(cp.n_tiles + g) * 8;
+        ti[0] = 0; ti[1] = g * 32 * cp.shared_nq; ti[2] = cp.shared_len; ti[3] = (int)n_rows; ti[4] = 0; ti[5] = d[cp.o_bt + 0];
+        ti[6] = cp.shared_len; ti[7] = 0;
     }
     return AX_OK;
 }
@@ -354,6 +390,7 @@ ax_status enqueue_call(ax_model* m, const CallPlan& cp, void* out, hipStream_t s
     sv.seq_row0 = dev_d + cp.o_row0; sv.seq_bt = dev_d + cp.o_bt;   sv.tile_info = dev_d + cp.o_tinfo;
     sv.bt = dev_d + cp.o_tab;
     sv.n_rows = cp.n_rows; sv.n_seq = cp.n; sv.n_out = cp.n_out; sv.n_tiles = cp.n_tiles; sv.tile_nq = cp.tile_nq;
+    sv.n_tiles_shared = cp.n_tiles_shared; sv.shared_nq = cp.shared_nq; sv.shared_len = cp.shared_len; sv.shared_splits = cp.shared_splits;
 
     const ax::DType dt = c.dtype == AX_F32 ? ax::F32 : ax::BF16;
     const ax::KVGeom& kg = cp.pool->geom;

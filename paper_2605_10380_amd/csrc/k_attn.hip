@@ -179,9 +179,13 @@ struct AttnArgs {
     f16* out;
     KVGeom kv;
     int layer, Hq, n_splits;
-    const int* tile_info;      // per q-tile group, 8 ints: seq, first stacked row, P, T, row0, block-table offset
+    const int* tile_info;      // per q-tile group, 8 ints: seq, first stacked row, P, T, row0, block-table offset,
+                               // key limit (0 = none: causal bound of the rows), first key
     const int* bt;
     float* partials;
+    // shared-prefix pass of a many-sequence call (see launch_attention); unused otherwise
+    const float* shared_partials;
+    int shared_splits, shared_nq, shared_len;
 };
 
 // Everything a step needs from memory is requested as early as possible, because at verify
@@ -206,9 +210,10 @@ __global__ __launch_bounds__(64) void attn_split_kernel(AttnArgs a) {
     // keys this group can see at all: up to the position of its last valid row
     const int r_last = min(r0 + NQ * 32 - 1, n_stacked - 1);
     const int kv_end = P + r_last / G + 1;
+    const int first = ti1.w >> 5;                        // first key step (keys before it belong to the shared pass)
     const int steps = (kv_end + 31) / 32;
-    const int per = (steps + a.n_splits - 1) / a.n_splits;
-    const int s_lo = split * per, s_hi = min(steps, s_lo + per);
+    const int per = (steps - first + a.n_splits - 1) / a.n_splits;
+    const int s_lo = first + split * per, s_hi = min(steps, s_lo + per);
 
     // this lane's query rows (clamped rows compute garbage that is never written)
     int pos_q[NQ], pos_min[NQ];          // pos_min: earliest position among the tile's rows (uniform)
@@ -354,10 +359,11 @@ __global__ __launch_bounds__(64 * NQ) void attn_block_kernel(AttnArgs a) {
     const int r0 = ti0.y, P = ti0.z, T = ti0.w, row0 = ti1.x;
     const int n_stacked = T * G;
     const int* tab = a.bt + ti1.y;
-    const int kv_len = P + T, last_blk = (kv_len - 1) >> 4;
+    const int klimit = ti1.z;                                  // > 0: keys [0, klimit) only (shared pass)
+    const int kv_len = klimit > 0 ? klimit : P + T, last_blk = (kv_len - 1) >> 4;
 
     const int r_last = min(r0 + NQ * 32 - 1, n_stacked - 1);
-    const int kv_end = P + r_last / G + 1;
+    const int kv_end = klimit > 0 ? klimit : P + r_last / G + 1;
     const int steps = (kv_end + 31) / 32;
     const int per = (steps + a.n_splits - 1) / a.n_splits;
     const int s_lo = split * per, s_hi = min(steps, s_lo + per);
@@ -491,7 +497,9 @@ __global__ __launch_bounds__(64 * NQ) void attn_block_kernel(AttnArgs a) {
 // Merges the key slices of one q tile.  grid (n_groups * Hkv * NQ, HD / 4), 256 threads =
 // 32 query rows x 8 slice groups; a block produces 4 output channels.  A thread loads the
 // (m, l, 4 channels) of its slices s = sg, sg + 8, ... in one go (up to 16 slices in registers),
-// the row maximum and then the weighted sums meet in LDS.
+// the row maximum and then the weighted sums meet in LDS.  With a shared-prefix pass the slices
+// of that pass follow the tile's own: they live in the records of the shared pass's tile group
+// that holds the row (rows of all sequences stacked: global row * G + g).
 template <int HD, int NQ>
 __global__ __launch_bounds__(256) void attn_combine_kernel(AttnArgs a) {
     constexpr int PS = HD * 32 + 64;
@@ -507,9 +515,17 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(AttnArgs a) {
     if (r_first >= n_stacked) return;                          // whole q tile past the end (block-uniform)
     const int r = r_first + ql;
     const bool valid = r < n_stacked;
-    const int n_splits = a.n_splits;
-    const float* base = a.partials + ((long long)(tile * Hkv + hk) * n_splits * NQ + t) * PS;
+    const int own_splits = a.n_splits, n_splits = own_splits + a.shared_splits;
+    const float* base = a.partials + ((long long)(tile * Hkv + hk) * own_splits * NQ + t) * PS + ql;
     const long long stride = (long long)NQ * PS;               // between slices
+    const float* sbase = nullptr;                              // the row's record in the shared pass, slice 0
+    long long sstride = 0;
+    if (a.shared_splits > 0) {
+        const int rc = min(r, n_stacked - 1), R = (row0 + rc / G) * G + rc % G, gsz = 32 * a.shared_nq;
+        sbase = a.shared_partials + ((long long)((R / gsz) * Hkv + hk) * a.shared_splits * a.shared_nq + (R % gsz) / 32) * PS + (R & 31);
+        sstride = (long long)a.shared_nq * PS;
+    }
+    auto slice = [&](int s) { return s < own_splits ? base + s * stride : sbase + (s - own_splits) * sstride; };
 
     float mv[MAXS], lv[MAXS], ov[MAXS][4];
     float mloc = -INFINITY;
@@ -521,17 +537,17 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(AttnArgs a) {
 #pragma unroll
         for (int c = 0; c < 4; ++c) ov[i][c] = 0.f;
         if (valid && s < n_splits) {
-            const float* p = base + s * stride;
-            mv[i] = p[HD * 32 + ql];
-            lv[i] = p[HD * 32 + 32 + ql];
+            const float* p = slice(s);
+            mv[i] = p[HD * 32];
+            lv[i] = p[HD * 32 + 32];
 #pragma unroll
-            for (int c = 0; c < 4; ++c) ov[i][c] = p[(ch0 + c) * 32 + ql];
+            for (int c = 0; c < 4; ++c) ov[i][c] = p[(ch0 + c) * 32];
         }
     }
 #pragma unroll
     for (int i = 0; i < MAXS; ++i) mloc = fmaxf(mloc, mv[i]);
     if (valid)                                                 // more than 128 slices: the rest from memory
-        for (int s = sg + 8 * MAXS; s < n_splits; s += 8) mloc = fmaxf(mloc, base[s * stride + HD * 32 + ql]);
+        for (int s = sg + 8 * MAXS; s < n_splits; s += 8) mloc = fmaxf(mloc, slice(s)[HD * 32]);
     red[sg][0][ql] = mloc;
     __syncthreads();
     float M = red[0][0][ql];
@@ -549,11 +565,11 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(AttnArgs a) {
     }
     if (valid)
         for (int s = sg + 8 * MAXS; s < n_splits; s += 8) {
-            const float* p = base + s * stride;
-            const float w = exp2f(p[HD * 32 + ql] - M);
-            l += w * p[HD * 32 + 32 + ql];
+            const float* p = slice(s);
+            const float w = exp2f(p[HD * 32] - M);
+            l += w * p[HD * 32 + 32];
 #pragma unroll
-            for (int c = 0; c < 4; ++c) acc[c] += w * p[(ch0 + c) * 32 + ql];
+            for (int c = 0; c < 4; ++c) acc[c] += w * p[(ch0 + c) * 32];
         }
     red[sg][1][ql] = l;
 #pragma unroll
@@ -671,6 +687,27 @@ void launch_attention(DType dt, const void* q, void* out, KVGeom kv, int layer, 
             }
         }
     } else {
+        if (sv.n_tiles_shared > 0) {
+            // Many sequences that share a cached prefix (the same leading blocks): the keys of the
+            // prefix are applied ONCE to the rows of all sequences - a pass of the block kernel over
+            // one virtual sequence made of every row of the call, keys [0, shared_len), no causal
+            // mask needed - instead of being pulled from L2 once per sequence; the per-sequence
+            // wavefronts below start at shared_len, and the merge adds the shared pass's slices.
+            AttnArgs sh = a;
+            sh.tile_info = sv.tile_info + (size_t)sv.n_tiles * 8;
+            sh.n_splits = sv.shared_splits;
+            sh.partials = partials + attention_partial_floats(sv.n_tiles, kv.n_kv_heads, hd, n_splits);
+            dim3 grid(sv.n_tiles_shared, kv.n_kv_heads, sv.shared_splits);
+            if (sv.shared_nq == 4) {
+                if (hd == 64) attn_block_kernel<64, 4><<<grid, 256, 0, s>>>(sh); else attn_block_kernel<128, 4><<<grid, 256, 0, s>>>(sh);
+            } else {
+                if (hd == 64) attn_block_kernel<64, 8><<<grid, 512, 0, s>>>(sh); else attn_block_kernel<128, 8><<<grid, 512, 0, s>>>(sh);
+            }
+            a.shared_partials = sh.partials;
+            a.shared_splits = sv.shared_splits;
+            a.shared_nq = sv.shared_nq;
+            a.shared_len = sv.shared_len;
+        }
         if (hd == 64) launch_attn_mfma<64, 1>(a, sv.n_tiles, s); else launch_attn_mfma<128, 1>(a, sv.n_tiles, s);
     }
 }

@@ -35,10 +35,14 @@ struct StepView {
     const int* seq_bt;      // [n_seq] offset of the sequence's block table inside bt
     const int* bt;          // concatenated block tables
     const int* out_rows;    // [n_out] rows that go through the LM head
-    const int* tile_info;   // [n_tiles][8] attention q-tile groups over stacked rows (t, g): sequence,
-                            // first stacked row, P, T, first row of the sequence, block-table offset, 0, 0
+    const int* tile_info;   // [n_tiles + n_tiles_shared][8] attention q-tile groups over stacked rows (t, g):
+                            // sequence, first stacked row, P, T, first row of the sequence, block-table offset,
+                            // key limit (0 = the rows' causal bound), first key
                             // (a group = tile_nq tiles of 32 rows; 32-byte aligned records)
     int n_rows, n_seq, n_out, n_tiles, tile_nq;
+    // shared-prefix pass (calls with several sequences whose block tables start alike): groups of
+    // shared_nq tiles over ALL rows of the call against keys [0, shared_len); 0 groups = no such pass
+    int n_tiles_shared, shared_nq, shared_len, shared_splits;
 };
 
 enum Epilogue { EPI_STORE_F32 = 0, EPI_RESIDUAL = 1, EPI_SWIGLU = 2, EPI_QKV = 3 };

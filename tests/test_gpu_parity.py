@@ -574,6 +574,44 @@ def test_batched_verify_mixed_k(B, which):
     dm.close()
 
 
+@pytest.mark.parametrize("which", ["bf16-hd64-g4", "bf16-hd128-g3"])
+def test_batched_verify_over_a_long_shared_prefix(B, which):
+    """Sessions forked from one 600-token prefix (it ends inside a block, so the last shared
+    block is copied on the first private write): the batched verify applies the prefix keys to all
+    sessions' rows in one shared pass and the rest per session.  Acceptance per session equals
+    the oracle's; a batched extend with LAST_LOGITS over the same forks also matches."""
+    sh = SMALL[which]
+    w = I.make_weights(sh, 33)
+    prefix = I.templated_prompt(sh.vocab, 33, 600)
+    dm = B.DeviceModel(sh, w, max_pos=1024, max_tokens=320, pool_tokens=8192, max_seqs=6)
+    root, root_ref = dm.new_kv(), okv(sh)
+    dm.extend(root, prefix[:300])
+    dm.extend(root, prefix[300:])
+    O.forward(sh, w, prefix, root_ref)
+    kvs, refs, pend = [], [], []
+    for s, hl in enumerate([0, 5, 40, 17, 90, 33]):
+        kv, ref = B.ax_kv_fork(root, -1), root_ref.fork()
+        h = I.zipf_tokens(sh.vocab, 33, f"h{s}", hl + 1)
+        if hl:
+            dm.extend(kv, h[:hl])
+            O.forward(sh, w, h[:hl], ref)
+        kvs.append(kv)
+        refs.append(ref)
+        pend.append(int(h[hl]))
+    # short batched extend (single-tile path): logits of every session against the oracle
+    news = [I.zipf_tokens(sh.vocab, 33, f"n{s}", 3 + s) for s in range(6)]
+    got = dm.extend_batch(kvs, news, B.AX_OUT_LAST_LOGITS).cpu().numpy()
+    for s in range(6):
+        check_logits(sh, got[s], O.forward(sh, w, news[s], refs[s])[-1], f"shared-prefix batch, session {s}")
+    ks = [[8, 0, 3, 16, 1, 5], [4, 4, 4, 4, 4, 4], [1, 16, 0, 2, 9, 7]]
+    total, exempt = _batched_rounds(B, dm, sh, w, kvs, refs, pend, 3, lambda r, s: ks[r][s], 33)
+    print(which, "accepted", total, "exempt", exempt)
+    assert total > 0 and exempt <= 3
+    for kv in kvs + [root]:
+        B.ax_kv_free(kv)
+    dm.close()
+
+
 def test_two_resident_models_forked_sessions(B):
     """The plan-out agent's shape at a size the oracle can follow: two decoders with their own
     weights and pools resident together; per model, sessions fork one shared prefix, build
