@@ -196,8 +196,8 @@ int choose_splits(const ax_model* m, int items, int nq, int max_steps) {
     const int target = nq == 1 ? 512 : 2048;
     int want = std::max(1, target / std::max(1, items * nq));
     // many sequences in one call: 512 wavefronts would leave each with a long serial key loop;
-    // go up to 2048 wavefronts while a slice still has a dozen key steps
-    if (nq == 1 && max_steps / want > 16) want = std::max(want, std::min(2048 / std::max(1, items), (max_steps + 11) / 12));
+    // go up to 2048 wavefronts while a slice still has ~8 key steps
+    if (nq == 1 && max_steps / want > 8) want = std::max(want, std::min(2048 / std::max(1, items), (max_steps + 7) / 8));
     want = std::min(want, std::max(1, max_steps / 2));
     const size_t cap = std::max<size_t>(SPLIT_ITEMS, (size_t)m->lay.max_tiles * m->cfg.n_kv_heads) / ((size_t)items * nq);
     want = std::min(want, std::max(1, (int)cap));

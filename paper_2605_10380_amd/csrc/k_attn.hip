@@ -582,7 +582,8 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(AttnArgs a) {
     a.out[((long long)(row0 + r / G) * a.Hq + hk * G + r % G) * HD + ch0 + sg] = (f16)(o / L);
 }
 
-// Slice merge for the block kernel (groups of 4 tiles, long extends: many tiles, few slices).
+// Slice merge for launches with many tile records and few slices each (the block kernel's groups
+// of 4 or 8 tiles; single-tile launches over many sequences, with their shared-prefix slices).
 // One block per (group, KV head, tile): 256 threads = 32 query rows x 8 channel groups, a thread
 // owns HD/8 consecutive channels of its row and walks the slices itself, so nothing meets in
 // LDS and every load of a pass is independent.  Pass 1: the row's reference exponents of all
@@ -598,18 +599,26 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a) {
     const int row0 = a.tile_info[tile * 8 + 4];
     const int r = ti0.y + t * 32 + ql, n_stacked = ti0.w * G;
     if (r >= n_stacked) return;
-    const int n_splits = a.n_splits;
-    const float* base = a.partials + ((long long)(tile * Hkv + hk) * n_splits * NQ + t) * PS;
+    const int own_splits = a.n_splits, n_splits = own_splits + a.shared_splits;
+    const float* base = a.partials + ((long long)(tile * Hkv + hk) * own_splits * NQ + t) * PS + ql;
     const long long stride = (long long)NQ * PS;               // between slices
+    const float* sbase = nullptr;                              // the row's record in a shared-prefix pass, slice 0
+    long long sstride = 0;
+    if (a.shared_splits > 0) {
+        const int R = (row0 + r / G) * G + r % G, gsz = 32 * a.shared_nq;
+        sbase = a.shared_partials + ((long long)((R / gsz) * Hkv + hk) * a.shared_splits * a.shared_nq + (R % gsz) / 32) * PS + (R & 31);
+        sstride = (long long)a.shared_nq * PS;
+    }
+    auto slice = [&](int s) { return s < own_splits ? base + s * stride : sbase + (s - own_splits) * sstride; };
 
     float M = -INFINITY;
     for (int s0 = 0; s0 < n_splits; s0 += 8) {
         float mv[8];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) mv[i] = s0 + i < n_splits ? base[(s0 + i) * stride + HD * 32 + ql] : -INFINITY;
+        for (int i = 0; i < 8; ++i) mv[i] = s0 + i < n_splits ? slice(s0 + i)[HD * 32] : -INFINITY;
 #pragma unroll
         for (int i = 0; i < 8; ++i) M = fmaxf(M, mv[i]);
-    }                                                          // finite: slice 0 always sees key 0
+    }                                                          // finite: slice 0 always sees its first key
     float L = 0.f, acc[CPT];
 #pragma unroll
     for (int c = 0; c < CPT; ++c) acc[c] = 0.f;
@@ -617,11 +626,11 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a) {
         float mv[SU], lv[SU], ov[SU][CPT];
 #pragma unroll
         for (int i = 0; i < SU; ++i) {
-            const float* p = base + (long long)min(s0 + i, n_splits - 1) * stride;
-            mv[i] = s0 + i < n_splits ? p[HD * 32 + ql] : -INFINITY;       // absent slice: weight 0
-            lv[i] = p[HD * 32 + 32 + ql];
+            const float* p = slice(min(s0 + i, n_splits - 1));
+            mv[i] = s0 + i < n_splits ? p[HD * 32] : -INFINITY;            // absent slice: weight 0
+            lv[i] = p[HD * 32 + 32];
 #pragma unroll
-            for (int c = 0; c < CPT; ++c) ov[i][c] = p[(cg * CPT + c) * 32 + ql];
+            for (int c = 0; c < CPT; ++c) ov[i][c] = p[(cg * CPT + c) * 32];
         }
 #pragma unroll
         for (int i = 0; i < SU; ++i) {
@@ -650,7 +659,12 @@ template <int HD, int NQ>
 static void launch_attn_mfma(const AttnArgs& a, int n_groups, hipStream_t s) {
     dim3 grid(n_groups, a.kv.n_kv_heads, a.n_splits), cgrid(n_groups * a.kv.n_kv_heads * NQ, HD / 4);
     attn_split_kernel<HD, NQ><<<grid, 64, 0, s>>>(a);
-    attn_combine_kernel<HD, NQ><<<cgrid, 256, 0, s>>>(a);
+    // few records with many slices (one session): blocks of 4 channels that spread the slices over
+    // threads; many records with few slices (many sessions): one block per record
+    if (n_groups * a.kv.n_kv_heads >= 64 && a.n_splits + a.shared_splits <= 32)
+        attn_merge_kernel<HD, NQ><<<n_groups * a.kv.n_kv_heads * NQ, 256, 0, s>>>(a);
+    else
+        attn_combine_kernel<HD, NQ><<<cgrid, 256, 0, s>>>(a);
 }
 
 void launch_attention(DType dt, const void* q, void* out, KVGeom kv, int layer, const StepView& sv,
