@@ -660,8 +660,8 @@ void gemm_bf16_skinny_kernel(GemmArgs g) {
         auto loads = [&](int set, int kk) {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                rw[set][0][u] = (COLS == 16 || wlane) ? *(const u32x4*)(wp + (long long)(kk + 32 * u) * 16) : (u32x4){0u, 0u, 0u, 0u};
-                if (NB == 2) rw[set][NB - 1][u] = *(const u32x4*)(wp2 + (long long)(kk + 32 * u) * 16);
+                rw[set][0][u] = (COLS == 16 || wlane) ? __builtin_nontemporal_load((const u32x4*)(wp + (long long)(kk + 32 * u) * 16)) : (u32x4){0u, 0u, 0u, 0u};
+                if (NB == 2) rw[set][NB - 1][u] = __builtin_nontemporal_load((const u32x4*)(wp2 + (long long)(kk + 32 * u) * 16));
             }
 #pragma unroll
             for (int t = 0; t < MT; ++t)
@@ -702,8 +702,8 @@ void gemm_bf16_skinny_kernel(GemmArgs g) {
             f16x8 fx[MT][4];
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                rw[0][u] = (COLS == 16 || wlane) ? *(const u32x4*)(wp + (long long)(k + 32 * u) * 16) : (u32x4){0u, 0u, 0u, 0u};
-                if (NB == 2) rw[NB - 1][u] = *(const u32x4*)(wp2 + (long long)(k + 32 * u) * 16);
+                rw[0][u] = (COLS == 16 || wlane) ? __builtin_nontemporal_load((const u32x4*)(wp + (long long)(k + 32 * u) * 16)) : (u32x4){0u, 0u, 0u, 0u};
+                if (NB == 2) rw[NB - 1][u] = __builtin_nontemporal_load((const u32x4*)(wp2 + (long long)(k + 32 * u) * 16));
             }
 #pragma unroll
             for (int t = 0; t < MT; ++t)
