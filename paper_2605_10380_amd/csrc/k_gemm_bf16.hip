@@ -196,8 +196,8 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_tile_kernel(GemmArgs g
         for (int i = 0; i < A_CH; ++i) ra[slot][i] = *(const f16x8*)(A + a_off[i] + k0);
 #pragma unroll
         for (int i = 0; i < B_CH; ++i) {
-            rb[slot][0][i] = *(const u32x4*)(W + b_off[i] + (long long)k0 * 16);
-            if (NB == 2) rb[slot][NB - 1][i] = *(const u32x4*)(W2 + b_off[i] + (long long)k0 * 16);
+            rb[slot][0][i] = __builtin_nontemporal_load((const u32x4*)(W + b_off[i] + (long long)k0 * 16));
+            if (NB == 2) rb[slot][NB - 1][i] = __builtin_nontemporal_load((const u32x4*)(W2 + b_off[i] + (long long)k0 * 16));
         }
     };
     auto store_lds = [&](int slot, int buf) {
@@ -494,7 +494,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_stream_swiglu_kernel(GemmArgs g
 #pragma unroll
         for (int t = 0; t < 2; ++t)
 #pragma unroll
-            for (int c = 0; c < 4; ++c) rw[slot][t][c] = *(const u32x4*)(wp[t] + (long long)k0 * 16 + (c >> 1) * PK_CHUNK + (c & 1) * 2 * PK_KG);
+            for (int c = 0; c < 4; ++c) rw[slot][t][c] = __builtin_nontemporal_load((const u32x4*)(wp[t] + (long long)k0 * 16 + (c >> 1) * PK_CHUNK + (c & 1) * 2 * PK_KG));
 #pragma unroll
         for (int i = 0; i < A_CH; ++i) ra[slot][i] = *(const f16x8*)(A + a_off[i] + k0);
     };
