@@ -326,6 +326,12 @@ def main():
 
     traffic = load_traffic(args.workload)
 
+    # what this machine delivers, beside the nominal peaks the fractions are quoted against
+    probe = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+    torch.cuda.synchronize()
+    read_gbs, copy_gbs, mfma_tf = B.ax_dbg_peaks(probe.data_ptr(), probe.numel(), 5, dm.stream)
+    del probe
+
     def kernel_roofline(tag, name):
         ms, n = prof[tag][name]
         if n == 0:
@@ -387,6 +393,10 @@ def main():
                            "import_gbs": round(image.numel() / (load_ms * 1e-3) / 1e9, 1),
                            "prefill_ms": round(t_prefill * 1e3, 2),
                            "load_over_prefill": round(load_ms / (t_prefill * 1e3), 4)},
+        "measured_peaks": {"hbm_read_gbs": round(read_gbs, 1), "hbm_copy_gbs": round(copy_gbs, 1),
+                           "mfma_f16_tflops": round(mfma_tf, 1),
+                           "note": "1 GiB read-only stream, 512 MiB -> 512 MiB copy (read + written bytes), "
+                                   "register-resident 32x32x16 fp16 MFMA loop on all compute units"},
         "kernel_ms": {tag: {n: round(v[0], 4) for n, v in prof[tag].items()} for tag in prof},
     }
     if not args.no_cpu_baseline:

@@ -32,6 +32,15 @@ ax_status ax_dbg_gemm_time(int dtype, int epilogue, const void *A, const void *W
  * 16): the kernel of known traffic that hardware-counter readings are scaled against. */
 ax_status ax_dbg_copy(void *dst, const void *src, size_t bytes, void *hip_stream);
 
+/* What the machine delivers, measured beside the nominal peaks the roofline fractions are quoted
+ * against.  buf: device memory of `bytes` bytes (a multiple of 16; use a few hundred MiB so that no
+ * cache holds it).  Runs 2 untimed and `reps` timed launches each of (i) a read-only stream over buf,
+ * (ii) the plain copy kernel from the first half of buf to the second, (iii) a register-resident
+ * fp16 MFMA loop (32x32x16, fp32 accumulate) on every compute unit; HIP events on hip_stream.
+ * Writes GB/s read, GB/s copied (read + written bytes) and TFLOP/s.  Synchronises. */
+ax_status ax_dbg_peaks(void *buf, size_t bytes, int reps, float *read_gbs, float *copy_gbs,
+                       float *mfma_f16_tflops, void *hip_stream);
+
 /* Copies a workspace buffer as left by the last ax_extend* call to host memory (synchronises).
  * which: 0 residual stream x float[rows][d_model]; 1 qkv float[rows][(Hq+2Hkv)*hd] (pre-rotary,
  * last layer); 2 q after rotary, act[rows][Hq*hd]; 3 attention output act[rows][Hq*hd];

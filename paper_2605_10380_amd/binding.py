@@ -83,6 +83,8 @@ def _load():
         "ax_dbg_gemm_time": (C.c_int, [C.c_int, C.c_int, vp, vp, vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_size_t,
                                        C.c_int, C.POINTER(C.c_float), vp]),
         "ax_dbg_copy": (C.c_int, [vp, vp, C.c_size_t, vp]),
+        "ax_dbg_peaks": (C.c_int, [vp, C.c_size_t, C.c_int, C.POINTER(C.c_float), C.POINTER(C.c_float),
+                                   C.POINTER(C.c_float), vp]),
         "ax_dbg_read": (C.c_int, [vp, C.c_int, vp, C.c_size_t]),
         "ax_dbg_profile": (C.c_int, [vp, C.c_int]),
         "ax_dbg_profile_read": (C.c_int, [vp, C.POINTER(C.c_double), C.POINTER(i64)]),
@@ -375,6 +377,13 @@ def ax_dbg_gemm_time(dtype: int, epilogue: int, A: int, W: int, W2: int, Cptr: i
 
 def ax_dbg_copy(dst: int, src: int, nbytes: int, stream: int = 0):
     _check(lib.ax_dbg_copy(C.c_void_p(dst), C.c_void_p(src), nbytes, C.c_void_p(stream)))
+
+
+def ax_dbg_peaks(buf: int, nbytes: int, reps: int = 5, stream: int = 0):
+    """(GB/s of a read-only stream, GB/s of a plain copy counting both directions, fp16 MFMA TFLOP/s)."""
+    r, c, m = C.c_float(), C.c_float(), C.c_float()
+    _check(lib.ax_dbg_peaks(C.c_void_p(buf), nbytes, reps, C.byref(r), C.byref(c), C.byref(m), C.c_void_p(stream)))
+    return r.value, c.value, m.value
 
 
 def ax_dbg_read(model: int, which: int, dst: np.ndarray):

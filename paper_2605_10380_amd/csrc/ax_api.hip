@@ -1294,6 +1294,39 @@ ax_status ax_dbg_copy(void* dst, const void* src, size_t bytes, void* hip_stream
     return AX_OK;
 }
 
+ax_status ax_dbg_peaks(void* buf, size_t bytes, int reps, float* read_gbs, float* copy_gbs,
+                       float* mfma_f16_tflops, void* hip_stream) {
+    if (!buf || bytes < 64 || bytes % 32 != 0 || reps < 1 || !read_gbs || !copy_gbs || !mfma_f16_tflops)
+        return fail(AX_ERR_INVALID, "bad argument");
+    hipStream_t s = (hipStream_t)hip_stream;
+    hipEvent_t e0, e1;
+    HIP_TRY(hipEventCreate(&e0));
+    HIP_TRY(hipEventCreate(&e1));
+    char* p = (char*)buf;
+    const size_t half = bytes / 2;
+    double flops = 0.0;
+    float ms[3] = {0.f, 0.f, 0.f};
+    for (int which = 0; which < 3; ++which) {
+        for (int r = -2; r < reps; ++r) {
+            if (r == 0) HIP_TRY(hipEventRecord(e0, s));
+            // the sink of the two read-only kernels is never written (see the kernels)
+            if (which == 0) ax::launch_read_stream(p, bytes / 16, p, s);
+            else if (which == 1) ax::launch_plain_copy(p + half, p, half / 16, s);
+            else flops = ax::launch_mfma_loop(4096, p, s);
+        }
+        HIP_TRY(hipEventRecord(e1, s));
+        HIP_TRY(hipEventSynchronize(e1));
+        HIP_TRY(hipGetLastError());
+        HIP_TRY(hipEventElapsedTime(&ms[which], e0, e1));
+    }
+    hipEventDestroy(e0);
+    hipEventDestroy(e1);
+    *read_gbs = (float)((double)bytes * reps / (ms[0] * 1e-3) / 1e9);
+    *copy_gbs = (float)((double)half * 2.0 * reps / (ms[1] * 1e-3) / 1e9);
+    *mfma_f16_tflops = (float)(flops * reps / (ms[2] * 1e-3) / 1e12);
+    return AX_OK;
+}
+
 ax_status ax_dbg_read(ax_model* m, int which, void* host_dst, size_t bytes) {
     if (!ok(m) || !host_dst) return fail(AX_ERR_INVALID, "bad argument");
     const Layout& L = m->lay;

@@ -124,6 +124,8 @@ void launch_argmax(const float* logits, int rows, int V, int* out, int* scratch,
 void launch_accept(const int* g, const StepView& sv, int* result, hipStream_t s);
 // Plain copy of n16 16-byte words (calibration kernel for hardware counters).
 void launch_plain_copy(void* dst, const void* src, size_t n16, hipStream_t s);
+void launch_read_stream(const void* src, size_t n16, void* sink, hipStream_t s);   // read-only stream; sink: 4 writable bytes, never written
+double launch_mfma_loop(int iters, void* sink, hipStream_t s);                    // register-resident fp16 MFMA loop; returns its flops
 // Copy one KV block (all layers, K and V, all heads) src -> dst: copy on write.
 void launch_block_copy(DType dt, KVGeom kv, int n_layers, int src, int dst, hipStream_t s);
 

@@ -129,3 +129,21 @@ def test_single_layer_stages(torch_cuda, which, P, T):
     for name, e in errs.items():
         assert e <= tol, (name, errs)
     dm.close()
+
+
+def test_measured_peaks_probe(torch_cuda):
+    """The machine-rate probes leave their buffer's first half untouched (the read-only stream writes
+    nothing, the copy kernel fills the second half with the first) and report rates that a working
+    MI355X-class device delivers and that do not exceed the nominal peaks."""
+    torch = torch_cuda
+    from paper_2605_10380_amd import binding as B
+    n = 256 << 20
+    buf = torch.arange(n // 4, dtype=torch.int32, device="cuda")
+    before = buf[: n // 8].clone()
+    torch.cuda.synchronize()
+    read_gbs, copy_gbs, mfma_tf = B.ax_dbg_peaks(buf.data_ptr(), n, 3)
+    assert torch.equal(buf[: n // 8], before) and torch.equal(buf[n // 8:], before)
+    assert 1000.0 < read_gbs <= 8000.0 and 1000.0 < copy_gbs <= 8000.0
+    assert 500.0 < mfma_tf <= 2520.0
+    with pytest.raises(B.AxError):
+        B.ax_dbg_peaks(buf.data_ptr(), 48, 3)
