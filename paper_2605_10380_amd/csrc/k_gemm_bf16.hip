@@ -862,58 +862,89 @@ static int env_int(const char* name, int dflt) {
 static const int kForceNW = env_int("AX_SKINNY_NW", 0);   // experiment knob: wavefronts per block, 0 = automatic
 
 // M > 64: LDS-staged tiles.
+static const int kQkvTile = env_int("AX_QKV_TILE", -1);   // experiment knobs: force 64-row (0) or 128-row (1) blocks
+static const int kResTile = env_int("AX_RES_TILE", -1);
+static const int kResBig = env_int("AX_RES_BIG", 256);
 static const int kQkvKs = env_int("AX_QKV_KS", 0);   // experiment knob: K slices of the QKV GEMM (1 = never split)
 template <int EPI>
 static void launch_lds_tile(const GemmArgs& g, hipStream_t s) {
     const int M = g.M, N = g.N, K = g.K;
+    // Two block shapes, both of 8 wavefronts: 64 x 128 (2 x 4 wavefronts of 32 x 32) and 128 x 128
+    // (wavefront tile 64 x 32).  The larger one pulls a third fewer operand bytes per output and
+    // wins wherever it still gives the chip enough blocks (measured per GEMM class below).
+    const long long tiles64 = (long long)((N + 127) / 128) * ((M + 63) / 64);
+    const long long tiles128 = (long long)((N + 127) / 128) * ((M + 127) / 128);
+    // 128-row blocks only when their row padding costs at most ~15 % more rows than 64-row blocks' (M = 144 does not qualify)
+    const bool pad_ok = (long long)((M + 127) / 128) * 128 * 100 <= (long long)((M + 63) / 64) * 64 * 115;
     if constexpr (EPI == EPI_QKV) {
-        // Plain 64 x 128 tiles (8 wavefronts) write fp32 products, a second kernel does the rms
-        // scaling, rotary embedding and KV append: measured faster than a fused epilogue (one
-        // head per wavefront) at every size tried (M = 256 / 512, all three model shapes).  With fewer than 1024
-        // tiles K is cut in two slices that the second kernel adds up.
+        // A plain store GEMM writes fp32 products, a second kernel does the rms scaling, rotary
+        // embedding and KV append: measured faster than a fused epilogue (one head per wavefront)
+        // at every size tried (M = 256 / 512, all three model shapes).  With few tiles K is cut in
+        // two slices that the second kernel adds up.
         // (The workspace always holds at least one [M, N] fp32 slab: it is sized for 8 slabs of
         // [max_tokens, d_model] and N <= 3 d_model.)
-        const long long tiles = (long long)((N + 127) / 128) * ((M + 63) / 64);
-        int ks = (tiles < 1024 && K % 128 == 0) ? 2 : 1;
-        if (kQkvKs > 0 && K % (kQkvKs * 64) == 0) ks = kQkvKs;
-        while (ks > 1 && (size_t)ks * M * N * sizeof(float) > g.split_ws_bytes) ks >>= 1;
+        // 128-row blocks from 80 tiles up (~3B / ~8B at M = 256: 36 -> 29 / 43 -> 34 us; M = 3584:
+        // 275 -> 221 / 443 -> 329 us); the ~1B shape at M = 256 has 48 such tiles and stays with 64 rows
+        const bool big = kQkvTile >= 0 ? kQkvTile > 0 : (pad_ok && tiles128 >= 80);
+        int ks = big ? (tiles128 < 128 ? 2 : 1) : (tiles64 < 1024 ? 2 : 1);
+        if (kQkvKs > 0) ks = kQkvKs;
+        while (ks > 1 && (K % (ks * 64) != 0 || (size_t)ks * M * N * sizeof(float) > g.split_ws_bytes)) ks >>= 1;
         GemmArgs gs = g;
         gs.ksplit = ks;
         GemmArgs gp = gs;                                 // the products: no scaling, no epilogue work
         gp.ssq = nullptr;
         gp.Cf = g.split_ws;
-        dim3 grid((N + 127) / 128, (M + 63) / 64, ks);
-        gemm_bf16_tile_kernel<EPI_STORE_F32, 1, 1, 2, 4><<<grid, 512, 0, s>>>(gp);
+        if (big) {
+            dim3 grid((N + 127) / 128, (M + 127) / 128, ks);
+            gemm_bf16_tile_kernel<EPI_STORE_F32, 2, 1, 2, 4><<<grid, 512, 0, s>>>(gp);
+        } else {
+            dim3 grid((N + 127) / 128, (M + 63) / 64, ks);
+            gemm_bf16_tile_kernel<EPI_STORE_F32, 1, 1, 2, 4><<<grid, 512, 0, s>>>(gp);
+        }
         qkv_reduce_rope_kernel<<<dim3((unsigned)M, (unsigned)((N / 2 + 255) / 256)), 256, 0, s>>>(gs);
         return;
-    } else {
-    // 64 x 128 tiles, 2 x 4 wavefronts of 32 x 32 each: two wavefronts per SIMD cover each
-    // other's LDS and barrier waits (measured 10-20 % faster than 2 x 2 wavefronts of 32 x 64)
-    dim3 grid((N + 127) / 128, (M + 63) / 64);
-    if (EPI == EPI_RESIDUAL && g.split_ws && N % 64 == 0) {
-        // few output tiles (M = 256 against N = 2048 is 64 tiles for 256 CUs): cut K until
-        // there are ~256 blocks, each still with 8 or more k-steps
+    } else if constexpr (EPI == EPI_RESIDUAL) {
+        // Few output tiles (M = 256 against N = 2048 is 64 tiles of 64 x 128 for 256 CUs): cut K
+        // until there are ~256 blocks, each still with 8 or more k-steps; fp32 partial slabs go to
+        // the workspace and residual_reduce_kernel finishes.
+        auto slices = [&](long long tiles) {
+            int ks = 1;
+            if (!g.split_ws || N % 64 != 0) return ks;
+            while (ks < SPLITK_MAX && tiles * ks < 256 && K % (ks * 2 * 64) == 0 && K / (ks * 2 * 64) >= 8 &&
+                   (size_t)ks * 2 * M * N * sizeof(float) <= g.split_ws_bytes)
+                ks *= 2;
+            return ks;
+        };
+        // 128-row blocks: when there are plenty of tiles without any cut, or when K is long (down
+        // projection) and at most 4 slices give ~200 blocks or more.  Measured against 64-row
+        // blocks: ~8B down projection 57 -> 49 us at M = 256, 98 -> 81 at 512, 907 -> 564 at 3584;
+        // ~1B at M = 256 would need 8 slices and is no faster, so it keeps 64-row blocks.
+        const int ks128 = slices(tiles128);
+        const bool big = kResTile >= 0 ? kResTile > 0 : (M > 128 && pad_ok && (tiles128 >= kResBig || (K >= 4096 && ks128 <= 4 && tiles128 * ks128 >= 192)));
+        const int ks = big ? ks128 : slices(tiles64);
         GemmArgs gs = g;
-        int ks = 1;
-        while (ks < SPLITK_MAX && (long long)grid.x * grid.y * ks < 256 && K % (ks * 2 * 64) == 0 &&
-               K / (ks * 2 * 64) >= 8 && (size_t)ks * 2 * M * N * sizeof(float) <= g.split_ws_bytes)
-            ks *= 2;
-        if (ks > 1) {
-            gs.ksplit = ks;
-            grid.z = ks;
-            gemm_bf16_tile_kernel<EPI, 1, 1, 2, 4><<<grid, 512, 0, s>>>(gs);
-            residual_reduce_kernel<<<(unsigned)(((long long)M * (N / 64) + 3) / 4), 256, 0, s>>>(gs);
+        gs.ksplit = ks;
+        if (big) {
+            dim3 grid((N + 127) / 128, (M + 127) / 128, ks);
+            gemm_bf16_tile_kernel<EPI_RESIDUAL, 2, 1, 2, 4><<<grid, 512, 0, s>>>(gs);
+        } else {
+            dim3 grid((N + 127) / 128, (M + 63) / 64, ks);
+            gemm_bf16_tile_kernel<EPI_RESIDUAL, 1, 1, 2, 4><<<grid, 512, 0, s>>>(gs);
+        }
+        if (ks > 1) residual_reduce_kernel<<<(unsigned)(((long long)M * (N / 64) + 3) / 4), 256, 0, s>>>(gs);
+        return;
+    } else if constexpr (EPI == EPI_SWIGLU) {
+        // gate/up with two or more 128-row tiles: 128 x 64 tiles make a CU pull (128 + 2 * 64) rows of
+        // operands per k instead of (64 + 2 * 128) for the same number of blocks (2-3 % faster)
+        if (M > 128) {
+            dim3 tgrid((N + 63) / 64, (M + 127) / 128);
+            gemm_bf16_tile_kernel<EPI_SWIGLU, 1, 1, 4, 2><<<tgrid, 512, 0, s>>>(g);
             return;
         }
     }
-    // gate/up with two or more 128-row tiles: 128 x 64 tiles make a CU pull (128 + 2 * 64) rows of
-    // operands per k instead of (64 + 2 * 128) for the same number of blocks (2-3 % faster)
-    if (EPI == EPI_SWIGLU && M > 128) {
-        dim3 tgrid((N + 63) / 64, (M + 127) / 128);
-        gemm_bf16_tile_kernel<EPI_SWIGLU, 1, 1, 4, 2><<<tgrid, 512, 0, s>>>(g);
-        return;
-    }
-    gemm_bf16_tile_kernel<EPI, 1, 1, 2, 4><<<grid, 512, 0, s>>>(g);
+    if constexpr (EPI == EPI_STORE_F32 || EPI == EPI_SWIGLU) {
+        dim3 grid((N + 127) / 128, (M + 63) / 64);
+        gemm_bf16_tile_kernel<EPI, 1, 1, 2, 4><<<grid, 512, 0, s>>>(g);
     }
 }
 
