@@ -1319,8 +1319,8 @@ ax_status ax_dbg_peaks(void* buf, size_t bytes, int reps, float* read_gbs, float
         HIP_TRY(hipGetLastError());
         HIP_TRY(hipEventElapsedTime(&ms[which], e0, e1));
     }
-    hipEventDestroy(e0);
-    hipEventDestroy(e1);
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
     *read_gbs = (float)((double)bytes * reps / (ms[0] * 1e-3) / 1e9);
     *copy_gbs = (float)((double)half * 2.0 * reps / (ms[1] * 1e-3) / 1e9);
     *mfma_f16_tflops = (float)(flops * reps / (ms[2] * 1e-3) / 1e12);
