@@ -82,6 +82,8 @@ def _load():
         "ax_dbg_gemm": (C.c_int, [C.c_int, C.c_int, vp, vp, vp, vp, C.c_int, C.c_int, C.c_int, vp]),
         "ax_dbg_gemm_time": (C.c_int, [C.c_int, C.c_int, vp, vp, vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_size_t,
                                        C.c_int, C.POINTER(C.c_float), vp]),
+        "ax_dbg_gemm_residual": (C.c_int, [vp, vp, vp, vp, vp, vp, C.POINTER(C.c_int), C.c_int, C.c_int, C.c_int, vp,
+                                           C.c_size_t, vp]),
         "ax_dbg_copy": (C.c_int, [vp, vp, C.c_size_t, vp]),
         "ax_dbg_peaks": (C.c_int, [vp, C.c_size_t, C.c_int, C.POINTER(C.c_float), C.POINTER(C.c_float),
                                    C.POINTER(C.c_float), vp]),
@@ -373,6 +375,16 @@ def ax_dbg_gemm_time(dtype: int, epilogue: int, A: int, W: int, W2: int, Cptr: i
     _check(lib.ax_dbg_gemm_time(dtype, epilogue, C.c_void_p(A), C.c_void_p(W), C.c_void_p(W2), C.c_void_p(Cptr), M, N, K,
                                 iters, w_stride_bytes, w_count, C.byref(us), C.c_void_p(stream)))
     return us.value
+
+
+def ax_dbg_gemm_residual(A: int, W: int, gain: int, x: int, a16: int, ssq: int, M: int, N: int, K: int,
+                         split_ws: int = 0, split_ws_bytes: int = 0, stream: int = 0) -> int:
+    """Returns the number of sum-of-squares partials per row the call wrote."""
+    parts = C.c_int()
+    _check(lib.ax_dbg_gemm_residual(C.c_void_p(A), C.c_void_p(W), C.c_void_p(gain), C.c_void_p(x), C.c_void_p(a16),
+                                    C.c_void_p(ssq), C.byref(parts), M, N, K, C.c_void_p(split_ws), split_ws_bytes,
+                                    C.c_void_p(stream)))
+    return parts.value
 
 
 def ax_dbg_copy(dst: int, src: int, nbytes: int, stream: int = 0):

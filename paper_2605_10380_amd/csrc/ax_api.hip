@@ -1242,6 +1242,30 @@ ax_status ax_dbg_gemm(int dtype, int epilogue, const void* A, const void* W, con
     return AX_OK;
 }
 
+ax_status ax_dbg_gemm_residual(const void* A, const void* W, const void* gain, float* x, void* a16, float* ssq,
+                               int* n_parts, int M, int N, int K, void* split_ws, size_t split_ws_bytes,
+                               void* hip_stream) {
+    if (!A || !W || !gain || !x || !a16 || !ssq || !n_parts || M <= 0 || N <= 0 || K <= 0 || (split_ws_bytes && !split_ws))
+        return fail(AX_ERR_INVALID, "bad argument");
+    if (K % 64 != 0 || N % 16 != 0) return fail(AX_ERR_UNSUPPORTED, "bf16 needs K %% 64 == 0, N %% 16 == 0");
+    hipStream_t s = (hipStream_t)hip_stream;
+    void* pw = nullptr;
+    HIP_TRY(hipMalloc(&pw, (size_t)N * K * 2));
+    ax::launch_pack_weights(W, pw, N, K, s);
+    ax::GemmArgs g{};
+    g.A = A; g.W = pw; g.M = M; g.N = N; g.K = K;
+    g.Cf = x; g.C16 = a16; g.gain_next = gain; g.ssq_out = ssq;
+    g.split_ws = split_ws_bytes ? (float*)split_ws : nullptr;
+    g.split_ws_bytes = split_ws_bytes;
+    *n_parts = ax::gemm_ssq_parts(M, N);
+    ax::launch_gemm_bf16(ax::EPI_RESIDUAL, g, s);
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    (void)hipFree(pw);
+    if (e != hipSuccess) return fail(AX_ERR_DEVICE, "debug GEMM: %s", hipGetErrorString(e));
+    return AX_OK;
+}
+
 ax_status ax_dbg_gemm_time(int dtype, int epilogue, const void* A, const void* W, const void* W2, void* C, int M,
                            int N, int K, int iters, size_t w_stride_bytes, int w_count, float* avg_us,
                            void* hip_stream) {

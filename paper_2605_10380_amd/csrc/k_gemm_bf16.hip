@@ -450,9 +450,13 @@ __global__ __launch_bounds__(256) void qkv_reduce_rope_kernel(GemmArgs g) {
 //
 // Blocks are renumbered so that the gy row tiles that share a weight tile have consecutive ids
 // on one XCD (workgroups are dealt to the 8 XCDs round robin), i.e. share that XCD's L2.
-template <int TM, int D>
-__global__ __launch_bounds__(256) void gemm_bf16_stream_swiglu_kernel(GemmArgs g, int gx, int gy) {
-    constexpr int BM = TM * 32, BN = 128, BK = 64, LS = BK + 8;
+//
+// The same kernel serves the other GEMMs of calls with thousands of rows (EPI_STORE_F32: the QKV
+// products, EPI_RESIDUAL): there a wavefront's two weight streams are two 32-row tiles of the ONE
+// matrix, 32 columns apart, and a block covers 256 output columns.
+template <int EPI, int TM, int D>
+__global__ __launch_bounds__(256) void gemm_bf16_stream_kernel(GemmArgs g, int gx, int gy) {
+    constexpr int BM = TM * 32, BN = EPI == EPI_SWIGLU ? 128 : 256, BK = 64, LS = BK + 8;
     constexpr int A_CH = BM * 8 / 256;                       // 16-byte chunks of the A tile per thread
     __shared__ __attribute__((aligned(16))) f16 sA[2][BM * LS];
     __shared__ float s_inv[BM];
@@ -467,11 +471,15 @@ __global__ __launch_bounds__(256) void gemm_bf16_stream_swiglu_kernel(GemmArgs g
     const int bx = bid / gy, by = bid - bx * gy;
     const int m0 = by * BM, n0 = bx * BN;
 
-    const int ncol = n0 + wave * 32 + lrow;                  // this lane's output column = row of W and W2
+    // this lane's output columns = weight rows of its two streams: row n of W and of W2 (SwiGLU),
+    // or rows n and n + 32 of W
+    int ncol[2];
+    ncol[0] = n0 + wave * (BN / 4) + lrow;
+    ncol[1] = EPI == EPI_SWIGLU ? ncol[0] : ncol[0] + 32;
     const bf16* wp[2];
     // packed layout: MFMA step c of a k-step covers k = 16 c + 8 lg .. + 7, i.e. chunk c / 2, k-group 2 (c % 2) + lg
-    wp[0] = (const bf16*)g.W + packed_row(min(ncol, N - 1), K) + lg * PK_KG;
-    wp[1] = (const bf16*)g.W2 + packed_row(min(ncol, N - 1), K) + lg * PK_KG;
+    wp[0] = (const bf16*)g.W + packed_row(min(ncol[0], N - 1), K) + lg * PK_KG;
+    wp[1] = (const bf16*)(EPI == EPI_SWIGLU ? g.W2 : g.W) + packed_row(min(ncol[1], N - 1), K) + lg * PK_KG;
     long long a_off[A_CH];
 #pragma unroll
     for (int i = 0; i < A_CH; ++i) {
@@ -555,16 +563,64 @@ __global__ __launch_bounds__(256) void gemm_bf16_stream_swiglu_kernel(GemmArgs g
         }
     }
 
-    f16* __restrict__ out = (f16*)g.C16;
+    auto row_of = [&](int i, int r) { return i * 32 + (r >> 2) * 8 + lg * 4 + (r & 3); };
+    if constexpr (EPI == EPI_SWIGLU) {
+        f16* __restrict__ out = (f16*)g.C16;
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+        for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int row = i * 32 + (r >> 2) * 8 + lg * 4 + (r & 3), m = m0 + row;
-            const float inv = g.ssq ? s_inv[row] : 1.0f;
-            if (m < M && ncol < N)
-                out[(long long)m * N + ncol] = (f16)(silu_f(acc[0][i][r] * inv) * (acc[1][i][r] * inv));
+            for (int r = 0; r < 16; ++r) {
+                const int row = row_of(i, r), m = m0 + row;
+                const float inv = g.ssq ? s_inv[row] : 1.0f;
+                if (m < M && ncol[0] < N)
+                    out[(long long)m * N + ncol[0]] = (f16)(silu_f(acc[0][i][r] * inv) * (acc[1][i][r] * inv));
+            }
+    } else if constexpr (EPI == EPI_STORE_F32) {
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int row = row_of(i, r), m = m0 + row;
+                    const float inv = g.ssq ? s_inv[row] : 1.0f;
+                    if (m < M && ncol[t] < N) g.Cf[(long long)m * N + ncol[t]] = acc[t][i][r] * inv;
+                }
+    } else {                                                  // EPI_RESIDUAL; N % 32 == 0 (checked by the launcher)
+        f16* __restrict__ a16 = (f16*)g.C16;
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const int n = min(ncol[t], N - 1);
+            const float gain = g.gain_next ? (float)((const bf16*)g.gain_next)[n] : 0.f;
+#pragma unroll
+            for (int i0 = 0; i0 < TM; i0 += 2) {
+            float xv[2][16];                                  // the loads of two row tiles first, then their stores
+#pragma unroll
+            for (int i = i0; i < i0 + 2; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) xv[i - i0][r] = g.Cf[(long long)min(m0 + row_of(i, r), M - 1) * N + n];
+#pragma unroll
+            for (int i = i0; i < i0 + 2; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int m = m0 + row_of(i, r);
+                    const bool live = m < M && ncol[t] < N;
+                    const float xn = xv[i - i0][r] + acc[t][i][r];
+                    float ss = live ? xn * xn : 0.f;
+                    if (live) {
+                        const long long o = (long long)m * N + n;
+                        g.Cf[o] = xn;
+                        if (g.gain_next) a16[o] = (f16)(xn * gain);
+                    }
+                    if (g.gain_next) {                        // partial sum of squares over this tile's 32 columns
+#pragma unroll
+                        for (int o = 16; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
+                        if (lrow == 0 && live) g.ssq_out[(long long)m * (N / 32) + (ncol[t] >> 5)] = ss;
+                    }
+                }
+            }
         }
+    }
 }
 
 // ------------------------------------------------------------------------------ skinny kernel
@@ -862,6 +918,7 @@ static int env_int(const char* name, int dflt) {
 static const int kForceNW = env_int("AX_SKINNY_NW", 0);   // experiment knob: wavefronts per block, 0 = automatic
 
 // M > 64: LDS-staged tiles.
+static const int kStreamMinM = env_int("AX_STREAM_MIN_M", 1024);   // rows from which QKV / residual GEMMs stream their weights (0 = never)
 static const int kQkvTile = env_int("AX_QKV_TILE", -1);   // experiment knobs: force 64-row (0) or 128-row (1) blocks
 static const int kResTile = env_int("AX_RES_TILE", -1);
 static const int kResBig = env_int("AX_RES_BIG", 256);
@@ -876,7 +933,28 @@ static void launch_lds_tile(const GemmArgs& g, hipStream_t s) {
     const long long tiles128 = (long long)((N + 127) / 128) * ((M + 127) / 128);
     // 128-row blocks only when their row padding costs at most ~15 % more rows than 64-row blocks' (M = 144 does not qualify)
     const bool pad_ok = (long long)((M + 127) / 128) * 128 * 100 <= (long long)((M + 63) / 64) * 64 * 115;
+    // Calls with a thousand rows or more: the streaming kernel (weights straight to the MFMA operands,
+    // 128 x 256 blocks, one block per CU at a time) where its blocks fill the 256 CUs evenly - a
+    // single round of 160 or more blocks, or rounds that are at least 3/4 full - and, for the
+    // residual GEMMs, only with the long K of the down projection.  Measured against the tile
+    // kernel: ~8B QKV 106 -> 88 us at M = 1024 and 326 -> 278 at 3584, ~8B down 293 -> 259 at 2048
+    // and 558 -> 493 at 3584, ~3B down 168 -> 153 at 2048; O projections and half-empty last
+    // rounds (336 blocks) lose 5-40 % and stay with the tile kernel.
+    const long long sblocks = (long long)((N + 255) / 256) * ((M + 127) / 128), rounds = (sblocks + 255) / 256;
+    const bool stream = kStreamMinM > 0 && M >= kStreamMinM && N % 32 == 0 && sblocks >= 160 &&
+                        (rounds == 1 || sblocks * 4 >= rounds * 256 * 3) && (EPI != EPI_RESIDUAL || K >= 8192);
     if constexpr (EPI == EPI_QKV) {
+        if (stream && (size_t)M * N * sizeof(float) <= g.split_ws_bytes) {
+            GemmArgs gs = g;
+            gs.ksplit = 1;
+            GemmArgs gp = gs;
+            gp.ssq = nullptr;
+            gp.Cf = g.split_ws;
+            const int gx = (N + 255) / 256, gy = (M + 127) / 128;
+            gemm_bf16_stream_kernel<EPI_STORE_F32, 4, 3><<<gx * gy, 256, 0, s>>>(gp, gx, gy);
+            qkv_reduce_rope_kernel<<<dim3((unsigned)M, (unsigned)((N / 2 + 255) / 256)), 256, 0, s>>>(gs);
+            return;
+        }
         // A plain store GEMM writes fp32 products, a second kernel does the rms scaling, rotary
         // embedding and KV append: measured faster than a fused epilogue (one head per wavefront)
         // at every size tried (M = 256 / 512, all three model shapes).  With few tiles K is cut in
@@ -904,6 +982,11 @@ static void launch_lds_tile(const GemmArgs& g, hipStream_t s) {
         qkv_reduce_rope_kernel<<<dim3((unsigned)M, (unsigned)((N / 2 + 255) / 256)), 256, 0, s>>>(gs);
         return;
     } else if constexpr (EPI == EPI_RESIDUAL) {
+        if (stream) {
+            const int gx = (N + 255) / 256, gy = (M + 127) / 128;
+            gemm_bf16_stream_kernel<EPI_RESIDUAL, 4, 3><<<gx * gy, 256, 0, s>>>(g, gx, gy);
+            return;
+        }
         // Few output tiles (M = 256 against N = 2048 is 64 tiles of 64 x 128 for 256 CUs): cut K
         // until there are ~256 blocks, each still with 8 or more k-steps; fp32 partial slabs go to
         // the workspace and residual_reduce_kernel finishes.
@@ -943,6 +1026,11 @@ static void launch_lds_tile(const GemmArgs& g, hipStream_t s) {
         }
     }
     if constexpr (EPI == EPI_STORE_F32 || EPI == EPI_SWIGLU) {
+        if (EPI == EPI_STORE_F32 && stream) {              // logits of thousands of rows
+            const int gx = (N + 255) / 256, gy = (M + 127) / 128;
+            gemm_bf16_stream_kernel<EPI_STORE_F32, 4, 3><<<gx * gy, 256, 0, s>>>(g, gx, gy);
+            return;
+        }
         dim3 grid((N + 127) / 128, (M + 63) / 64);
         gemm_bf16_tile_kernel<EPI, 1, 1, 2, 4><<<grid, 512, 0, s>>>(g);
     }
@@ -967,7 +1055,7 @@ static void launch_bf16(const GemmArgs& g, hipStream_t s) {
     }
     if (EPI == EPI_SWIGLU && M >= 384) {
         const int gx = (N + 127) / 128, gy = (M + 127) / 128;
-        gemm_bf16_stream_swiglu_kernel<4, 3><<<gx * gy, 256, 0, s>>>(g, gx, gy);
+        gemm_bf16_stream_kernel<EPI_SWIGLU, 4, 3><<<gx * gy, 256, 0, s>>>(g, gx, gy);
         return;
     }
     launch_lds_tile<EPI>(g, s);

@@ -24,7 +24,9 @@ def torch_cuda():
 # streaming SwiGLU kernel (steady-state loop and drain, ragged rows and columns)
 GEMM_CASES = [(1, 64, 64), (9, 3072, 2048), (9, 2048, 8192), (17, 512, 256), (33, 128, 1024), (64, 2064, 192),
               (65, 384, 128), (100, 200 * 16, 320), (256, 3072, 2048), (300, 1024, 512), (512, 33 * 128, 256),
-              (400, 1040, 1024), (384, 2048, 576)]
+              (400, 1040, 1024), (384, 2048, 576),
+              # thousands of rows: every epilogue through the streaming kernel (ragged rows and columns, drain path)
+              (1600, 7712, 192), (1664, 7680, 448)]
 
 
 @pytest.mark.parametrize("M,N,K", GEMM_CASES)
@@ -55,6 +57,44 @@ def test_bf16_gemm(torch_cuda, M, N, K, epi):
     else:
         want = O.silu(ref) * (A64 @ O.widen(W2).T)
         assert np.abs(got - want).max() <= 2 ** -11 * np.abs(want).max() + 1e-6
+
+
+# the residual GEMM with the next norm's preparation, through every kernel that implements it:
+# skinny with 8 / 12 / 16 columns per block, tile kernels unsplit and with K slices (64- and 128-row
+# blocks), streaming kernel
+RESIDUAL_CASES = [(9, 2048, 512, False), (9, 3072, 256, False), (33, 4096, 192, False), (64, 1040, 128, False),
+                  (100, 512, 256, False), (256, 2048, 2048, True), (256, 2048, 2048, False), (300, 1024, 4096, True),
+                  (512, 4096, 4096, True), (520, 3072, 8192, True), (1600, 7712, 192, True),
+                  (1030, 5088, 8192, True)]        # long K and one even round of blocks: streaming kernel
+
+
+@pytest.mark.parametrize("M,N,K,split", RESIDUAL_CASES)
+def test_bf16_residual_gemm_with_norm_preparation(torch_cuda, M, N, K, split):
+    torch = torch_cuda
+    from paper_2605_10380_amd import binding as B
+    rng = np.random.default_rng(M * 3 + N + K)
+    A = (rng.standard_normal((M, K), dtype=np.float32) * 0.5).astype(np.float16)
+    W = I.f32_to_bf16_bits(rng.standard_normal((N, K), dtype=np.float32) * 0.05)
+    gain = I.f32_to_bf16_bits(1.0 + 0.1 * rng.standard_normal(N, dtype=np.float32))
+    x0 = rng.standard_normal((M, N), dtype=np.float32)
+    bf = lambda a: torch.from_numpy(a).view(torch.bfloat16).cuda()
+    dA, dW, dg, dx = torch.from_numpy(A).cuda(), bf(W), bf(gain), torch.from_numpy(x0.copy()).cuda()
+    da16 = torch.zeros((M, N), dtype=torch.float16, device="cuda")
+    dssq = torch.full((M, N // 8), float("nan"), dtype=torch.float32, device="cuda")
+    ws_bytes = 8 * M * N * 4 if split else 0
+    dws = torch.empty(max(ws_bytes, 4), dtype=torch.uint8, device="cuda")
+    parts = B.ax_dbg_gemm_residual(dA.data_ptr(), dW.data_ptr(), dg.data_ptr(), dx.data_ptr(), da16.data_ptr(),
+                                   dssq.data_ptr(), M, N, K, dws.data_ptr() if split else 0, ws_bytes)
+    assert 1 <= parts <= N // 8
+    want = x0.astype(np.float64) + A.astype(np.float64) @ O.widen(W).T
+    got = dx.cpu().numpy().astype(np.float64)
+    assert np.abs(got - want).max() <= 2e-5 * np.abs(want).max() + 1e-5
+    a16 = da16.float().cpu().numpy().astype(np.float64)
+    want16 = want * O.widen(gain)[None, :]
+    assert np.abs(a16 - want16).max() <= 2 ** -10 * np.abs(want16).max() + 1e-6
+    ssq = dssq.cpu().numpy().reshape(-1)[:M * parts].reshape(M, parts)        # rows are `parts` apart
+    assert np.isfinite(ssq).all()
+    assert np.allclose(ssq.astype(np.float64).sum(axis=1), (want ** 2).sum(axis=1), rtol=2e-5)
 
 
 @pytest.mark.parametrize("M,N,K", [(5, 37, 19), (64, 688, 256), (70, 256, 688), (130, 4096, 256)])
