@@ -120,7 +120,8 @@ __global__ __launch_bounds__(64) void attn_simple_kernel(const T* __restrict__ q
 // lane (channel d) is two 8-byte loads from its channel's 16-token row.
 // One 32-key step of the online softmax for the lane's query row.  s: raw scores q.k of the
 // lane's 16 keys (key of register r: kv0 + (r/4)*8 + g*4 + r%4); c = log2(e)/sqrt(hd).  m is the
-// reference exponent of the row (scaled, base-2 domain), l the running sum of 2^(s*c - m).  The
+// reference exponent of the row (scaled, base-2 domain), l the running sum of 2^(s*c - m) over the
+// LANE's keys (the caller adds l of lane and lane ^ 32 when it is done).  The
 // reference is NOT kept equal to the running maximum: it is only raised when some row of the
 // wavefront has a score more than SOFTMAX_SLACK above it (then every row moves to its current
 // maximum, the function returns true and the caller multiplies its output accumulators by
@@ -146,10 +147,14 @@ __device__ __forceinline__ bool online_softmax_step(f32x16& s, int kv0, int g, i
     float mx = s[0];
 #pragma unroll
     for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[r]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * c;                // c > 0: max commutes with the scaling
+    mx *= c;                                                    // c > 0: max commutes with the scaling
+    // mx covers the lane's 16 keys, i.e. half of its row's 32: the test below is the same over
+    // half rows as over whole rows, so the two halves only meet (one cross-lane exchange) when the
+    // reference really moves
     const bool raise = __any(mx > m + SOFTMAX_SLACK);           // m = -inf: any visible key raises it
     alpha = 1.0f;
     if (raise) {
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
         const float mn = fmaxf(m, mx);
         alpha = (mn == -INFINITY) ? 1.0f : __builtin_amdgcn_exp2f(m - mn);   // m = -inf -> 0
         l *= alpha;
@@ -169,8 +174,7 @@ __device__ __forceinline__ bool online_softmax_step(f32x16& s, int kv0, int g, i
     }
     pb[0] = __builtin_bit_cast(f16x8, pw[0]);
     pb[1] = __builtin_bit_cast(f16x8, pw[1]);
-    ps += __shfl_xor(ps, 32, 64);
-    l += ps;
+    l += ps;                                                    // the lane's half of the row; halves are added at the end
     return raise;
 }
 
@@ -311,6 +315,9 @@ __global__ __launch_bounds__(64) void attn_split_kernel(AttnArgs a) {
 
     // partials of the group: NQ consecutive (O^T, m, l) records per (group, KV head, slice);
     // rows past the end of the sequence are not written (and never read)
+    float l_row[NQ];
+#pragma unroll
+    for (int t = 0; t < NQ; ++t) l_row[t] = l[t] + __shfl_xor(l[t], 32, 64);    // both halves of each row
 #pragma unroll
     for (int t = 0; t < NQ; ++t) {
         if (r0 + t * 32 + ql >= n_stacked) continue;
@@ -324,7 +331,7 @@ __global__ __launch_bounds__(64) void attn_split_kernel(AttnArgs a) {
             }
         if (g == 0) {
             part[HD * 32 + ql] = m[t];
-            part[HD * 32 + 32 + ql] = l[t];
+            part[HD * 32 + 32 + ql] = l_row[t];
         }
     }
 }
@@ -390,20 +397,35 @@ __global__ __launch_bounds__(64 * NQ) void attn_block_kernel(AttnArgs a) {
         for (int r = 0; r < 16; ++r) o[d][r] = 0.f;
 
     // operand chunks of this thread: K chunk i covers key (cidx / (HD/8)), columns 8*(cidx % (HD/8));
-    // V chunk i covers block (cidx / (2*HD)), channel ((cidx / 2) % HD), tokens 8*(cidx % 2)..+7
+    // V chunk i covers block (cidx / (2*HD)), channel ((cidx / 2) % HD), tokens 8*(cidx % 2)..+7.
+    // The 64 chunks of a wavefront lie inside ONE 16-token block of the step (8 or 4 whole keys of K,
+    // half or a quarter of a V block), so which of the step's two blocks a chunk belongs to is
+    // wavefront-uniform: the block ids are read out of the table register into scalars, the block's
+    // base address is scalar arithmetic, and what is left per lane is a constant offset computed once.
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    unsigned k_off[CH], v_off[CH];
+    bool k_second[CH], v_second[CH];
+#pragma unroll
+    for (int i = 0; i < CH; ++i) {
+        const int cidx = min(tid + NT * i, TCH - 1), c0 = min(wave_u * 64 + NT * i, TCH - 1);
+        k_off[i] = (unsigned)(((cidx / (HD / 8)) & 15) * HD + (cidx % (HD / 8)) * 8) * 2u;      // bytes
+        v_off[i] = (unsigned)(((cidx / 2) % HD) * 16 + (cidx % 2) * 8) * 2u;
+        k_second[i] = ((c0 / (HD / 8)) >> 4) != 0;
+        v_second[i] = (c0 / (2 * HD)) != 0;
+    }
     u32x4 rk[D][CH], rv[D][CH];
+    // keys past the end of the sequence (last step only) read slots of the last block that hold
+    // stale but finite values, or the last block twice; the causal mask discards their scores
     auto gload = [&](int slot, int st, int tabv, int chunk) {
-        const int kv0 = st * 32;
+        const int rel = 2 * (st - chunk), lim = last_blk - 2 * chunk;     // table lanes of the step's two blocks
+        const int b0 = __builtin_amdgcn_readlane(tabv, min(rel, lim)), b1 = __builtin_amdgcn_readlane(tabv, min(rel + 1, lim));
 #pragma unroll
         for (int i = 0; i < CH; ++i) {
-            const int cidx = min(tid + NT * i, TCH - 1);
-            if (TCH % NT != 0 && tid + NT * i >= TCH) continue;            // more threads than chunks: the rest load nothing
-            const int key = min(kv0 + cidx / (HD / 8), kv_len - 1);
-            const int kblk = __shfl(tabv, (key >> 4) - 2 * chunk, 64);
-            rk[slot][i] = *(const u32x4*)(Kp + ((long long)kblk * 16 + (key & 15)) * HD + (cidx % (HD / 8)) * 8);
-            const int vb = min((kv0 >> 4) + cidx / (2 * HD), last_blk);
-            const int vblk = __shfl(tabv, vb - 2 * chunk, 64);
-            rv[slot][i] = *(const u32x4*)(Vp + ((long long)vblk * HD + (cidx / 2) % HD) * 16 + (cidx % 2) * 8);
+            if (TCH % NT != 0 && wave_u * 64 + NT * i >= TCH) continue;     // more threads than chunks: the rest load nothing
+            const char* kb = (const char*)(Kp + (long long)(k_second[i] ? b1 : b0) * 16 * HD);
+            const char* vb = (const char*)(Vp + (long long)(v_second[i] ? b1 : b0) * 16 * HD);
+            rk[slot][i] = *(const u32x4*)(kb + k_off[i]);
+            rv[slot][i] = *(const u32x4*)(vb + v_off[i]);
         }
     };
     auto lstore = [&](int slot, int buf) {
@@ -478,6 +500,7 @@ __global__ __launch_bounds__(64 * NQ) void attn_block_kernel(AttnArgs a) {
         }
     }
 
+    const float l_row = l + __shfl_xor(l, 32, 64);               // both halves of the row
     if (r0 + wave * 32 + ql < n_stacked) {
         float* part = a.partials + (((long long)(tile * Hkv + hk) * a.n_splits + split) * NQ + wave) * PS;
 #pragma unroll
@@ -489,7 +512,7 @@ __global__ __launch_bounds__(64 * NQ) void attn_block_kernel(AttnArgs a) {
             }
         if (g == 0) {
             part[HD * 32 + ql] = m;
-            part[HD * 32 + 32 + ql] = l;
+            part[HD * 32 + 32 + ql] = l_row;
         }
     }
 }
