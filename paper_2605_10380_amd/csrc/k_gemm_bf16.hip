@@ -454,9 +454,15 @@ __global__ __launch_bounds__(256) void qkv_reduce_rope_kernel(GemmArgs g) {
 // The same kernel serves the other GEMMs of calls with thousands of rows (EPI_STORE_F32: the QKV
 // products, EPI_RESIDUAL): there a wavefront's two weight streams are two 32-row tiles of the ONE
 // matrix, 32 columns apart, and a block covers 256 output columns.
-template <int EPI, int TM, int D>
+//
+// NS = 1: one weight stream per wavefront (block = 128 columns), and K may be cut into g.ksplit
+// slices over extra blocks whose raw fp32 partial products go to slabs that qkv_reduce_rope_kernel /
+// residual_reduce_kernel add up: calls of 129-192 rows (16 sessions verified together), where one
+// 160- or 192-row block reads each weight once and the slices give the chip its ~200 blocks.
+template <int EPI, int TM, int D, int NS = 2>
 __global__ __launch_bounds__(256) void gemm_bf16_stream_kernel(GemmArgs g, int gx, int gy) {
-    constexpr int BM = TM * 32, BN = EPI == EPI_SWIGLU ? 128 : 256, BK = 64, LS = BK + 8;
+    static_assert(EPI != EPI_SWIGLU || NS == 2, "SwiGLU streams gate and up");
+    constexpr int BM = TM * 32, BN = EPI == EPI_SWIGLU ? 128 : NS * 128, BK = 64, LS = BK + 8;
     constexpr int A_CH = BM * 8 / 256;                       // 16-byte chunks of the A tile per thread
     __shared__ __attribute__((aligned(16))) f16 sA[2][BM * LS];
     __shared__ float s_inv[BM];
@@ -465,42 +471,46 @@ __global__ __launch_bounds__(256) void gemm_bf16_stream_kernel(GemmArgs g, int g
     const int M = g.M, N = g.N, K = g.K;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int lrow = lane & 31, lg = lane >> 5;
-    int bid = blockIdx.x;
     const int nblk = gx * gy;
+    const int kz = blockIdx.x / nblk;                        // K slice (0 unless g.ksplit > 1)
+    int bid = blockIdx.x - kz * nblk;
     if ((nblk & 7) == 0) bid = (bid & 7) * (nblk >> 3) + (bid >> 3);
     const int bx = bid / gy, by = bid - bx * gy;
     const int m0 = by * BM, n0 = bx * BN;
+    const int kspan = g.ksplit > 1 ? K / g.ksplit : K, kbase = kz * kspan;
 
     // this lane's output columns = weight rows of its two streams: row n of W and of W2 (SwiGLU),
     // or rows n and n + 32 of W
-    int ncol[2];
-    ncol[0] = n0 + wave * (BN / 4) + lrow;
-    ncol[1] = EPI == EPI_SWIGLU ? ncol[0] : ncol[0] + 32;
-    const bf16* wp[2];
+    int ncol[NS];
+    const bf16* wp[NS];
     // packed layout: MFMA step c of a k-step covers k = 16 c + 8 lg .. + 7, i.e. chunk c / 2, k-group 2 (c % 2) + lg
-    wp[0] = (const bf16*)g.W + packed_row(min(ncol[0], N - 1), K) + lg * PK_KG;
-    wp[1] = (const bf16*)(EPI == EPI_SWIGLU ? g.W2 : g.W) + packed_row(min(ncol[1], N - 1), K) + lg * PK_KG;
+#pragma unroll
+    for (int t = 0; t < NS; ++t) {
+        ncol[t] = n0 + wave * (BN / 4) + lrow + (EPI == EPI_SWIGLU ? 0 : 32 * t);
+        wp[t] = (const bf16*)(EPI == EPI_SWIGLU && t == 1 ? g.W2 : g.W) + packed_row(min(ncol[t], N - 1), K) +
+                (long long)kbase * 16 + lg * PK_KG;
+    }
     long long a_off[A_CH];
 #pragma unroll
     for (int i = 0; i < A_CH; ++i) {
         const int c = tid + 256 * i, row = c >> 3, cc = c & 7;
         const int gm = min(m0 + row, M - 1);
-        a_off[i] = (long long)(g.a_rows ? g.a_rows[gm] : gm) * K + cc * 8;
+        a_off[i] = (long long)(g.a_rows ? g.a_rows[gm] : gm) * K + kbase + cc * 8;
     }
 
-    f32x16 acc[2][TM];
+    f32x16 acc[NS][TM];
 #pragma unroll
-    for (int t = 0; t < 2; ++t)
+    for (int t = 0; t < NS; ++t)
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[t][i][r] = 0.f;
 
-    u32x4 rw[D][2][4];              // raw bf16 weights: 4 chunks of 8 k per matrix and k-step
+    u32x4 rw[D][NS][4];             // weights: 4 chunks of 8 k per stream and k-step
     f16x8 ra[D][A_CH];
     auto load_global = [&](int slot, int k0) {
 #pragma unroll
-        for (int t = 0; t < 2; ++t)
+        for (int t = 0; t < NS; ++t)
 #pragma unroll
             for (int c = 0; c < 4; ++c) rw[slot][t][c] = __builtin_nontemporal_load((const u32x4*)(wp[t] + (long long)k0 * 16 + (c >> 1) * PK_CHUNK + (c & 1) * 2 * PK_KG));
 #pragma unroll
@@ -516,20 +526,20 @@ __global__ __launch_bounds__(256) void gemm_bf16_stream_kernel(GemmArgs g, int g
     auto multiply = [&](int slot, int buf) {
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-            f16x8 fa[TM], fw[2];
+            f16x8 fa[TM], fw[NS];
 #pragma unroll
             for (int i = 0; i < TM; ++i) fa[i] = *(const f16x8*)(sA[buf] + (i * 32 + lrow) * LS + c * 16 + lg * 8);
 #pragma unroll
-            for (int t = 0; t < 2; ++t) fw[t] = __builtin_bit_cast(f16x8, rw[slot][t][c]);
+            for (int t = 0; t < NS; ++t) fw[t] = __builtin_bit_cast(f16x8, rw[slot][t][c]);
 #pragma unroll
-            for (int t = 0; t < 2; ++t)
+            for (int t = 0; t < NS; ++t)
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
                     acc[t][i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[i], fw[t], acc[t][i], 0, 0, 0);
         }
     };
 
-    const int nsteps = K / BK;
+    const int nsteps = kspan / BK;
 #pragma unroll
     for (int s = 0; s < D; ++s)
         if (s < nsteps) load_global(s, s * BK);
@@ -575,21 +585,22 @@ __global__ __launch_bounds__(256) void gemm_bf16_stream_kernel(GemmArgs g, int g
                 if (m < M && ncol[0] < N)
                     out[(long long)m * N + ncol[0]] = (f16)(silu_f(acc[0][i][r] * inv) * (acc[1][i][r] * inv));
             }
-    } else if constexpr (EPI == EPI_STORE_F32) {
+    } else if (EPI == EPI_STORE_F32 || g.ksplit > 1) {      // K slice: its own slab of raw products
+        float* __restrict__ C = g.ksplit > 1 ? (EPI == EPI_STORE_F32 ? g.Cf : g.split_ws) + (long long)kz * M * N : g.Cf;
 #pragma unroll
-        for (int t = 0; t < 2; ++t)
+        for (int t = 0; t < NS; ++t)
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int row = row_of(i, r), m = m0 + row;
                     const float inv = g.ssq ? s_inv[row] : 1.0f;
-                    if (m < M && ncol[t] < N) g.Cf[(long long)m * N + ncol[t]] = acc[t][i][r] * inv;
+                    if (m < M && ncol[t] < N) C[(long long)m * N + ncol[t]] = acc[t][i][r] * inv;
                 }
-    } else {                                                  // EPI_RESIDUAL; N % 32 == 0 (checked by the launcher)
+    } else if constexpr (TM % 2 == 0) {                      // EPI_RESIDUAL; N % 32 == 0 (checked by the launcher)
         f16* __restrict__ a16 = (f16*)g.C16;
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
+        for (int t = 0; t < NS; ++t) {
             const int n = min(ncol[t], N - 1);
             const float gain = g.gain_next ? (float)((const bf16*)g.gain_next)[n] : 0.f;
 #pragma unroll
@@ -919,6 +930,7 @@ static const int kForceNW = env_int("AX_SKINNY_NW", 0);   // experiment knob: wa
 
 // M > 64: LDS-staged tiles.
 static const int kStreamMinM = env_int("AX_STREAM_MIN_M", 1024);   // rows from which QKV / residual GEMMs stream their weights (0 = never)
+static const int kMidStream = env_int("AX_MID_STREAM", 1);   // experiment knob: 0 = tile kernels for 129-192 rows
 static const int kQkvTile = env_int("AX_QKV_TILE", -1);   // experiment knobs: force 64-row (0) or 128-row (1) blocks
 static const int kResTile = env_int("AX_RES_TILE", -1);
 static const int kResBig = env_int("AX_RES_BIG", 256);
@@ -943,6 +955,18 @@ static void launch_lds_tile(const GemmArgs& g, hipStream_t s) {
     const long long sblocks = (long long)((N + 255) / 256) * ((M + 127) / 128), rounds = (sblocks + 255) / 256;
     const bool stream = kStreamMinM > 0 && M >= kStreamMinM && N % 32 == 0 && sblocks >= 160 &&
                         (rounds == 1 || sblocks * 4 >= rounds * 256 * 3) && (EPI != EPI_RESIDUAL || K >= 8192);
+    // 129-192 rows (16 sessions verified together), residual GEMM with a long K (down projection):
+    // one 160- or 192-row streaming block per 128 columns reads every weight once (64-row tiles
+    // pull it three times out of L2) and K slices give the chip its ~200 blocks: ~3B down
+    // projection at M = 144 36 -> 27 us.  With the shorter K of the QKV and O projections the
+    // slices are too short for a kernel with one wavefront per SIMD (QKV 24 -> 29 us): tile kernels.
+    const int mid_cb = (N + 127) / 128;
+    int mid_ks = 1;
+    if (EPI == EPI_RESIDUAL && kMidStream && M > 128 && M <= 192 && K >= 8192 && N % 64 == 0 && g.split_ws)
+        for (int ks : {8, 6, 4, 3, 2})
+            if (mid_ks == 1 && mid_cb * ks <= 288 && K % (ks * 64) == 0 && K / (ks * 64) >= 4 &&
+                (size_t)ks * 2 * M * N * sizeof(float) <= g.split_ws_bytes)
+                mid_ks = ks;
     if constexpr (EPI == EPI_QKV) {
         if (stream && (size_t)M * N * sizeof(float) <= g.split_ws_bytes) {
             GemmArgs gs = g;
@@ -982,6 +1006,14 @@ static void launch_lds_tile(const GemmArgs& g, hipStream_t s) {
         qkv_reduce_rope_kernel<<<dim3((unsigned)M, (unsigned)((N / 2 + 255) / 256)), 256, 0, s>>>(gs);
         return;
     } else if constexpr (EPI == EPI_RESIDUAL) {
+        if (mid_ks > 1) {
+            GemmArgs gs = g;
+            gs.ksplit = mid_ks;
+            if (M <= 160) gemm_bf16_stream_kernel<EPI_RESIDUAL, 5, 3, 1><<<mid_cb * mid_ks, 256, 0, s>>>(gs, mid_cb, 1);
+            else gemm_bf16_stream_kernel<EPI_RESIDUAL, 6, 3, 1><<<mid_cb * mid_ks, 256, 0, s>>>(gs, mid_cb, 1);
+            residual_reduce_kernel<<<(unsigned)(((long long)M * (N / 64) + 3) / 4), 256, 0, s>>>(gs);
+            return;
+        }
         if (stream) {
             const int gx = (N + 255) / 256, gy = (M + 127) / 128;
             gemm_bf16_stream_kernel<EPI_RESIDUAL, 4, 3><<<gx * gy, 256, 0, s>>>(g, gx, gy);
@@ -1026,6 +1058,13 @@ static void launch_lds_tile(const GemmArgs& g, hipStream_t s) {
         }
     }
     if constexpr (EPI == EPI_STORE_F32 || EPI == EPI_SWIGLU) {
+        if (EPI == EPI_STORE_F32 && M > 128 && M <= 160 && N >= 256 * 256 && N % 32 == 0) {
+            // logits of 129-160 rows (batched verify of 16 sessions): one 160-row block per 256
+            // columns reads the weights once, where 64-row tiles pull them three times out of L2
+            const int gx = (N + 255) / 256;
+            gemm_bf16_stream_kernel<EPI_STORE_F32, 5, 3><<<gx, 256, 0, s>>>(g, gx, 1);
+            return;
+        }
         if (EPI == EPI_STORE_F32 && stream) {              // logits of thousands of rows
             const int gx = (N + 255) / 256, gy = (M + 127) / 128;
             gemm_bf16_stream_kernel<EPI_STORE_F32, 4, 3><<<gx * gy, 256, 0, s>>>(g, gx, gy);

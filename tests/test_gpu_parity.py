@@ -241,8 +241,10 @@ def test_prefix_reuse_fork_cow_and_rollback(B, which):
     dm.close()
 
 
+# 113, 143 and 180 rows in all: row counts on both sides of the 128-row block shapes
+@pytest.mark.parametrize("T_each", [[33, 1, 70, 9], [33, 1, 100, 9], [60, 1, 110, 9]], ids=["113rows", "143rows", "180rows"])
 @pytest.mark.parametrize("which", ["bf16-hd64-g4", "bf16-hd128-g3", "f32-hd32"])
-def test_batched_mixed_length_equals_separate(B, which):
+def test_batched_mixed_length_equals_separate(B, which, T_each):
     """Several sessions with different cached lengths and different T in one pass, sharing a
     forked prefix, against the oracle and against one-at-a-time calls."""
     sh = SMALL[which]
@@ -251,7 +253,7 @@ def test_batched_mixed_length_equals_separate(B, which):
     dm = B.DeviceModel(sh, w, max_pos=512, max_tokens=256, pool_tokens=4096, max_seqs=4)
     root = dm.new_kv()
     dm.extend(root, prefix)
-    hist_len, T_each = [0, 19, 40, 5], [33, 1, 70, 9]
+    hist_len = [0, 19, 40, 5]
     kvs, refs, news = [], [], []
     for s in range(4):
         kv = B.ax_kv_fork(root, 72 if s != 2 else 50)             # one session shares less
@@ -682,6 +684,17 @@ def test_full_width_3b_batched_sessions(B):
         pend[s] = O.argmax_lowest(ref[-1])
     total, exempt = _batched_rounds(B, dm, sh, w, kvs, refs, pend, 2, lambda r, s: 8, 5005)
     print("3b batched: accepted", total, "exempt", exempt)
+    # 155 rows in one pass: the row count of 16 sessions verified together (160-row blocks, K slices
+    # in the down projection, 160-row blocks in the LM head when all logits are asked for)
+    more = [I.zipf_tokens(sh.vocab, 5005, f"m{s}", t) for s, t in enumerate([40, 50, 30, 35])]
+    for kv, ref in zip(kvs, refs):
+        assert B.ax_kv_len(kv) == len(ref)
+    got = dm.extend_batch(kvs, more, B.AX_OUT_ALL_LOGITS).cpu().numpy()
+    at = 0
+    for s in range(4):
+        ref = O.forward(sh, w, more[s], refs[s])
+        check_logits(sh, got[at:at + len(more[s])], ref, f"3b session {s}, 155-row pass")
+        at += len(more[s])
     for kv in kvs + [root]:
         B.ax_kv_free(kv)
     dm.close()
