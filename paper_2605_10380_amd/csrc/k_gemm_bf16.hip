@@ -930,6 +930,7 @@ static const int kForceNW = env_int("AX_SKINNY_NW", 0);   // experiment knob: wa
 
 // M > 64: LDS-staged tiles.
 static const int kStreamMinM = env_int("AX_STREAM_MIN_M", 1024);   // rows from which QKV / residual GEMMs stream their weights (0 = never)
+static const int kSliceStream = env_int("AX_SLICE_STREAM", 1);   // experiment knob
 static const int kMidStream = env_int("AX_MID_STREAM", 1);   // experiment knob: 0 = tile kernels for 129-192 rows
 static const int kQkvTile = env_int("AX_QKV_TILE", -1);   // experiment knobs: force 64-row (0) or 128-row (1) blocks
 static const int kResTile = env_int("AX_RES_TILE", -1);
@@ -1018,6 +1019,25 @@ static void launch_lds_tile(const GemmArgs& g, hipStream_t s) {
             const int gx = (N + 255) / 256, gy = (M + 127) / 128;
             gemm_bf16_stream_kernel<EPI_RESIDUAL, 4, 3><<<gx * gy, 256, 0, s>>>(g, gx, gy);
             return;
+        }
+        // a few hundred rows against the long K of the down projection: too few 128 x 256 blocks for
+        // the streaming kernel as it is, enough once K is cut into 2-4 slices (160-256 blocks).
+        // Against the tile kernel: ~8B 85 -> 71 us at M = 384, 145 -> 118 at 768, 145 -> 131 at 1024;
+        // ~3B 58 -> 50 at 512, 93 -> 78 at 1024; ~1B 57 -> 49 at 768.
+        if (kSliceStream && M >= 384 && K >= 8192 && N % 64 == 0 && g.split_ws) {
+            int ks = 1;
+            for (int c : {4, 3, 2})                        // one block per CU at a time: at most 256 blocks
+                if (ks == 1 && sblocks * c <= 256 && K % (c * 64) == 0 && K / (c * 64) >= 16 &&
+                    (size_t)c * 2 * M * N * sizeof(float) <= g.split_ws_bytes)
+                    ks = c;
+            if (ks > 1 && sblocks * ks >= 160) {
+                GemmArgs gs = g;
+                gs.ksplit = ks;
+                const int gx = (N + 255) / 256, gy = (M + 127) / 128;
+                gemm_bf16_stream_kernel<EPI_RESIDUAL, 4, 3><<<gx * gy * ks, 256, 0, s>>>(gs, gx, gy);
+                residual_reduce_kernel<<<(unsigned)(((long long)M * (N / 64) + 3) / 4), 256, 0, s>>>(gs);
+                return;
+            }
         }
         // Few output tiles (M = 256 against N = 2048 is 64 tiles of 64 x 128 for 256 CUs): cut K
         // until there are ~256 blocks, each still with 8 or more k-steps; fp32 partial slabs go to
