@@ -459,7 +459,7 @@ __global__ __launch_bounds__(256) void qkv_reduce_rope_kernel(GemmArgs g) {
 // slices over extra blocks whose raw fp32 partial products go to slabs that qkv_reduce_rope_kernel /
 // residual_reduce_kernel add up: calls of 129-192 rows (16 sessions verified together), where one
 // 160- or 192-row block reads each weight once and the slices give the chip its ~200 blocks.
-template <int EPI, int TM, int D, int NS = 2>
+template <int EPI, int TM, int D, int NS = 2, bool SLICED = false>
 __global__ __launch_bounds__(256) void gemm_bf16_stream_kernel(GemmArgs g, int gx, int gy) {
     static_assert(EPI != EPI_SWIGLU || NS == 2, "SwiGLU streams gate and up");
     constexpr int BM = TM * 32, BN = EPI == EPI_SWIGLU ? 128 : NS * 128, BK = 64, LS = BK + 8;
@@ -477,7 +477,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_stream_kernel(GemmArgs g, int g
     if ((nblk & 7) == 0) bid = (bid & 7) * (nblk >> 3) + (bid >> 3);
     const int bx = bid / gy, by = bid - bx * gy;
     const int m0 = by * BM, n0 = bx * BN;
-    const int kspan = g.ksplit > 1 ? K / g.ksplit : K, kbase = kz * kspan;
+    const int kspan = SLICED ? K / g.ksplit : K, kbase = kz * kspan;      // SLICED: g.ksplit > 1 slices, a slab each
 
     // this lane's output columns = weight rows of its two streams: row n of W and of W2 (SwiGLU),
     // or rows n and n + 32 of W
@@ -585,8 +585,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_stream_kernel(GemmArgs g, int g
                 if (m < M && ncol[0] < N)
                     out[(long long)m * N + ncol[0]] = (f16)(silu_f(acc[0][i][r] * inv) * (acc[1][i][r] * inv));
             }
-    } else if (EPI == EPI_STORE_F32 || g.ksplit > 1) {      // K slice: its own slab of raw products
-        float* __restrict__ C = g.ksplit > 1 ? (EPI == EPI_STORE_F32 ? g.Cf : g.split_ws) + (long long)kz * M * N : g.Cf;
+    } else if constexpr (EPI == EPI_STORE_F32 || SLICED) {  // K slice: its own slab of raw products
+        float* __restrict__ C = SLICED ? (EPI == EPI_STORE_F32 ? g.Cf : g.split_ws) + (long long)kz * M * N : g.Cf;
 #pragma unroll
         for (int t = 0; t < NS; ++t)
 #pragma unroll
@@ -597,7 +597,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_stream_kernel(GemmArgs g, int g
                     const float inv = g.ssq ? s_inv[row] : 1.0f;
                     if (m < M && ncol[t] < N) C[(long long)m * N + ncol[t]] = acc[t][i][r] * inv;
                 }
-    } else if constexpr (TM % 2 == 0) {                      // EPI_RESIDUAL; N % 32 == 0 (checked by the launcher)
+    } else {                                                  // EPI_RESIDUAL; N % 32 == 0 (checked by the launcher)
+        static_assert(TM % 2 == 0, "the residual epilogue works on pairs of row tiles");
         f16* __restrict__ a16 = (f16*)g.C16;
 #pragma unroll
         for (int t = 0; t < NS; ++t) {
@@ -1010,8 +1011,8 @@ static void launch_lds_tile(const GemmArgs& g, hipStream_t s) {
         if (mid_ks > 1) {
             GemmArgs gs = g;
             gs.ksplit = mid_ks;
-            if (M <= 160) gemm_bf16_stream_kernel<EPI_RESIDUAL, 5, 3, 1><<<mid_cb * mid_ks, 256, 0, s>>>(gs, mid_cb, 1);
-            else gemm_bf16_stream_kernel<EPI_RESIDUAL, 6, 3, 1><<<mid_cb * mid_ks, 256, 0, s>>>(gs, mid_cb, 1);
+            if (M <= 160) gemm_bf16_stream_kernel<EPI_RESIDUAL, 5, 3, 1, true><<<mid_cb * mid_ks, 256, 0, s>>>(gs, mid_cb, 1);
+            else gemm_bf16_stream_kernel<EPI_RESIDUAL, 6, 3, 1, true><<<mid_cb * mid_ks, 256, 0, s>>>(gs, mid_cb, 1);
             residual_reduce_kernel<<<(unsigned)(((long long)M * (N / 64) + 3) / 4), 256, 0, s>>>(gs);
             return;
         }
@@ -1034,7 +1035,7 @@ static void launch_lds_tile(const GemmArgs& g, hipStream_t s) {
                 GemmArgs gs = g;
                 gs.ksplit = ks;
                 const int gx = (N + 255) / 256, gy = (M + 127) / 128;
-                gemm_bf16_stream_kernel<EPI_RESIDUAL, 4, 3><<<gx * gy * ks, 256, 0, s>>>(gs, gx, gy);
+                gemm_bf16_stream_kernel<EPI_RESIDUAL, 4, 3, 2, true><<<gx * gy * ks, 256, 0, s>>>(gs, gx, gy);
                 residual_reduce_kernel<<<(unsigned)(((long long)M * (N / 64) + 3) / 4), 256, 0, s>>>(gs);
                 return;
             }
