@@ -1233,11 +1233,25 @@ ax_status ax_dbg_gemm(int dtype, int epilogue, const void* A, const void* W, con
             ax::launch_pack_weights(W2, pw2, N, K, s);
         }
     }
-    ax::launch_gemm(dtype == AX_F32 ? ax::F32 : ax::BF16, (ax::Epilogue)epilogue, A, pw ? pw : W, pw2 ? pw2 : W2, C, M, N, K, s);
+    void* scratch = nullptr;
+    if (dtype == AX_BF16 && epilogue == 2 && M > 128 && M <= 192) {
+        // the row counts at which the SwiGLU GEMM may cut K into slices: give it the slab scratch a model's workspace has
+        const size_t bytes = (size_t)ax::SPLITK_MAX * 2 * M * N * sizeof(float);
+        if (hipMalloc(&scratch, bytes) != hipSuccess) scratch = nullptr;
+        ax::GemmArgs g{};
+        g.A = A; g.W = pw; g.W2 = pw2; g.M = M; g.N = N; g.K = K;
+        g.Cf = (float*)C; g.C16 = C;
+        g.split_ws = (float*)scratch;
+        g.split_ws_bytes = scratch ? bytes : 0;
+        ax::launch_gemm_bf16(ax::EPI_SWIGLU, g, s);
+    } else {
+        ax::launch_gemm(dtype == AX_F32 ? ax::F32 : ax::BF16, (ax::Epilogue)epilogue, A, pw ? pw : W, pw2 ? pw2 : W2, C, M, N, K, s);
+    }
     hipError_t e = hipGetLastError();
     if (e == hipSuccess) e = hipStreamSynchronize(s);
     if (pw) (void)hipFree(pw);
     if (pw2) (void)hipFree(pw2);
+    if (scratch) (void)hipFree(scratch);
     if (e != hipSuccess) return fail(AX_ERR_DEVICE, "debug GEMM: %s", hipGetErrorString(e));
     return AX_OK;
 }

@@ -436,6 +436,32 @@ __global__ __launch_bounds__(256) void qkv_reduce_rope_kernel(GemmArgs g) {
     }
 }
 
+// Second half of a K-sliced SwiGLU GEMM: out[m, n] = fp16(silu(gate * inv) * (up * inv)) with gate
+// and up the sums of the slices' raw products (slabs [ksplit][M][2 N]: gate | up) and inv the row's
+// 1 / rms.  grid (rows, ceil(N / 256)).
+__global__ __launch_bounds__(256) void swiglu_reduce_kernel(GemmArgs g) {
+    __shared__ float s_inv;
+    const int m = blockIdx.x, N = g.N, n = blockIdx.y * 256 + threadIdx.x;
+    const long long slab = (long long)g.M * 2 * N;
+    const float* p = g.split_ws + (long long)m * 2 * N + min(n, N - 1);
+    float pa[SPLITK_MAX], pb[SPLITK_MAX];
+#pragma unroll
+    for (int ks = 0; ks < SPLITK_MAX; ++ks) {
+        pa[ks] = ks < g.ksplit ? p[ks * slab] : 0.f;
+        pb[ks] = ks < g.ksplit ? p[ks * slab + N] : 0.f;
+    }
+    if (threadIdx.x < 64) {
+        const float inv = g.ssq ? wave_inv_rms(g.ssq, g.a_rows ? g.a_rows[m] : m, g.nparts, g.d_norm, g.eps, threadIdx.x) : 1.0f;
+        if (threadIdx.x == 0) s_inv = inv;
+    }
+    __syncthreads();
+    if (n >= N) return;
+    float a = 0.f, b = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < SPLITK_MAX; ++ks) { a += pa[ks]; b += pb[ks]; }
+    ((f16*)g.C16)[(long long)m * N + n] = (f16)(silu_f(a * s_inv) * (b * s_inv));
+}
+
 // ------------------------------------------------------------------------------ stream SwiGLU kernel
 // SwiGLU gate/up GEMM for M >= 384.  The LDS-staged kernel above moves both operands through
 // LDS and spends more cycles there than on the matrix cores (a 32 x 64 wavefront tile reads
@@ -543,7 +569,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_stream_kernel(GemmArgs g, int g
 #pragma unroll
     for (int s = 0; s < D; ++s)
         if (s < nsteps) load_global(s, s * BK);
-    if (g.ssq) block_inv_rms(g, m0, BM, s_inv);
+    if (g.ssq && !(EPI == EPI_SWIGLU && SLICED)) block_inv_rms(g, m0, BM, s_inv);    // sliced SwiGLU: the reduce kernel scales
     store_lds(0, 0);
     __syncthreads();
     // steady state, branch free: multiply step s out of ring slot s % D and LDS buffer s % 2,
@@ -574,7 +600,18 @@ __global__ __launch_bounds__(256) void gemm_bf16_stream_kernel(GemmArgs g, int g
     }
 
     auto row_of = [&](int i, int r) { return i * 32 + (r >> 2) * 8 + lg * 4 + (r & 3); };
-    if constexpr (EPI == EPI_SWIGLU) {
+    if constexpr (EPI == EPI_SWIGLU && SLICED) {             // raw gate | up products of this K slice: slab [M][2 N]
+        float* __restrict__ C = g.split_ws + (long long)kz * M * 2 * N;
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int m = m0 + row_of(i, r);
+                    if (m < M && ncol[0] < N) C[(long long)m * 2 * N + t * N + ncol[0]] = acc[t][i][r];
+                }
+    } else if constexpr (EPI == EPI_SWIGLU) {
         f16* __restrict__ out = (f16*)g.C16;
 #pragma unroll
         for (int i = 0; i < TM; ++i)
@@ -1070,6 +1107,25 @@ static void launch_lds_tile(const GemmArgs& g, hipStream_t s) {
         if (ks > 1) residual_reduce_kernel<<<(unsigned)(((long long)M * (N / 64) + 3) / 4), 256, 0, s>>>(gs);
         return;
     } else if constexpr (EPI == EPI_SWIGLU) {
+        // 129-192 rows: 160- or 192-row streaming blocks over K slices (raw gate | up products in
+        // slabs, swiglu_reduce_kernel finishes): every weight is read once where the 128 x 64 tiles
+        // below pull it twice out of L2
+        if (kMidStream && M > 128 && M <= 192 && g.split_ws) {
+            const int cb = (N + 127) / 128;
+            int ks = 1;
+            for (int c : {8, 6, 4, 3, 2})
+                if (ks == 1 && cb * c <= 288 && K % (c * 64) == 0 && K / (c * 64) >= 6 &&
+                    (size_t)c * 2 * M * N * sizeof(float) <= g.split_ws_bytes)
+                    ks = c;
+            if (ks > 1 && cb * ks >= 128) {
+                GemmArgs gs = g;
+                gs.ksplit = ks;
+                if (M <= 160) gemm_bf16_stream_kernel<EPI_SWIGLU, 5, 3, 2, true><<<cb * ks, 256, 0, s>>>(gs, cb, 1);
+                else gemm_bf16_stream_kernel<EPI_SWIGLU, 6, 3, 2, true><<<cb * ks, 256, 0, s>>>(gs, cb, 1);
+                swiglu_reduce_kernel<<<dim3((unsigned)M, (unsigned)((N + 255) / 256)), 256, 0, s>>>(gs);
+                return;
+            }
+        }
         // gate/up with two or more 128-row tiles: 128 x 64 tiles make a CU pull (128 + 2 * 64) rows of
         // operands per k instead of (64 + 2 * 128) for the same number of blocks (2-3 % faster)
         if (M > 128) {

@@ -27,7 +27,8 @@ GEMM_CASES = [(1, 64, 64), (9, 3072, 2048), (9, 2048, 8192), (17, 512, 256), (33
               (400, 1040, 1024), (384, 2048, 576),
               # thousands of rows: every epilogue through the streaming kernel (ragged rows and columns, drain path)
               (1600, 7712, 192), (1664, 7680, 448),
-              (144, 65600, 128), (131, 65536, 192)]            # 160-row streaming blocks for wide outputs
+              (144, 65600, 128), (131, 65536, 192),            # 160-row streaming blocks for wide outputs
+              (144, 8192, 3072), (190, 4096, 1536), (150, 4112, 1536)]  # 129-192 rows: SwiGLU over K slices (160- / 192-row blocks)
 
 
 @pytest.mark.parametrize("M,N,K", GEMM_CASES)
