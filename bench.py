@@ -107,7 +107,13 @@ def cpu_oracle_baseline(torch, shape, w_dev, prompt, P, T, layers=8, reps=3):
     except Exception:
         cores = os.cpu_count() or 1
     scale = shape.n_layers / layers
-    return {"value": T / (t_ext * scale), "unit": "extend tok/s", "cores": int(cores), "kind": "oracle",
+    cpu_model = "unknown"
+    try:
+        with open("/proc/cpuinfo") as f:
+            cpu_model = next((ln.split(":", 1)[1].strip() for ln in f if ln.startswith("model name")), "unknown")
+    except OSError:
+        pass
+    return {"value": T / (t_ext * scale), "unit": "extend tok/s", "cores": int(cores), "kind": "oracle", "cpu": cpu_model,
             "sample": f"float64 numpy oracle, first {layers} of {shape.n_layers} layers at full width, "
                       f"P={P}, {reps} extends of T={T} took {t_ext:.2f} s each (mean); rate scaled by {layers}/{shape.n_layers}"}
 
@@ -230,6 +236,8 @@ def main():
                     help="also run a plain 256 MiB copy kernel three times (known traffic, for scaling "
                          "hardware-counter readings taken under rocprofv3 --pmc)")
     ap.add_argument("--seed", type=int, default=2000)
+    ap.add_argument("--extend-T", type=int, default=0, help="override the workload's T (the configurations list several for config 3)")
+    ap.add_argument("--verify-k", type=int, default=-1, help="override the workload's draft count k")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (sessions would shard across GPUs with no "
@@ -246,11 +254,15 @@ def main():
         return
     wl = I.WORKLOADS[args.workload]
     sh, P, T, k, rounds = wl.shape, wl.P, wl.T, wl.k, wl.rounds
+    if args.extend_T > 0:
+        T = args.extend_T
+    if args.verify_k >= 0:
+        k = args.verify_k
     dev = torch.device("cuda:0")
     w = torch_weights(torch, sh, args.seed, dev)
     prompt = I.templated_prompt(sh.vocab, args.seed, P + T)
     max_pos = P + T + rounds * (k + 1) + 64
-    dm = B.DeviceModel(sh, w, max_pos=max_pos, max_tokens=512, pool_tokens=max_pos + 64 + P + 16)
+    dm = B.DeviceModel(sh, w, max_pos=max_pos, max_tokens=max(512, T), pool_tokens=max_pos + 64 + P + 16)
     kv = dm.new_kv()
     torch.cuda.synchronize()
     t_prefill = time.perf_counter()
@@ -300,6 +312,9 @@ def main():
 
     ext_ms = float(np.mean([t[0] for t in timers]))
     ver_ms = float(np.mean([t[1] for t in timers])) / rounds
+    ext_all = sorted(t[0] for t in timers)
+    ver_all = sorted(t[1] / rounds for t in timers)
+    emitted_per_s = sum(t[2] + rounds for t in timers) / (sum(t[1] for t in timers) * 1e-3)   # accepted drafts + one token per round
     alg = algorithmic(sh, P, T, k)
 
     # per-kernel timing with HIP events, on extra steps outside the timed region
@@ -395,6 +410,11 @@ def main():
         "verify_gbs": round(alg["verify_bytes"] / (ver_ms * 1e-3) / 1e9, 1),
         "verify_frac_of_hbm_peak": round(alg["verify_bytes"] / (ver_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
         "accepted_drafts_per_step": float(np.mean([t[2] for t in timers])),
+        "extend_ms_median_min": [round(ext_all[len(ext_all) // 2], 4), round(ext_all[0], 4)],
+        "verify_ms_per_step_median_min": [round(ver_all[len(ver_all) // 2], 4), round(ver_all[0], 4)],
+        "verify_emitted_tokens_per_s": round(emitted_per_s, 1),
+        "extend_frac_of_measured_mfma": None if args.calibrate_copy else round(alg["extend_flops"] / (ext_ms * 1e-3) / 1e12 / mfma_tf, 4),
+        "verify_frac_of_measured_hbm_read": None if args.calibrate_copy else round(alg["verify_bytes"] / (ver_ms * 1e-3) / 1e9 / read_gbs, 4),
         "roofline": kernel_roofline(main_tag, dominant[main_tag]),
         "roofline_extend": kernel_roofline("extend", dominant["extend"]),
         "roofline_verify": kernel_roofline("verify", dominant["verify"]),

@@ -24,7 +24,8 @@ ax_status ax_dbg_gemm(int dtype, int epilogue, const void *A, const void *W, con
  * updated in place) += A[M,K] W[N,K]^T, then a16[M,N] = fp16(x * gain[n]) and per-row partial sums
  * of x^2: ssq[m * (*n_parts) + p], p < *n_parts (written by the call; at most N / 8), whose sum
  * over p is sum_n x[m,n]^2.  A fp16, W and gain bf16, all device memory; ssq must hold M * N / 8
- * floats.  split_ws / split_ws_bytes: device scratch for K-slice partial products (the launcher
+ * floats.  K % 64 == 0, N % 16 == 0, and N % 32 == 0 with more than 16 rows (N is a model width there).
+ * split_ws / split_ws_bytes: device scratch for K-slice partial products (the launcher
  * cuts K only when scratch is given and it pays); 0 bytes = never.  Synchronises. */
 ax_status ax_dbg_gemm_residual(const void *A, const void *W, const void *gain, float *x, void *a16, float *ssq,
                                int *n_parts, int M, int N, int K, void *split_ws, size_t split_ws_bytes,

@@ -447,7 +447,8 @@ ax_status enqueue_call(ax_model* m, const CallPlan& cp, void* out, hipStream_t s
         // writes x (gain-scaled fp16 copy + per-row partial sums of x^2) and the GEMM that reads
         // it (1/rms in the epilogue); rotary embedding and the KV append live in the QKV epilogue.
         float* ssq = (float*)(ws + L.ssq);
-        const int nparts = ax::gemm_ssq_parts(R, d_model);
+        // partial sums of x^2 per row: as many as the GEMM that wrote x produces (O projection / down projection)
+        const int nparts_o = ax::gemm_ssq_parts(R, d_model, qdim), nparts = ax::gemm_ssq_parts(R, d_model, c.d_ff);
         ax::GemmArgs base{};
         base.M = R;
         base.split_ws = (float*)(ws + L.splitk);
@@ -478,6 +479,7 @@ ax_status enqueue_call(ax_model* m, const CallPlan& cp, void* out, hipStream_t s
             {
                 ax::GemmArgs g = base;
                 normed(g);
+                g.nparts = nparts_o;
                 g.W = m->w_gate[(size_t)l]; g.W2 = m->w_up[(size_t)l]; g.N = c.d_ff; g.C16 = ffn;
                 ProfScope ps(m, 3, stream);
                 ax::launch_gemm_bf16(ax::EPI_SWIGLU, g, stream);
@@ -1234,7 +1236,7 @@ ax_status ax_dbg_gemm(int dtype, int epilogue, const void* A, const void* W, con
         }
     }
     void* scratch = nullptr;
-    if (dtype == AX_BF16 && epilogue == 2 && M > 128 && M <= 192) {
+    if (dtype == AX_BF16 && epilogue == 2 && M > 16 && M <= 192) {
         // the row counts at which the SwiGLU GEMM may cut K into slices: give it the slab scratch a model's workspace has
         const size_t bytes = (size_t)ax::SPLITK_MAX * 2 * M * N * sizeof(float);
         if (hipMalloc(&scratch, bytes) != hipSuccess) scratch = nullptr;
@@ -1262,6 +1264,7 @@ ax_status ax_dbg_gemm_residual(const void* A, const void* W, const void* gain, f
     if (!A || !W || !gain || !x || !a16 || !ssq || !n_parts || M <= 0 || N <= 0 || K <= 0 || (split_ws_bytes && !split_ws))
         return fail(AX_ERR_INVALID, "bad argument");
     if (K % 64 != 0 || N % 16 != 0) return fail(AX_ERR_UNSUPPORTED, "bf16 needs K %% 64 == 0, N %% 16 == 0");
+    if (M > 16 && N % 32 != 0) return fail(AX_ERR_UNSUPPORTED, "more than 16 rows need N %% 32 == 0 (N is a model width)");
     hipStream_t s = (hipStream_t)hip_stream;
     void* pw = nullptr;
     HIP_TRY(hipMalloc(&pw, (size_t)N * K * 2));
@@ -1271,7 +1274,7 @@ ax_status ax_dbg_gemm_residual(const void* A, const void* W, const void* gain, f
     g.Cf = x; g.C16 = a16; g.gain_next = gain; g.ssq_out = ssq;
     g.split_ws = split_ws_bytes ? (float*)split_ws : nullptr;
     g.split_ws_bytes = split_ws_bytes;
-    *n_parts = ax::gemm_ssq_parts(M, N);
+    *n_parts = ax::gemm_ssq_parts(M, N, K);
     ax::launch_gemm_bf16(ax::EPI_RESIDUAL, g, s);
     hipError_t e = hipGetLastError();
     if (e == hipSuccess) e = hipStreamSynchronize(s);

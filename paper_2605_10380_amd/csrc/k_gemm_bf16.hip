@@ -6,10 +6,10 @@
 // bf16 one.  Reason: bf16 activations (8 significant bits) put the logits of a 16-layer decoder
 // ~0.05 away from the exact result; fp16 activations (11 bits) keep them within 0.01.
 //
-//   * skinny kernel (M <= 64, verify steps: pure weight streaming): one block owns 16 output
+//   * skinny kernel (M <= 16, the O projection and logits to 32: verify steps, pure weight streaming): one block owns 16 output
 //     columns, its wavefronts split K, W goes HBM -> registers -> v_mfma_f32_16x16x32_f16
 //     with no LDS in the streaming loop; the per-wavefront partial sums meet in LDS.
-//   * tile kernel   (M > 64): 8 wavefronts, LDS-staged 64 x 128 x 64 tiles,
+//   * tile kernel   (more rows): 8 wavefronts, LDS-staged 64 x 128 x 64 tiles,
 //     v_mfma_f32_32x32x16_f16, global loads several K slices ahead.
 //   * stream kernel (SwiGLU, M >= 384): activations through LDS, weights straight into MFMA operands.
 //
@@ -964,9 +964,10 @@ static int env_int(const char* name, int dflt) {
     const char* v = std::getenv(name);
     return v && *v ? std::atoi(v) : dflt;
 }
+static const int kSkinnyMaxM = std::min(32, env_int("AX_SKINNY_MAX_M", 32));   // experiment knob: rows up to which the skinny kernel may run
 static const int kForceNW = env_int("AX_SKINNY_NW", 0);   // experiment knob: wavefronts per block, 0 = automatic
 
-// M > 64: LDS-staged tiles.
+// More rows: LDS-staged tiles.
 static const int kStreamMinM = env_int("AX_STREAM_MIN_M", 1024);   // rows from which QKV / residual GEMMs stream their weights (0 = never)
 static const int kSliceStream = env_int("AX_SLICE_STREAM", 1);   // experiment knob
 static const int kMidStream = env_int("AX_MID_STREAM", 1);   // experiment knob: 0 = tile kernels for 129-192 rows
@@ -1107,10 +1108,13 @@ static void launch_lds_tile(const GemmArgs& g, hipStream_t s) {
         if (ks > 1) residual_reduce_kernel<<<(unsigned)(((long long)M * (N / 64) + 3) / 4), 256, 0, s>>>(gs);
         return;
     } else if constexpr (EPI == EPI_SWIGLU) {
-        // 129-192 rows: 160- or 192-row streaming blocks over K slices (raw gate | up products in
-        // slabs, swiglu_reduce_kernel finishes): every weight is read once where the 128 x 64 tiles
-        // below pull it twice out of L2
-        if (kMidStream && M > 128 && M <= 192 && g.split_ws) {
+        // 17-192 rows: one streaming block of all the rows (32 to 192) per 128 columns, over K slices
+        // (raw gate | up products in slabs, swiglu_reduce_kernel finishes): every weight is read
+        // once and the slices give the chip ~256 blocks, where the tile kernels have 64 blocks (up
+        // to 64 rows: no K slices for two products) or pull every weight twice out of L2, and the
+        // skinny kernel re-reads its activations per 16 columns.  ~3B shape: 33 -> 26 us at 32 rows,
+        // 48 -> 28 us at 64 rows, 49 -> 42 us at 144 rows; ~8B: 72 -> 48 us at 32-48 rows.
+        if (kMidStream && M > 16 && M <= 192 && g.split_ws) {
             const int cb = (N + 127) / 128;
             int ks = 1;
             for (int c : {8, 6, 4, 3, 2})
@@ -1120,8 +1124,15 @@ static void launch_lds_tile(const GemmArgs& g, hipStream_t s) {
             if (ks > 1 && cb * ks >= 128) {
                 GemmArgs gs = g;
                 gs.ksplit = ks;
-                if (M <= 160) gemm_bf16_stream_kernel<EPI_SWIGLU, 5, 3, 2, true><<<cb * ks, 256, 0, s>>>(gs, cb, 1);
-                else gemm_bf16_stream_kernel<EPI_SWIGLU, 6, 3, 2, true><<<cb * ks, 256, 0, s>>>(gs, cb, 1);
+                const unsigned nb = (unsigned)(cb * ks);
+                switch ((M + 31) / 32) {
+                    case 1: gemm_bf16_stream_kernel<EPI_SWIGLU, 1, 3, 2, true><<<nb, 256, 0, s>>>(gs, cb, 1); break;
+                    case 2: gemm_bf16_stream_kernel<EPI_SWIGLU, 2, 3, 2, true><<<nb, 256, 0, s>>>(gs, cb, 1); break;
+                    case 3: gemm_bf16_stream_kernel<EPI_SWIGLU, 3, 3, 2, true><<<nb, 256, 0, s>>>(gs, cb, 1); break;
+                    case 4: gemm_bf16_stream_kernel<EPI_SWIGLU, 4, 3, 2, true><<<nb, 256, 0, s>>>(gs, cb, 1); break;
+                    case 5: gemm_bf16_stream_kernel<EPI_SWIGLU, 5, 3, 2, true><<<nb, 256, 0, s>>>(gs, cb, 1); break;
+                    default: gemm_bf16_stream_kernel<EPI_SWIGLU, 6, 3, 2, true><<<nb, 256, 0, s>>>(gs, cb, 1); break;
+                }
                 swiglu_reduce_kernel<<<dim3((unsigned)M, (unsigned)((N + 255) / 256)), 256, 0, s>>>(gs);
                 return;
             }
@@ -1152,10 +1163,23 @@ static void launch_lds_tile(const GemmArgs& g, hipStream_t s) {
     }
 }
 
+// Which rows go to the skinny kernel: a block of it re-reads the whole activation slice of its
+// wavefronts (M x K / NW fp16) per 8-16 columns, so its time grows with M while one 64-row tile
+// costs the same for any M <= 64.  Measured crossovers (all three model shapes): every GEMM is
+// faster on the other kernels from 33 rows up (64 rows of the ~3B shape: 172 -> 114 us per layer);
+// from 17 rows up the QKV GEMM and the residual GEMM with the long K (down projection) are too
+// (~3B at 17-32 rows: 18-22 -> 17-19 us and 18-23 -> 15-16 us) and so is the SwiGLU GEMM on its
+// K-sliced streaming blocks (see launch_lds_tile); the O projection is not.
+static bool use_skinny(int epi, int M, int N, int K) {
+    if (M <= 16) return true;
+    if (M > kSkinnyMaxM) return false;
+    return !(epi == EPI_QKV || epi == EPI_SWIGLU || (epi == EPI_RESIDUAL && K >= 2 * N));
+}
+
 template <int EPI>
 static void launch_bf16(const GemmArgs& g, hipStream_t s) {
     const int M = g.M, N = g.N, K = g.K;
-    if (M <= 64) {
+    if (use_skinny(EPI, M, N, K)) {
         // wavefronts per block (= K slices): enough to keep ~2k wavefronts in flight, each with
         // at least 128 of K; K / nw must stay a multiple of the MFMA k (32)
         const int cols = skinny_cols(EPI, N);
@@ -1165,8 +1189,7 @@ static void launch_bf16(const GemmArgs& g, hipStream_t s) {
         if (kForceNW && K % (kForceNW * 32) == 0) nw = kForceNW;
         if (EPI == EPI_SWIGLU && nw == 16) nw = 8;        // LDS reduction buffer stays <= 64 KB
         if (M <= 16) launch_skinny_nw<EPI, 1>(g, nw, s);
-        else if (M <= 32) launch_skinny_nw<EPI, 2>(g, nw, s);
-        else launch_skinny_nw<EPI, 4>(g, nw == 16 ? 8 : nw, s);
+        else launch_skinny_nw<EPI, 2>(g, nw, s);
         return;
     }
     if (EPI == EPI_SWIGLU && M >= 384) {
@@ -1177,7 +1200,7 @@ static void launch_bf16(const GemmArgs& g, hipStream_t s) {
     launch_lds_tile<EPI>(g, s);
 }
 
-int gemm_ssq_parts(int M, int N) { return M <= 64 ? N / skinny_cols(EPI_RESIDUAL, N) : N / 32; }
+int gemm_ssq_parts(int M, int N, int K) { return use_skinny(EPI_RESIDUAL, M, N, K) ? N / skinny_cols(EPI_RESIDUAL, N) : N / 32; }
 
 void launch_gemm_bf16(Epilogue epi, const GemmArgs& g, hipStream_t s) {
     if (epi == EPI_STORE_F32) launch_bf16<EPI_STORE_F32>(g, s);

@@ -28,7 +28,8 @@ GEMM_CASES = [(1, 64, 64), (9, 3072, 2048), (9, 2048, 8192), (17, 512, 256), (33
               # thousands of rows: every epilogue through the streaming kernel (ragged rows and columns, drain path)
               (1600, 7712, 192), (1664, 7680, 448),
               (144, 65600, 128), (131, 65536, 192),            # 160-row streaming blocks for wide outputs
-              (144, 8192, 3072), (190, 4096, 1536), (150, 4112, 1536)]  # 129-192 rows: SwiGLU over K slices (160- / 192-row blocks)
+              (144, 8192, 3072), (190, 4096, 1536), (150, 4112, 1536),  # 17-192 rows: SwiGLU over K slices (32- to 192-row blocks)
+              (40, 8192, 2048), (96, 4112, 1536), (128, 4096, 3072), (17, 8192, 2048), (30, 4112, 1536)]
 
 
 @pytest.mark.parametrize("M,N,K", GEMM_CASES)
@@ -62,9 +63,11 @@ def test_bf16_gemm(torch_cuda, M, N, K, epi):
 
 
 # the residual GEMM with the next norm's preparation, through every kernel that implements it:
-# skinny with 8 / 12 / 16 columns per block, tile kernels unsplit and with K slices (64- and 128-row
+# skinny with 8 / 12 / 16 columns per block (to 16 rows, and to 32 rows when K is short), tile kernels
+# unsplit and with K slices (64- and 128-row
 # blocks), streaming kernel
-RESIDUAL_CASES = [(9, 2048, 512, False), (9, 3072, 256, False), (33, 4096, 192, False), (64, 1040, 128, False),
+RESIDUAL_CASES = [(9, 2048, 512, False), (9, 3072, 256, False), (33, 4096, 192, False), (16, 1040, 128, False),
+                  (24, 2048, 256, False), (24, 1024, 4096, True), (64, 1024, 128, False),
                   (100, 512, 256, False), (256, 2048, 2048, True), (256, 2048, 2048, False), (300, 1024, 4096, True),
                   (512, 4096, 4096, True), (520, 3072, 8192, True), (1600, 7712, 192, True),
                   (1030, 5088, 8192, True),        # long K and one even round of blocks: streaming kernel
