@@ -964,6 +964,7 @@ static int env_int(const char* name, int dflt) {
     const char* v = std::getenv(name);
     return v && *v ? std::atoi(v) : dflt;
 }
+static const int kSwigluStreamMinNK = env_int("AX_SWIGLU_STREAM_MIN_NK", 40);   // gate/up weights (2^20) per matrix from which verify-size calls stream
 static const int kSkinnyMaxM = std::min(32, env_int("AX_SKINNY_MAX_M", 32));   // experiment knob: rows up to which the skinny kernel may run
 static const int kForceNW = env_int("AX_SKINNY_NW", 0);   // experiment knob: wavefronts per block, 0 = automatic
 
@@ -1114,7 +1115,7 @@ static void launch_lds_tile(const GemmArgs& g, hipStream_t s) {
         // to 64 rows: no K slices for two products) or pull every weight twice out of L2, and the
         // skinny kernel re-reads its activations per 16 columns.  ~3B shape: 33 -> 26 us at 32 rows,
         // 48 -> 28 us at 64 rows, 49 -> 42 us at 144 rows; ~8B: 72 -> 48 us at 32-48 rows.
-        if (kMidStream && M > 16 && M <= 192 && g.split_ws) {
+        if (kMidStream && M <= 192 && g.split_ws) {
             const int cb = (N + 127) / 128;
             int ks = 1;
             for (int c : {8, 6, 4, 3, 2})
@@ -1171,6 +1172,9 @@ static void launch_lds_tile(const GemmArgs& g, hipStream_t s) {
 // (~3B at 17-32 rows: 18-22 -> 17-19 us and 18-23 -> 15-16 us) and so is the SwiGLU GEMM on its
 // K-sliced streaming blocks (see launch_lds_tile); the O projection is not.
 static bool use_skinny(int epi, int M, int N, int K) {
+    // the largest gate/up matrices (~8B shape, 2 x 59 M weights) stream faster through the K-sliced
+    // streaming blocks even at verify sizes: 51 -> 44 us at 9 rows; smaller ones (~3B, ~1B) do not
+    if (epi == EPI_SWIGLU && (long long)N * K >= (long long)kSwigluStreamMinNK << 20) return false;
     if (M <= 16) return true;
     if (M > kSkinnyMaxM) return false;
     return !(epi == EPI_QKV || epi == EPI_SWIGLU || (epi == EPI_RESIDUAL && K >= 2 * N));
