@@ -405,6 +405,8 @@ def main():
         "extend_ms": round(ext_ms, 4),
         "extend_tflops": round(alg["extend_flops"] / (ext_ms * 1e-3) / 1e12, 2),
         "extend_frac_of_mfma_peak": round(alg["extend_flops"] / (ext_ms * 1e-3) / 1e12 / MFMA16_PEAK_TFLOPS, 4),
+        "extend_gbs": round(alg["extend_bytes"] / (ext_ms * 1e-3) / 1e9, 1),
+        "extend_frac_of_hbm_peak": round(alg["extend_bytes"] / (ext_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
         "verify_steps_per_s": round(1e3 / ver_ms, 1),
         "verify_ms_per_step": round(ver_ms, 4),
         "verify_gbs": round(alg["verify_bytes"] / (ver_ms * 1e-3) / 1e9, 1),
