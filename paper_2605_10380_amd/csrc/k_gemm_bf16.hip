@@ -970,6 +970,7 @@ static const int kForceNW = env_int("AX_SKINNY_NW", 0);   // experiment knob: wa
 
 // More rows: LDS-staged tiles.
 static const int kStreamMinM = env_int("AX_STREAM_MIN_M", 1024);   // rows from which QKV / residual GEMMs stream their weights (0 = never)
+static const int kSliceMinM = env_int("AX_SLICE_MIN_M", 257);   // rows from which the down projection may stream over K slices
 static const int kSliceStream = env_int("AX_SLICE_STREAM", 1);   // experiment knob
 static const int kMidStream = env_int("AX_MID_STREAM", 1);   // experiment knob: 0 = tile kernels for 129-192 rows
 static const int kQkvTile = env_int("AX_QKV_TILE", -1);   // experiment knobs: force 64-row (0) or 128-row (1) blocks
@@ -1062,9 +1063,9 @@ static void launch_lds_tile(const GemmArgs& g, hipStream_t s) {
         }
         // a few hundred rows against the long K of the down projection: too few 128 x 256 blocks for
         // the streaming kernel as it is, enough once K is cut into 2-4 slices (160-256 blocks).
-        // Against the tile kernel: ~8B 85 -> 71 us at M = 384, 145 -> 118 at 768, 145 -> 131 at 1024;
+        // Against the tile kernel: ~8B 107 -> 70 us at M = 288-320, 85 -> 71 at 384, 145 -> 118 at 768, 145 -> 131 at 1024;
         // ~3B 58 -> 50 at 512, 93 -> 78 at 1024; ~1B 57 -> 49 at 768.
-        if (kSliceStream && M >= 384 && K >= 8192 && N % 64 == 0 && g.split_ws) {
+        if (kSliceStream && M >= kSliceMinM && K >= 8192 && N % 64 == 0 && g.split_ws) {
             int ks = 1;
             for (int c : {4, 3, 2})                        // one block per CU at a time: at most 256 blocks
                 if (ks == 1 && sblocks * c <= 256 && K % (c * 64) == 0 && K / (c * 64) >= 16 &&
@@ -1196,7 +1197,10 @@ static void launch_bf16(const GemmArgs& g, hipStream_t s) {
         else launch_skinny_nw<EPI, 2>(g, nw, s);
         return;
     }
-    if (EPI == EPI_SWIGLU && M >= 384) {
+    // streaming SwiGLU kernel: from three 128-row blocks up, and with two when the matrix is wide
+    // enough for ~200 blocks (~8B shape at 193-256 rows: 118 -> 97 us; ~1B / ~3B have 128 blocks
+    // there and lose: 32 -> 52, 45 -> 68 us)
+    if (EPI == EPI_SWIGLU && (M > 256 || (M > 192 && (long long)((N + 127) / 128) * ((M + 127) / 128) >= 192))) {
         const int gx = (N + 127) / 128, gy = (M + 127) / 128;
         gemm_bf16_stream_kernel<EPI_SWIGLU, 4, 3><<<gx * gy, 256, 0, s>>>(g, gx, gy);
         return;

@@ -24,7 +24,7 @@ def torch_cuda():
 # streaming SwiGLU kernel (steady-state loop and drain, ragged rows and columns)
 GEMM_CASES = [(1, 64, 64), (9, 3072, 2048), (9, 2048, 8192), (17, 512, 256), (33, 128, 1024), (64, 2064, 192),
               (65, 384, 128), (100, 200 * 16, 320), (256, 3072, 2048), (300, 1024, 512), (512, 33 * 128, 256),
-              (400, 1040, 1024), (384, 2048, 576),
+              (400, 1040, 1024), (384, 2048, 576), (300, 2048, 256), (230, 14336, 128),
               # thousands of rows: every epilogue through the streaming kernel (ragged rows and columns, drain path)
               (1600, 7712, 192), (1664, 7680, 448),
               (144, 65600, 128), (131, 65536, 192),            # 160-row streaming blocks for wide outputs
@@ -69,7 +69,7 @@ def test_bf16_gemm(torch_cuda, M, N, K, epi):
 RESIDUAL_CASES = [(9, 2048, 512, False), (9, 3072, 256, False), (33, 4096, 192, False), (16, 1040, 128, False),
                   (24, 2048, 256, False), (24, 1024, 4096, True), (64, 1024, 128, False),
                   (100, 512, 256, False), (256, 2048, 2048, True), (256, 2048, 2048, False), (300, 1024, 4096, True),
-                  (512, 4096, 4096, True), (520, 3072, 8192, True), (1600, 7712, 192, True),
+                  (512, 4096, 4096, True), (520, 3072, 8192, True), (300, 4096, 14336, True), (1600, 7712, 192, True),
                   (1030, 5088, 8192, True),        # long K and one even round of blocks: streaming kernel
                   (144, 3072, 8192, True), (131, 2048, 8192, True), (190, 2048, 8192, True), (161, 1024, 12288, True)]   # 160- / 192-row streaming blocks, K slices
 
