@@ -969,7 +969,8 @@ static const int kSkinnyMaxM = std::min(32, env_int("AX_SKINNY_MAX_M", 32));   /
 static const int kForceNW = env_int("AX_SKINNY_NW", 0);   // experiment knob: wavefronts per block, 0 = automatic
 
 // More rows: LDS-staged tiles.
-static const int kStreamMinM = env_int("AX_STREAM_MIN_M", 1024);   // rows from which QKV / residual GEMMs stream their weights (0 = never)
+static const int kStreamMinBlocks = env_int("AX_STREAM_MIN_BLOCKS", 128);
+static const int kStreamMinM = env_int("AX_STREAM_MIN_M", 512);   // rows from which QKV / residual GEMMs stream their weights (0 = never)
 static const int kSliceMinM = env_int("AX_SLICE_MIN_M", 257);   // rows from which the down projection may stream over K slices
 static const int kSliceStream = env_int("AX_SLICE_STREAM", 1);   // experiment knob
 static const int kMidStream = env_int("AX_MID_STREAM", 1);   // experiment knob: 0 = tile kernels for 129-192 rows
@@ -987,15 +988,16 @@ static void launch_lds_tile(const GemmArgs& g, hipStream_t s) {
     const long long tiles128 = (long long)((N + 127) / 128) * ((M + 127) / 128);
     // 128-row blocks only when their row padding costs at most ~15 % more rows than 64-row blocks' (M = 144 does not qualify)
     const bool pad_ok = (long long)((M + 127) / 128) * 128 * 100 <= (long long)((M + 63) / 64) * 64 * 115;
-    // Calls with a thousand rows or more: the streaming kernel (weights straight to the MFMA operands,
-    // 128 x 256 blocks, one block per CU at a time) where its blocks fill the 256 CUs evenly - a
-    // single round of 160 or more blocks, or rounds that are at least 3/4 full - and, for the
-    // residual GEMMs, only with the long K of the down projection.  Measured against the tile
-    // kernel: ~8B QKV 106 -> 88 us at M = 1024 and 326 -> 278 at 3584, ~8B down 293 -> 259 at 2048
-    // and 558 -> 493 at 3584, ~3B down 168 -> 153 at 2048; O projections and half-empty last
-    // rounds (336 blocks) lose 5-40 % and stay with the tile kernel.
+    // Calls with several hundred rows or more: the streaming kernel (weights straight to the MFMA
+    // operands, 128 x 256 blocks, one block per CU at a time) where its blocks fill the 256 CUs
+    // evenly - a single round of 128 or more blocks (160 for the down projection, which otherwise
+    // goes over K slices), or rounds that are at least 3/4 full - and,
+    // for the residual GEMMs, only with the long K of the down projection.  Measured against the
+    // tile kernel: ~8B QKV 94-101 -> 81 us at M = 704-768, 106 -> 88 at 1024, 326 -> 278 at 3584;
+    // ~8B down 293 -> 259 at 2048 and 558 -> 493 at 3584, ~3B down 168 -> 153 at 2048; O projections
+    // and half-empty last rounds (336 blocks) lose 5-40 % and stay with the tile kernel.
     const long long sblocks = (long long)((N + 255) / 256) * ((M + 127) / 128), rounds = (sblocks + 255) / 256;
-    const bool stream = kStreamMinM > 0 && M >= kStreamMinM && N % 32 == 0 && sblocks >= 160 &&
+    const bool stream = kStreamMinM > 0 && M >= kStreamMinM && N % 32 == 0 && sblocks >= (EPI == EPI_RESIDUAL ? 160 : kStreamMinBlocks) &&
                         (rounds == 1 || sblocks * 4 >= rounds * 256 * 3) && (EPI != EPI_RESIDUAL || K >= 8192);
     // 129-192 rows (16 sessions verified together), residual GEMM with a long K (down projection):
     // one 160- or 192-row streaming block per 128 columns reads every weight once (64-row tiles
