@@ -1093,12 +1093,13 @@ static void launch_lds_tile(const GemmArgs& g, hipStream_t s) {
                 ks *= 2;
             return ks;
         };
-        // 128-row blocks: when there are plenty of tiles without any cut, or when K is long (down
+        // 128-row blocks: when there are plenty of tiles without any cut (or more 64-row tiles than one
+        // round of two per CU: ~3B O projection at 704-768 rows 52 -> 45-48 us), or when K is long (down
         // projection) and at most 4 slices give ~200 blocks or more.  Measured against 64-row
         // blocks: ~8B down projection 57 -> 49 us at M = 256, 98 -> 81 at 512, 907 -> 564 at 3584;
         // ~1B at M = 256 would need 8 slices and is no faster, so it keeps 64-row blocks.
         const int ks128 = slices(tiles128);
-        const bool big = kResTile >= 0 ? kResTile > 0 : (M > 128 && pad_ok && (tiles128 >= kResBig || (K >= 4096 && ks128 <= 4 && tiles128 * ks128 >= 192)));
+        const bool big = kResTile >= 0 ? kResTile > 0 : (M > 128 && pad_ok && (tiles128 >= kResBig || tiles64 > 256 || (K >= 4096 && ks128 <= 4 && tiles128 * ks128 >= 192)));
         const int ks = big ? ks128 : slices(tiles64);
         GemmArgs gs = g;
         gs.ksplit = ks;
