@@ -1073,7 +1073,7 @@ static void launch_lds_tile(const GemmArgs& g, hipStream_t s) {
                 if (ks == 1 && sblocks * c <= 256 && K % (c * 64) == 0 && K / (c * 64) >= 16 &&
                     (size_t)c * 2 * M * N * sizeof(float) <= g.split_ws_bytes)
                     ks = c;
-            if (ks > 1 && sblocks * ks >= 160) {
+            if (ks > 1 && sblocks * ks >= (ks == 2 ? 128 : 160)) {       // two slices pay from half the CUs up (~3B at 704-768 rows: 88 -> 74 us)
                 GemmArgs gs = g;
                 gs.ksplit = ks;
                 const int gx = (N + 255) / 256, gy = (M + 127) / 128;
