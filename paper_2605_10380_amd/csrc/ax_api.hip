@@ -264,13 +264,16 @@ ax_status prepare_call(ax_model* m, int n, ax_kv* const* kvs, const int32_t* tok
     cp.n_rows = (int)n_rows;
     cp.out_mode = out_mode;
     cp.pool = pool;
-    // attention q tiles (32 stacked rows).  Verify steps and short extends (<= 64 stacked rows
-    // per sequence): one tile per wavefront - measured, a wavefront that carries two tiles
-    // (sharing the K/V loads) is no faster, its serial softmax chain per key step is twice as
-    // long.  Longer extends: blocks of 4 or 8 tiles that share LDS-staged K/V.
+    // attention q tiles (32 stacked rows).  Verify steps and short extends (<= 128 stacked rows
+    // per sequence, <= 256 at head_dim 64): one tile per wavefront - measured, a wavefront that
+    // carries two tiles (sharing the K/V loads) is no faster, its serial softmax chain per key step
+    // is twice as long.  Longer extends: blocks of 4 or 8 tiles that share LDS-staged K/V.  (With
+    // 65-128 stacked rows the blocks were tried first and lost by far: a verify round at k = 16
+    // of the ~1B model 1.58 -> 1.29 ms, of the ~8B model 5.0 -> 4.4 ms.)
+    const int split_rows_max = c.head_dim == 64 ? 256 : 128;
     cp.tile_nq = 1;
     for (int s = 0; s < n; ++s) {
-        if (T_each[s] * G > 64 && cp.tile_nq < 4) cp.tile_nq = 4;
+        if (T_each[s] * G > split_rows_max && cp.tile_nq < 4) cp.tile_nq = 4;
         if (T_each[s] * G >= 2048) cp.tile_nq = 8;    // 8 tiles per block: ~10 % on the ~8B shape at T = 512, none below
     }
     cp.n_tiles = cp.bt_total = 0;
