@@ -1050,7 +1050,7 @@ static void launch_lds_tile(const GemmArgs& g, hipStream_t s) {
         qkv_reduce_rope_kernel<<<dim3((unsigned)M, (unsigned)((N / 2 + 255) / 256)), 256, 0, s>>>(gs);
         return;
     } else if constexpr (EPI == EPI_RESIDUAL) {
-        if (mid_ks > 1) {
+        if (mid_ks > 1 && mid_cb * mid_ks >= 160) {            // (~1B width: 128 blocks, slower than the tile kernels)
             GemmArgs gs = g;
             gs.ksplit = mid_ks;
             if (M <= 160) gemm_bf16_stream_kernel<EPI_RESIDUAL, 5, 3, 1, true><<<mid_cb * mid_ks, 256, 0, s>>>(gs, mid_cb, 1);
@@ -1119,7 +1119,8 @@ static void launch_lds_tile(const GemmArgs& g, hipStream_t s) {
         // to 64 rows: no K slices for two products) or pull every weight twice out of L2, and the
         // skinny kernel re-reads its activations per 16 columns.  ~3B shape: 33 -> 26 us at 32 rows,
         // 48 -> 28 us at 64 rows, 49 -> 42 us at 144 rows; ~8B: 72 -> 48 us at 32-48 rows.
-        if (kMidStream && M <= 192 && g.split_ws) {
+        // (above 128 rows only for matrices of the ~3B size or larger: at the ~1B size the 128 x 64 tiles are as fast or faster)
+        if (kMidStream && M <= 192 && (M <= 128 || (long long)N * K >= (20LL << 20)) && g.split_ws) {
             const int cb = (N + 127) / 128;
             int ks = 1;
             for (int c : {8, 6, 4, 3, 2})
