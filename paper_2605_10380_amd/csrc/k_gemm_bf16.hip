@@ -965,6 +965,7 @@ static int env_int(const char* name, int dflt) {
     return v && *v ? std::atoi(v) : dflt;
 }
 static const int kSwigluStreamMinNK = env_int("AX_SWIGLU_STREAM_MIN_NK", 40);   // gate/up weights (2^20) per matrix from which verify-size calls stream
+static const int kStreamTm = env_int("AX_STREAM_TM", 1);   // experiment knob: 0 = always 128-row blocks
 static const int kSkinnyMaxM = std::min(32, env_int("AX_SKINNY_MAX_M", 32));   // experiment knob: rows up to which the skinny kernel may run
 static const int kForceNW = env_int("AX_SKINNY_NW", 0);   // experiment knob: wavefronts per block, 0 = automatic
 
@@ -1205,8 +1206,27 @@ static void launch_bf16(const GemmArgs& g, hipStream_t s) {
     // enough for ~200 blocks (~8B shape at 193-256 rows: 118 -> 97 us; ~1B / ~3B have 128 blocks
     // there and lose: 32 -> 52, 45 -> 68 us)
     if (EPI == EPI_SWIGLU && (M > 256 || (M > 192 && (long long)((N + 127) / 128) * ((M + 127) / 128) >= 192))) {
-        const int gx = (N + 127) / 128, gy = (M + 127) / 128;
-        gemm_bf16_stream_kernel<EPI_SWIGLU, 4, 3><<<gx * gy, 256, 0, s>>>(g, gx, gy);
+        // rows per block: 96, 128, 160 or 192.  One block runs per CU at a time, so a launch takes
+        // (rounds of 256 blocks) x (time of a block), and a block's time grows with the operand rows
+        // it pulls (its activation rows + 2 x 128 weight rows): pick the shape with the smallest
+        // product.  257 rows of the ~1B shape: 3 x 96 rows (192 blocks) instead of 3 x 128, 56 -> 45 us;
+        // 640 rows: 4 x 160 (256 blocks, one round) instead of 5 x 128 (320 blocks, two), 99 -> 65 us.
+        int tm = 4;
+        if (kStreamTm) {
+            long long best = -1;
+            for (int t : {4, 3, 5, 6}) {
+                const long long blocks = (long long)((N + 127) / 128) * ((M + 32 * t - 1) / (32 * t));
+                const long long cost = ((blocks + 255) / 256) * (32 * t + 256) * (t >= 5 ? 115 : 100);   // the two large shapes run ~15 % below the model
+                if (best < 0 || cost < best) { best = cost; tm = t; }
+            }
+        }
+        const int gx = (N + 127) / 128, gy = (M + 32 * tm - 1) / (32 * tm);
+        switch (tm) {
+            case 3: gemm_bf16_stream_kernel<EPI_SWIGLU, 3, 3><<<gx * gy, 256, 0, s>>>(g, gx, gy); break;
+            case 5: gemm_bf16_stream_kernel<EPI_SWIGLU, 5, 3><<<gx * gy, 256, 0, s>>>(g, gx, gy); break;
+            case 6: gemm_bf16_stream_kernel<EPI_SWIGLU, 6, 3><<<gx * gy, 256, 0, s>>>(g, gx, gy); break;
+            default: gemm_bf16_stream_kernel<EPI_SWIGLU, 4, 3><<<gx * gy, 256, 0, s>>>(g, gx, gy); break;
+        }
         return;
     }
     launch_lds_tile<EPI>(g, s);

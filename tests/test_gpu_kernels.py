@@ -24,7 +24,7 @@ def torch_cuda():
 # streaming SwiGLU kernel (steady-state loop and drain, ragged rows and columns)
 GEMM_CASES = [(1, 64, 64), (9, 3072, 2048), (9, 2048, 8192), (17, 512, 256), (33, 128, 1024), (64, 2064, 192),
               (65, 384, 128), (100, 200 * 16, 320), (256, 3072, 2048), (300, 1024, 512), (512, 33 * 128, 256),
-              (400, 1040, 1024), (384, 2048, 576), (300, 2048, 256), (230, 14336, 128),
+              (400, 1040, 1024), (384, 2048, 576), (300, 2048, 256), (230, 14336, 128), (257, 8192, 128), (640, 8192, 192), (320, 14336, 128),
               # thousands of rows: every epilogue through the streaming kernel (ragged rows and columns, drain path)
               (1600, 7712, 192), (1664, 7680, 448),
               (144, 65600, 128), (131, 65536, 192),            # 160-row streaming blocks for wide outputs
