@@ -966,6 +966,7 @@ static int env_int(const char* name, int dflt) {
 }
 static const int kSwigluStreamMinNK = env_int("AX_SWIGLU_STREAM_MIN_NK", 40);   // gate/up weights (2^20) per matrix from which verify-size calls stream
 static const int kStreamTm = env_int("AX_STREAM_TM", 1);   // experiment knob: 0 = always 128-row blocks
+static const int kSwigluWaves = env_int("AX_SWIGLU_WAVES", 4096);   // wavefronts in flight the SwiGLU launch aims for (two weight streams per wavefront)
 static const int kSkinnyMaxM = std::min(32, env_int("AX_SKINNY_MAX_M", 32));   // experiment knob: rows up to which the skinny kernel may run
 static const int kForceNW = env_int("AX_SKINNY_NW", 0);   // experiment knob: wavefronts per block, 0 = automatic
 
@@ -1190,12 +1191,14 @@ template <int EPI>
 static void launch_bf16(const GemmArgs& g, hipStream_t s) {
     const int M = g.M, N = g.N, K = g.K;
     if (use_skinny(EPI, M, N, K)) {
-        // wavefronts per block (= K slices): enough to keep ~2k wavefronts in flight, each with
+        // wavefronts per block (= K slices): enough to keep ~2k wavefronts in flight (~4k for the SwiGLU
+        // GEMM: 8 instead of 4 wavefronts per block took the ~1B verify kernel from 16.6 to 14.7 us), each with
         // at least 128 of K; K / nw must stay a multiple of the MFMA k (32)
         const int cols = skinny_cols(EPI, N);
         const long long tiles = (N + cols - 1) / cols;
         int nw = 1;
-        while (nw < 16 && tiles * nw < 2048 && K % (nw * 2 * 32) == 0 && K / (nw * 2) >= 128) nw *= 2;
+        const int wave_target = EPI == EPI_SWIGLU ? kSwigluWaves : 2048;
+        while (nw < 16 && tiles * nw < wave_target && K % (nw * 2 * 32) == 0 && K / (nw * 2) >= 128) nw *= 2;
         if (kForceNW && K % (kForceNW * 32) == 0) nw = kForceNW;
         if (EPI == EPI_SWIGLU && nw == 16) nw = 8;        // LDS reduction buffer stays <= 64 KB
         if (M <= 16) launch_skinny_nw<EPI, 1>(g, nw, s);
