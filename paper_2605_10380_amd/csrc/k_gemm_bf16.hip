@@ -967,6 +967,7 @@ static int env_int(const char* name, int dflt) {
 static const int kSwigluStreamMinNK = env_int("AX_SWIGLU_STREAM_MIN_NK", 40);   // gate/up weights (2^20) per matrix from which verify-size calls stream
 static const int kStreamTm = env_int("AX_STREAM_TM", 1);   // experiment knob: 0 = always 128-row blocks
 static const int kSwigluWaves = env_int("AX_SWIGLU_WAVES", 4096);   // wavefronts in flight the SwiGLU launch aims for (two weight streams per wavefront)
+static const int kLmStream = env_int("AX_LM_STREAM", 1);   // experiment knob
 static const int kSkinnyMaxM = std::min(32, env_int("AX_SKINNY_MAX_M", 32));   // experiment knob: rows up to which the skinny kernel may run
 static const int kForceNW = env_int("AX_SKINNY_NW", 0);   // experiment knob: wavefronts per block, 0 = automatic
 
@@ -1154,6 +1155,20 @@ static void launch_lds_tile(const GemmArgs& g, hipStream_t s) {
         }
     }
     if constexpr (EPI == EPI_STORE_F32 || EPI == EPI_SWIGLU) {
+        // logits (N >= 64 K columns) of 17-128 rows: one streaming block of all the rows per 256 columns
+        // reads the LM head once at 5-6 TB/s; the skinny kernel re-reads its activations per 16 columns
+        // (17 rows of the ~3B shape: 182 -> 128 us) and two 64-row tiles read the weights twice
+        // (96-128 rows: 282-294 -> 149-157 us)
+        if (EPI == EPI_STORE_F32 && M > 16 && M <= 128 && N >= 256 * 256 && N % 32 == 0 && kLmStream) {
+            const int gx = (N + 255) / 256;
+            switch ((M + 31) / 32) {
+                case 1: gemm_bf16_stream_kernel<EPI_STORE_F32, 1, 3><<<gx, 256, 0, s>>>(g, gx, 1); break;
+                case 2: gemm_bf16_stream_kernel<EPI_STORE_F32, 2, 3><<<gx, 256, 0, s>>>(g, gx, 1); break;
+                case 3: gemm_bf16_stream_kernel<EPI_STORE_F32, 3, 3><<<gx, 256, 0, s>>>(g, gx, 1); break;
+                default: gemm_bf16_stream_kernel<EPI_STORE_F32, 4, 3><<<gx, 256, 0, s>>>(g, gx, 1); break;
+            }
+            return;
+        }
         if (EPI == EPI_STORE_F32 && M > 128 && M <= 160 && N >= 256 * 256 && N % 32 == 0) {
             // logits of 129-160 rows (batched verify of 16 sessions): one 160-row block per 256
             // columns reads the weights once, where 64-row tiles pull them three times out of L2
@@ -1184,6 +1199,7 @@ static bool use_skinny(int epi, int M, int N, int K) {
     if (epi == EPI_SWIGLU && (long long)N * K >= (long long)kSwigluStreamMinNK << 20) return false;
     if (M <= 16) return true;
     if (M > kSkinnyMaxM) return false;
+    if (epi == EPI_STORE_F32 && N >= 256 * 256 && kLmStream) return false;    // logits: streaming blocks (see launch_lds_tile)
     return !(epi == EPI_QKV || epi == EPI_SWIGLU || (epi == EPI_RESIDUAL && K >= 2 * N));
 }
 
