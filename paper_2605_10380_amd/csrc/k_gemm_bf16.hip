@@ -1155,25 +1155,33 @@ static void launch_lds_tile(const GemmArgs& g, hipStream_t s) {
         }
     }
     if constexpr (EPI == EPI_STORE_F32 || EPI == EPI_SWIGLU) {
-        // logits (N >= 64 K columns) of 17-128 rows: one streaming block of all the rows per 256 columns
-        // reads the LM head once at 5-6 TB/s; the skinny kernel re-reads its activations per 16 columns
-        // (17 rows of the ~3B shape: 182 -> 128 us) and two 64-row tiles read the weights twice
-        // (96-128 rows: 282-294 -> 149-157 us)
-        if (EPI == EPI_STORE_F32 && M > 16 && M <= 128 && N >= 256 * 256 && N % 32 == 0 && kLmStream) {
+        // logits (N >= 64 K columns) of 17 rows or more: streaming blocks of up to 192 rows per 256 columns
+        // read the LM head once per block row at 5-6 TB/s; the skinny kernel re-reads its activations
+        // per 16 columns (17 rows of the ~3B shape: 182 -> 128 us) and 64-row tiles read the weights
+        // once per tile (96-128 rows: 282-294 -> 149-157 us; 144 rows: 436 -> 202 us).  Rows per
+        // block by the same rounds x block cost as the SwiGLU kernel.
+        if (EPI == EPI_STORE_F32 && M > 16 && N >= 256 * 256 && N % 32 == 0 && kLmStream) {
             const int gx = (N + 255) / 256;
-            switch ((M + 31) / 32) {
-                case 1: gemm_bf16_stream_kernel<EPI_STORE_F32, 1, 3><<<gx, 256, 0, s>>>(g, gx, 1); break;
-                case 2: gemm_bf16_stream_kernel<EPI_STORE_F32, 2, 3><<<gx, 256, 0, s>>>(g, gx, 1); break;
-                case 3: gemm_bf16_stream_kernel<EPI_STORE_F32, 3, 3><<<gx, 256, 0, s>>>(g, gx, 1); break;
-                default: gemm_bf16_stream_kernel<EPI_STORE_F32, 4, 3><<<gx, 256, 0, s>>>(g, gx, 1); break;
+            int tm = (M + 31) / 32;
+            if (M > 512) {
+                tm = 4;                                    // compute-bound there: 128-row blocks (1024 rows: 669 us against 804 with 192-row blocks)
+            } else if (tm > 6) {
+                long long best = -1;
+                for (int t : {4, 3, 5, 6}) {
+                    const long long blocks = (long long)gx * ((M + 32 * t - 1) / (32 * t));
+                    const long long cost = ((blocks + 255) / 256) * (32 * t + 512) * (t >= 5 ? 115 : 100);
+                    if (best < 0 || cost < best) { best = cost; tm = t; }
+                }
             }
-            return;
-        }
-        if (EPI == EPI_STORE_F32 && M > 128 && M <= 160 && N >= 256 * 256 && N % 32 == 0) {
-            // logits of 129-160 rows (batched verify of 16 sessions): one 160-row block per 256
-            // columns reads the weights once, where 64-row tiles pull them three times out of L2
-            const int gx = (N + 255) / 256;
-            gemm_bf16_stream_kernel<EPI_STORE_F32, 5, 3><<<gx, 256, 0, s>>>(g, gx, 1);
+            const int gy = (M + 32 * tm - 1) / (32 * tm);
+            switch (tm) {
+                case 1: gemm_bf16_stream_kernel<EPI_STORE_F32, 1, 3><<<gx * gy, 256, 0, s>>>(g, gx, gy); break;
+                case 2: gemm_bf16_stream_kernel<EPI_STORE_F32, 2, 3><<<gx * gy, 256, 0, s>>>(g, gx, gy); break;
+                case 3: gemm_bf16_stream_kernel<EPI_STORE_F32, 3, 3><<<gx * gy, 256, 0, s>>>(g, gx, gy); break;
+                case 4: gemm_bf16_stream_kernel<EPI_STORE_F32, 4, 3><<<gx * gy, 256, 0, s>>>(g, gx, gy); break;
+                case 5: gemm_bf16_stream_kernel<EPI_STORE_F32, 5, 3><<<gx * gy, 256, 0, s>>>(g, gx, gy); break;
+                default: gemm_bf16_stream_kernel<EPI_STORE_F32, 6, 3><<<gx * gy, 256, 0, s>>>(g, gx, gy); break;
+            }
             return;
         }
         if (EPI == EPI_STORE_F32 && stream) {              // logits of thousands of rows

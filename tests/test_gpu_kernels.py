@@ -27,7 +27,7 @@ GEMM_CASES = [(1, 64, 64), (9, 3072, 2048), (9, 2048, 8192), (17, 512, 256), (33
               (400, 1040, 1024), (384, 2048, 576), (300, 2048, 256), (230, 14336, 128), (257, 8192, 128), (640, 8192, 192), (320, 14336, 128),
               # thousands of rows: every epilogue through the streaming kernel (ragged rows and columns, drain path)
               (1600, 7712, 192), (1664, 7680, 448),
-              (144, 65600, 128), (131, 65536, 192), (17, 65600, 128), (40, 65536, 192), (100, 65568, 128),   # streaming blocks for wide outputs (logits) from 17 rows
+              (144, 65600, 128), (131, 65536, 192), (17, 65600, 128), (40, 65536, 192), (100, 65568, 128), (190, 65536, 128), (300, 65600, 128),   # streaming blocks for wide outputs (logits) from 17 rows
               (144, 8192, 3072), (190, 4096, 1536), (150, 4112, 1536),  # 17-192 rows: SwiGLU over K slices (32- to 192-row blocks)
               (40, 8192, 2048), (96, 4112, 1536), (128, 4096, 3072), (17, 8192, 2048), (30, 4112, 1536)]
 
