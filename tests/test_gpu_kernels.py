@@ -62,6 +62,26 @@ def test_bf16_gemm(torch_cuda, M, N, K, epi):
         assert np.abs(got - want).max() <= 2 ** -11 * np.abs(want).max() + 1e-6
 
 
+def _random_gemm_cases(n, seed=20260517):
+    """Seeded shapes around the launcher's row-count crossovers (16/17, 32/33, 64/65, 128/129, 192/193, 256/257,
+    512/513) with ragged column counts (multiples of 16) and K a multiple of 64: every (kernel, epilogue)
+    pair is reached at shapes nobody picked by hand."""
+    rng = np.random.default_rng(seed)
+    edges = [16, 17, 32, 33, 64, 65, 128, 129, 160, 161, 192, 193, 256, 257, 384, 512, 513, 640]
+    cases = []
+    for i in range(n):
+        M = int(rng.choice(edges)) if i % 2 == 0 else int(rng.integers(1, 700))
+        N = 16 * int(rng.integers(4, 560))
+        K = 64 * int(rng.integers(1, 40))
+        cases.append((M, N, K, i % 3))
+    return cases
+
+
+@pytest.mark.parametrize("M,N,K,epi", _random_gemm_cases(36))
+def test_bf16_gemm_seeded_random_shapes(torch_cuda, M, N, K, epi):
+    test_bf16_gemm(torch_cuda, M, N, K, epi)
+
+
 # the residual GEMM with the next norm's preparation, through every kernel that implements it:
 # skinny with 8 / 12 / 16 columns per block (to 16 rows, and to 32 rows when K is short), tile kernels
 # unsplit and with K slices (64- and 128-row
@@ -101,6 +121,25 @@ def test_bf16_residual_gemm_with_norm_preparation(torch_cuda, M, N, K, split):
     ssq = dssq.cpu().numpy().reshape(-1)[:M * parts].reshape(M, parts)        # rows are `parts` apart
     assert np.isfinite(ssq).all()
     assert np.allclose(ssq.astype(np.float64).sum(axis=1), (want ** 2).sum(axis=1), rtol=2e-5)
+
+
+def _random_residual_cases(n, seed=20260518):
+    """Seeded shapes for the residual GEMM with norm preparation: N a multiple of 64 (K slices and the
+    streaming kernels need it), long and short K, rows around the launcher's crossovers."""
+    rng = np.random.default_rng(seed)
+    edges = [9, 16, 17, 32, 33, 64, 128, 129, 160, 161, 192, 193, 256, 257, 512, 640]
+    cases = []
+    for i in range(n):
+        M = int(rng.choice(edges)) if i % 2 == 0 else int(rng.integers(1, 700))
+        N = 64 * int(rng.integers(2, 70))
+        K = 64 * int(rng.integers(1, 40)) if i % 3 else 1024 * int(rng.integers(8, 15))
+        cases.append((M, N, K, True))
+    return cases
+
+
+@pytest.mark.parametrize("M,N,K,split", _random_residual_cases(18))
+def test_bf16_residual_gemm_seeded_random_shapes(torch_cuda, M, N, K, split):
+    test_bf16_residual_gemm_with_norm_preparation(torch_cuda, M, N, K, split)
 
 
 @pytest.mark.parametrize("M,N,K", [(5, 37, 19), (64, 688, 256), (70, 256, 688), (130, 4096, 256)])
