@@ -89,50 +89,66 @@ void launch_pack_weights(const void* src, void* dst, int N, int K, hipStream_t s
 }
 
 // 1 / rms of A rows from the column-block partial sums of x^2 their producer left behind.
-// Block-wide: 1 / rms of `rows` A-rows into s_inv[0..rows).  Half a wavefront (32 lanes)
-// owns a row; the partial sums of all of a thread's rows are requested before anything is
-// reduced, so the whole table costs one memory round trip instead of one per row.
-// The caller synchronises before reading s_inv.
-// One row by one wavefront (lanes stride over the partials); every lane gets the result.
+// A kernel of this size is a chain of memory round trips, so every helper here requests all
+// the partials it will need before it adds anything up: the index is clamped instead of
+// branched on (no load sits behind a branch), values past the end are dropped when summing.
+//
+// One row's partials spread over a group of G lanes (gl = lane within the group), 4 G per round.
+template <int G>
+__device__ __forceinline__ float ssq_lane_sum(const float* __restrict__ src, int nparts, int gl) {
+    float v = 0.f;
+    for (int base = 0; base < nparts; base += 4 * G) {
+        float t[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) t[u] = src[min(base + u * G + gl, nparts - 1)];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v += base + u * G + gl < nparts ? t[u] : 0.f;
+    }
+    return v;
+}
+// One row by one wavefront; every lane gets the result.
 __device__ __forceinline__ float wave_inv_rms(const float* __restrict__ ssq, int row, int nparts,
                                               int d_norm, float eps, int lane) {
-    float v = 0.f;
-    for (int p = lane; p < nparts; p += 64) v += ssq[(long long)row * nparts + p];
+    float v = ssq_lane_sum<64>(ssq + (long long)row * nparts, nparts, lane);
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
     return 1.0f / sqrtf(v / (float)d_norm + eps);
 }
 
-constexpr int INV_BATCH = 8;                           // rows per thread whose loads are in flight together
-__device__ __forceinline__ void inv_rms_load(const GemmArgs& g, int first_row, int rows, int base, float (&v)[INV_BATCH]) {
-    const int hw = threadIdx.x >> 5, hl = threadIdx.x & 31, nhw = blockDim.x >> 5;
-#pragma unroll
-    for (int p = 0; p < INV_BATCH; ++p) {
-        const int r = base + p * nhw + hw;
-        v[p] = 0.f;
-        if (r < rows) {
-            const int gm = min(first_row + r, g.M - 1);
-            const float* src = g.ssq + (long long)(g.a_rows ? g.a_rows[gm] : gm) * g.nparts;
-            for (int q = hl; q < g.nparts; q += 32) v[p] += src[q];
-        }
-    }
-}
-__device__ __forceinline__ void inv_rms_finish(const GemmArgs& g, int rows, int base, float (&v)[INV_BATCH], float* s_inv) {
-    const int hw = threadIdx.x >> 5, hl = threadIdx.x & 31, nhw = blockDim.x >> 5;
-#pragma unroll
-    for (int p = 0; p < INV_BATCH; ++p) {
-#pragma unroll
-        for (int o = 16; o > 0; o >>= 1) v[p] += __shfl_xor(v[p], o, 64);
-        const int r = base + p * nhw + hw;
-        if (hl == 0 && r < rows) s_inv[r] = 1.0f / sqrtf(v[p] / (float)g.d_norm + g.eps);
-    }
-}
+// Block-wide: 1 / rms of `rows` A-rows into s_inv[0..rows).  Half a wavefront (32 lanes) owns a
+// row and a thread works on INV_BATCH rows at a time: their 4 x INV_BATCH loads are in flight
+// together, so the table costs one memory round trip per INV_BATCH rows of a thread (and per 128
+// partials of a row), not one per load.  The caller synchronises before reading s_inv.
+template <int INV_BATCH>
 __device__ __forceinline__ void block_inv_rms(const GemmArgs& g, int first_row, int rows, float* s_inv) {
-    const int nhw = blockDim.x >> 5;
+    const int hw = threadIdx.x >> 5, hl = threadIdx.x & 31, nhw = blockDim.x >> 5;
     for (int base = 0; base < rows; base += INV_BATCH * nhw) {
+        long long src[INV_BATCH];
         float v[INV_BATCH];
-        inv_rms_load(g, first_row, rows, base, v);
-        inv_rms_finish(g, rows, base, v, s_inv);
+#pragma unroll
+        for (int p = 0; p < INV_BATCH; ++p) {
+            const int gm = min(first_row + min(base + p * nhw + hw, rows - 1), g.M - 1);
+            src[p] = (long long)(g.a_rows ? g.a_rows[gm] : gm) * g.nparts;
+            v[p] = 0.f;
+        }
+        for (int q0 = 0; q0 < g.nparts; q0 += 128) {
+            float t[INV_BATCH][4];
+#pragma unroll
+            for (int p = 0; p < INV_BATCH; ++p)
+#pragma unroll
+                for (int u = 0; u < 4; ++u) t[p][u] = g.ssq[src[p] + min(q0 + u * 32 + hl, g.nparts - 1)];
+#pragma unroll
+            for (int p = 0; p < INV_BATCH; ++p)
+#pragma unroll
+                for (int u = 0; u < 4; ++u) v[p] += q0 + u * 32 + hl < g.nparts ? t[p][u] : 0.f;
+        }
+#pragma unroll
+        for (int p = 0; p < INV_BATCH; ++p) {
+#pragma unroll
+            for (int o = 16; o > 0; o >>= 1) v[p] += __shfl_xor(v[p], o, 64);
+            const int r = base + p * nhw + hw;
+            if (hl == 0 && r < rows) s_inv[r] = 1.0f / sqrtf(v[p] / (float)g.d_norm + g.eps);
+        }
     }
 }
 
@@ -240,7 +256,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_tile_kernel(GemmArgs g
 #pragma unroll
     for (int s = 0; s < D; ++s)
         if (s < nsteps) load_global(s, s * BK);
-    if (g.ssq) block_inv_rms(g, m0, BM, s_inv);   // deferred RMSNorm: 1/rms of this block's rows
+    if (g.ssq) block_inv_rms<4>(g, m0, BM, s_inv);   // deferred RMSNorm: 1/rms of this block's rows (a batch of 4 rows per thread = 64 rows: more in flight would cost the 64-row blocks their second block per CU)
     store_lds(0, 0);
     __syncthreads();
     // steady state: groups of D steps with every load and store unconditional (branch-free, so
@@ -566,10 +582,13 @@ __global__ __launch_bounds__(256) void gemm_bf16_stream_kernel(GemmArgs g, int g
     };
 
     const int nsteps = kspan / BK;
+    // deferred RMSNorm: 1/rms of this block's rows, before the operand rings take the registers (16
+    // rows x 4 loads per thread in flight: one or two round trips; behind the ring loads the same
+    // table cost four to six, 10-15 % of the launch at 512-1024 rows).  Sliced SwiGLU: the reduce kernel scales.
+    if (g.ssq && !(EPI == EPI_SWIGLU && SLICED)) block_inv_rms<16>(g, m0, BM, s_inv);
 #pragma unroll
     for (int s = 0; s < D; ++s)
         if (s < nsteps) load_global(s, s * BK);
-    if (g.ssq && !(EPI == EPI_SWIGLU && SLICED)) block_inv_rms(g, m0, BM, s_inv);    // sliced SwiGLU: the reduce kernel scales
     store_lds(0, 0);
     __syncthreads();
     // steady state, branch free: multiply step s out of ring slot s % D and LDS buffer s % 2,
@@ -754,6 +773,23 @@ void gemm_bf16_skinny_kernel(GemmArgs g) {
         }
     }
 
+    // The same for the partial sums of x^2 behind the deferred RMSNorm: wavefront w turns those of
+    // rows w, w + NW, .. into 1 / rms after the K loop, from registers filled here (up to 16 rows, 256
+    // partials per row and 4 rows per wavefront; anything larger is fetched after the loop).
+    constexpr int RPW = (MT * 16 + NW - 1) / NW;
+    constexpr bool PRE_SSQ = MT == 1 && RPW <= 4;          // 17-32 rows: only small test shapes arrive here with a norm pending
+    float pre_ss[PRE_SSQ ? RPW : 1][4];
+    const bool pre_ssq = PRE_SSQ && g.ssq && g.nparts <= 256;
+    if (pre_ssq) {
+#pragma unroll
+        for (int j = 0; j < (PRE_SSQ ? RPW : 1); ++j) {
+            const int m = min(wave + j * NW, M - 1);
+            const float* src = g.ssq + (long long)(g.a_rows ? g.a_rows[m] : m) * g.nparts;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) pre_ss[j][u] = src[min(u * 64 + lane, g.nparts - 1)];
+        }
+    }
+
     // One trip = U MFMA k-steps (32 each).  All weight and activation loads of trip i + 1 are issued
     // before trip i is multiplied (two register sets), so a wavefront always has a trip's worth
     // of loads (U KB of weights) in flight while its matrix pipe is busy.
@@ -841,10 +877,20 @@ void gemm_bf16_skinny_kernel(GemmArgs g) {
     for (int b = 0; b < NB; ++b)
 #pragma unroll
         for (int t = 0; t < MT; ++t) red[wave][b][t][lane] = acc[b][t];
-    if (g.ssq) {                         // deferred RMSNorm: the wavefronts share the rows
-        for (int r = wave; r < MT * 16; r += NW) {
-            const int m = min(r, M - 1);
-            const float inv = wave_inv_rms(g.ssq, g.a_rows ? g.a_rows[m] : m, g.nparts, g.d_norm, g.eps, lane);
+    if (pre_ssq) {                       // deferred RMSNorm: the wavefronts share the rows
+#pragma unroll
+        for (int j = 0; j < (PRE_SSQ ? RPW : 1); ++j) {
+            float v = 0.f;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) v += u * 64 + lane < g.nparts ? pre_ss[j][u] : 0.f;
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+            const int r = wave + j * NW;
+            if (lane == 0 && r < MT * 16) s_inv[r] = 1.0f / sqrtf(v / (float)g.d_norm + g.eps);
+        }
+    } else if (g.ssq) {
+        for (int r = wave; r < min(MT * 16, M); r += NW) {
+            const float inv = wave_inv_rms(g.ssq, g.a_rows ? g.a_rows[r] : r, g.nparts, g.d_norm, g.eps, lane);
             if (lane == 0) s_inv[r] = inv;
         }
     }
