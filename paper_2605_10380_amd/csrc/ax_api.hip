@@ -398,6 +398,11 @@ ax_status enqueue_call(ax_model* m, const CallPlan& cp, void* out, hipStream_t s
     const ax::DType dt = c.dtype == AX_F32 ? ax::F32 : ax::BF16;
     const ax::KVGeom& kg = cp.pool->geom;
     const int out_mode = cp.out_mode, n_out = cp.n_out;
+    // verify calls whose rows fit one LM-head pass: second argmax stage, acceptance and the result's way to the
+    // host in one launch (two launches and a copy node fewer per step)
+    static const bool allow_fused = !(std::getenv("AX_FUSED_ACCEPT") && std::atoi(std::getenv("AX_FUSED_ACCEPT")) == 0);   // measurement switch
+    const bool fused_accept = allow_fused && verify_k >= 0 && n_out > 0 && n_out <= std::min(c.max_tokens, LOGIT_ROWS) &&
+                              n_out <= ax::ACCEPT_MAX_ROWS;
 
     char* ws = m->ws;
     float* x = (float*)(ws + L.x);
@@ -441,7 +446,8 @@ ax_status enqueue_call(ax_model* m, const CallPlan& cp, void* out, hipStream_t s
                     { ProfScope ps(m, 5, stream);
                       ax::launch_gemm(dt, ax::EPI_STORE_F32, (const char*)h + (size_t)r0 * d_model * 4, m->lm_head,
                                       nullptr, logits, rows, c.vocab, d_model, stream); }
-                    ax::launch_argmax(logits, rows, c.vocab, (int*)out + r0, (int*)(ws + L.amax_scratch), stream);
+                    if (fused_accept) ax::launch_argmax_partials(logits, rows, c.vocab, (int*)(ws + L.amax_scratch), stream);
+                    else ax::launch_argmax(logits, rows, c.vocab, (int*)out + r0, (int*)(ws + L.amax_scratch), stream);
                 }
             }
         }
@@ -515,15 +521,21 @@ ax_status enqueue_call(ax_model* m, const CallPlan& cp, void* out, hipStream_t s
                     gc.a_rows = sv.out_rows + r0;            // out_rows lists every row in ALL modes
                     { ProfScope ps(m, 5, stream);
                       ax::launch_gemm_bf16(ax::EPI_STORE_F32, gc, stream); }
-                    ax::launch_argmax(logits, rows, c.vocab, (int*)out + r0, (int*)(ws + L.amax_scratch), stream);
+                    if (fused_accept) ax::launch_argmax_partials(logits, rows, c.vocab, (int*)(ws + L.amax_scratch), stream);
+                    else ax::launch_argmax(logits, rows, c.vocab, (int*)out + r0, (int*)(ws + L.amax_scratch), stream);
                 }
             }
         }
     }
     if (verify_k >= 0) {
         int* res = (int*)(ws + L.result);
-        ax::launch_accept((const int*)out, sv, res, stream);
-        HIP_TRY(hipMemcpyAsync(host_result, res, 2 * sizeof(int) * (size_t)cp.n, hipMemcpyDeviceToHost, stream));
+        if (fused_accept) {
+            // host_result is pinned memory the device addresses directly: the kernel writes it, no copy node
+            ax::launch_argmax_accept((const int*)(ws + L.amax_scratch), n_out, (int*)out, sv, res, host_result, stream);
+        } else {
+            ax::launch_accept((const int*)out, sv, res, stream);
+            HIP_TRY(hipMemcpyAsync(host_result, res, 2 * sizeof(int) * (size_t)cp.n, hipMemcpyDeviceToHost, stream));
+        }
     }
     if (!capturing) {
         HIP_TRY(hipGetLastError());

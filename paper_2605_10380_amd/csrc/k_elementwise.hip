@@ -227,6 +227,54 @@ void launch_accept(const int* g, const StepView& sv, int* result, hipStream_t s)
     accept_kernel<<<sv.n_seq, 64, 0, s>>>(g, sv.row_tok, sv.seq_row0, sv.seq_T, result);
 }
 
+// Stage 2 of the argmax and the acceptance in one launch (a verify step is a chain of launches
+// that each cost a few microseconds whatever they do).  Block = one sequence, 16 wavefronts:
+// wavefront w finishes rows w, w + 16, .. from their stage-1 candidates, the greedy tokens meet
+// in LDS, wavefront 0 votes as accept_kernel does.
+__global__ __launch_bounds__(1024) void argmax_accept_kernel(const float* __restrict__ pv, const int* __restrict__ pi,
+                                                             int* __restrict__ g, const int* __restrict__ row_tok,
+                                                             const int* __restrict__ seq_row0,
+                                                             const int* __restrict__ seq_T, int* __restrict__ result,
+                                                             int* __restrict__ result_host) {
+    __shared__ int s_g[ACCEPT_MAX_ROWS];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, s = blockIdx.x;
+    const int row0 = seq_row0[s], T = seq_T[s], k = T - 1;
+    for (int i = wave; i < T; i += 16) {
+        float bv = pv[(long long)(row0 + i) * ARGMAX_PARTS + lane];
+        int bi = pi[(long long)(row0 + i) * ARGMAX_PARTS + lane];
+        argmax_wave(bv, bi);
+        if (lane == 0) { s_g[i] = bi; g[row0 + i] = bi; }
+    }
+    __syncthreads();
+    if (wave != 0) return;
+    int a = 0;
+    for (int base = 0; base < k; base += 64) {
+        const int i = base + lane;
+        const bool ok = (i < k) && (row_tok[row0 + 1 + i] == s_g[i]);
+        const unsigned long long mism = ~__ballot(ok);
+        const int first_bad = __ffsll((long long)mism) - 1;
+        if (first_bad >= 0) { a = base + first_bad; break; }
+        a = base + 64;
+    }
+    if (a > k) a = k;
+    if (lane == 0) {
+        const int next = s_g[a];
+        result[2 * s] = a;
+        result[2 * s + 1] = next;
+        if (result_host) { result_host[2 * s] = a; result_host[2 * s + 1] = next; }
+    }
+}
+
+void launch_argmax_partials(const float* logits, int rows, int V, int* scratch, hipStream_t s) {
+    argmax_stage1<<<dim3(ARGMAX_PARTS, rows), 256, 0, s>>>(logits, V, (float*)scratch, scratch + (size_t)rows * ARGMAX_PARTS);
+}
+
+void launch_argmax_accept(const int* scratch, int rows, int* g, const StepView& sv, int* result, int* result_host,
+                          hipStream_t s) {
+    argmax_accept_kernel<<<sv.n_seq, 1024, 0, s>>>((const float*)scratch, scratch + (size_t)rows * ARGMAX_PARTS, g,
+                                                   sv.row_tok, sv.seq_row0, sv.seq_T, result, result_host);
+}
+
 // ---------------------------------------------------------------- copy-on-write block copy
 // grid = 2 * n_layers * Hkv planes; each block copies B*hd elements of one plane as 16-byte
 // words (B*hd*itemsize is a multiple of 16 for every supported shape).

@@ -122,6 +122,15 @@ void launch_argmax(const float* logits, int rows, int V, int* out, int* scratch,
 // g[row] the greedy token after each row.  result[2s] = a (longest prefix of the drafts equal to
 // g), result[2s + 1] = g[row0 + a].
 void launch_accept(const int* g, const StepView& sv, int* result, hipStream_t s);
+// The same two steps fused for verify calls whose rows fit one LM-head pass: launch_argmax_partials
+// is stage 1 alone (per row ARGMAX_PARTS (value, id) candidates into scratch), launch_argmax_accept
+// finishes every row of a sequence (g[row], as launch_argmax would write it), votes, and writes
+// (a, next token) to result and - when result_host is given: pinned host memory the device can
+// address - straight to the host, so no copy has to follow.  At most ACCEPT_MAX_ROWS rows per sequence.
+constexpr int ACCEPT_MAX_ROWS = 1024;
+void launch_argmax_partials(const float* logits, int rows, int V, int* scratch, hipStream_t s);
+void launch_argmax_accept(const int* scratch, int rows, int* g, const StepView& sv, int* result, int* result_host,
+                          hipStream_t s);
 // Plain copy of n16 16-byte words (calibration kernel for hardware counters).
 void launch_plain_copy(void* dst, const void* src, size_t n16, hipStream_t s);
 void launch_read_stream(const void* src, size_t n16, void* sink, hipStream_t s);   // read-only stream; sink: 4 writable bytes, never written
