@@ -456,8 +456,9 @@ ax_status enqueue_call(ax_model* m, const CallPlan& cp, void* out, hipStream_t s
         // writes x (gain-scaled fp16 copy + per-row partial sums of x^2) and the GEMM that reads
         // it (1/rms in the epilogue); rotary embedding and the KV append live in the QKV epilogue.
         float* ssq = (float*)(ws + L.ssq);
-        // partial sums of x^2 per row: as many as the GEMM that wrote x produces (O projection / down projection)
-        const int nparts_o = ax::gemm_ssq_parts(R, d_model, qdim), nparts = ax::gemm_ssq_parts(R, d_model, c.d_ff);
+        // partial sums of x^2 per row behind the pending norm: as many as the launch that wrote x left (the
+        // embedding leaves one; the O and down projections report theirs)
+        int nparts = 1;
         ax::GemmArgs base{};
         base.M = R;
         base.split_ws = (float*)(ws + L.splitk);
@@ -483,12 +484,11 @@ ax_status enqueue_call(ax_model* m, const CallPlan& cp, void* out, hipStream_t s
                 g.A = attn; g.K = qdim; g.W = m->wo[(size_t)l]; g.N = d_model;
                 g.Cf = x; g.C16 = h; g.gain_next = m->norm_mlp[(size_t)l]; g.ssq_out = ssq;
                 ProfScope ps(m, 2, stream);
-                ax::launch_gemm_bf16(ax::EPI_RESIDUAL, g, stream);
+                nparts = ax::launch_gemm_bf16(ax::EPI_RESIDUAL, g, stream);
             }
             {
                 ax::GemmArgs g = base;
                 normed(g);
-                g.nparts = nparts_o;
                 g.W = m->w_gate[(size_t)l]; g.W2 = m->w_up[(size_t)l]; g.N = c.d_ff; g.C16 = ffn;
                 ProfScope ps(m, 3, stream);
                 ax::launch_gemm_bf16(ax::EPI_SWIGLU, g, stream);
@@ -499,7 +499,7 @@ ax_status enqueue_call(ax_model* m, const CallPlan& cp, void* out, hipStream_t s
                 g.Cf = x; g.C16 = h; g.ssq_out = ssq;
                 g.gain_next = l + 1 < c.n_layers ? m->norm_attn[(size_t)l + 1] : m->final_norm;
                 ProfScope ps(m, 4, stream);
-                ax::launch_gemm_bf16(ax::EPI_RESIDUAL, g, stream);
+                nparts = ax::launch_gemm_bf16(ax::EPI_RESIDUAL, g, stream);
             }
         }
         if (n_out > 0) {
@@ -1289,8 +1289,7 @@ ax_status ax_dbg_gemm_residual(const void* A, const void* W, const void* gain, f
     g.Cf = x; g.C16 = a16; g.gain_next = gain; g.ssq_out = ssq;
     g.split_ws = split_ws_bytes ? (float*)split_ws : nullptr;
     g.split_ws_bytes = split_ws_bytes;
-    *n_parts = ax::gemm_ssq_parts(M, N, K);
-    ax::launch_gemm_bf16(ax::EPI_RESIDUAL, g, s);
+    *n_parts = ax::launch_gemm_bf16(ax::EPI_RESIDUAL, g, s);
     hipError_t e = hipGetLastError();
     if (e == hipSuccess) e = hipStreamSynchronize(s);
     (void)hipFree(pw);

@@ -116,11 +116,19 @@ __device__ __forceinline__ float wave_inv_rms(const float* __restrict__ ssq, int
 }
 
 // Block-wide: 1 / rms of `rows` A-rows into s_inv[0..rows).  Half a wavefront (32 lanes) owns a
-// row and a thread works on INV_BATCH rows at a time: their 4 x INV_BATCH loads are in flight
-// together, so the table costs one memory round trip per INV_BATCH rows of a thread (and per 128
-// partials of a row), not one per load.  The caller synchronises before reading s_inv.
+// row and a thread works on INV_BATCH rows at a time (a power of two up to 16): their
+// 4 x INV_BATCH loads are in flight together, so the table costs one memory round trip per
+// INV_BATCH rows of a thread (and per 128 partials of a row), not one per load.
+// The INV_BATCH per-lane sums are then added across the 32 lanes with a transposing butterfly:
+// at each stage a lane hands half of its values to its partner and keeps the other half, so the
+// batch costs INV_BATCH - 1 + (5 - log2 INV_BATCH) cross-lane exchanges instead of 5 per row and
+// ends with each row's total in its own lanes - one division and square root per thread, not one
+// per row.  (Five exchanges and a square root per row, one row after the other, were ~4 us of a
+// 128-row block's prologue.)  The caller synchronises before reading s_inv.
 template <int INV_BATCH>
 __device__ __forceinline__ void block_inv_rms(const GemmArgs& g, int first_row, int rows, float* s_inv) {
+    static_assert(INV_BATCH == 1 || INV_BATCH == 2 || INV_BATCH == 4 || INV_BATCH == 8 || INV_BATCH == 16, "power of two up to 16");
+    constexpr int LOG = INV_BATCH == 16 ? 4 : INV_BATCH == 8 ? 3 : INV_BATCH == 4 ? 2 : INV_BATCH == 2 ? 1 : 0;
     const int hw = threadIdx.x >> 5, hl = threadIdx.x & 31, nhw = blockDim.x >> 5;
     for (int base = 0; base < rows; base += INV_BATCH * nhw) {
         long long src[INV_BATCH];
@@ -142,12 +150,47 @@ __device__ __forceinline__ void block_inv_rms(const GemmArgs& g, int first_row, 
 #pragma unroll
                 for (int u = 0; u < 4; ++u) v[p] += q0 + u * 32 + hl < g.nparts ? t[p][u] : 0.f;
         }
+        // stage st: partner = lane ^ (16 >> st); the lane with that bit set keeps the upper half of
+        // the remaining values, so after LOG stages it holds the row whose index (within the batch)
+        // is the top LOG bits of its lane number
 #pragma unroll
-        for (int p = 0; p < INV_BATCH; ++p) {
+        for (int st = 0; st < LOG; ++st) {
+            const int n = INV_BATCH >> st, o = 16 >> st;
+            const bool upper = (hl & o) != 0;
 #pragma unroll
-            for (int o = 16; o > 0; o >>= 1) v[p] += __shfl_xor(v[p], o, 64);
-            const int r = base + p * nhw + hw;
-            if (hl == 0 && r < rows) s_inv[r] = 1.0f / sqrtf(v[p] / (float)g.d_norm + g.eps);
+            for (int j = 0; j < n / 2; ++j) {
+                const float send = upper ? v[j] : v[j + n / 2];
+                const float keep = upper ? v[j + n / 2] : v[j];
+                v[j] = keep + __shfl_xor(send, o, 64);
+            }
+        }
+#pragma unroll
+        for (int o = 16 >> LOG; o > 0; o >>= 1) v[0] += __shfl_xor(v[0], o, 64);
+        const int r = base + (hl >> (5 - LOG)) * nhw + hw;
+        if ((hl & ((32 >> LOG) - 1)) == 0 && r < rows) s_inv[r] = 1.0f / sqrtf(v[0] / (float)g.d_norm + g.eps);
+    }
+}
+
+// The same for rows that left at most 4 partial sums behind (their producer was a K-split GEMM's
+// reduce kernel, or the embedding): four lanes per row, one load each, the rows of up to four
+// passes in flight together - cheap enough in registers to sit behind the operand loads of a
+// kernel's prologue, where its cold misses overlap theirs.
+__device__ __forceinline__ void block_inv_rms_few(const GemmArgs& g, int first_row, int rows, float* s_inv) {
+    const int p = threadIdx.x & 3, per_pass = blockDim.x >> 2;
+    for (int base = 0; base < rows; base += 4 * per_pass) {
+        float v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int gm = min(first_row + min(base + u * per_pass + (int)(threadIdx.x >> 2), rows - 1), g.M - 1);
+            v[u] = g.ssq[(long long)(g.a_rows ? g.a_rows[gm] : gm) * g.nparts + min(p, g.nparts - 1)];
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            float t = p < g.nparts ? v[u] : 0.f;
+            t += __shfl_xor(t, 1, 64);
+            t += __shfl_xor(t, 2, 64);
+            const int r = base + u * per_pass + (int)(threadIdx.x >> 2);
+            if (p == 0 && r < rows) s_inv[r] = 1.0f / sqrtf(t / (float)g.d_norm + g.eps);
         }
     }
 }
@@ -256,7 +299,12 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_tile_kernel(GemmArgs g
 #pragma unroll
     for (int s = 0; s < D; ++s)
         if (s < nsteps) load_global(s, s * BK);
-    if (g.ssq) block_inv_rms<4>(g, m0, BM, s_inv);   // deferred RMSNorm: 1/rms of this block's rows (a batch of 4 rows per thread = 64 rows: more in flight would cost the 64-row blocks their second block per CU)
+    // deferred RMSNorm: 1/rms of this block's rows, 64 rows per batch (more loads in flight would cost the 64-row
+    // blocks the registers for their second block per CU)
+    if (g.ssq) {
+        if (g.nparts <= 4) block_inv_rms_few(g, m0, BM, s_inv);
+        else block_inv_rms<BM >= 128 ? 4 : 2>(g, m0, BM, s_inv);
+    }
     store_lds(0, 0);
     __syncthreads();
     // steady state: groups of D steps with every load and store unconditional (branch-free, so
@@ -378,30 +426,53 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_tile_kernel(GemmArgs g
 }
 
 // Second half of a K-split residual GEMM: x += sum of the K-slice partials (in slice order),
-// a = fp16(x * gain_next), per-row partial sums of x^2 over blocks of 32 columns (the layout the
-// unsplit tile kernel writes).  One wavefront per (row, 64 columns); N % 64 == 0.
+// a = fp16(x * gain_next), and the sum of x^2 over the block's columns.  Block = 1024 columns of
+// one row (four per thread, every operand requested before anything is added), so a row leaves
+// only ceil(N / 1024) partial sums behind - the GEMM that consumes the pending norm reads 2-4
+// values per row instead of N / 32.  grid (ceil(N / 1024), M); N % 4 == 0.
+constexpr int REDUCE_COLS = 1024;
 __global__ __launch_bounds__(256) void residual_reduce_kernel(GemmArgs g) {
-    const int lane = threadIdx.x & 63;
-    const long long item = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
-    const int nb = g.N / 64;
-    if (item >= (long long)g.M * nb) return;
-    const int m = (int)(item / nb), n = (int)(item % nb) * 64 + lane;
-    const long long o = (long long)m * g.N + n, slab = (long long)g.M * g.N;
-    float part[SPLITK_MAX];
+    __shared__ float s_ss[4];
+    const int m = blockIdx.y, n = (blockIdx.x * 256 + threadIdx.x) * 4;
+    const bool live = n < g.N;
+    const int nc = min(n, g.N - 4);
+    const long long o = (long long)m * g.N + nc, slab = (long long)g.M * g.N;
+    f32x4 part[SPLITK_MAX];
 #pragma unroll
-    for (int ks = 0; ks < SPLITK_MAX; ++ks) part[ks] = ks < g.ksplit ? g.split_ws[ks * slab + o] : 0.f;
-    float xn = g.Cf[o];
-    const float gain = g.gain_next ? (float)((const bf16*)g.gain_next)[n] : 0.f;
+    for (int ks = 0; ks < SPLITK_MAX; ++ks)
+        part[ks] = ks < g.ksplit ? *(const f32x4*)(g.split_ws + ks * slab + o) : (f32x4){0.f, 0.f, 0.f, 0.f};
+    f32x4 xn = *(const f32x4*)(g.Cf + o);
+    float gain[4] = {0.f, 0.f, 0.f, 0.f};
+    if (g.gain_next) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) gain[r] = (float)((const bf16*)g.gain_next)[nc + r];
+    }
 #pragma unroll
     for (int ks = 0; ks < SPLITK_MAX; ++ks) xn += part[ks];
-    g.Cf[o] = xn;
+    if (live) *(f32x4*)(g.Cf + o) = xn;
     if (g.gain_next) {
-        ((f16*)g.C16)[o] = (f16)(xn * gain);
-        float ss = xn * xn;
+        float ss = 0.f;
+        if (live) {
+            f16x4 h;
 #pragma unroll
-        for (int w = 16; w > 0; w >>= 1) ss += __shfl_xor(ss, w, 64);
-        if ((lane & 31) == 0) g.ssq_out[(long long)m * (g.N / 32) + n / 32] = ss;
+            for (int r = 0; r < 4; ++r) {
+                h[r] = (f16)(xn[r] * gain[r]);
+                ss += xn[r] * xn[r];
+            }
+            *(f16x4*)((f16*)g.C16 + o) = h;
+        }
+#pragma unroll
+        for (int w = 32; w > 0; w >>= 1) ss += __shfl_xor(ss, w, 64);
+        if ((threadIdx.x & 63) == 0) s_ss[threadIdx.x >> 6] = ss;
+        __syncthreads();
+        if (threadIdx.x == 0) g.ssq_out[(long long)m * gridDim.x + blockIdx.x] = (s_ss[0] + s_ss[1]) + (s_ss[2] + s_ss[3]);
     }
+}
+// launches it; returns the partial sums per row it leaves
+static int launch_residual_reduce(const GemmArgs& g, hipStream_t s) {
+    const int parts = (g.N + REDUCE_COLS - 1) / REDUCE_COLS;
+    residual_reduce_kernel<<<dim3((unsigned)parts, (unsigned)g.M), 256, 0, s>>>(g);
+    return parts;
 }
 
 // Second half of a K-split QKV GEMM: sums the K-slice partials, applies 1 / rms of the row,
@@ -585,10 +656,13 @@ __global__ __launch_bounds__(256) void gemm_bf16_stream_kernel(GemmArgs g, int g
     // deferred RMSNorm: 1/rms of this block's rows, before the operand rings take the registers (16
     // rows x 4 loads per thread in flight: one or two round trips; behind the ring loads the same
     // table cost four to six, 10-15 % of the launch at 512-1024 rows).  Sliced SwiGLU: the reduce kernel scales.
-    if (g.ssq && !(EPI == EPI_SWIGLU && SLICED)) block_inv_rms<16>(g, m0, BM, s_inv);
+    // Few partials per row (K-split producer): behind the ring loads, their cold misses overlap.
+    const bool inv_here = g.ssq && !(EPI == EPI_SWIGLU && SLICED);
+    if (inv_here && g.nparts > 4) block_inv_rms<16>(g, m0, BM, s_inv);
 #pragma unroll
     for (int s = 0; s < D; ++s)
         if (s < nsteps) load_global(s, s * BK);
+    if (inv_here && g.nparts <= 4) block_inv_rms_few(g, m0, BM, s_inv);
     store_lds(0, 0);
     __syncthreads();
     // steady state, branch free: multiply step s out of ring slot s % D and LDS buffer s % 2,
@@ -1028,7 +1102,7 @@ static const int kResTile = env_int("AX_RES_TILE", -1);
 static const int kResBig = env_int("AX_RES_BIG", 256);
 static const int kQkvKs = env_int("AX_QKV_KS", 0);   // experiment knob: K slices of the QKV GEMM (1 = never split)
 template <int EPI>
-static void launch_lds_tile(const GemmArgs& g, hipStream_t s) {
+static int launch_lds_tile(const GemmArgs& g, hipStream_t s) {
     const int M = g.M, N = g.N, K = g.K;
     // Two block shapes, both of 8 wavefronts: 64 x 128 (2 x 4 wavefronts of 32 x 32) and 128 x 128
     // (wavefront tile 64 x 32).  The larger one pulls a third fewer operand bytes per output and
@@ -1070,7 +1144,7 @@ static void launch_lds_tile(const GemmArgs& g, hipStream_t s) {
             const int gx = (N + 255) / 256, gy = (M + 127) / 128;
             gemm_bf16_stream_kernel<EPI_STORE_F32, 4, 3><<<gx * gy, 256, 0, s>>>(gp, gx, gy);
             qkv_reduce_rope_kernel<<<dim3((unsigned)M, (unsigned)((N / 2 + 255) / 256)), 256, 0, s>>>(gs);
-            return;
+            return 0;
         }
         // A plain store GEMM writes fp32 products, a second kernel does the rms scaling, rotary
         // embedding and KV append: measured faster than a fused epilogue (one head per wavefront)
@@ -1097,20 +1171,19 @@ static void launch_lds_tile(const GemmArgs& g, hipStream_t s) {
             gemm_bf16_tile_kernel<EPI_STORE_F32, 1, 1, 2, 4><<<grid, 512, 0, s>>>(gp);
         }
         qkv_reduce_rope_kernel<<<dim3((unsigned)M, (unsigned)((N / 2 + 255) / 256)), 256, 0, s>>>(gs);
-        return;
+        return 0;
     } else if constexpr (EPI == EPI_RESIDUAL) {
         if (mid_ks > 1 && mid_cb * mid_ks >= 160) {            // (~1B width: 128 blocks, slower than the tile kernels)
             GemmArgs gs = g;
             gs.ksplit = mid_ks;
             if (M <= 160) gemm_bf16_stream_kernel<EPI_RESIDUAL, 5, 3, 1, true><<<mid_cb * mid_ks, 256, 0, s>>>(gs, mid_cb, 1);
             else gemm_bf16_stream_kernel<EPI_RESIDUAL, 6, 3, 1, true><<<mid_cb * mid_ks, 256, 0, s>>>(gs, mid_cb, 1);
-            residual_reduce_kernel<<<(unsigned)(((long long)M * (N / 64) + 3) / 4), 256, 0, s>>>(gs);
-            return;
+            return launch_residual_reduce(gs, s);
         }
         if (stream) {
             const int gx = (N + 255) / 256, gy = (M + 127) / 128;
             gemm_bf16_stream_kernel<EPI_RESIDUAL, 4, 3><<<gx * gy, 256, 0, s>>>(g, gx, gy);
-            return;
+            return N / 32;
         }
         // a few hundred rows against the long K of the down projection: too few 128 x 256 blocks for
         // the streaming kernel as it is, enough once K is cut into 2-4 slices (160-256 blocks).
@@ -1127,8 +1200,7 @@ static void launch_lds_tile(const GemmArgs& g, hipStream_t s) {
                 gs.ksplit = ks;
                 const int gx = (N + 255) / 256, gy = (M + 127) / 128;
                 gemm_bf16_stream_kernel<EPI_RESIDUAL, 4, 3, 2, true><<<gx * gy * ks, 256, 0, s>>>(gs, gx, gy);
-                residual_reduce_kernel<<<(unsigned)(((long long)M * (N / 64) + 3) / 4), 256, 0, s>>>(gs);
-                return;
+                return launch_residual_reduce(gs, s);
             }
         }
         // Few output tiles (M = 256 against N = 2048 is 64 tiles of 64 x 128 for 256 CUs): cut K
@@ -1159,8 +1231,7 @@ static void launch_lds_tile(const GemmArgs& g, hipStream_t s) {
             dim3 grid((N + 127) / 128, (M + 63) / 64, ks);
             gemm_bf16_tile_kernel<EPI_RESIDUAL, 1, 1, 2, 4><<<grid, 512, 0, s>>>(gs);
         }
-        if (ks > 1) residual_reduce_kernel<<<(unsigned)(((long long)M * (N / 64) + 3) / 4), 256, 0, s>>>(gs);
-        return;
+        return ks > 1 ? launch_residual_reduce(gs, s) : N / 32;
     } else if constexpr (EPI == EPI_SWIGLU) {
         // 17-192 rows: one streaming block of all the rows (32 to 192) per 128 columns, over K slices
         // (raw gate | up products in slabs, swiglu_reduce_kernel finishes): every weight is read
@@ -1189,7 +1260,7 @@ static void launch_lds_tile(const GemmArgs& g, hipStream_t s) {
                     default: gemm_bf16_stream_kernel<EPI_SWIGLU, 6, 3, 2, true><<<nb, 256, 0, s>>>(gs, cb, 1); break;
                 }
                 swiglu_reduce_kernel<<<dim3((unsigned)M, (unsigned)((N + 255) / 256)), 256, 0, s>>>(gs);
-                return;
+                return 0;
             }
         }
         // gate/up with two or more 128-row tiles: 128 x 64 tiles make a CU pull (128 + 2 * 64) rows of
@@ -1197,7 +1268,7 @@ static void launch_lds_tile(const GemmArgs& g, hipStream_t s) {
         if (M > 128) {
             dim3 tgrid((N + 63) / 64, (M + 127) / 128);
             gemm_bf16_tile_kernel<EPI_SWIGLU, 1, 1, 4, 2><<<tgrid, 512, 0, s>>>(g);
-            return;
+            return 0;
         }
     }
     if constexpr (EPI == EPI_STORE_F32 || EPI == EPI_SWIGLU) {
@@ -1228,16 +1299,17 @@ static void launch_lds_tile(const GemmArgs& g, hipStream_t s) {
                 case 5: gemm_bf16_stream_kernel<EPI_STORE_F32, 5, 3><<<gx * gy, 256, 0, s>>>(g, gx, gy); break;
                 default: gemm_bf16_stream_kernel<EPI_STORE_F32, 6, 3><<<gx * gy, 256, 0, s>>>(g, gx, gy); break;
             }
-            return;
+            return 0;
         }
         if (EPI == EPI_STORE_F32 && stream) {              // logits of thousands of rows
             const int gx = (N + 255) / 256, gy = (M + 127) / 128;
             gemm_bf16_stream_kernel<EPI_STORE_F32, 4, 3><<<gx * gy, 256, 0, s>>>(g, gx, gy);
-            return;
+            return 0;
         }
         dim3 grid((N + 127) / 128, (M + 63) / 64);
         gemm_bf16_tile_kernel<EPI, 1, 1, 2, 4><<<grid, 512, 0, s>>>(g);
     }
+    return 0;
 }
 
 // Which rows go to the skinny kernel: a block of it re-reads the whole activation slice of its
@@ -1258,7 +1330,7 @@ static bool use_skinny(int epi, int M, int N, int K) {
 }
 
 template <int EPI>
-static void launch_bf16(const GemmArgs& g, hipStream_t s) {
+static int launch_bf16(const GemmArgs& g, hipStream_t s) {
     const int M = g.M, N = g.N, K = g.K;
     if (use_skinny(EPI, M, N, K)) {
         // wavefronts per block (= K slices): enough to keep ~2k wavefronts in flight (~4k for the SwiGLU
@@ -1273,7 +1345,7 @@ static void launch_bf16(const GemmArgs& g, hipStream_t s) {
         if (EPI == EPI_SWIGLU && nw == 16) nw = 8;        // LDS reduction buffer stays <= 64 KB
         if (M <= 16) launch_skinny_nw<EPI, 1>(g, nw, s);
         else launch_skinny_nw<EPI, 2>(g, nw, s);
-        return;
+        return EPI == EPI_RESIDUAL ? N / cols : 0;
     }
     // streaming SwiGLU kernel: from three 128-row blocks up, and with two when the matrix is wide
     // enough for ~200 blocks (~8B shape at 193-256 rows: 118 -> 97 us; ~1B / ~3B have 128 blocks
@@ -1300,18 +1372,16 @@ static void launch_bf16(const GemmArgs& g, hipStream_t s) {
             case 6: gemm_bf16_stream_kernel<EPI_SWIGLU, 6, 3><<<gx * gy, 256, 0, s>>>(g, gx, gy); break;
             default: gemm_bf16_stream_kernel<EPI_SWIGLU, 4, 3><<<gx * gy, 256, 0, s>>>(g, gx, gy); break;
         }
-        return;
+        return 0;
     }
-    launch_lds_tile<EPI>(g, s);
+    return launch_lds_tile<EPI>(g, s);
 }
 
-int gemm_ssq_parts(int M, int N, int K) { return use_skinny(EPI_RESIDUAL, M, N, K) ? N / skinny_cols(EPI_RESIDUAL, N) : N / 32; }
-
-void launch_gemm_bf16(Epilogue epi, const GemmArgs& g, hipStream_t s) {
-    if (epi == EPI_STORE_F32) launch_bf16<EPI_STORE_F32>(g, s);
-    else if (epi == EPI_RESIDUAL) launch_bf16<EPI_RESIDUAL>(g, s);
-    else if (epi == EPI_SWIGLU) launch_bf16<EPI_SWIGLU>(g, s);
-    else launch_bf16<EPI_QKV>(g, s);
+int launch_gemm_bf16(Epilogue epi, const GemmArgs& g, hipStream_t s) {
+    if (epi == EPI_STORE_F32) return launch_bf16<EPI_STORE_F32>(g, s);
+    if (epi == EPI_RESIDUAL) return launch_bf16<EPI_RESIDUAL>(g, s);
+    if (epi == EPI_SWIGLU) return launch_bf16<EPI_SWIGLU>(g, s);
+    return launch_bf16<EPI_QKV>(g, s);
 }
 
 void launch_gemm(DType dt, Epilogue epi, const void* A, const void* W, const void* W2, void* C,

@@ -71,7 +71,7 @@ struct GemmArgs {
     float* Cf;                        // EPI_STORE_F32: out [M,N]; EPI_RESIDUAL: x [M,N], updated in place
     void* C16;                        // EPI_SWIGLU: fp16 out [M,N]; EPI_RESIDUAL: fp16(x * gain_next) [M,N]
     const void* gain_next;            // EPI_RESIDUAL: bf16 [N] gain of the next norm, NULL = plain residual add
-    float* ssq_out;                   // EPI_RESIDUAL: [M][gemm_ssq_parts(M, N, K)] partial sums of x^2
+    float* ssq_out;                   // EPI_RESIDUAL: [M][parts] partial sums of x^2, parts = what launch_gemm_bf16 returns
     RopeArgs rope;                    // EPI_QKV
     // EPI_RESIDUAL on the tile kernels with few output tiles: K may be cut into ksplit slices (chosen by
     // the launcher) whose fp32 partial products go to split_ws [ksplit][M][N]; a second kernel
@@ -81,12 +81,14 @@ struct GemmArgs {
     int ksplit;
 };
 constexpr int SPLITK_MAX = 8;
-void launch_gemm_bf16(Epilogue epi, const GemmArgs& g, hipStream_t s);
+// EPI_RESIDUAL with gain_next: returns the number of partial sums of x^2 per row the launch leaves in
+// ssq_out (rows are that many floats apart): the consumer of the pending norm passes it as nparts.
+// It depends on which kernel ran (a few per row after a K-split reduce kernel, N / 32 or N / 8-16
+// from kernels that finish a column block on their own).  Other epilogues return 0.
+int launch_gemm_bf16(Epilogue epi, const GemmArgs& g, hipStream_t s);
 // Repacks a row-major bf16 [N, K] matrix (N % 16 == 0, K % 32 == 0) into what every bf16-model GEMM
 // kernel reads: fp16 values in 16-row panels, 32-k chunks in MFMA operand order; src and dst must not overlap.
 void launch_pack_weights(const void* src, void* dst, int N, int K, hipStream_t s);
-// Number of sum-of-squares partials per row that an EPI_RESIDUAL launch with this M, N, K writes.
-int gemm_ssq_parts(int M, int N, int K);
 // bf16-weight models: x[r,:] = emb[tok], a[r,:] = fp16(x * gain), ssq[r][0] = sum x^2, ssq[r][1..nparts) = 0
 void launch_embed_norm(const void* emb, const int* row_tok, const void* gain, float* x, void* a,
                        float* ssq, int nparts, int n_rows, int d, hipStream_t s);
