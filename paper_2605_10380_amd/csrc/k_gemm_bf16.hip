@@ -806,6 +806,13 @@ void gemm_bf16_skinny_kernel(GemmArgs g) {
     const bool wlane = lr < COLS;      // COLS < 16: the other MFMA rows are zero, their lanes request nothing
     const bf16* wp = W + packed_row(wrow, K) + lg * PK_KG;          // packed layout: k advances by 32 -> + 512 elements
     const bf16* wp2 = NB == 2 ? W2 + packed_row(wrow, K) + lg * PK_KG : nullptr;
+    // 8-column blocks: a load instruction costs the memory pipeline the same with half of its lanes
+    // idle (the 8 MFMA rows that are not there), and these launches are bound by exactly that - a CU
+    // pulled 16 GB/s of weights against 26 GB/s from 16-column blocks.  So the upper half of each
+    // 16-lane row fetches the block's 8 rows at the NEXT k-step (one chunk further), and for that
+    // step the operand is shifted down 8 lanes; MFMA rows 8-15 then hold products nobody reads.
+    constexpr bool DUAL = COLS == 8 && MT <= 2 && NB == 1;
+    const bf16* wpd = W + packed_row(min(n0 + (lr & 7), N - 1), K) + lg * PK_KG + (lr >> 3) * PK_CHUNK;
     const f16* xp[MT];
 #pragma unroll
     for (int t = 0; t < MT; ++t) {
@@ -870,25 +877,46 @@ void gemm_bf16_skinny_kernel(GemmArgs g) {
     int k = kbeg;
     if constexpr (MT <= 2) {
         constexpr int U = 4, S = 32 * U;
-        u32x4 rw[2][NB][U];
+        u32x4 rw[2][NB][DUAL ? U / 2 : U];
         f16x8 fx[2][MT][U];
-        auto loads = [&](int set, int kk) {
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                rw[set][0][u] = (COLS == 16 || wlane) ? __builtin_nontemporal_load((const u32x4*)(wp + (long long)(kk + 32 * u) * 16)) : (u32x4){0u, 0u, 0u, 0u};
-                if (NB == 2) rw[set][NB - 1][u] = __builtin_nontemporal_load((const u32x4*)(wp2 + (long long)(kk + 32 * u) * 16));
-            }
+        for (int set = 0; set < 2; ++set)
 #pragma unroll
             for (int t = 0; t < MT; ++t)
 #pragma unroll
-                for (int u = 0; u < U; ++u) fx[set][t][u] = *(const f16x8*)(xp[t] + kk + 32 * u);
+                for (int u = 0; u < U; ++u) fx[set][t][u] = (f16x8){0, 0, 0, 0, 0, 0, 0, 0};   // rows past M stay zero
+        auto loads = [&](int set, int kk) {
+            if constexpr (DUAL) {
+#pragma unroll
+                for (int v = 0; v < U / 2; ++v) rw[set][0][v] = __builtin_nontemporal_load((const u32x4*)(wpd + (long long)(kk + 64 * v) * 16));
+            } else {
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    rw[set][0][u] = (COLS == 16 || wlane) ? __builtin_nontemporal_load((const u32x4*)(wp + (long long)(kk + 32 * u) * 16)) : (u32x4){0u, 0u, 0u, 0u};
+                    if (NB == 2) rw[set][NB - 1][u] = __builtin_nontemporal_load((const u32x4*)(wp2 + (long long)(kk + 32 * u) * 16));
+                }
+            }
+            // activation rows past M: no load (a block re-reads its wavefronts' whole activation slice, and at
+            // 9 rows of 16 that is most of what the CU's load pipeline carries)
+#pragma unroll
+            for (int t = 0; t < MT; ++t) {
+                if (EPI == EPI_SWIGLU || t * 16 + lr < M) {   // (SwiGLU: two weight streams per activation load, and no register to spare for the mask)
+#pragma unroll
+                    for (int u = 0; u < U; ++u) fx[set][t][u] = *(const f16x8*)(xp[t] + kk + 32 * u);
+                }
+            }
         };
         auto compute = [&](int set) {
 #pragma unroll
             for (int u = 0; u < U; ++u)
 #pragma unroll
                 for (int b = 0; b < NB; ++b) {
-                    const f16x8 fw = __builtin_bit_cast(f16x8, rw[set][b][u]);
+                    u32x4 raw = rw[set][b][DUAL ? u >> 1 : u];
+                    if (DUAL && (u & 1)) {                 // odd k-step: lanes 8-15 of each row hold it; row_shl:8 brings it to lanes 0-7
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) raw[i] = (unsigned)__builtin_amdgcn_update_dpp(0, (int)raw[i], 0x108, 0xf, 0xf, true);
+                    }
+                    const f16x8 fw = __builtin_bit_cast(f16x8, raw);
 #pragma unroll
                     for (int t = 0; t < MT; ++t)
                         acc[b][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fw, fx[set][t][u], acc[b][t], 0, 0, 0);
