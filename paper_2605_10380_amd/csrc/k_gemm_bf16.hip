@@ -871,6 +871,22 @@ void gemm_bf16_skinny_kernel(GemmArgs g) {
         }
     }
 
+    // ... and turned into 1 / rms while the first trip's operands are on their way (the partial sums were
+    // requested before them, so waiting for these does not wait for those): nothing of it is left after the K loop,
+    // and its registers are free during the loop.
+    auto finish_pre_ssq = [&]() {
+#pragma unroll
+        for (int j = 0; j < (PRE_SSQ ? RPW : 1); ++j) {
+            float v = 0.f;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) v += u * 64 + lane < g.nparts ? pre_ss[j][u] : 0.f;
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+            const int r = wave + j * NW;
+            if (lane == 0 && r < MT * 16) s_inv[r] = 1.0f / sqrtf(v / (float)g.d_norm + g.eps);
+        }
+    };
+
     // One trip = U MFMA k-steps (32 each).  All weight and activation loads of trip i + 1 are issued
     // before trip i is multiplied (two register sets), so a wavefront always has a trip's worth
     // of loads (U KB of weights) in flight while its matrix pipe is busy.
@@ -900,7 +916,7 @@ void gemm_bf16_skinny_kernel(GemmArgs g) {
             // 9 rows of 16 that is most of what the CU's load pipeline carries)
 #pragma unroll
             for (int t = 0; t < MT; ++t) {
-                if (EPI == EPI_SWIGLU || t * 16 + lr < M) {   // (SwiGLU: two weight streams per activation load, and no register to spare for the mask)
+                if (t * 16 + lr < M) {
 #pragma unroll
                     for (int u = 0; u < U; ++u) fx[set][t][u] = *(const f16x8*)(xp[t] + kk + 32 * u);
                 }
@@ -924,6 +940,7 @@ void gemm_bf16_skinny_kernel(GemmArgs g) {
         };
         const int ntr = kslice / S;
         if (ntr > 0) loads(0, kbeg);
+        if (pre_ssq) finish_pre_ssq();
         int t = 0;
         for (; t + 2 < ntr; t += 2) {                                // both loads unconditional
             loads(1, kbeg + (t + 1) * S);
@@ -980,16 +997,7 @@ void gemm_bf16_skinny_kernel(GemmArgs g) {
 #pragma unroll
         for (int t = 0; t < MT; ++t) red[wave][b][t][lane] = acc[b][t];
     if (pre_ssq) {                       // deferred RMSNorm: the wavefronts share the rows
-#pragma unroll
-        for (int j = 0; j < (PRE_SSQ ? RPW : 1); ++j) {
-            float v = 0.f;
-#pragma unroll
-            for (int u = 0; u < 4; ++u) v += u * 64 + lane < g.nparts ? pre_ss[j][u] : 0.f;
-#pragma unroll
-            for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-            const int r = wave + j * NW;
-            if (lane == 0 && r < MT * 16) s_inv[r] = 1.0f / sqrtf(v / (float)g.d_norm + g.eps);
-        }
+        if (MT > 2) finish_pre_ssq();    // (the MT <= 2 loop did it behind its first loads)
     } else if (g.ssq) {
         for (int r = wave; r < min(MT * 16, M); r += NW) {
             const float inv = wave_inv_rms(g.ssq, g.a_rows ? g.a_rows[r] : r, g.nparts, g.d_norm, g.eps, lane);
