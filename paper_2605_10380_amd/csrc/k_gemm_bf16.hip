@@ -1120,7 +1120,7 @@ static int env_int(const char* name, int dflt) {
     const char* v = std::getenv(name);
     return v && *v ? std::atoi(v) : dflt;
 }
-static const int kSwigluStreamMinNK = env_int("AX_SWIGLU_STREAM_MIN_NK", 40);   // gate/up weights (2^20) per matrix from which verify-size calls stream
+static const int kSwigluStreamMinNK = env_int("AX_SWIGLU_STREAM_MIN_NK", 0);   // measurement switch: gate/up weights (2^20) per matrix from which verify-size calls stream (0 = never)
 static const int kStreamTm = env_int("AX_STREAM_TM", 1);   // experiment knob: 0 = always 128-row blocks
 static const int kSwigluWaves = env_int("AX_SWIGLU_WAVES", 4096);   // wavefronts in flight the SwiGLU launch aims for (two weight streams per wavefront)
 static const int kLmStream = env_int("AX_LM_STREAM", 1);   // experiment knob
@@ -1356,9 +1356,11 @@ static int launch_lds_tile(const GemmArgs& g, hipStream_t s) {
 // (~3B at 17-32 rows: 18-22 -> 17-19 us and 18-23 -> 15-16 us) and so is the SwiGLU GEMM on its
 // K-sliced streaming blocks (see launch_lds_tile); the O projection is not.
 static bool use_skinny(int epi, int M, int N, int K) {
-    // the largest gate/up matrices (~8B shape, 2 x 59 M weights) stream faster through the K-sliced
-    // streaming blocks even at verify sizes: 51 -> 44 us at 9 rows; smaller ones (~3B, ~1B) do not
-    if (epi == EPI_SWIGLU && (long long)N * K >= (long long)kSwigluStreamMinNK << 20) return false;
+    // (the largest gate/up matrices - ~8B shape, 2 x 59 M weights - once streamed faster through the K-sliced
+    // streaming blocks even at verify sizes, 51 -> 44 us at 9 rows; since this kernel skips activation rows
+    // past M and finishes 1 / rms behind its first loads it is ahead again: 37.8 / 38.3 / 41.0 us at 1 / 9 / 16
+    // rows against 41.9 / 42.1 / 42.2.  The switch stays for measurements: weights (2^20) per matrix from which to stream.)
+    if (epi == EPI_SWIGLU && kSwigluStreamMinNK > 0 && (long long)N * K >= (long long)kSwigluStreamMinNK << 20) return false;
     if (M <= 16) return true;
     if (M > kSkinnyMaxM) return false;
     if (epi == EPI_STORE_F32 && N >= 256 * 256 && kLmStream) return false;    // logits: streaming blocks (see launch_lds_tile)
