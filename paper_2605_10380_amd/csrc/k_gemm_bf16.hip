@@ -6,12 +6,14 @@
 // bf16 one.  Reason: bf16 activations (8 significant bits) put the logits of a 16-layer decoder
 // ~0.05 away from the exact result; fp16 activations (11 bits) keep them within 0.01.
 //
-//   * skinny kernel (M <= 16, the O projection and logits to 32: verify steps, pure weight streaming): one block owns 16 output
+//   * skinny kernel (M <= 16, the O projection and narrow stores to 32: verify steps, pure weight streaming): one block owns 16 output
 //     columns, its wavefronts split K, W goes HBM -> registers -> v_mfma_f32_16x16x32_f16
 //     with no LDS in the streaming loop; the per-wavefront partial sums meet in LDS.
 //   * tile kernel   (more rows): 8 wavefronts, LDS-staged 64 x 128 x 64 tiles,
 //     v_mfma_f32_32x32x16_f16, global loads several K slices ahead.
-//   * stream kernel (SwiGLU, M >= 384): activations through LDS, weights straight into MFMA operands.
+//   * stream kernel (SwiGLU from 193-257 rows, logits from 17 rows, QKV / down projection of many rows, and - over K
+//     slices - the SwiGLU GEMM of 17-192 rows and the down projection of 129 rows up): activations through LDS,
+//     weights straight into MFMA operands.  The launcher states each crossover with the figures behind it.
 //
 // RMSNorm is folded into the GEMMs around it.  The GEMM that produces the residual stream x
 // also writes a = fp16(x * gain_next) and, per row and per block of columns, a partial sum of
@@ -550,7 +552,7 @@ __global__ __launch_bounds__(256) void swiglu_reduce_kernel(GemmArgs g) {
 }
 
 // ------------------------------------------------------------------------------ stream SwiGLU kernel
-// SwiGLU gate/up GEMM for M >= 384.  The LDS-staged kernel above moves both operands through
+// First written for the SwiGLU gate/up GEMM of a few hundred rows.  The LDS-staged kernel above moves both operands through
 // LDS and spends more cycles there than on the matrix cores (a 32 x 64 wavefront tile reads
 // 1.5 KB of LDS per MFMA).  Here only the activation tile goes through LDS; every wavefront
 // streams its own weight rows HBM/L2 -> registers -> MFMA, as the skinny kernel does.  Block = 4

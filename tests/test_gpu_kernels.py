@@ -19,9 +19,9 @@ def torch_cuda():
     return torch
 
 
-# M values: skinny path (<= 64, MT 1/2/4, ragged) and tile path (> 64, ragged); K / N pick
-# different wavefront counts in the skinny kernel and both tile shapes; M >= 384 takes the
-# streaming SwiGLU kernel (steady-state loop and drain, ragged rows and columns)
+# M values: skinny path (<= 16, and to 32 rows for some epilogues) and tile path (ragged); K / N pick
+# different wavefront counts in the skinny kernel and both tile shapes; M >= 257 (and 193-256 for
+# wide matrices) takes the streaming SwiGLU kernel (steady-state loop and drain, ragged rows and columns)
 GEMM_CASES = [(1, 64, 64), (9, 3072, 2048), (9, 2048, 8192), (17, 512, 256), (33, 128, 1024), (64, 2064, 192),
               (65, 384, 128), (100, 200 * 16, 320), (256, 3072, 2048), (300, 1024, 512), (512, 33 * 128, 256),
               (400, 1040, 1024), (384, 2048, 576), (300, 2048, 256), (230, 14336, 128), (257, 8192, 128), (640, 8192, 192), (320, 14336, 128),
