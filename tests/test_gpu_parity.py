@@ -695,6 +695,12 @@ def test_full_width_3b_batched_sessions(B):
         ref = O.forward(sh, w, more[s], refs[s])
         check_logits(sh, got[at:at + len(more[s])], ref, f"3b session {s}, 155-row pass")
         at += len(more[s])
+    # 256 rows in one pass: 128-row blocks everywhere, the QKV GEMM over three K slices
+    more = [I.zipf_tokens(sh.vocab, 5005, f"q{s}", t) for s, t in enumerate([60, 70, 66, 60])]
+    got = dm.extend_batch(kvs, more, B.AX_OUT_LAST_LOGITS).cpu().numpy()
+    for s in range(4):
+        ref = O.forward(sh, w, more[s], refs[s])
+        check_logits(sh, got[s], ref[-1], f"3b session {s}, 256-row pass")
     for kv in kvs + [root]:
         B.ax_kv_free(kv)
     dm.close()
