@@ -1252,8 +1252,13 @@ static int launch_lds_tile(const GemmArgs& g, hipStream_t s) {
         auto slices = [&](long long tiles) {
             int ks = 1;
             if (!g.split_ws || N % 64 != 0) return ks;
-            while (ks < SPLITK_MAX && tiles * ks < 256 && K % (ks * 2 * 64) == 0 && K / (ks * 2 * 64) >= 8 &&
-                   (size_t)ks * 2 * M * N * sizeof(float) <= g.split_ws_bytes)
+            // (a cut that would overshoot one round of 256 blocks is not taken once 144 or more CUs have a block:
+            // ~3B at 193-256 rows, 96 tiles: 192 blocks instead of 384, O projection 20.6 -> 18.7 us, down projection -
+            // then on 128-row blocks, 4 slices, 192 blocks - 39.1 -> 30.7 us; ~1B at 384 rows 37.5 -> 30.2 us,
+            // ~8B O projection at 384 rows 39.3 -> 31.0 us, ~3B at 144 rows 18.5 -> 16.8 us)
+            static const int fill = env_int("AX_SLICE_FILL", 144);   // measurement switch: 256 = always cut up to a full round
+            while (ks < SPLITK_MAX && tiles * ks < 256 && !(tiles * ks >= fill && tiles * ks * 2 > 256) &&
+                   K % (ks * 2 * 64) == 0 && K / (ks * 2 * 64) >= 8 && (size_t)ks * 2 * M * N * sizeof(float) <= g.split_ws_bytes)
                 ks *= 2;
             return ks;
         };
