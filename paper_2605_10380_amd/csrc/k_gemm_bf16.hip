@@ -1193,7 +1193,9 @@ static int launch_lds_tile(const GemmArgs& g, hipStream_t s) {
         // 128-row blocks from 80 tiles up (~3B / ~8B at M = 256: 36 -> 29 / 43 -> 34 us; M = 3584:
         // 275 -> 221 / 443 -> 329 us); the ~1B shape at M = 256 has 48 such tiles and stays with 64 rows
         const bool big = kQkvTile >= 0 ? kQkvTile > 0 : (pad_ok && tiles128 >= 80);
-        int ks = big ? (tiles128 < 128 ? 2 : 1) : (tiles64 < 1024 ? 2 : 1);
+        // 64-row blocks: two slices only while both fit one round of 256 blocks (more blocks than CUs run two to a
+        // CU and gain nothing from the cut: ~1B at 384 rows 26.8 -> 24.7 us, ~3B / ~8B at 320 rows 35.2 -> 32.3 / 43.0 -> 39.1 us)
+        int ks = big ? (tiles128 < 128 ? 2 : 1) : (tiles64 * 2 <= 256 ? 2 : 1);
         // three slices where they fill the chip better than two and K divides (~3B at 193-256 rows: 80 tiles,
         // 240 blocks instead of 160: 30.6 -> 28.8 us; four slices, 320 blocks in two rounds: 37.5 us)
         if (big && ks == 2 && tiles128 * 3 <= 256 && K % (3 * 64) == 0 && K / (3 * 64) >= 8 &&
