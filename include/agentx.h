@@ -119,9 +119,8 @@ void ax_model_destroy(ax_model *m);
 /* Bytes one block occupies = 2 * n_layers * n_kv_heads * head_dim * block_tokens * itemsize. */
 size_t ax_pool_block_bytes(const ax_model_config *cfg, int block_tokens);
 
-/* `dev_mem` must be zero-filled (or hold finite values): slots past the end of a sequence are
- * read and multiplied by an exact zero weight.  It may be NULL only for host-side bookkeeping
- * tests (no ax_extend on such a pool).
+/* `dev_mem` need not be initialised: slots past the end of a sequence are never used, whatever
+ * they hold.  It may be NULL only for host-side bookkeeping tests (no ax_extend on such a pool).
  * block_tokens must be 16.  The pool holds floor(bytes / block_bytes) blocks (>= 1).      */
 ax_status ax_pool_create(const ax_model_config *cfg, void *dev_mem, size_t bytes,
                          int block_tokens, ax_pool **out);
@@ -182,8 +181,9 @@ ax_status ax_extend_batch(ax_model *model, int n, ax_kv *const *kvs, const int32
 ax_status ax_verify(ax_model *model, ax_kv *kv, int32_t pending, const int32_t *drafts, int k,
                     int *accepted, int32_t *next_token, void *hip_stream);
 
-/* ax_verify over n sequences of one pool in a single forward (paper Sec. 3.2: several agent
- * sessions decode concurrently; Sec. 4.3 for the round itself): sequence s contributes the rows
+/* ax_verify over n sequences of one pool in a single forward (the round itself is that of Sec. 2.3
+ * and Sec. 4.3; running several agent sessions through one forward is this library's addition, the
+ * paper evaluates one session at a time): sequence s contributes the rows
  * [pending[s], its k_each[s] drafts] (drafts_concat holds the drafts back to back; host memory),
  * the weights are streamed once for all sum(1 + k_s) rows, acceptance and rollback are per
  * sequence.  accepted[s], next_token[s] (host) as in ax_verify.  All or nothing on errors. */
@@ -211,8 +211,8 @@ ax_status ax_kv_export(ax_model *model, const ax_kv *kv, int64_t n_tokens, void 
 ax_status ax_kv_import(ax_model *model, ax_pool *pool, const void *image, int64_t image_bytes,
                        ax_kv **out, void *hip_stream);
 
-/* ---- automatic prefix reuse (paper Sec. 3.1: KV is reused for all tokens before the first one
- * that differs; Sec. 4.2: a cached "1-3-2" serves a prompt that activates "1-3" by cutting the
+/* ---- automatic prefix reuse (paper Sec. 2.3, "Prefix caching": KV is reused for all tokens before
+ * the first one that differs; Sec. 4.2: a cached "1-3-2" serves a prompt that activates "1-3" by cutting the
  * tail).  An index remembers which token sequence each registered KV holds.  Host only.
  * The index keeps its own reference (a fork) to every registered sequence, so the blocks stay
  * alive after the caller frees its handle; destroy the index before its pool. */

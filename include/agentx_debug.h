@@ -62,6 +62,10 @@ ax_status ax_dbg_peaks(void *buf, size_t bytes, int reps, float *read_gbs, float
  * Copies min(bytes, buffer size) bytes. */
 ax_status ax_dbg_read(ax_model *model, int which, void *host_dst, size_t bytes);
 
+/* ax_verify replays one captured HIP graph per (draft count, key-slice count); enable = 0 makes it
+ * enqueue the same launches one by one instead (the reference a test compares the replays with). */
+ax_status ax_dbg_use_graphs(ax_model *model, int enable);
+
 /* Per-kernel timing with HIP events on the caller's stream.  While enabled, every launch of the
  * classes below inside ax_extend* / ax_verify is bracketed by a pair of events (this perturbs
  * the step a little, so enable it only for steps whose total time is not reported).

@@ -67,6 +67,12 @@ def draft(lut: dict, n: int, context, k: int, selective: bool, vocab: int, seed:
     return out, hits
 
 
+def draft_accuracy(stats: dict) -> float:
+    """Draft-token accuracy as the paper's Table 3 tabulates it: accepted drafts over generated
+    drafts (0 when nothing was drafted)."""
+    return stats["accepted"] / stats["drafted"] if stats["drafted"] else 0.0
+
+
 def generate(shape, weights, kv, lut: dict, n: int, history, pending: int, max_new: int, k: int,
              selective: bool, seed: int = 0):
     """ExSpec decode loop: draft from the table, verify with the target model, roll back.

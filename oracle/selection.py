@@ -1,5 +1,5 @@
 """CPU oracle for the offline cluster-combination selection (paper Sec. 4.2, Algorithm 1) and for
-longest-cached-prefix lookup (Sec. 3.1 / 4.2: reuse up to the first mismatch, cut the tail).
+longest-cached-prefix lookup (Sec. 2.3 / 4.2: reuse up to the first mismatch, cut the tail).
 TEST INFRASTRUCTURE ONLY - never imported by the product path.
 
 A data sample is the ordered tuple of clusters it activates (the order is the fixed, theme-based

@@ -89,6 +89,7 @@ def _load():
                                    C.POINTER(C.c_float), vp]),
         "ax_dbg_read": (C.c_int, [vp, C.c_int, vp, C.c_size_t]),
         "ax_dbg_profile": (C.c_int, [vp, C.c_int]),
+        "ax_dbg_use_graphs": (C.c_int, [vp, C.c_int]),
         "ax_dbg_profile_read": (C.c_int, [vp, C.POINTER(C.c_double), C.POINTER(i64)]),
         "ax_verify": (C.c_int, [vp, vp, C.c_int32, i32p, C.c_int, C.POINTER(C.c_int), i32p, vp]),
         "ax_verify_batch": (C.c_int, [vp, C.c_int, C.POINTER(vp), i32p, i32p, C.POINTER(C.c_int), C.POINTER(C.c_int), i32p, vp]),
@@ -407,6 +408,10 @@ def ax_dbg_read(model: int, which: int, dst: np.ndarray):
 PROFILE_CLASSES = ("qkv_proj", "attention", "o_proj", "swiglu_gate_up", "down_proj", "lm_head", "empty_bracket")
 
 
+def ax_dbg_use_graphs(model: int, enable: bool):
+    _check(lib.ax_dbg_use_graphs(model, int(enable)))
+
+
 def ax_dbg_profile(model: int, enable: bool):
     _check(lib.ax_dbg_profile(model, int(enable)))
 
@@ -428,7 +433,7 @@ class DeviceModel:
     """
 
     def __init__(self, shape, weights: dict, max_pos: int, max_tokens: int, pool_tokens: int,
-                 max_seqs: int = 1, device: str = "cuda:0"):
+                 max_seqs: int = 1, device: str = "cuda:0", pool_fill=None):
         import torch
         if not torch.cuda.is_available():
             raise RuntimeError("no GPU: the extend / verify path has no CPU fallback")
@@ -454,8 +459,8 @@ class DeviceModel:
         self.model = ax_model_create(self.cfg, ptrs, self.ws.data_ptr(), ws_bytes)
         bb = ax_pool_block_bytes(self.cfg)
         n_blocks = -(-pool_tokens // 16)
-        # zero-filled: masked key slots are multiplied by probability 0 and must be finite
-        self.pool_mem = torch.zeros(n_blocks * bb, dtype=torch.uint8, device=self.device)
+        # pool_fill: byte the pool memory starts out with (tests use 0xFF: every slot a NaN)
+        self.pool_mem = torch.full((n_blocks * bb,), pool_fill or 0, dtype=torch.uint8, device=self.device)
         self.pool = ax_pool_create(self.cfg, self.pool_mem.data_ptr(), n_blocks * bb)
 
     @property

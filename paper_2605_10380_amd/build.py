@@ -29,8 +29,14 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-u
 EXTRA_FLAGS = {"k_attn.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
 
 
+# `python -m paper_2605_10380_amd.build --tuning` compiles the dispatch thresholds as environment-overridable
+# knobs (kernel tuning sessions only; the product build has them as constants)
+TUNING_FLAGS = []
+
+
 def sources():
-    return sorted(f for f in os.listdir(CSRC) if f.endswith(".hip"))
+    """HIP sources (kernels, GPU half of the ABI) and plain C++ sources (host-only half of the ABI)."""
+    return sorted(f for f in os.listdir(CSRC) if f.endswith((".hip", ".cpp")))
 
 
 def _newest_header():
@@ -40,12 +46,15 @@ def _newest_header():
 
 
 def _compile(src: str, force: bool) -> str:
-    obj = os.path.join(BUILD, src[:-4] + ".o")
+    obj = os.path.join(BUILD, os.path.splitext(src)[0] + ".o")
     spath = os.path.join(CSRC, src)
     if (not force and os.path.exists(obj)
             and os.path.getmtime(obj) > max(os.path.getmtime(spath), _newest_header())):
         return obj
-    cmd = [HIPCC, *FLAGS, *EXTRA_FLAGS.get(src, []), "-c", spath, "-o", obj]
+    if src.endswith(".cpp"):        # no device code: host compiler flags only
+        cmd = [HIPCC, "-O2", "-std=c++17", "-fPIC", "-Wall", "-c", spath, "-o", obj]
+    else:
+        cmd = [HIPCC, *FLAGS, *EXTRA_FLAGS.get(src, []), *TUNING_FLAGS, "-c", spath, "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
     if r.returncode != 0:
@@ -68,4 +77,6 @@ def build(force: bool = False) -> str:
 
 
 if __name__ == "__main__":
-    print(build(force="--force" in sys.argv))
+    if "--tuning" in sys.argv:
+        TUNING_FLAGS.append("-DAX_TUNING_KNOBS")
+    print(build(force="--force" in sys.argv or "--tuning" in sys.argv))

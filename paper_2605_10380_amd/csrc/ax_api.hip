@@ -1,6 +1,7 @@
-// Host side of the C ABI: handle validation, paged-KV bookkeeping, per-call descriptors and the
-// kernel sequence of one extend forward.  No device memory is allocated here: weights, KV
-// pool and workspace are borrowed from the caller.
+// GPU half of the C ABI: models, per-call descriptors and the kernel sequence of one extend
+// forward, verification, KV images, the draft / verify loop and the test-only entries.  (Pool,
+// sequence, index and table handles live in ax_host.cpp.)  No device memory is allocated here:
+// weights, KV pool and workspace are borrowed from the caller.
 #include "../../include/agentx.h"
 #include "../../include/agentx_debug.h"
 
@@ -14,23 +15,13 @@
 #include <cstring>
 #include <vector>
 
-#include "block_manager.h"
+#include "handles.h"
 #include "kernels.h"
-#include "cluster_select.h"
-#include "ngram_lut.h"
-#include "prefix_index.h"
 
 namespace {
 
-thread_local char g_err[512] = "";
-
-ax_status fail(ax_status st, const char* fmt, ...) {
-    va_list ap;
-    va_start(ap, fmt);
-    vsnprintf(g_err, sizeof g_err, fmt, ap);
-    va_end(ap);
-    return st;
-}
+using ax::fail;
+using ax::ok;
 
 #define HIP_TRY(expr)                                                                       \
     do {                                                                                    \
@@ -38,38 +29,21 @@ ax_status fail(ax_status st, const char* fmt, ...) {
         if (e_ != hipSuccess) return fail(AX_ERR_DEVICE, "%s: %s", #expr, hipGetErrorString(e_)); \
     } while (0)
 
-constexpr uint32_t MAGIC_MODEL = 0x41584d44, MAGIC_POOL = 0x4158504c, MAGIC_KV = 0x41584b56, MAGIC_LUT = 0x41584c54, MAGIC_INDEX = 0x41584958;
 constexpr int N_SLOTS = 4;            // staging ring for per-call descriptors
 constexpr int LOGIT_ROWS = 256;       // rows per LM-head pass when only the argmax is wanted
-const long long kSharedMinKeys = std::getenv("AX_SHARED_MIN_KEYS") ? std::atoll(std::getenv("AX_SHARED_MIN_KEYS")) : 2048;   // (sequences - 1) x shared keys that justify a shared-prefix pass
+constexpr long long kSharedMinKeys = 2048;   // (sequences - 1) x shared keys that justify a shared-prefix pass
 constexpr int SPLIT_ITEMS = 2048;     // partial records the split attention may use (workspace size)
 
 size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
-int isz(int dtype) { return dtype == AX_F32 ? 4 : 2; }
+int isz(int dtype) { return ax::itemsize(dtype); }
 
-bool config_ok(const ax_model_config* c, ax_status* why) {
-    *why = AX_ERR_INVALID;
-    if (!c) return false;
-    if (c->n_layers <= 0 || c->d_model <= 0 || c->n_q_heads <= 0 || c->n_kv_heads <= 0 ||
-        c->head_dim <= 0 || c->d_ff <= 0 || c->vocab <= 0 || c->max_pos <= 0 ||
-        c->max_tokens <= 0 || c->max_seqs <= 0)
-        return false;
-    if (c->n_q_heads % c->n_kv_heads != 0) return false;
-    if (c->dtype != AX_F32 && c->dtype != AX_BF16) return false;
-    if (!(c->rms_eps >= 0.f) || !(c->rope_base > 0.f)) return false;
-    *why = AX_ERR_UNSUPPORTED;
-    if (c->head_dim % 2 != 0 || c->head_dim > 256) return false;
-    if (c->dtype == AX_BF16) {
-        if (c->head_dim != 64 && c->head_dim != 128) return false;
-        if (c->d_model % 64 || c->d_ff % 64 || c->vocab % 64) return false;
-    }
-    return true;
-}
+using ax::config_ok;
 
 struct Layout {                       // byte offsets into the workspace
     size_t rope_cos, rope_sin, desc, x, h, ssq, qkv, q, attn, ffn, partials, splitk, logits, amax_scratch,
         amax_out, result, packed, total;
     size_t desc_ints;                 // capacity of one descriptor slot
+    size_t max_records;               // split-attention partial records one pass may write (there is room for two passes)
     int max_tiles, max_bt;
 };
 
@@ -98,8 +72,12 @@ Layout make_layout(const ax_model_config& c) {
     L.q = take(T * (size_t)c.n_q_heads * c.head_dim * a);
     L.attn = take(T * (size_t)c.n_q_heads * c.head_dim * a);
     L.ffn = take(T * (size_t)c.d_ff * a);
-    const size_t items = std::max<size_t>(SPLIT_ITEMS, (size_t)L.max_tiles * c.n_kv_heads);
-    L.partials = take(c.dtype == AX_BF16 ? 2 * items * ((size_t)c.head_dim * 32 + 64) * 4 : 0);   // second half: shared-prefix pass
+    // Partial records of the split attention: one per (q tile of 32 stacked rows, KV head, key slice).  A call
+    // whose longest sequence runs on blocks of 4 or 8 tiles pads EVERY sequence to whole blocks, so the most a
+    // call can need with one slice is (T G / 32 + 8 per sequence) tiles per KV head; the slice count is then
+    // chosen to stay inside this capacity.  Room for two passes: the per-sequence one and the shared-prefix one.
+    L.max_records = std::max<size_t>(SPLIT_ITEMS, ((T * G + 31) / 32 + 8 * S + 2) * (size_t)c.n_kv_heads);
+    L.partials = take(c.dtype == AX_BF16 ? 2 * L.max_records * ((size_t)c.head_dim * 32 + 64) * 4 : 0);
     L.splitk = take(c.dtype == AX_BF16 ? T * c.d_model * 4 * ax::SPLITK_MAX : 0);   // K-slice partials of residual GEMMs
     L.logits = take(std::min<size_t>(T, LOGIT_ROWS) * (size_t)c.vocab * 4);
     L.amax_scratch = take(2 * std::min<size_t>(T, LOGIT_ROWS) * ax::ARGMAX_PARTS * 4);
@@ -114,7 +92,6 @@ Layout make_layout(const ax_model_config& c) {
 }  // namespace
 
 struct ax_model {
-    uint32_t magic;
     ax_model_config cfg;
     Layout lay;
     char* ws;
@@ -136,38 +113,9 @@ struct ax_model {
     std::vector<hipEvent_t> prof_free;     // events ready for reuse
 };
 
-struct ax_pool {
-    uint32_t magic;
-    uint64_t uid;                     // never reused: captured graphs are keyed by it
-    ax_model_config cfg;              // geometry fields only are compared with the model's
-    ax::KVGeom geom;
-    ax::BlockPool blocks;
-};
-
-struct ax_lut {
-    uint32_t magic;
-    ax::NgramLut lut;
-};
-
-struct ax_index {
-    uint32_t magic;
-    ax_pool* pool;
-    ax::PrefixIndex idx;
-};
-
-struct ax_kv {
-    uint32_t magic;
-    ax_pool* pool;
-    ax::Sequence seq;
-};
-
 namespace {
 
-bool ok(const ax_model* m) { return m && m->magic == MAGIC_MODEL; }
-bool ok(const ax_pool* p) { return p && p->magic == MAGIC_POOL; }
-bool ok(const ax_kv* k) { return k && k->magic == MAGIC_KV && ok(k->pool); }
-bool ok(const ax_lut* l) { return l && l->magic == MAGIC_LUT; }
-bool ok(const ax_index* x) { return x && x->magic == MAGIC_INDEX && ok(x->pool); }
+bool ok(const ax_model* m) { return ax::handle_live(m, ax::H_MODEL); }
 
 struct ProfScope {                     // records a pair of events around one launch when profiling
     ax_model* m; hipStream_t st; hipEvent_t b = nullptr;
@@ -199,7 +147,7 @@ int choose_splits(const ax_model* m, int items, int nq, int max_steps) {
     // go up to 2048 wavefronts while a slice still has ~8 key steps
     if (nq == 1 && max_steps / want > 8) want = std::max(want, std::min(2048 / std::max(1, items), (max_steps + 7) / 8));
     want = std::min(want, std::max(1, max_steps / 2));
-    const size_t cap = std::max<size_t>(SPLIT_ITEMS, (size_t)m->lay.max_tiles * m->cfg.n_kv_heads) / ((size_t)items * nq);
+    const size_t cap = m->lay.max_records / ((size_t)items * nq);      // >= 1 for every call prepare_call lets through
     want = std::min(want, std::max(1, (int)cap));
     int p2 = 1;
     while (p2 * 2 <= want) p2 *= 2;
@@ -301,8 +249,7 @@ ax_status prepare_call(ax_model* m, int n, ax_kv* const* kvs, const int32_t* tok
             cp.n_tiles_shared = (int)((n_rows * G + 32 * cp.shared_nq - 1) / (32 * cp.shared_nq));
             int want = std::max(1, 2048 / (cp.n_tiles_shared * c.n_kv_heads * cp.shared_nq));
             want = std::min(want, std::max(1, shared / 64));
-            const size_t cap = std::max<size_t>(SPLIT_ITEMS, (size_t)m->lay.max_tiles * c.n_kv_heads) /
-                               ((size_t)cp.n_tiles_shared * c.n_kv_heads * cp.shared_nq);
+            const size_t cap = m->lay.max_records / ((size_t)cp.n_tiles_shared * c.n_kv_heads * cp.shared_nq);
             want = std::min(want, std::max(1, (int)cap));
             cp.shared_splits = 1;
             while (cp.shared_splits * 2 <= want) cp.shared_splits *= 2;
@@ -322,6 +269,14 @@ ax_status prepare_call(ax_model* m, int n, ax_kv* const* kvs, const int32_t* tok
     cp.ints = at;
     if (cp.ints > m->slot_ints || cp.bt_total > n * m->lay.max_bt)
         return fail(AX_ERR_INVALID, "call descriptor does not fit its slot");
+    // the split attention writes one partial record per (q tile, KV head, key slice): even with a single slice
+    // each pass must fit the workspace region sized for it (it does for every call within max_tokens / max_seqs;
+    // checked all the same, before anything is committed, because a kernel would write past the region otherwise)
+    if (c.dtype == AX_BF16 &&
+        ((size_t)cp.n_tiles * cp.tile_nq * c.n_kv_heads > m->lay.max_records ||
+         (size_t)cp.n_tiles_shared * cp.shared_nq * c.n_kv_heads * cp.shared_splits > m->lay.max_records))
+        return fail(AX_ERR_UNSUPPORTED, "%d attention tile groups of %d tiles exceed the workspace's %zu partial records",
+                    cp.n_tiles, cp.tile_nq, m->lay.max_records);
 
     // ---- staging slot: the ring behind events, or the slot reserved for captured graphs
     if (graph_slot) {
@@ -400,8 +355,7 @@ ax_status enqueue_call(ax_model* m, const CallPlan& cp, void* out, hipStream_t s
     const int out_mode = cp.out_mode, n_out = cp.n_out;
     // verify calls whose rows fit one LM-head pass: second argmax stage, acceptance and the result's way to the
     // host in one launch (two launches and a copy node fewer per step)
-    static const bool allow_fused = !(std::getenv("AX_FUSED_ACCEPT") && std::atoi(std::getenv("AX_FUSED_ACCEPT")) == 0);   // measurement switch
-    const bool fused_accept = allow_fused && verify_k >= 0 && n_out > 0 && n_out <= std::min(c.max_tokens, LOGIT_ROWS) &&
+    const bool fused_accept = verify_k >= 0 && n_out > 0 && n_out <= std::min(c.max_tokens, LOGIT_ROWS) &&
                               n_out <= ax::ACCEPT_MAX_ROWS;
 
     char* ws = m->ws;
@@ -595,8 +549,6 @@ ax_status run_verify_graph(ax_model* m, ax_kv* kv, const int32_t* toks, int T, v
 
 extern "C" {
 
-const char* ax_last_error(void) { return g_err; }
-
 size_t ax_workspace_bytes(const ax_model_config* cfg) {
     ax_status why;
     if (!config_ok(cfg, &why)) return 0;
@@ -656,8 +608,6 @@ ax_status ax_model_create(const ax_model_config* cfg, const ax_weights* w, void*
     }
     e = hipStreamCreateWithFlags(&m->capture_stream, hipStreamNonBlocking);
     if (e != hipSuccess) { m->capture_stream = nullptr; cleanup(); return fail(AX_ERR_DEVICE, "hipStreamCreate: %s", hipGetErrorString(e)); }
-    const char* no_graph = std::getenv("AX_NO_GRAPH");
-    m->use_graphs = !(no_graph && no_graph[0] == '1');
     // rotary table: angle = pos * base^(-2j/hd), evaluated in double on the host
     const int half = cfg->head_dim / 2;
     std::vector<float> cs((size_t)cfg->max_pos * half), sn((size_t)cfg->max_pos * half);
@@ -692,7 +642,7 @@ ax_status ax_model_create(const ax_model_config* cfg, const ax_weights* w, void*
         if (e == hipSuccess) e = hipDeviceSynchronize();
         if (e != hipSuccess) { cleanup(); return fail(AX_ERR_DEVICE, "weight repack: %s", hipGetErrorString(e)); }
     }
-    m->magic = MAGIC_MODEL;
+    ax::handle_register(m, ax::H_MODEL);
     *out = m;
     return AX_OK;
 }
@@ -706,127 +656,8 @@ void ax_model_destroy(ax_model* m) {
     for (auto& sp : m->prof_spans) { (void)hipEventDestroy(sp.a); (void)hipEventDestroy(sp.b); }
     for (auto& e : m->prof_free) (void)hipEventDestroy(e);
     (void)hipHostFree(m->stage);
-    m->magic = 0;
+    ax::handle_unregister(m);
     delete m;
-}
-
-size_t ax_pool_block_bytes(const ax_model_config* cfg, int block_tokens) {
-    ax_status why;
-    if (!config_ok(cfg, &why) || block_tokens <= 0) return 0;
-    return (size_t)2 * cfg->n_layers * cfg->n_kv_heads * cfg->head_dim * block_tokens * isz(cfg->dtype);
-}
-
-ax_status ax_pool_create(const ax_model_config* cfg, void* dev_mem, size_t bytes, int block_tokens,
-                         ax_pool** out) {
-    ax_status why;
-    if (!out) return fail(AX_ERR_INVALID, "out is NULL");
-    *out = nullptr;
-    if (!config_ok(cfg, &why)) return fail(why, "model config rejected");
-    if (block_tokens != 16) return fail(AX_ERR_UNSUPPORTED, "block_tokens must be 16");
-    if (((uintptr_t)dev_mem & 255) != 0) return fail(AX_ERR_INVALID, "pool memory not 256-byte aligned");
-    const size_t bb = ax_pool_block_bytes(cfg, block_tokens);
-    const size_t nb = bytes / bb;
-    if (nb < 1) return fail(AX_ERR_OOM, "pool of %zu bytes holds no %zu-byte block", bytes, bb);
-    if (nb > 0x7fffffff) return fail(AX_ERR_INVALID, "too many blocks");
-    ax_pool* p = new ax_pool();
-    p->cfg = *cfg;
-    p->geom.base = dev_mem;
-    p->geom.n_blocks = (long long)nb;
-    p->geom.n_kv_heads = cfg->n_kv_heads;
-    p->geom.head_dim = cfg->head_dim;
-    p->geom.block_tokens = block_tokens;
-    p->blocks.init((int64_t)nb, block_tokens);
-    static uint64_t next_uid = 1;
-    p->uid = next_uid++;
-    p->magic = MAGIC_POOL;
-    *out = p;
-    return AX_OK;
-}
-
-ax_status ax_pool_destroy(ax_pool* p) {
-    if (!ok(p)) return fail(AX_ERR_INVALID, "bad pool handle");
-    if (p->blocks.live_seqs != 0) return fail(AX_ERR_STATE, "%lld sequences still alive", (long long)p->blocks.live_seqs);
-    p->magic = 0;
-    delete p;
-    return AX_OK;
-}
-
-ax_status ax_pool_stats(const ax_pool* p, int64_t* free_blocks, int64_t* total_blocks, int64_t* live_seqs) {
-    if (!ok(p)) return fail(AX_ERR_INVALID, "bad pool handle");
-    if (free_blocks) *free_blocks = p->blocks.n_free();
-    if (total_blocks) *total_blocks = p->blocks.n_total();
-    if (live_seqs) *live_seqs = p->blocks.live_seqs;
-    return AX_OK;
-}
-
-ax_status ax_kv_alloc(ax_pool* p, ax_kv** out) {
-    if (!out) return fail(AX_ERR_INVALID, "out is NULL");
-    *out = nullptr;
-    if (!ok(p)) return fail(AX_ERR_INVALID, "bad pool handle");
-    ax_kv* k = new ax_kv();
-    k->pool = p;
-    k->magic = MAGIC_KV;
-    ++p->blocks.live_seqs;
-    *out = k;
-    return AX_OK;
-}
-
-ax_status ax_kv_fork(const ax_kv* src, int64_t n_tokens, ax_kv** out) {
-    if (!out) return fail(AX_ERR_INVALID, "out is NULL");
-    *out = nullptr;
-    if (!ok(src)) return fail(AX_ERR_INVALID, "bad KV handle");
-    if (n_tokens < 0) n_tokens = src->seq.len;
-    if (n_tokens > src->seq.len) return fail(AX_ERR_INVALID, "fork of %lld tokens from a sequence of %lld",
-                                             (long long)n_tokens, (long long)src->seq.len);
-    ax_kv* k = new ax_kv();
-    k->pool = src->pool;
-    ax::fork(src->pool->blocks, src->seq, n_tokens, k->seq);
-    k->magic = MAGIC_KV;
-    ++src->pool->blocks.live_seqs;
-    *out = k;
-    return AX_OK;
-}
-
-ax_status ax_kv_truncate(ax_kv* kv, int64_t new_len) {
-    if (!ok(kv)) return fail(AX_ERR_INVALID, "bad KV handle");
-    if (new_len < 0 || new_len > kv->seq.len)
-        return fail(AX_ERR_INVALID, "truncate to %lld, length is %lld", (long long)new_len, (long long)kv->seq.len);
-    ax::truncate(kv->pool->blocks, kv->seq, new_len);
-    return AX_OK;
-}
-
-int64_t ax_kv_len(const ax_kv* kv) { return ok(kv) ? kv->seq.len : -1; }
-
-ax_status ax_kv_free(ax_kv* kv) {
-    if (!ok(kv)) return fail(AX_ERR_INVALID, "bad KV handle (double free?)");
-    ax::truncate(kv->pool->blocks, kv->seq, 0);
-    --kv->pool->blocks.live_seqs;
-    kv->magic = 0;
-    delete kv;
-    return AX_OK;
-}
-
-int64_t ax_kv_blocks(const ax_kv* kv, int32_t* ids, int64_t cap) {
-    if (!ok(kv)) return -1;
-    const int64_t n = (int64_t)kv->seq.blocks.size();
-    if (ids) for (int64_t i = 0; i < n && i < cap; ++i) ids[i] = kv->seq.blocks[(size_t)i];
-    return n;
-}
-
-int ax_pool_refcount(const ax_pool* p, int64_t block) {
-    if (!ok(p) || block < 0 || block >= p->blocks.n_total()) return -1;
-    return p->blocks.refcount[(size_t)block];
-}
-
-ax_status ax_kv_reserve_host(ax_kv* kv, int64_t n, int32_t* cow_src, int32_t* cow_dst) {
-    if (!ok(kv)) return fail(AX_ERR_INVALID, "bad KV handle");
-    if (n <= 0 || !cow_src || !cow_dst) return fail(AX_ERR_INVALID, "bad argument");
-    ax::BlockPool& bp = kv->pool->blocks;
-    const ax::AppendPlan plan = ax::plan_append(bp, kv->seq, n);
-    if (plan.need() > bp.n_free())
-        return fail(AX_ERR_OOM, "need %lld KV blocks, %lld free", (long long)plan.need(), (long long)bp.n_free());
-    ax::apply_append(bp, kv->seq, n, plan, cow_src, cow_dst);
-    return AX_OK;
 }
 
 ax_status ax_extend(ax_model* model, ax_kv* kv, const int32_t* tokens, int T, int out_mode, void* out,
@@ -1062,136 +893,6 @@ ax_status ax_verify_batch(ax_model* model, int n, ax_kv* const* kvs, const int32
     return AX_OK;
 }
 
-// ---- automatic prefix reuse and offline combination selection (host only) --------------------
-
-ax_status ax_index_create(ax_pool* pool, ax_index** out) {
-    if (!out) return fail(AX_ERR_INVALID, "out is NULL");
-    *out = nullptr;
-    if (!ok(pool)) return fail(AX_ERR_INVALID, "bad pool handle");
-    ax_index* x = new ax_index();
-    x->pool = pool;
-    x->magic = MAGIC_INDEX;
-    *out = x;
-    return AX_OK;
-}
-
-void ax_index_destroy(ax_index* x) {
-    if (!ok(x)) return;
-    for (auto& e : x->idx.entries)
-        if (e.live) ax_kv_free((ax_kv*)e.owner);
-    x->magic = 0;
-    delete x;
-}
-
-int64_t ax_index_entries(const ax_index* x) {
-    if (!ok(x)) return -1;
-    int64_t n = 0;
-    for (auto& e : x->idx.entries) n += e.live ? 1 : 0;
-    return n;
-}
-
-ax_status ax_index_insert(ax_index* x, const ax_kv* kv, const int32_t* tokens, int64_t n) {
-    if (!ok(x)) return fail(AX_ERR_INVALID, "bad index handle");
-    if (!ok(kv)) return fail(AX_ERR_INVALID, "bad KV handle");
-    if (kv->pool != x->pool) return fail(AX_ERR_INVALID, "sequence lives in another pool");
-    if (n <= 0 || !tokens) return fail(AX_ERR_INVALID, "bad argument");
-    if (n > kv->seq.len) return fail(AX_ERR_INVALID, "%lld tokens given, the sequence holds %lld", (long long)n, (long long)kv->seq.len);
-    ax_kv* held = nullptr;
-    ax_status st = ax_kv_fork(kv, n, &held);
-    if (st != AX_OK) return st;
-    x->idx.insert(tokens, n, held);
-    return AX_OK;
-}
-
-ax_status ax_index_match(ax_index* x, const int32_t* prompt, int64_t n, int64_t max_reuse, ax_kv** out, int64_t* matched) {
-    if (!out || !matched) return fail(AX_ERR_INVALID, "NULL argument");
-    *out = nullptr;
-    *matched = 0;
-    if (!ok(x)) return fail(AX_ERR_INVALID, "bad index handle");
-    if (n < 0 || (n > 0 && !prompt)) return fail(AX_ERR_INVALID, "bad argument");
-    int64_t m = 0;
-    const int id = x->idx.match(prompt, n, &m);
-    if (max_reuse >= 0 && m > max_reuse) m = max_reuse;
-    if (id < 0 || m == 0) return ax_kv_alloc(x->pool, out);
-    ax_status st = ax_kv_fork((const ax_kv*)x->idx.entries[(size_t)id].owner, m, out);
-    if (st == AX_OK) *matched = m;
-    return st;
-}
-
-namespace {
-bool unpack_seqs(const int32_t* concat, const int32_t* len, int64_t n, std::vector<ax::ClusterSeq>& out) {
-    if (n < 0 || (n > 0 && (!concat || !len))) return false;
-    const int32_t* at = concat;
-    for (int64_t i = 0; i < n; ++i) {
-        if (len[i] < 0) return false;
-        out.emplace_back(at, at + len[i]);
-        at += len[i];
-    }
-    return true;
-}
-}  // namespace
-
-ax_status ax_select_combinations(const int32_t* samples_concat, const int32_t* sample_len, int64_t n_samples, int budget,
-                                 int32_t* chosen_concat, int64_t chosen_cap, int32_t* chosen_len,
-                                 int64_t* coverage_after, int* n_chosen) {
-    if (!n_chosen || budget < 0) return fail(AX_ERR_INVALID, "bad argument");
-    *n_chosen = 0;
-    std::vector<ax::ClusterSeq> samples;
-    if (!unpack_seqs(samples_concat, sample_len, n_samples, samples)) return fail(AX_ERR_INVALID, "bad sample list");
-    const ax::SelectionResult r = ax::select_combinations(samples, budget);
-    int64_t total = 0;
-    for (auto& c : r.chosen) total += (int64_t)c.size();
-    if (!r.chosen.empty() && (!chosen_concat || !chosen_len || total > chosen_cap))
-        return fail(AX_ERR_INVALID, "output holds %lld cluster ids, %lld needed", (long long)chosen_cap, (long long)total);
-    int32_t* at = chosen_concat;
-    for (size_t i = 0; i < r.chosen.size(); ++i) {
-        chosen_len[i] = (int32_t)r.chosen[i].size();
-        for (int32_t c : r.chosen[i]) *at++ = c;
-        if (coverage_after) coverage_after[i] = r.coverage[i];
-    }
-    *n_chosen = (int)r.chosen.size();
-    return AX_OK;
-}
-
-int64_t ax_coverage(const int32_t* samples_concat, const int32_t* sample_len, int64_t n_samples,
-                    const int32_t* cached_concat, const int32_t* cached_len, int64_t n_cached) {
-    std::vector<ax::ClusterSeq> samples, cached;
-    if (!unpack_seqs(samples_concat, sample_len, n_samples, samples) || !unpack_seqs(cached_concat, cached_len, n_cached, cached))
-        return -1;
-    return ax::coverage(samples, cached);
-}
-
-ax_status ax_lut_build(const int32_t* stream, int64_t n_tokens, int n, int vocab, ax_lut** out) {
-    if (!out) return fail(AX_ERR_INVALID, "out is NULL");
-    *out = nullptr;
-    if (n < 1 || vocab <= 0 || n_tokens < 0 || (n_tokens > 0 && !stream)) return fail(AX_ERR_INVALID, "bad argument");
-    for (int64_t i = 0; i < n_tokens; ++i)
-        if (stream[i] < 0 || stream[i] >= vocab) return fail(AX_ERR_INVALID, "token %d outside the vocabulary", stream[i]);
-    ax_lut* l = new ax_lut();
-    l->lut.build(stream, n_tokens, n, vocab);
-    l->magic = MAGIC_LUT;
-    *out = l;
-    return AX_OK;
-}
-
-void ax_lut_free(ax_lut* lut) {
-    if (!ok(lut)) return;
-    lut->magic = 0;
-    delete lut;
-}
-
-int64_t ax_lut_size(const ax_lut* lut) { return ok(lut) ? (int64_t)lut->lut.table.size() : -1; }
-
-int ax_lut_draft(const ax_lut* lut, const int32_t* context, int64_t n_context, int k, int selective, uint64_t seed,
-                 int64_t stream_pos, int32_t* drafts, int* hits) {
-    if (!ok(lut) || k < 0 || n_context < 0 || (n_context > 0 && !context) || (k > 0 && !drafts)) return -1;
-    std::vector<int32_t> ctx(context, context + n_context);
-    int h = 0;
-    const int n = lut->lut.draft(ctx, k, selective != 0, seed, stream_pos, drafts, &h);
-    if (hits) *hits = h;
-    return n;
-}
-
 ax_status ax_exspec_generate(ax_model* model, ax_kv* kv, const ax_lut* lut, const int32_t* history, int64_t n_history,
                              int32_t pending, int max_new, int k, int selective, uint64_t seed, int32_t* out_tokens,
                              ax_exspec_stats* stats, void* hip_stream) {
@@ -1390,6 +1091,12 @@ ax_status ax_dbg_read(ax_model* m, int which, void* host_dst, size_t bytes) {
     if (which < 0 || which > 5) return fail(AX_ERR_INVALID, "bad buffer id");
     HIP_TRY(hipDeviceSynchronize());
     HIP_TRY(hipMemcpy(host_dst, m->ws + off[which], std::min(bytes, end[which] - off[which]), hipMemcpyDeviceToHost));
+    return AX_OK;
+}
+
+ax_status ax_dbg_use_graphs(ax_model* m, int enable) {
+    if (!ok(m)) return fail(AX_ERR_INVALID, "bad model handle");
+    m->use_graphs = enable != 0;
     return AX_OK;
 }
 

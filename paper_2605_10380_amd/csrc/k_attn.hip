@@ -211,7 +211,9 @@ __global__ __launch_bounds__(64) void attn_split_kernel(AttnArgs a) {
     const int* tab = a.bt + ti1.y;
     const int kv_len = P + T, last_blk = (kv_len - 1) >> 4;
 
-    // keys this group can see at all: up to the position of its last valid row
+    // keys this group can see at all: up to the position of its last valid row.  (Keys past the end of the
+    // sequence, reached only by its last step, re-read the last valid K row - see fetch - and their scores are
+    // replaced by -inf, so K is never read from unwritten slots; V is, and process() zeroes those operands.)
     const int r_last = min(r0 + NQ * 32 - 1, n_stacked - 1);
     const int kv_end = P + r_last / G + 1;
     const int first = ti1.w >> 5;                        // first key step (keys before it belong to the shared pass)
@@ -273,6 +275,18 @@ __global__ __launch_bounds__(64) void attn_split_kernel(AttnArgs a) {
     };
     auto process = [&](int buf, int st) {
         const int kv0 = st * 32;
+        if (kv0 + 32 > kv_len) {
+            // the sequence ends inside this step (its last one): slots of the last block past the end were never
+            // written by this sequence and may hold anything - their V operands become exact zeros, so that a
+            // probability of 0 times whatever lies in caller memory cannot turn into a NaN
+#pragma unroll
+            for (int d = 0; d < DT; ++d)
+#pragma unroll
+                for (int qd = 0; qd < 4; ++qd)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        if (kv0 + qd * 8 + g * 4 + i >= kv_len) vq[buf][d][qd][i] = (f16)0.f;
+        }
 #pragma unroll
         for (int t = 0; t < NQ; ++t) {
             f32x16 s;
@@ -414,8 +428,9 @@ __global__ __launch_bounds__(64 * NQ) void attn_block_kernel(AttnArgs a) {
         v_second[i] = (c0 / (2 * HD)) != 0;
     }
     u32x4 rk[D][CH], rv[D][CH];
-    // keys past the end of the sequence (last step only) read slots of the last block that hold
-    // stale but finite values, or the last block twice; the causal mask discards their scores
+    // keys past the end of the sequence (last step only) read slots of the last block that were never
+    // written, or the last block twice: their scores are replaced by -inf whatever they are, and
+    // process() zeroes their V operands
     auto gload = [&](int slot, int st, int tabv, int chunk) {
         const int rel = 2 * (st - chunk), lim = last_blk - 2 * chunk;     // table lanes of the step's two blocks
         const int b0 = __builtin_amdgcn_readlane(tabv, min(rel, lim)), b1 = __builtin_amdgcn_readlane(tabv, min(rel + 1, lim));
@@ -459,10 +474,22 @@ __global__ __launch_bounds__(64 * NQ) void attn_block_kernel(AttnArgs a) {
                 for (int r = 0; r < 16; ++r) o[d][r] *= alpha;
         }
         const f16x8* pb = pb_out;
+        const bool ragged = kv0 + 32 > kv_len;          // block-uniform: the sequence ends inside this step
 #pragma unroll
         for (int d = 0; d < DT; ++d) {
-            const f16x8 va = *(const f16x8*)(sV[buf] + (d * 32 + ql) * VLS + g * 8);
-            const f16x8 vb = *(const f16x8*)(sV[buf] + (HD + d * 32 + ql) * VLS + g * 8);
+            f16x8 va = *(const f16x8*)(sV[buf] + (d * 32 + ql) * VLS + g * 8);
+            f16x8 vb = *(const f16x8*)(sV[buf] + (HD + d * 32 + ql) * VLS + g * 8);
+            if (ragged) {
+                // slots past the end of the sequence hold whatever the pool memory held: exact zeros instead, so
+                // that their probability of 0 cannot meet a NaN or an infinity (element i of va is token
+                // (i / 4) * 8 + 4 g + i % 4 of the step's first block, of vb the same of its second block)
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const int key = kv0 + (i >> 2) * 8 + g * 4 + (i & 3);
+                    if (key >= kv_len) va[i] = (f16)0.f;
+                    if (key + 16 >= kv_len) vb[i] = (f16)0.f;
+                }
+            }
             o[d] = __builtin_amdgcn_mfma_f32_32x32x16_f16(va, pb[0], o[d], 0, 0, 0);
             o[d] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vb, pb[1], o[d], 0, 0, 0);
         }

@@ -23,6 +23,7 @@
 // Epilogues: fp32 store (optionally rms-scaled), residual add (+ norm preparation), SwiGLU
 // (two weight matrices share the A operand), and QKV (rms scale, rotary embedding, q to the
 // activation buffer, k and v straight into the KV pages).
+#include <algorithm>
 #include <cstdlib>
 #include <type_traits>
 
@@ -1118,10 +1119,16 @@ static void launch_skinny_nw(const GemmArgs& g, int nw, hipStream_t s) {
     launch_skinny_cols<EPI, MT, 16>(g, nw, s);
 }
 
+// Dispatch thresholds.  Each is a measured crossover (figures at its use); the product build compiles them in
+// as constants.  Only a build with -DAX_TUNING_KNOBS (kernel tuning sessions) lets the environment override them.
+#ifdef AX_TUNING_KNOBS
 static int env_int(const char* name, int dflt) {
     const char* v = std::getenv(name);
     return v && *v ? std::atoi(v) : dflt;
 }
+#else
+static constexpr int env_int(const char*, int dflt) { return dflt; }
+#endif
 static const int kSwigluStreamMinNK = env_int("AX_SWIGLU_STREAM_MIN_NK", 0);   // measurement switch: gate/up weights (2^20) per matrix from which verify-size calls stream (0 = never)
 static const int kStreamTm = env_int("AX_STREAM_TM", 1);   // experiment knob: 0 = always 128-row blocks
 static const int kSwigluWaves = env_int("AX_SWIGLU_WAVES", 4096);   // wavefronts in flight the SwiGLU launch aims for (two weight streams per wavefront)
@@ -1393,7 +1400,7 @@ static int launch_bf16(const GemmArgs& g, hipStream_t s) {
         int nw = 1;
         const int wave_target = EPI == EPI_SWIGLU ? kSwigluWaves : 2048;
         while (nw < 16 && tiles * nw < wave_target && K % (nw * 2 * 32) == 0 && K / (nw * 2) >= 128) nw *= 2;
-        if (kForceNW && K % (kForceNW * 32) == 0) nw = kForceNW;
+        if (kForceNW > 0 && K % (std::max(kForceNW, 1) * 32) == 0) nw = kForceNW;
         if (EPI == EPI_SWIGLU && nw == 16) nw = 8;        // LDS reduction buffer stays <= 64 KB
         if (M <= 16) launch_skinny_nw<EPI, 1>(g, nw, s);
         else launch_skinny_nw<EPI, 2>(g, nw, s);

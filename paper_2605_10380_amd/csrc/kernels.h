@@ -5,23 +5,13 @@
 #include <hip/hip_runtime.h>
 #include <cstdint>
 
+#include "kv_geom.h"
+
 namespace ax {
 
 // F32: fp32 weights, activations and KV.  BF16: bf16 weights; activations and KV are fp16
 // ("the activation type" below), products on the fp16 MFMA with fp32 accumulation.
 enum DType { F32 = 0, BF16 = 1 };
-
-// Geometry of the paged KV pool.  Element offsets (not bytes):
-//   K(l, hk, blk, slot, c) = (((l*2 + 0)*Hkv + hk)*n_blocks + blk)*B*hd + slot*hd + c
-//   V(l, hk, blk, c, slot) = (((l*2 + 1)*Hkv + hk)*n_blocks + blk)*B*hd + c*B + slot
-struct KVGeom {
-    void* base;
-    long long n_blocks;
-    int n_kv_heads, head_dim, block_tokens;
-    __host__ __device__ long long plane(int layer, int kv, int hk) const {
-        return ((long long)(layer * 2 + kv) * n_kv_heads + hk) * n_blocks * block_tokens * head_dim;
-    }
-};
 
 // Device views of the per-call descriptor (one packed int32 buffer uploaded per call).
 struct StepView {

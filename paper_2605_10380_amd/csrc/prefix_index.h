@@ -1,4 +1,4 @@
-// Index of cached token sequences for automatic prefix reuse (paper Sec. 3.1 and 4.2: a new
+// Index of cached token sequences for automatic prefix reuse (paper Sec. 2.3 and 4.2: a new
 // prompt reuses the cached KV up to the first mismatching token, the rest of the cached entry is
 // cut off).  Host only.  Every 16-token block boundary of an inserted sequence is entered under a
 // chained hash of the tokens up to it, so a lookup walks the prompt block by block in O(length),

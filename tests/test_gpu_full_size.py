@@ -3,7 +3,7 @@ benchmark times, checked through properties that hold at any size.
 
 A float64 prefix of 28 / 32 layers over 6144 / 8192 tokens is beyond what the CPU oracle does in
 test time (element-wise parity for these widths runs at 2 layers elsewhere), so these tests use
-what the method itself guarantees (paper Sec. 2.2 prefix reuse, Sec. 2.2 / 4.3 draft verification):
+what the method itself guarantees (paper Sec. 2.3 prefix reuse, Sec. 2.3 / 4.3 draft verification):
 the result of an extend does not depend on how the tokens were cut into calls; a verify round
 accepts exactly the prefix of the drafts that greedy decoding would have produced and hands back
 the greedy token; a rollback leaves no trace in what follows.  Tolerance for logits of two valid

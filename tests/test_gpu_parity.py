@@ -389,16 +389,15 @@ def test_full_width_two_layers(B, name, P, T, k):
     dm.close()
 
 
-def test_graph_replays_match_eager_verify(B, monkeypatch):
+def test_graph_replays_match_eager_verify(B):
     """Verify rounds replay a captured graph.  Several replays, with eager extends and
     synchronisations in between and the cache growing across a block boundary and across a
     change of the key-slice count, must give exactly what the uncaptured path gives."""
     sh = SMALL["bf16-hd64-g4"]
     w = I.make_weights(sh, 17)
     prompt = I.templated_prompt(sh.vocab, 17, 400)
-    monkeypatch.setenv("AX_NO_GRAPH", "1")
     eager = B.DeviceModel(sh, w, max_pos=1024, max_tokens=128, pool_tokens=2048)
-    monkeypatch.setenv("AX_NO_GRAPH", "0")
+    B.ax_dbg_use_graphs(eager.model, False)
     graph = B.DeviceModel(sh, w, max_pos=1024, max_tokens=128, pool_tokens=2048)
     ke, kg = eager.new_kv(), graph.new_kv()
     eager.extend(ke, prompt[:100])

@@ -384,12 +384,40 @@ def test_kv_footprint_matches_the_papers_figures():
     assert O.kv_bytes_per_token(sh.n_layers, sh.n_kv_heads, sh.head_dim, sh.itemsize) == bpt
 
 
-def test_draft_accuracy_bookkeeping_matches_table3():
+def test_draft_accuracy_matches_table3():
+    """accuracy = accepted / generated drafts: the oracle's bookkeeping reproduces the paper's column."""
+    from oracle import exspec as X
+    rows = 0
     for line in open(os.path.join(GOLDEN, "draft_accuracy.txt")):
         if line.startswith("#"):
             continue
         *_, gen, acc, ratio = line.split()
-        assert round(int(acc) / int(gen), 2) == float(ratio)
+        assert round(X.draft_accuracy(dict(drafted=int(gen), accepted=int(acc))), 2) == float(ratio)
+        rows += 1
+    assert rows == 4
+    assert X.draft_accuracy(dict(drafted=0, accepted=0)) == 0.0
+
+
+def test_top2_margin_hand_written_rows():
+    """The function that decides which GPU / oracle disagreements are exempt: gap between the two
+    largest entries, 0 on an exact tie for first place."""
+    assert O.top2_margin(np.array([1.0, 3.0, 2.0])) == 1.0
+    assert O.top2_margin(np.array([5.0, 5.0, 1.0])) == 0.0              # tie for first place
+    assert O.top2_margin(np.array([-3.0, -1.0, -2.0])) == 1.0            # all negative
+    assert O.top2_margin(np.array([9.0, 0.0, 0.0, 1.0])) == 8.0          # maximum first
+    assert O.top2_margin(np.array([0.0, 1.0, 0.0, 9.0])) == 8.0          # maximum last
+    assert O.top2_margin(np.array([2.0, 2.5])) == 0.5                    # two entries
+    assert O.top2_margin(np.array([7.0, -7.0, 7.0, 7.0])) == 0.0
+    assert abs(O.top2_margin(np.array([0.125, 0.120, -4.0])) - 0.005) < 1e-15
+    # not the range, not the gap to the mean, not the signed gap in storage order
+    row = np.array([4.0, 1.0, 3.5, -10.0])
+    assert O.top2_margin(row) == 0.5 and O.top2_margin(row[::-1].copy()) == 0.5
+    # brute force over random rows
+    rng = np.random.default_rng(5)
+    for _ in range(50):
+        r = rng.standard_normal(int(rng.integers(2, 40)))
+        s_ = sorted(r.tolist())
+        assert O.top2_margin(r) == s_[-1] - s_[-2]
 
 
 # ------------------------------------------------------------------ planted mistakes are caught
@@ -455,6 +483,70 @@ def test_ngram_lut_matches_hand_worked_example():
     uni = X.build_lut(ex["stream"], 1)
     assert uni == {(): 3}
     assert X.splitmix64(0) == 0xE220A8397B1DCDAF          # published first output for seed 0
+
+
+def _loop_example():
+    ex = {}
+    for line in open(os.path.join(GOLDEN, "exspec_loop_example.txt")):
+        if line.startswith("#") or ":" not in line:
+            continue
+        k, v = line.split(":")
+        ex[k.strip()] = [float(t) if "." in t else int(t) for t in v.split()]
+    return ex
+
+
+def successor_model(vocab=8):
+    """A decoder whose greedy token after t is (t + 1) mod vocab whatever the context: identity
+    embedding, zero attention-output and MLP-down projections, permutation LM head (the closed
+    form logits = rmsnorm(E[t]) W_lm^T pinned above)."""
+    sh = small_shape(d_model=vocab, n_q_heads=2, n_kv_heads=1, head_dim=vocab // 2, d_ff=16, vocab=vocab)
+    w = I.make_weights(sh, 91)
+    w["tok_emb"] = np.eye(vocab, dtype=np.float32)
+    w["final_norm"] = np.ones(vocab, dtype=np.float32)
+    lm = np.zeros((vocab, vocab), dtype=np.float32)
+    for t in range(vocab):
+        lm[(t + 1) % vocab, t] = 1.0
+    w["lm_head"] = lm
+    w["wo"] = [np.zeros_like(a) for a in w["wo"]]
+    w["w_down"] = [np.zeros_like(a) for a in w["w_down"]]
+    return sh, w
+
+
+def test_exspec_loop_counters_match_hand_worked_run():
+    """rounds / fallbacks / drafted / accepted of the decode loop, exactly, on a run worked by hand
+    (tests/golden/exspec_loop_example.txt): partial acceptance, a first-lookup miss that falls
+    back, a later miss that still drafts, and the cut of the last round's draft length."""
+    from oracle import exspec as X
+    ex = _loop_example()
+    sh, w = successor_model(ex["vocab"][0])
+    assert O.greedy_decode(sh, w, new_kv(sh), ex["pending"][0], 10) == ex["tokens"]
+    lut = X.build_lut(ex["stream"], ex["n"][0])
+    assert len(lut) == 9
+    kv = new_kv(sh)
+    O.forward(sh, w, ex["history"], kv)
+    out, st = X.generate(sh, w, kv, lut, ex["n"][0], ex["history"], ex["pending"][0], ex["max_new"][0], ex["k"][0],
+                         True, seed=1)
+    assert out == ex["tokens"]
+    assert st == dict(rounds=ex["rounds"][0], fallbacks=ex["fallbacks"][0], drafted=ex["drafted"][0],
+                      accepted=ex["accepted"][0])
+    assert X.draft_accuracy(st) == ex["accuracy"][0]
+    assert len(kv) == len(ex["history"]) + ex["max_new"][0]      # everything but the last emitted token
+    full = X.build_lut(ex["full_stream"], ex["n"][0])
+    for selective in (True, False):
+        kv = new_kv(sh)
+        O.forward(sh, w, ex["history"], kv)
+        out, st = X.generate(sh, w, kv, full, ex["n"][0], ex["history"], ex["pending"][0], ex["max_new"][0], ex["k"][0],
+                             selective, seed=1)
+        assert out == ex["tokens"]
+        assert st == dict(rounds=ex["full_rounds"][0], fallbacks=ex["full_fallbacks"][0], drafted=ex["full_drafted"][0],
+                          accepted=ex["full_accepted"][0])
+    # non-selective, first table: round 2 drafts three guesses instead of falling back, so no round
+    # falls back and 3 more drafts are generated (whether a guess happens to be right is up to the generator)
+    kv = new_kv(sh)
+    O.forward(sh, w, ex["history"], kv)
+    out, st = X.generate(sh, w, kv, lut, ex["n"][0], ex["history"], ex["pending"][0], ex["max_new"][0], ex["k"][0],
+                         False, seed=1)
+    assert out == ex["tokens"] and st["fallbacks"] == 0 and st["drafted"] >= st["accepted"] >= 0
 
 
 @pytest.mark.parametrize("selective", [True, False])

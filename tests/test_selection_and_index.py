@@ -133,6 +133,23 @@ def pool():
     B.ax_pool_destroy(p)
 
 
+def test_longest_cached_prefix_hand_worked():
+    """The oracle's lookup on sequences compared by eye (reuse stops at the first mismatch, paper
+    Sec. 2.3; a longer cached entry serves a shorter prompt by cutting its tail, Sec. 4.2)."""
+    cached = [[1, 2, 3, 4, 5], [1, 2, 3, 9], [1, 2, 3, 4, 5, 6, 7], [8, 8]]
+    assert S.longest_cached_prefix(cached, [1, 2, 3, 4, 5]) == (0, 5)           # full match; entry 2 ties at 5: lowest index
+    assert S.longest_cached_prefix(cached, [1, 2, 3, 4, 5, 6]) == (2, 6)        # entry 2 is longer
+    assert S.longest_cached_prefix(cached, [1, 2, 3, 9, 9]) == (1, 4)
+    assert S.longest_cached_prefix(cached, [1, 2, 7]) == (0, 2)                 # three entries tie at 2
+    assert S.longest_cached_prefix(cached, [8]) == (3, 1)                       # prompt shorter than the entry
+    assert S.longest_cached_prefix(cached, [7, 1, 2, 3]) == (-1, 0)             # mismatch at position 0
+    assert S.longest_cached_prefix(cached, []) == (-1, 0)                       # empty prompt
+    assert S.longest_cached_prefix([], [1, 2]) == (-1, 0)                       # nothing cached
+    assert S.longest_cached_prefix([[1, 2, 3], [1, 2, 3]], [1, 2, 3, 4]) == (0, 3)   # identical entries: the first
+    # later identical tokens do not count once one has differed
+    assert S.longest_cached_prefix([[1, 2, 3, 4, 5]], [1, 2, 0, 4, 5]) == (0, 2)
+
+
 def test_index_finds_longest_common_prefix(pool):
     rng = np.random.default_rng(3)
     base = I.templated_prompt(4096, 3, 200)
