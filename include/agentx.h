@@ -205,6 +205,18 @@ int64_t ax_kv_image_bytes(const ax_pool *p, int64_t n_tokens);          /* -1 on
 /* Writes the image of the first n_tokens (-1 = all) of kv; returns after the image is complete. */
 ax_status ax_kv_export(ax_model *model, const ax_kv *kv, int64_t n_tokens, void *image,
                        int64_t image_bytes, void *hip_stream);
+/* ax_kv_export for callers that cannot allocate or wait: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same image, byte for byte, but no model is needed (the
+ * block-id list the gather kernel walks is staged in a fixed 64 KiB device array of the library's
+ * own instead of a model's workspace) and nothing is allocated, copied through host staging or
+ * waited for: the call enqueues a few kernels on hip_stream and returns; the image is complete once
+ * the stream has passed them.  The pool's memory must live on the current device.  Limit: 16 384
+ * blocks (262 144 tokens), AX_ERR_UNSUPPORTED beyond.  `image` must be 4-byte aligned.
+ * All calls on one GPU share that GPU's array: calls on one stream are ordered, calls that overlap
+ * on different streams race on it.  Nothing in it has to start out as zero - every id a call reads
+ * it has staged itself. */
+ax_status ax_kv_export_static(const ax_kv *kv, int64_t n_tokens, void *image, int64_t image_bytes,
+                              void *hip_stream);
 /* Creates a sequence in `pool` holding the image's tokens.  Only enqueues: the image must stay
  * valid and unchanged until the stream has passed the copy; later calls on the same stream see
  * the imported values.  AX_ERR_OOM (nothing changed) if the pool lacks the blocks. */

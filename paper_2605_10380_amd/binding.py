@@ -66,6 +66,7 @@ def _load():
         "ax_kv_image_bytes": (i64, [vp, i64]),
         "ax_kv_export": (C.c_int, [vp, vp, i64, vp, i64, vp]),
         "ax_kv_import": (C.c_int, [vp, vp, vp, i64, C.POINTER(vp), vp]),
+        "ax_kv_export_static": (C.c_int, [vp, i64, vp, i64, vp]),
         "ax_index_create": (C.c_int, [vp, C.POINTER(vp)]),
         "ax_index_destroy": (None, [vp]),
         "ax_index_entries": (i64, [vp]),
@@ -242,6 +243,11 @@ def ax_kv_image_bytes(pool: int, n_tokens: int) -> int:
 
 def ax_kv_export(model: int, kv: int, n_tokens: int, image_ptr: int, image_bytes: int, stream: int = 0):
     _check(lib.ax_kv_export(model, kv, n_tokens, C.c_void_p(image_ptr), image_bytes, C.c_void_p(stream)))
+
+
+def ax_kv_export_static(kv: int, n_tokens: int, image_ptr: int, image_bytes: int, stream: int = 0):
+    """Enqueues only: synchronise the stream before reading the image."""
+    _check(lib.ax_kv_export_static(kv, n_tokens, C.c_void_p(image_ptr), image_bytes, C.c_void_p(stream)))
 
 
 def ax_kv_import(model: int, pool: int, image_ptr: int, image_bytes: int, stream: int = 0) -> int:

@@ -13,6 +13,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <vector>
 
 #include "handles.h"
@@ -800,6 +801,105 @@ ax_status ax_kv_export(ax_model* model, const ax_kv* kv, int64_t n_tokens, void*
         HIP_TRY(hipEventRecord(model->slot_done[slot], stream));
     }
     HIP_TRY(hipStreamSynchronize(stream));
+    return AX_OK;
+}
+
+// ---- export that allocates nothing --------------------------------------------------------------
+// ax_kv_export borrows a descriptor slot of a model's workspace for the device copy of the sequence's
+// block ids (the list the gather kernel walks).  This variant keeps that list in a fixed array of the
+// library's own instead, so it needs no model, no workspace and no allocation of any kind.
+
+constexpr int EXPORT_STATIC_MAX_BLOCKS = 16384;          // 64 KiB of block ids: sequences of up to 262 144 tokens
+static __device__ __align__(256) int scratch[EXPORT_STATIC_MAX_BLOCKS];
+
+namespace {
+
+constexpr int MAX_DEVICES = 64;
+int* g_scratch_ptr[MAX_DEVICES];                         // per device: where that GPU's copy of `scratch` lives
+std::mutex g_scratch_mu;
+
+// The array's name is only a stand-in on the host; its address on the current device is looked up
+// once per device and kept.
+ax_status scratch_of_current_device(int** out) {
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= MAX_DEVICES) return fail(AX_ERR_UNSUPPORTED, "device %d outside the %d this library keeps scratch for", dev, MAX_DEVICES);
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        int* p = nullptr;
+        HIP_TRY(hipGetSymbolAddress((void**)&p, HIP_SYMBOL(scratch)));
+        if (!p) return fail(AX_ERR_DEVICE, "hipGetSymbolAddress returned no address");
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return AX_OK;
+}
+
+// Block ids travel as kernel arguments, 512 at a time: no host staging buffer, no copy node.
+constexpr int ID_CHUNK = 512;
+struct IdChunk { int first, count; int ids[ID_CHUNK]; };
+__global__ __launch_bounds__(ID_CHUNK) void stage_ids_kernel(IdChunk c, int* __restrict__ dst) {
+    const int i = threadIdx.x;
+    if (i < c.count) dst[c.first + i] = c.ids[i];
+}
+struct HeaderWords { int w[16]; };
+__global__ __launch_bounds__(64) void image_header_kernel(HeaderWords h, int* __restrict__ dst) {
+    if (threadIdx.x < 16) dst[threadIdx.x] = h.w[threadIdx.x];
+}
+
+}  // namespace
+
+ax_status ax_kv_export_static(const ax_kv* kv, int64_t n_tokens, void* image, int64_t image_bytes, void* hip_stream) {
+    if (!ok(kv)) return fail(AX_ERR_INVALID, "bad KV handle");
+    if (n_tokens < 0) n_tokens = kv->seq.len;
+    if (n_tokens > kv->seq.len)
+        return fail(AX_ERR_INVALID, "export of %lld tokens from a sequence of %lld", (long long)n_tokens, (long long)kv->seq.len);
+    const ax_pool* pool = kv->pool;
+    if (!pool->geom.base) return fail(AX_ERR_INVALID, "pool has no device memory");
+    const int64_t nb = ax::blocks_for(n_tokens, 16);
+    if (nb > EXPORT_STATIC_MAX_BLOCKS)
+        return fail(AX_ERR_UNSUPPORTED, "%lld blocks (%lld tokens) exceed the %d blocks (%d tokens) of the library's static scratch; use ax_kv_export",
+                    (long long)nb, (long long)n_tokens, EXPORT_STATIC_MAX_BLOCKS, EXPORT_STATIC_MAX_BLOCKS * 16);
+    const int64_t need = ax_kv_image_bytes(pool, n_tokens);
+    if (!image || image_bytes < need || ((uintptr_t)image & 3) != 0)
+        return fail(AX_ERR_INVALID, "image buffer of %lld bytes, %lld needed (4-byte aligned)", (long long)image_bytes, (long long)need);
+    char* dev = nullptr;
+    ax_status st = device_view(image, (size_t)need, &dev);
+    if (st != AX_OK) return st;
+    // the scratch used is the current device's: the pool must live there too
+    hipPointerAttribute_t at{};
+    int cur = -1;
+    HIP_TRY(hipGetDevice(&cur));
+    if (hipPointerGetAttributes(&at, pool->geom.base) != hipSuccess || at.type != hipMemoryTypeDevice) {
+        (void)hipGetLastError();
+        return fail(AX_ERR_INVALID, "pool memory is not device memory");
+    }
+    if (at.device != cur) return fail(AX_ERR_INVALID, "pool memory lives on device %d, the current device is %d", at.device, cur);
+    int* ids = nullptr;
+    st = scratch_of_current_device(&ids);
+    if (st != AX_OK) return st;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    ImageHeader h{};
+    h.magic = IMAGE_MAGIC; h.version = 1;
+    h.n_layers = pool->cfg.n_layers; h.n_kv_heads = pool->cfg.n_kv_heads; h.head_dim = pool->cfg.head_dim;
+    h.dtype = pool->cfg.dtype; h.block_tokens = 16;
+    h.n_tokens = n_tokens; h.payload_bytes = need - (int64_t)sizeof(ImageHeader);
+    HeaderWords hw;
+    static_assert(sizeof(HeaderWords) == sizeof(ImageHeader), "header travels as 16 words");
+    std::memcpy(&hw, &h, sizeof hw);
+    image_header_kernel<<<1, 64, 0, stream>>>(hw, (int*)dev);
+    for (int64_t b0 = 0; b0 < nb; b0 += ID_CHUNK) {
+        IdChunk c;
+        c.first = (int)b0;
+        c.count = (int)std::min<int64_t>(ID_CHUNK, nb - b0);
+        for (int i = 0; i < c.count; ++i) c.ids[i] = kv->seq.blocks[(size_t)(b0 + i)];
+        for (int i = c.count; i < ID_CHUNK; ++i) c.ids[i] = 0;
+        stage_ids_kernel<<<1, ID_CHUNK, 0, stream>>>(c, ids);
+    }
+    if (nb > 0)
+        ax::launch_kv_image(true, pool->cfg.dtype == AX_F32 ? ax::F32 : ax::BF16, pool->geom, pool->cfg.n_layers, ids,
+                            (int)nb, dev + sizeof(ImageHeader), (int)(n_tokens - (nb - 1) * 16), stream);
+    HIP_TRY(hipGetLastError());
     return AX_OK;
 }
 
