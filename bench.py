@@ -238,6 +238,8 @@ def main():
     ap.add_argument("--seed", type=int, default=2000)
     ap.add_argument("--extend-T", type=int, default=0, help="override the workload's T (the configurations list several for config 3)")
     ap.add_argument("--verify-k", type=int, default=-1, help="override the workload's draft count k")
+    ap.add_argument("--act-split", type=int, default=0, choices=(-1, 0, 1),
+                    help="ax_model_config.act_split: 0 = the library decides (hi + lo fp16 activations for deep wide models), 1 = on, -1 = off")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (sessions would shard across GPUs with no "
@@ -262,7 +264,8 @@ def main():
     w = torch_weights(torch, sh, args.seed, dev)
     prompt = I.templated_prompt(sh.vocab, args.seed, P + T)
     max_pos = P + T + rounds * (k + 1) + 64
-    dm = B.DeviceModel(sh, w, max_pos=max_pos, max_tokens=max(512, T), pool_tokens=max_pos + 64 + P + 16)
+    dm = B.DeviceModel(sh, w, max_pos=max_pos, max_tokens=max(512, T), pool_tokens=max_pos + 64 + P + 16,
+                       act_split=args.act_split)
     kv = dm.new_kv()
     torch.cuda.synchronize()
     t_prefill = time.perf_counter()

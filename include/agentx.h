@@ -71,7 +71,21 @@ typedef struct {
     int max_pos;      /* longest sequence (P + T) any KV of this model may reach                    */
     int max_tokens;   /* most rows (sum of T over the sequences) one ax_extend* call may carry      */
     int max_seqs;     /* most sequences one ax_extend_batch call may carry (>= 1)                   */
+    int act_split;    /* AX_BF16 models: activations between kernels as hi + lo fp16 pairs (see below).
+                         0 = automatic (on when n_layers * d_model >= 131072), 1 = on, -1 = off     */
 } ax_model_config;
+
+/* Precision of AX_BF16 models.  Between kernels an activation is one fp16 value (11 significant
+ * bits); the residual stream, norms, softmax and all accumulators are fp32.  The rounding of the
+ * activations is what separates the logits from the exact ones, and it grows with the square root
+ * of the depth and with the width: measured on N(0, 0.02) weights, max-abs over all logits of 128
+ * rows, 5e-3 for the ~1B shape (16 layers), 1.3e-2 for the ~3B shape (28 layers), 2.7e-2 for the
+ * ~8B shape (32 layers).  With act_split every such activation is kept as two fp16 values whose
+ * sum carries ~22 bits and every kernel multiplies both against the same weights: no extra weight
+ * traffic (few-row calls cost the same), twice the matrix-core work in many-row calls; the ~8B
+ * shape then stays near 1.2e-2.  The KV cache holds one fp16 per entry either way.
+ * Range: fp16(x * gain) must stay finite, i.e. |residual stream * norm gain| < 65504 (tested up
+ * to 6e3); beyond that the result is not finite. */
 
 /* Device pointers, row-major [out, in] (y = x W^T).  Element type = config.dtype.
  * Per-layer members are HOST arrays of n_layers device pointers (copied at create time).

@@ -22,7 +22,7 @@ AX_OUT_NONE, AX_OUT_LAST_LOGITS, AX_OUT_ALL_LOGITS, AX_OUT_LAST_ARGMAX, AX_OUT_A
 class ax_model_config(C.Structure):
     _fields_ = [(n, C.c_int) for n in ("n_layers", "d_model", "n_q_heads", "n_kv_heads", "head_dim", "d_ff", "vocab")] + [
         ("rms_eps", C.c_float), ("rope_base", C.c_float), ("dtype", C.c_int), ("max_pos", C.c_int),
-        ("max_tokens", C.c_int), ("max_seqs", C.c_int)]
+        ("max_tokens", C.c_int), ("max_seqs", C.c_int), ("act_split", C.c_int)]
 
 
 class ax_exspec_stats(C.Structure):
@@ -115,10 +115,11 @@ def _check(status: int):
         raise AxError(status)
 
 
-def make_config(shape, max_pos: int, max_tokens: int, max_seqs: int = 1) -> ax_model_config:
+def make_config(shape, max_pos: int, max_tokens: int, max_seqs: int = 1, act_split: int = 0) -> ax_model_config:
+    """act_split: 0 = the library decides (hi + lo fp16 activations for deep, wide bf16 models), 1 = on, -1 = off."""
     return ax_model_config(shape.n_layers, shape.d_model, shape.n_q_heads, shape.n_kv_heads, shape.head_dim,
                            shape.d_ff, shape.vocab, shape.rms_eps, shape.rope_base,
-                           AX_F32 if shape.dtype == "f32" else AX_BF16, max_pos, max_tokens, max_seqs)
+                           AX_F32 if shape.dtype == "f32" else AX_BF16, max_pos, max_tokens, max_seqs, act_split)
 
 
 def _i32(a):
@@ -439,7 +440,7 @@ class DeviceModel:
     """
 
     def __init__(self, shape, weights: dict, max_pos: int, max_tokens: int, pool_tokens: int,
-                 max_seqs: int = 1, device: str = "cuda:0", pool_fill=None):
+                 max_seqs: int = 1, device: str = "cuda:0", pool_fill=None, act_split: int = 0):
         import torch
         if not torch.cuda.is_available():
             raise RuntimeError("no GPU: the extend / verify path has no CPU fallback")
@@ -456,7 +457,7 @@ class DeviceModel:
             return t.to(self.device)
 
         self.w = {k: ([up(a) for a in v] if isinstance(v, list) else up(v)) for k, v in weights.items()}
-        self.cfg = make_config(shape, max_pos, max_tokens, max_seqs)
+        self.cfg = make_config(shape, max_pos, max_tokens, max_seqs, act_split)
         ws_bytes = ax_workspace_bytes(self.cfg)
         if ws_bytes == 0:
             raise AxError(AX_ERR_UNSUPPORTED)

@@ -46,6 +46,9 @@ struct Layout {                       // byte offsets into the workspace
     size_t desc_ints;                 // capacity of one descriptor slot
     size_t max_records;               // split-attention partial records one pass may write (there is room for two passes)
     int max_tiles, max_bt;
+    // split activations: element offsets from the hi part of each 16-bit activation buffer to its lo part (0 = off)
+    long long h_lo, q_lo, attn_lo, ffn_lo;
+    size_t h_bytes, q_bytes, attn_bytes, ffn_bytes;    // sizes of the hi parts (what ax_dbg_read hands out)
 };
 
 size_t packed_weight_bytes(const ax_model_config& c) {
@@ -66,13 +69,23 @@ Layout make_layout(const ax_model_config& c) {
     L.rope_cos = take((size_t)c.max_pos * (c.head_dim / 2) * 4);
     L.rope_sin = take((size_t)c.max_pos * (c.head_dim / 2) * 4);
     L.desc = take((N_SLOTS + 1) * align_up(L.desc_ints * 4));   // ring + the slot of captured graphs
+    const size_t parts = ax::act_split_on(c) ? 2 : 1;         // hi part, then (split activations) the lo part
+    const size_t qdim = (size_t)c.n_q_heads * c.head_dim;
     L.x = take(T * c.d_model * 4);
-    L.h = take(T * c.d_model * a);
+    L.h_bytes = T * c.d_model * a;
+    L.h = take(parts * L.h_bytes);
     L.ssq = take(T * (size_t)(c.d_model / 8 + 1) * 4);        // sum-of-squares partials per row
-    L.qkv = take(T * (size_t)(c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim * 4);
-    L.q = take(T * (size_t)c.n_q_heads * c.head_dim * a);
-    L.attn = take(T * (size_t)c.n_q_heads * c.head_dim * a);
-    L.ffn = take(T * (size_t)c.d_ff * a);
+    L.qkv = take(c.dtype == AX_F32 ? T * (size_t)(c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim * 4 : 0);   // fp32 models only
+    L.q_bytes = L.attn_bytes = T * qdim * a;
+    L.q = take(parts * L.q_bytes);
+    L.attn = take(parts * L.attn_bytes);
+    L.ffn_bytes = T * (size_t)c.d_ff * a;
+    L.ffn = take(parts * L.ffn_bytes);
+    if (parts == 2) {
+        L.h_lo = (long long)(T * c.d_model);
+        L.q_lo = L.attn_lo = (long long)(T * qdim);
+        L.ffn_lo = (long long)(T * c.d_ff);
+    }
     // Partial records of the split attention: one per (q tile of 32 stacked rows, KV head, key slice).  A call
     // whose longest sequence runs on blocks of 4 or 8 tiles pads EVERY sequence to whole blocks, so the most a
     // call can need with one slice is (T G / 32 + 8 per sequence) tiles per KV head; the slice count is then
@@ -418,40 +431,40 @@ ax_status enqueue_call(ax_model* m, const CallPlan& cp, void* out, hipStream_t s
         base.M = R;
         base.split_ws = (float*)(ws + L.splitk);
         base.split_ws_bytes = (size_t)c.max_tokens * c.d_model * 4 * ax::SPLITK_MAX;
-        auto normed = [&](ax::GemmArgs& g) { g.A = h; g.ssq = ssq; g.nparts = nparts; g.d_norm = d_model; g.eps = c.rms_eps; g.K = d_model; };
-        ax::launch_embed_norm(m->tok_emb, sv.row_tok, m->norm_attn[0], x, h, ssq, nparts, R, d_model, stream);
+        auto normed = [&](ax::GemmArgs& g) { g.A = h; g.a_lo_off = L.h_lo; g.ssq = ssq; g.nparts = nparts; g.d_norm = d_model; g.eps = c.rms_eps; g.K = d_model; };
+        ax::launch_embed_norm(m->tok_emb, sv.row_tok, m->norm_attn[0], x, h, L.h_lo, ssq, nparts, R, d_model, stream);
         for (int l = 0; l < c.n_layers; ++l) {
             {
                 ax::GemmArgs g = base;
                 normed(g);
                 g.W = m->wqkv[(size_t)l]; g.N = qkv_rows;
-                g.rope.kv = kg; g.rope.layer = l; g.rope.n_q_heads = c.n_q_heads; g.rope.q_out = qb;
+                g.rope.kv = kg; g.rope.layer = l; g.rope.n_q_heads = c.n_q_heads; g.rope.q_out = qb; g.c_lo_off = L.q_lo;
                 g.rope.row_pos = sv.row_pos; g.rope.row_slot = sv.row_slot;
                 g.rope.cos = (const float*)(ws + L.rope_cos); g.rope.sin = (const float*)(ws + L.rope_sin);
                 ProfScope ps(m, 0, stream);
                 ax::launch_gemm_bf16(ax::EPI_QKV, g, stream);
             }
             { ProfScope ps(m, 1, stream);
-              ax::launch_attention(dt, qb, attn, kg, l, sv, c.n_q_heads, (float*)(ws + L.partials), n_splits, stream); }
+              ax::launch_attention(dt, qb, attn, kg, l, sv, c.n_q_heads, (float*)(ws + L.partials), n_splits, stream, L.q_lo, L.attn_lo); }
             { ProfScope empty(m, 6, stream); }         // bracket around nothing: the cost of the two events
             {
                 ax::GemmArgs g = base;
-                g.A = attn; g.K = qdim; g.W = m->wo[(size_t)l]; g.N = d_model;
-                g.Cf = x; g.C16 = h; g.gain_next = m->norm_mlp[(size_t)l]; g.ssq_out = ssq;
+                g.A = attn; g.a_lo_off = L.attn_lo; g.K = qdim; g.W = m->wo[(size_t)l]; g.N = d_model;
+                g.Cf = x; g.C16 = h; g.c_lo_off = L.h_lo; g.gain_next = m->norm_mlp[(size_t)l]; g.ssq_out = ssq;
                 ProfScope ps(m, 2, stream);
                 nparts = ax::launch_gemm_bf16(ax::EPI_RESIDUAL, g, stream);
             }
             {
                 ax::GemmArgs g = base;
                 normed(g);
-                g.W = m->w_gate[(size_t)l]; g.W2 = m->w_up[(size_t)l]; g.N = c.d_ff; g.C16 = ffn;
+                g.W = m->w_gate[(size_t)l]; g.W2 = m->w_up[(size_t)l]; g.N = c.d_ff; g.C16 = ffn; g.c_lo_off = L.ffn_lo;
                 ProfScope ps(m, 3, stream);
                 ax::launch_gemm_bf16(ax::EPI_SWIGLU, g, stream);
             }
             {
                 ax::GemmArgs g = base;
-                g.A = ffn; g.K = c.d_ff; g.W = m->w_down[(size_t)l]; g.N = d_model;
-                g.Cf = x; g.C16 = h; g.ssq_out = ssq;
+                g.A = ffn; g.a_lo_off = L.ffn_lo; g.K = c.d_ff; g.W = m->w_down[(size_t)l]; g.N = d_model;
+                g.Cf = x; g.C16 = h; g.c_lo_off = L.h_lo; g.ssq_out = ssq;
                 g.gain_next = l + 1 < c.n_layers ? m->norm_attn[(size_t)l + 1] : m->final_norm;
                 ProfScope ps(m, 4, stream);
                 nparts = ax::launch_gemm_bf16(ax::EPI_RESIDUAL, g, stream);
@@ -1187,10 +1200,10 @@ ax_status ax_dbg_read(ax_model* m, int which, void* host_dst, size_t bytes) {
     if (!ok(m) || !host_dst) return fail(AX_ERR_INVALID, "bad argument");
     const Layout& L = m->lay;
     const size_t off[6] = {L.x, L.qkv, L.q, L.attn, L.ffn, L.h};
-    const size_t end[6] = {L.h, L.q, L.attn, L.ffn, L.partials, L.ssq};
+    const size_t len[6] = {L.h - L.x, L.q - L.qkv, L.q_bytes, L.attn_bytes, L.ffn_bytes, L.h_bytes};   // hi parts only
     if (which < 0 || which > 5) return fail(AX_ERR_INVALID, "bad buffer id");
     HIP_TRY(hipDeviceSynchronize());
-    HIP_TRY(hipMemcpy(host_dst, m->ws + off[which], std::min(bytes, end[which] - off[which]), hipMemcpyDeviceToHost));
+    HIP_TRY(hipMemcpy(host_dst, m->ws + off[which], std::min(bytes, len[which]), hipMemcpyDeviceToHost));
     return AX_OK;
 }
 

@@ -56,6 +56,7 @@ bool config_ok(const ax_model_config* c, ax_status* why) {
     if (c->n_q_heads % c->n_kv_heads != 0) return false;
     if (c->dtype != AX_F32 && c->dtype != AX_BF16) return false;
     if (!(c->rms_eps >= 0.f) || !(c->rope_base > 0.f)) return false;
+    if (c->act_split < -1 || c->act_split > 1) return false;
     *why = AX_ERR_UNSUPPORTED;
     if (c->head_dim % 2 != 0 || c->head_dim > 256) return false;
     if (c->dtype == AX_BF16) {

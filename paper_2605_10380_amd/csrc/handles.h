@@ -60,4 +60,10 @@ bool config_ok(const ax_model_config* c, ax_status* why);
 
 inline int itemsize(int dtype) { return dtype == AX_F32 ? 4 : 2; }
 
+// Whether a model keeps its activations as hi + lo fp16 pairs (ax_model_config.act_split; see agentx.h).
+inline bool act_split_on(const ax_model_config& c) {
+    if (c.dtype != AX_BF16 || c.act_split < 0) return false;
+    return c.act_split > 0 || (long long)c.n_layers * c.d_model >= 131072;
+}
+
 }  // namespace ax

@@ -181,6 +181,7 @@ __device__ __forceinline__ bool online_softmax_step(f32x16& s, int kv0, int g, i
 struct AttnArgs {
     const f16* q;
     f16* out;
+    long long q_lo_off, out_lo_off;   // split activations: lo parts of q / out this many elements behind (0 = not split)
     KVGeom kv;
     int layer, Hq, n_splits;
     const int* tile_info;      // per q-tile group, 8 ints: seq, first stacked row, P, T, row0, block-table offset,
@@ -197,9 +198,11 @@ struct AttnArgs {
 // record is one 32-byte load, the block-table entries of the whole key slice are fetched by
 // one wavefront-wide load (and handed out with shuffles), and the K/V operands of step s + 1
 // are in flight while step s is multiplied.
-template <int HD, int NQ>
+// QS: q comes as hi and lo parts (split activations): the score product takes both against the same K operand.
+template <int HD, int NQ, bool QS = false>
 __global__ __launch_bounds__(64) void attn_split_kernel(AttnArgs a) {
     constexpr int KQ = HD / 16;          // MFMA k-steps of the score product
+    constexpr int NP = QS ? 2 : 1;
     constexpr int DT = HD / 32;          // 32-channel tiles of the output
     constexpr int PS = HD * 32 + 64;     // floats of one partial: O^T [HD][32], m[32], l[32]
     const int tile = blockIdx.x, hk = blockIdx.y, split = blockIdx.z;
@@ -223,7 +226,7 @@ __global__ __launch_bounds__(64) void attn_split_kernel(AttnArgs a) {
 
     // this lane's query rows (clamped rows compute garbage that is never written)
     int pos_q[NQ], pos_min[NQ];          // pos_min: earliest position among the tile's rows (uniform)
-    f16x8 qf[NQ][KQ];
+    f16x8 qf[NQ][NP][KQ];
 #pragma unroll
     for (int t = 0; t < NQ; ++t) {
         const int rq = min(r0 + t * 32 + ql, n_stacked - 1);
@@ -232,7 +235,9 @@ __global__ __launch_bounds__(64) void attn_split_kernel(AttnArgs a) {
         pos_min[t] = P + min(r0 + t * 32, n_stacked - 1) / G;
         const f16* qrow = a.q + ((long long)(row0 + tq) * Hq + hk * G + gq) * HD;
 #pragma unroll
-        for (int kk = 0; kk < KQ; ++kk) qf[t][kk] = *(const f16x8*)(qrow + kk * 16 + g * 8);
+        for (int p = 0; p < NP; ++p)
+#pragma unroll
+            for (int kk = 0; kk < KQ; ++kk) qf[t][p][kk] = *(const f16x8*)(qrow + (p ? a.q_lo_off : 0) + kk * 16 + g * 8);
     }
 
     const f16* Kp = (const f16*)a.kv.base + a.kv.plane(a.layer, 0, hk);
@@ -293,7 +298,9 @@ __global__ __launch_bounds__(64) void attn_split_kernel(AttnArgs a) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) s[r] = 0.f;
 #pragma unroll
-            for (int kk = 0; kk < KQ; ++kk) s = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf[buf][kk], qf[t][kk], s, 0, 0, 0);
+            for (int kk = 0; kk < KQ; ++kk)
+#pragma unroll
+                for (int p = 0; p < NP; ++p) s = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf[buf][kk], qf[t][p][kk], s, 0, 0, 0);
             float alpha;
             f16x8 pb[2];
             if (online_softmax_step(s, kv0, g, pos_q[t], kv0 + 31 > pos_min[t], c, m[t], l[t], alpha, pb)) {
@@ -363,9 +370,10 @@ __global__ __launch_bounds__(64) void attn_split_kernel(AttnArgs a) {
 // free); V rows [2 blocks * HD channels][16 tokens in operand order + 8 pad], where operand order
 // puts tokens {0-3, 8-11, 4-7, 12-15} so that a lane's PV operand (tokens 4g..4g+3 and
 // 8+4g..8+4g+3 of its channel) is one 16-byte read.
-template <int HD, int NQ>
+template <int HD, int NQ, bool QS = false>
 __global__ __launch_bounds__(64 * NQ) void attn_block_kernel(AttnArgs a) {
     constexpr int KQ = HD / 16, DT = HD / 32, PS = HD * 32 + 64, NT = 64 * NQ;
+    constexpr int NP = QS ? 2 : 1;       // q in hi and lo parts (split activations)
     constexpr int D = 4;                              // prefetch distance in key steps (even)
     constexpr int KLS = HD + 8, VLS = 24;             // padded LDS row lengths (fp16 elements)
     constexpr int TCH = 32 * HD / 8;                  // 16-byte chunks of K (and of V) per step
@@ -394,9 +402,11 @@ __global__ __launch_bounds__(64 * NQ) void attn_block_kernel(AttnArgs a) {
     const int tq = rq / G, gq = rq % G;
     const int pos_q = P + tq;
     const f16* qrow = a.q + ((long long)(row0 + tq) * Hq + hk * G + gq) * HD;
-    f16x8 qf[KQ];
+    f16x8 qf[NP][KQ];
 #pragma unroll
-    for (int kk = 0; kk < KQ; ++kk) qf[kk] = *(const f16x8*)(qrow + kk * 16 + g * 8);
+    for (int p = 0; p < NP; ++p)
+#pragma unroll
+        for (int kk = 0; kk < KQ; ++kk) qf[p][kk] = *(const f16x8*)(qrow + (p ? a.q_lo_off : 0) + kk * 16 + g * 8);
 
     const f16* Kp = (const f16*)a.kv.base + a.kv.plane(a.layer, 0, hk);
     const f16* Vp = (const f16*)a.kv.base + a.kv.plane(a.layer, 1, hk);
@@ -464,7 +474,8 @@ __global__ __launch_bounds__(64 * NQ) void attn_block_kernel(AttnArgs a) {
 #pragma unroll
         for (int kk = 0; kk < KQ; ++kk) {
             const f16x8 kf = *(const f16x8*)(sK[buf] + ql * KLS + kk * 16 + g * 8);
-            s = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf, qf[kk], s, 0, 0, 0);
+#pragma unroll
+            for (int p = 0; p < NP; ++p) s = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf, qf[p][kk], s, 0, 0, 0);
         }
         if (online_softmax_step(s, kv0, g, pos_q, kv0 + 31 > pos_tile_min, c, m, l, alpha_out, pb_out)) {
             const float alpha = alpha_out;
@@ -629,7 +640,11 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(AttnArgs a) {
     float L = 0.f, o = 0.f;
 #pragma unroll
     for (int i = 0; i < 8; ++i) { L += red[i][1][ql]; o += red[i][2 + sg][ql]; }
-    a.out[((long long)(row0 + r / G) * a.Hq + hk * G + r % G) * HD + ch0 + sg] = (f16)(o / L);
+    f16* dst = a.out + ((long long)(row0 + r / G) * a.Hq + hk * G + r % G) * HD + ch0 + sg;
+    const float res = o / L;
+    const f16 hi = (f16)res;
+    *dst = hi;
+    if (a.out_lo_off) dst[a.out_lo_off] = (f16)(res - (float)hi);
 }
 
 // Slice merge for launches with many tile records and few slices each (the block kernel's groups
@@ -694,10 +709,15 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a) {
     f16* dst = a.out + ((long long)(row0 + r / G) * a.Hq + hk * G + r % G) * HD + cg * CPT;
 #pragma unroll
     for (int c0 = 0; c0 < CPT; c0 += 8) {
-        f16x8 v;
+        f16x8 v, lo;
 #pragma unroll
-        for (int c = 0; c < 8; ++c) v[c] = (f16)(acc[c0 + c] * inv);
+        for (int c = 0; c < 8; ++c) {
+            const float ov = acc[c0 + c] * inv;
+            v[c] = (f16)ov;
+            lo[c] = (f16)(ov - (float)v[c]);
+        }
         *(f16x8*)(dst + c0) = v;
+        if (a.out_lo_off) *(f16x8*)(dst + a.out_lo_off + c0) = lo;
     }
 }
 
@@ -708,7 +728,8 @@ size_t attention_partial_floats(int n_tiles, int n_kv_heads, int head_dim, int n
 template <int HD, int NQ>
 static void launch_attn_mfma(const AttnArgs& a, int n_groups, hipStream_t s) {
     dim3 grid(n_groups, a.kv.n_kv_heads, a.n_splits), cgrid(n_groups * a.kv.n_kv_heads * NQ, HD / 4);
-    attn_split_kernel<HD, NQ><<<grid, 64, 0, s>>>(a);
+    if (a.q_lo_off) attn_split_kernel<HD, NQ, true><<<grid, 64, 0, s>>>(a);
+    else attn_split_kernel<HD, NQ, false><<<grid, 64, 0, s>>>(a);
     // few records with many slices (one session): blocks of 4 channels that spread the slices over
     // threads; many records with few slices (many sessions): one block per record
     if (n_groups * a.kv.n_kv_heads >= 64 && a.n_splits + a.shared_splits <= 32)
@@ -717,8 +738,15 @@ static void launch_attn_mfma(const AttnArgs& a, int n_groups, hipStream_t s) {
         attn_combine_kernel<HD, NQ><<<cgrid, 256, 0, s>>>(a);
 }
 
+template <int HD, int NQ>
+static void launch_attn_block(const AttnArgs& a, dim3 grid, hipStream_t s) {
+    if (a.q_lo_off) attn_block_kernel<HD, NQ, true><<<grid, 64 * NQ, 0, s>>>(a);
+    else attn_block_kernel<HD, NQ, false><<<grid, 64 * NQ, 0, s>>>(a);
+}
+
 void launch_attention(DType dt, const void* q, void* out, KVGeom kv, int layer, const StepView& sv,
-                      int n_q_heads, float* partials, int n_splits, hipStream_t s) {
+                      int n_q_heads, float* partials, int n_splits, hipStream_t s, long long q_lo_off,
+                      long long out_lo_off) {
     if (dt == F32) {
         dim3 grid(sv.n_rows, n_q_heads);
         attn_simple_kernel<float, 256><<<grid, 64, 0, s>>>((const float*)q, (float*)out, kv, layer,
@@ -729,24 +757,25 @@ void launch_attention(DType dt, const void* q, void* out, KVGeom kv, int layer, 
     AttnArgs a{};
     a.q = (const f16*)q; a.out = (f16*)out; a.kv = kv; a.layer = layer; a.Hq = n_q_heads; a.n_splits = n_splits;
     a.tile_info = sv.tile_info; a.bt = sv.bt; a.partials = partials;
+    a.q_lo_off = q_lo_off; a.out_lo_off = out_lo_off;
     const int hd = kv.head_dim;
     if (sv.tile_nq >= 4) {                                     // long extends: 4 or 8 tiles per block, K/V through LDS
         dim3 grid(sv.n_tiles, kv.n_kv_heads, n_splits);
         const unsigned mgrid = (unsigned)(sv.n_tiles * kv.n_kv_heads * sv.tile_nq);
         if (sv.tile_nq == 4) {
             if (hd == 64) {
-                attn_block_kernel<64, 4><<<grid, 256, 0, s>>>(a);
+                launch_attn_block<64, 4>(a, grid, s);
                 attn_merge_kernel<64, 4><<<mgrid, 256, 0, s>>>(a);
             } else {
-                attn_block_kernel<128, 4><<<grid, 256, 0, s>>>(a);
+                launch_attn_block<128, 4>(a, grid, s);
                 attn_merge_kernel<128, 4><<<mgrid, 256, 0, s>>>(a);
             }
         } else {
             if (hd == 64) {
-                attn_block_kernel<64, 8><<<grid, 512, 0, s>>>(a);
+                launch_attn_block<64, 8>(a, grid, s);
                 attn_merge_kernel<64, 8><<<mgrid, 256, 0, s>>>(a);
             } else {
-                attn_block_kernel<128, 8><<<grid, 512, 0, s>>>(a);
+                launch_attn_block<128, 8>(a, grid, s);
                 attn_merge_kernel<128, 8><<<mgrid, 256, 0, s>>>(a);
             }
         }
@@ -763,9 +792,9 @@ void launch_attention(DType dt, const void* q, void* out, KVGeom kv, int layer, 
             sh.partials = partials + attention_partial_floats(sv.n_tiles, kv.n_kv_heads, hd, n_splits);
             dim3 grid(sv.n_tiles_shared, kv.n_kv_heads, sv.shared_splits);
             if (sv.shared_nq == 4) {
-                if (hd == 64) attn_block_kernel<64, 4><<<grid, 256, 0, s>>>(sh); else attn_block_kernel<128, 4><<<grid, 256, 0, s>>>(sh);
+                if (hd == 64) launch_attn_block<64, 4>(sh, grid, s); else launch_attn_block<128, 4>(sh, grid, s);
             } else {
-                if (hd == 64) attn_block_kernel<64, 8><<<grid, 512, 0, s>>>(sh); else attn_block_kernel<128, 8><<<grid, 512, 0, s>>>(sh);
+                if (hd == 64) launch_attn_block<64, 8>(sh, grid, s); else launch_attn_block<128, 8>(sh, grid, s);
             }
             a.shared_partials = sh.partials;
             a.shared_splits = sv.shared_splits;

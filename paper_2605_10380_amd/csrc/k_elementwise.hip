@@ -44,7 +44,7 @@ void launch_embed(DType dt, const void* emb, const int* row_tok, float* x, int n
 // zeroed so that the row looks like the output of a GEMM with `nparts` column blocks).
 __global__ void embed_norm_kernel(const bf16* __restrict__ emb, const int* __restrict__ row_tok,
                                   const bf16* __restrict__ gain, float* __restrict__ x,
-                                  f16* __restrict__ a, float* __restrict__ ssq, int nparts, int d) {
+                                  f16* __restrict__ a, long long a_lo_off, float* __restrict__ ssq, int nparts, int d) {
     __shared__ float part[4];
     const int r = blockIdx.x;
     const bf16* src = emb + (long long)row_tok[r] * d;
@@ -52,7 +52,10 @@ __global__ void embed_norm_kernel(const bf16* __restrict__ emb, const int* __res
     for (int c = threadIdx.x; c < d; c += 256) {
         const float v = (float)src[c];
         x[(long long)r * d + c] = v;
-        a[(long long)r * d + c] = (f16)(v * (float)gain[c]);
+        const float av = v * (float)gain[c];
+        const f16 hi = (f16)av;
+        a[(long long)r * d + c] = hi;
+        if (a_lo_off) a[(long long)r * d + c + a_lo_off] = (f16)(av - (float)hi);     // split activations: the rounding remainder
         ss += v * v;
     }
     ss = wave_sum(ss);
@@ -62,9 +65,9 @@ __global__ void embed_norm_kernel(const bf16* __restrict__ emb, const int* __res
         ssq[(long long)r * nparts + p] = p == 0 ? part[0] + part[1] + part[2] + part[3] : 0.f;
 }
 
-void launch_embed_norm(const void* emb, const int* row_tok, const void* gain, float* x, void* a,
+void launch_embed_norm(const void* emb, const int* row_tok, const void* gain, float* x, void* a, long long a_lo_off,
                        float* ssq, int nparts, int n_rows, int d, hipStream_t s) {
-    embed_norm_kernel<<<n_rows, 256, 0, s>>>((const bf16*)emb, row_tok, (const bf16*)gain, x, (f16*)a, ssq,
+    embed_norm_kernel<<<n_rows, 256, 0, s>>>((const bf16*)emb, row_tok, (const bf16*)gain, x, (f16*)a, a_lo_off, ssq,
                                              nparts, d);
 }
 

@@ -61,6 +61,23 @@ __device__ __forceinline__ f16x8 bf16x8_to_f16x8(u32x4 raw) {
 }
 __device__ __forceinline__ f16x8 load_w(const bf16* p) { return *(const f16x8*)p; }     // packed weights are already fp16
 
+// Split activations (see GemmArgs): v goes out as hi = fp16(v) and, lo_off elements further on, lo = fp16(v - hi).
+__device__ __forceinline__ void store_split(f16* p, long long lo_off, float v) {
+    const f16 hi = (f16)v;
+    *p = hi;
+    if (lo_off) p[lo_off] = (f16)(v - (float)hi);
+}
+__device__ __forceinline__ void store_split4(f16* p, long long lo_off, const float (&v)[4]) {
+    f16x4 hi, lo;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        hi[r] = (f16)v[r];
+        lo[r] = (f16)(v[r] - (float)hi[r]);
+    }
+    *(f16x4*)p = hi;
+    if (lo_off) *(f16x4*)(p + lo_off) = lo;
+}
+
 // ------------------------------------------------------------------------------ weight layout
 // bf16 weight matrices are not read as given.  ax_model_create repacks every [N, K] matrix once,
 // widening each bf16 to fp16 on the way (the round-toward-zero pack above: exact in fp16's normal
@@ -203,14 +220,17 @@ __device__ __forceinline__ void block_inv_rms_few(const GemmArgs& g, int first_r
 // 8*(l/32) .. +7; result register r of lane l is C[(r/4)*8 + (l/32)*4 + r%4][l % 32].
 // Block = WM x WN wavefronts, wavefront tile = (TM*32) x (TN*32).  (The QKV projection runs
 // as a plain store GEMM followed by qkv_reduce_rope_kernel.)
-template <int EPI, int TM, int TN, int WM = 2, int WN = 2>
+// SPLIT: the A operand comes as hi and lo parts (split activations): both are staged and multiplied against the
+// same B fragments.
+template <int EPI, int TM, int TN, int WM = 2, int WN = 2, bool SPLIT = false>
 __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_tile_kernel(GemmArgs g) {
     constexpr int NT = 64 * WM * WN;                                         // threads per block
     constexpr int BM = WM * TM * 32, BN = WN * TN * 32, BK = 64, LS = BK + 8;  // LS: padded row
     constexpr int NB = EPI == EPI_SWIGLU ? 2 : 1;
     constexpr int A_CH = BM * 8 / NT, B_CH = BN * 8 / NT;                  // 16-byte chunks per thread
     constexpr int D = (NB == 2 && B_CH > 2) ? 2 : 4;                         // prefetch distance (even)
-    __shared__ __attribute__((aligned(16))) f16 sA[2][BM * LS];
+    constexpr int NA = SPLIT ? 2 : 1;
+    __shared__ __attribute__((aligned(16))) f16 sA[2][NA][BM * LS];
     __shared__ __attribute__((aligned(16))) f16 sB[2][NB][BN * LS];
     __shared__ float s_inv[BM];
 
@@ -237,8 +257,8 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_tile_kernel(GemmArgs g
     // Software pipeline: global loads run D k-steps ahead in a register ring (slot = step % D),
     // LDS is double buffered, one barrier per k-step.  At step s: issue the loads of s + D,
     // multiply out of LDS buffer s % 2, move the registers of s + 1 into the other buffer.
-    f16x8 ra[D][A_CH];
-    u32x4 rb[D][NB][B_CH];          // raw bf16 weights; widened to fp16 on the way into LDS
+    f16x8 ra[D][NA][A_CH];
+    u32x4 rb[D][NB][B_CH];          // weights as packed (fp16, MFMA operand order)
     long long a_off[A_CH], b_off[B_CH];
 #pragma unroll
     for (int i = 0; i < A_CH; ++i) {
@@ -255,7 +275,10 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_tile_kernel(GemmArgs g
     }
     auto load_global = [&](int slot, int k0) {
 #pragma unroll
-        for (int i = 0; i < A_CH; ++i) ra[slot][i] = *(const f16x8*)(A + a_off[i] + k0);
+        for (int i = 0; i < A_CH; ++i) {
+            ra[slot][0][i] = *(const f16x8*)(A + a_off[i] + k0);
+            if (SPLIT) ra[slot][NA - 1][i] = *(const f16x8*)(A + a_off[i] + k0 + g.a_lo_off);
+        }
 #pragma unroll
         for (int i = 0; i < B_CH; ++i) {
             rb[slot][0][i] = __builtin_nontemporal_load((const u32x4*)(W + b_off[i] + (long long)k0 * 16));
@@ -266,7 +289,8 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_tile_kernel(GemmArgs g
 #pragma unroll
         for (int i = 0; i < A_CH; ++i) {
             const int c = tid + NT * i, row = c >> 3, cc = c & 7;
-            *(f16x8*)(sA[buf] + row * LS + cc * 8) = ra[slot][i];
+#pragma unroll
+            for (int p = 0; p < NA; ++p) *(f16x8*)(sA[buf][p] + row * LS + cc * 8) = ra[slot][p][i];
         }
 #pragma unroll
         for (int i = 0; i < B_CH; ++i) {
@@ -279,10 +303,12 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_tile_kernel(GemmArgs g
     auto multiply = [&](int buf) {
 #pragma unroll
         for (int kk = 0; kk < BK / 16; ++kk) {
-            f16x8 fa[TM], fb[NB][TN];
+            f16x8 fa[NA][TM], fb[NB][TN];
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
-                fa[i] = *(const f16x8*)(sA[buf] + ((wm * TM + i) * 32 + lrow) * LS + kk * 16 + lg * 8);
+            for (int p = 0; p < NA; ++p)
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+                    fa[p][i] = *(const f16x8*)(sA[buf][p] + ((wm * TM + i) * 32 + lrow) * LS + kk * 16 + lg * 8);
 #pragma unroll
             for (int b = 0; b < NB; ++b)
 #pragma unroll
@@ -294,7 +320,9 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_tile_kernel(GemmArgs g
                 for (int i = 0; i < TM; ++i)
 #pragma unroll
                     for (int j = 0; j < TN; ++j)
-                        acc[b][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[i], fb[b][j], acc[b][i][j], 0, 0, 0);
+#pragma unroll
+                        for (int p = 0; p < NA; ++p)
+                            acc[b][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[p][i], fb[b][j], acc[b][i][j], 0, 0, 0);
         }
     };
 
@@ -368,8 +396,8 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_tile_kernel(GemmArgs g
                 for (int j = 0; j < TN; ++j) {
                     const int m = m0 + row_of(i, r), n = col_of(j);
                     if (m < M && n < N)
-                        out[(long long)m * N + n] =
-                            (f16)(silu_f(acc[0][i][j][r] * inv[i][r]) * (acc[NB - 1][i][j][r] * inv[i][r]));
+                        store_split(out + (long long)m * N + n, g.c_lo_off,
+                                    silu_f(acc[0][i][j][r] * inv[i][r]) * (acc[NB - 1][i][j][r] * inv[i][r]));
                 }
     } else if constexpr (EPI == EPI_RESIDUAL) {
         if (g.ksplit > 1) {          // K slice: raw partial products, finished by residual_reduce_kernel
@@ -413,7 +441,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_tile_kernel(GemmArgs g
                         const float xn = xv[i][j][r] + acc[0][i][j][r];
                         g.Cf[o] = xn;
                         if (g.gain_next) {
-                            a16[o] = (f16)(xn * gain[j]);
+                            store_split(a16 + o, g.c_lo_off, xn * gain[j]);
                             ss += xn * xn;
                         }
                     }
@@ -456,13 +484,13 @@ __global__ __launch_bounds__(256) void residual_reduce_kernel(GemmArgs g) {
     if (g.gain_next) {
         float ss = 0.f;
         if (live) {
-            f16x4 h;
+            float h[4];
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                h[r] = (f16)(xn[r] * gain[r]);
+                h[r] = xn[r] * gain[r];
                 ss += xn[r] * xn[r];
             }
-            *(f16x4*)((f16*)g.C16 + o) = h;
+            store_split4((f16*)g.C16 + o, g.c_lo_off, h);
         }
 #pragma unroll
         for (int w = 32; w > 0; w >>= 1) ss += __shfl_xor(ss, w, 64);
@@ -517,8 +545,9 @@ __global__ __launch_bounds__(256) void qkv_reduce_rope_kernel(GemmArgs g) {
     if (head < Hq + Hkv) {
         f16* dst = head < Hq ? (f16*)ro.q_out + ((long long)m * Hq + head) * hd
                              : pool + ro.kv.plane(ro.layer, 0, head - Hq) + (long long)slot * hd;
-        dst[j] = (f16)(a * c - b * sg);
-        dst[j + half] = (f16)(b * c + a * sg);
+        const long long lo_off = head < Hq ? g.c_lo_off : 0;      // q may be split; the cache holds one fp16 per entry
+        store_split(dst + j, lo_off, a * c - b * sg);
+        store_split(dst + j + half, lo_off, b * c + a * sg);
     } else {
         f16* dst = pool + ro.kv.plane(ro.layer, 1, head - Hq - Hkv) + (long long)(slot >> 4) * 16 * hd + (slot & 15);
         dst[(long long)j * 16] = (f16)a;
@@ -549,7 +578,7 @@ __global__ __launch_bounds__(256) void swiglu_reduce_kernel(GemmArgs g) {
     float a = 0.f, b = 0.f;
 #pragma unroll
     for (int ks = 0; ks < SPLITK_MAX; ++ks) { a += pa[ks]; b += pb[ks]; }
-    ((f16*)g.C16)[(long long)m * N + n] = (f16)(silu_f(a * s_inv) * (b * s_inv));
+    store_split((f16*)g.C16 + (long long)m * N + n, g.c_lo_off, silu_f(a * s_inv) * (b * s_inv));
 }
 
 // ------------------------------------------------------------------------------ stream SwiGLU kernel
@@ -575,12 +604,16 @@ __global__ __launch_bounds__(256) void swiglu_reduce_kernel(GemmArgs g) {
 // slices over extra blocks whose raw fp32 partial products go to slabs that qkv_reduce_rope_kernel /
 // residual_reduce_kernel add up: calls of 129-192 rows (16 sessions verified together), where one
 // 160- or 192-row block reads each weight once and the slices give the chip its ~200 blocks.
-template <int EPI, int TM, int D, int NS = 2, bool SLICED = false>
+//
+// SPLIT: split activations - the hi and lo parts of the A tile are both staged in LDS and multiplied against the
+// same weight registers.
+template <int EPI, int TM, int D, int NS = 2, bool SLICED = false, bool SPLIT = false>
 __global__ __launch_bounds__(256) void gemm_bf16_stream_kernel(GemmArgs g, int gx, int gy) {
     static_assert(EPI != EPI_SWIGLU || NS == 2, "SwiGLU streams gate and up");
     constexpr int BM = TM * 32, BN = EPI == EPI_SWIGLU ? 128 : NS * 128, BK = 64, LS = BK + 8;
     constexpr int A_CH = BM * 8 / 256;                       // 16-byte chunks of the A tile per thread
-    __shared__ __attribute__((aligned(16))) f16 sA[2][BM * LS];
+    constexpr int NA = SPLIT ? 2 : 1;
+    __shared__ __attribute__((aligned(16))) f16 sA[2][NA][BM * LS];
     __shared__ float s_inv[BM];
 
     const f16* __restrict__ A = (const f16*)g.A;
@@ -623,35 +656,43 @@ __global__ __launch_bounds__(256) void gemm_bf16_stream_kernel(GemmArgs g, int g
             for (int r = 0; r < 16; ++r) acc[t][i][r] = 0.f;
 
     u32x4 rw[D][NS][4];             // weights: 4 chunks of 8 k per stream and k-step
-    f16x8 ra[D][A_CH];
+    f16x8 ra[D][NA][A_CH];
     auto load_global = [&](int slot, int k0) {
 #pragma unroll
         for (int t = 0; t < NS; ++t)
 #pragma unroll
             for (int c = 0; c < 4; ++c) rw[slot][t][c] = __builtin_nontemporal_load((const u32x4*)(wp[t] + (long long)k0 * 16 + (c >> 1) * PK_CHUNK + (c & 1) * 2 * PK_KG));
 #pragma unroll
-        for (int i = 0; i < A_CH; ++i) ra[slot][i] = *(const f16x8*)(A + a_off[i] + k0);
+        for (int i = 0; i < A_CH; ++i) {
+            ra[slot][0][i] = *(const f16x8*)(A + a_off[i] + k0);
+            if (SPLIT) ra[slot][NA - 1][i] = *(const f16x8*)(A + a_off[i] + k0 + g.a_lo_off);
+        }
     };
     auto store_lds = [&](int slot, int buf) {
 #pragma unroll
         for (int i = 0; i < A_CH; ++i) {
             const int c = tid + 256 * i, row = c >> 3, cc = c & 7;
-            *(f16x8*)(sA[buf] + row * LS + cc * 8) = ra[slot][i];
+#pragma unroll
+            for (int p = 0; p < NA; ++p) *(f16x8*)(sA[buf][p] + row * LS + cc * 8) = ra[slot][p][i];
         }
     };
     auto multiply = [&](int slot, int buf) {
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-            f16x8 fa[TM], fw[NS];
+            f16x8 fa[NA][TM], fw[NS];
 #pragma unroll
-            for (int i = 0; i < TM; ++i) fa[i] = *(const f16x8*)(sA[buf] + (i * 32 + lrow) * LS + c * 16 + lg * 8);
+            for (int p = 0; p < NA; ++p)
+#pragma unroll
+                for (int i = 0; i < TM; ++i) fa[p][i] = *(const f16x8*)(sA[buf][p] + (i * 32 + lrow) * LS + c * 16 + lg * 8);
 #pragma unroll
             for (int t = 0; t < NS; ++t) fw[t] = __builtin_bit_cast(f16x8, rw[slot][t][c]);
 #pragma unroll
             for (int t = 0; t < NS; ++t)
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
-                    acc[t][i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[i], fw[t], acc[t][i], 0, 0, 0);
+#pragma unroll
+                    for (int p = 0; p < NA; ++p)
+                        acc[t][i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[p][i], fw[t], acc[t][i], 0, 0, 0);
         }
     };
 
@@ -716,7 +757,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_stream_kernel(GemmArgs g, int g
                 const int row = row_of(i, r), m = m0 + row;
                 const float inv = g.ssq ? s_inv[row] : 1.0f;
                 if (m < M && ncol[0] < N)
-                    out[(long long)m * N + ncol[0]] = (f16)(silu_f(acc[0][i][r] * inv) * (acc[1][i][r] * inv));
+                    store_split(out + (long long)m * N + ncol[0], g.c_lo_off, silu_f(acc[0][i][r] * inv) * (acc[1][i][r] * inv));
             }
     } else if constexpr (EPI == EPI_STORE_F32 || SLICED) {  // K slice: its own slab of raw products
         float* __restrict__ C = SLICED ? (EPI == EPI_STORE_F32 ? g.Cf : g.split_ws) + (long long)kz * M * N : g.Cf;
@@ -755,7 +796,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_stream_kernel(GemmArgs g, int g
                     if (live) {
                         const long long o = (long long)m * N + n;
                         g.Cf[o] = xn;
-                        if (g.gain_next) a16[o] = (f16)(xn * gain);
+                        if (g.gain_next) store_split(a16 + o, g.c_lo_off, xn * gain);
                     }
                     if (g.gain_next) {                        // partial sum of squares over this tile's 32 columns
 #pragma unroll
@@ -780,10 +821,14 @@ __global__ __launch_bounds__(256) void gemm_bf16_stream_kernel(GemmArgs g, int g
 // For EPI_QKV the 16 columns of a block are 8 + 8 rotary partners of one head: local columns
 // 0..7 are channels j0..j0+7, local columns 8..15 are channels hd/2 + j0 .. +7, so the partner
 // of a lane's value lives in lane ^ 32.
-template <int EPI, int MT, int NW, int COLS = 16>
+//
+// SPLIT: split activations - each weight fragment meets the hi and the lo part of the activation rows (two MFMAs);
+// weight traffic is unchanged, the activation slice a wavefront reads doubles.
+template <int EPI, int MT, int NW, int COLS = 16, bool SPLIT = false>
 __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(1, NW >= 8 ? 4 : 8)))
 void gemm_bf16_skinny_kernel(GemmArgs g) {
     constexpr int NB = EPI == EPI_SWIGLU ? 2 : 1;
+    constexpr int NA = SPLIT ? 2 : 1;
     __shared__ __attribute__((aligned(16))) f32x4 red[NW][NB][MT][64];
     __shared__ float s_inv[MT * 16];
 
@@ -897,13 +942,15 @@ void gemm_bf16_skinny_kernel(GemmArgs g) {
     if constexpr (MT <= 2) {
         constexpr int U = 4, S = 32 * U;
         u32x4 rw[2][NB][DUAL ? U / 2 : U];
-        f16x8 fx[2][MT][U];
+        f16x8 fx[2][NA][MT][U];
 #pragma unroll
         for (int set = 0; set < 2; ++set)
 #pragma unroll
-            for (int t = 0; t < MT; ++t)
+            for (int p = 0; p < NA; ++p)
 #pragma unroll
-                for (int u = 0; u < U; ++u) fx[set][t][u] = (f16x8){0, 0, 0, 0, 0, 0, 0, 0};   // rows past M stay zero
+                for (int t = 0; t < MT; ++t)
+#pragma unroll
+                    for (int u = 0; u < U; ++u) fx[set][p][t][u] = (f16x8){0, 0, 0, 0, 0, 0, 0, 0};   // rows past M stay zero
         auto loads = [&](int set, int kk) {
             if constexpr (DUAL) {
 #pragma unroll
@@ -921,7 +968,11 @@ void gemm_bf16_skinny_kernel(GemmArgs g) {
             for (int t = 0; t < MT; ++t) {
                 if (t * 16 + lr < M) {
 #pragma unroll
-                    for (int u = 0; u < U; ++u) fx[set][t][u] = *(const f16x8*)(xp[t] + kk + 32 * u);
+                    for (int u = 0; u < U; ++u) fx[set][0][t][u] = *(const f16x8*)(xp[t] + kk + 32 * u);
+                    if (SPLIT) {
+#pragma unroll
+                        for (int u = 0; u < U; ++u) fx[set][NA - 1][t][u] = *(const f16x8*)(xp[t] + g.a_lo_off + kk + 32 * u);
+                    }
                 }
             }
         };
@@ -938,7 +989,9 @@ void gemm_bf16_skinny_kernel(GemmArgs g) {
                     const f16x8 fw = __builtin_bit_cast(f16x8, raw);
 #pragma unroll
                     for (int t = 0; t < MT; ++t)
-                        acc[b][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fw, fx[set][t][u], acc[b][t], 0, 0, 0);
+#pragma unroll
+                        for (int p = 0; p < NA; ++p)
+                            acc[b][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fw, fx[set][p][t][u], acc[b][t], 0, 0, 0);
                 }
         };
         const int ntr = kslice / S;
@@ -961,6 +1014,7 @@ void gemm_bf16_skinny_kernel(GemmArgs g) {
         k = kbeg + ntr * S;
     } else {
         for (; k + 128 <= kend; k += 128) {
+            static_assert(!SPLIT, "more than two row tiles: not instantiated with split activations");
             u32x4 rw[NB][4];
             f16x8 fx[MT][4];
 #pragma unroll
@@ -991,6 +1045,10 @@ void gemm_bf16_skinny_kernel(GemmArgs g) {
             for (int t = 0; t < MT; ++t) {
                 const f16x8 fx = *(const f16x8*)(xp[t] + k);
                 acc[b][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fw, fx, acc[b][t], 0, 0, 0);
+                if (SPLIT) {
+                    const f16x8 fl = *(const f16x8*)(xp[t] + g.a_lo_off + k);
+                    acc[b][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fw, fl, acc[b][t], 0, 0, 0);
+                }
             }
         }
     }
@@ -1027,10 +1085,10 @@ void gemm_bf16_skinny_kernel(GemmArgs g) {
             if (mok && n < N) *(f32x4*)(g.Cf + o) = sum[0] * inv;
         } else if (EPI == EPI_SWIGLU) {
             if (mok && n < N) {
-                f16x4 h;
+                float h[4];
 #pragma unroll
-                for (int r = 0; r < 4; ++r) h[r] = (f16)(silu_f(sum[0][r] * inv) * (sum[NB - 1][r] * inv));
-                *(f16x4*)((f16*)g.C16 + o) = h;
+                for (int r = 0; r < 4; ++r) h[r] = silu_f(sum[0][r] * inv) * (sum[NB - 1][r] * inv);
+                store_split4((f16*)g.C16 + o, g.c_lo_off, h);
             }
         } else if (EPI == EPI_RESIDUAL) {
             float ss = 0.f;
@@ -1038,13 +1096,13 @@ void gemm_bf16_skinny_kernel(GemmArgs g) {
                 const f32x4 xn = pre_x[t] + sum[0];
                 *(f32x4*)(g.Cf + o) = xn;
                 if (g.gain_next) {
-                    f16x4 h;
+                    float h[4];
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
-                        h[r] = (f16)(xn[r] * pre_g[r]);
+                        h[r] = xn[r] * pre_g[r];
                         ss += xn[r] * xn[r];
                     }
-                    *(f16x4*)((f16*)g.C16 + o) = h;
+                    store_split4((f16*)g.C16 + o, g.c_lo_off, h);
                 }
             }
             if (g.gain_next) {           // sum of squares over the block's COLS columns, per row
@@ -1063,18 +1121,20 @@ void gemm_bf16_skinny_kernel(GemmArgs g) {
             for (int r = 0; r < 4; ++r) other[r] = __shfl_xor(own[r], 32, 64);
             if (q_head < Hq + Hkv) {
                 const f32x4 cs = pre_cs[t], sn = pre_sn[t];      // angles q_j0 + (lg & 1) * 4 + r at the row's position
-                f16x4 h;
+                float h[4];
 #pragma unroll
                 for (int r = 0; r < 4; ++r)
-                    h[r] = lg < 2 ? (f16)(own[r] * cs[r] - other[r] * sn[r])            // first half: a c - b s
-                                  : (f16)(own[r] * cs[r] + other[r] * sn[r]);           // second half: b c + a s
+                    h[r] = lg < 2 ? own[r] * cs[r] - other[r] * sn[r]                   // first half: a c - b s
+                                  : own[r] * cs[r] + other[r] * sn[r];                  // second half: b c + a s
                 f16* dst;
+                long long lo_off = 0;                                                    // the cache holds one fp16 per entry
                 if (q_head < Hq) {
                     dst = (f16*)ro.q_out + ((long long)mm * Hq + q_head) * hd;
+                    lo_off = g.c_lo_off;
                 } else {
                     dst = pool + ro.kv.plane(ro.layer, 0, q_head - Hq) + (long long)pre_slot[t] * hd;
                 }
-                if (mok) *(f16x4*)(dst + chan) = h;
+                if (mok) store_split4(dst + chan, lo_off, h);
             } else if (mok) {
                 f16* dst = pool + ro.kv.plane(ro.layer, 1, q_head - Hq - Hkv) + (long long)(pre_slot[t] >> 4) * 16 * hd + (pre_slot[t] & 15);
 #pragma unroll
@@ -1083,6 +1143,14 @@ void gemm_bf16_skinny_kernel(GemmArgs g) {
         }
     }
 }
+
+// Launch KERNEL<TARGS..., SPLIT>: the split-activation instantiation when the GEMM's A operand comes in two parts.
+#define AX_UNPAREN(...) __VA_ARGS__
+#define AX_SPLIT_LAUNCH(split_, KERNEL, TARGS, GRID, BLOCK, ...)                                        \
+    do {                                                                                                \
+        if (split_) KERNEL<AX_UNPAREN TARGS, true><<<GRID, BLOCK, 0, s>>>(__VA_ARGS__);                  \
+        else KERNEL<AX_UNPAREN TARGS, false><<<GRID, BLOCK, 0, s>>>(__VA_ARGS__);                        \
+    } while (0)
 
 // Columns per block of the skinny kernel.  A CU pulls only ~26 GB/s of weights however many
 // wavefronts it runs (measured), so a launch streams at the chip's rate only if every CU has a
@@ -1102,11 +1170,11 @@ static int skinny_cols(int epi, int N) {
 template <int EPI, int MT, int COLS>
 static void launch_skinny_cols(const GemmArgs& g, int nw, hipStream_t s) {
     const int grid = (g.N + COLS - 1) / COLS;
-    if (nw == 16) gemm_bf16_skinny_kernel<EPI, MT, 16, COLS><<<grid, 1024, 0, s>>>(g);
-    else if (nw == 1) gemm_bf16_skinny_kernel<EPI, MT, 1, COLS><<<grid, 64, 0, s>>>(g);
-    else if (nw == 2) gemm_bf16_skinny_kernel<EPI, MT, 2, COLS><<<grid, 128, 0, s>>>(g);
-    else if (nw == 8) gemm_bf16_skinny_kernel<EPI, MT, 8, COLS><<<grid, 512, 0, s>>>(g);
-    else gemm_bf16_skinny_kernel<EPI, MT, 4, COLS><<<grid, 256, 0, s>>>(g);
+    if (nw == 16) AX_SPLIT_LAUNCH(g.a_lo_off != 0, gemm_bf16_skinny_kernel, (EPI, MT, 16, COLS), grid, 1024, g);
+    else if (nw == 1) AX_SPLIT_LAUNCH(g.a_lo_off != 0, gemm_bf16_skinny_kernel, (EPI, MT, 1, COLS), grid, 64, g);
+    else if (nw == 2) AX_SPLIT_LAUNCH(g.a_lo_off != 0, gemm_bf16_skinny_kernel, (EPI, MT, 2, COLS), grid, 128, g);
+    else if (nw == 8) AX_SPLIT_LAUNCH(g.a_lo_off != 0, gemm_bf16_skinny_kernel, (EPI, MT, 8, COLS), grid, 512, g);
+    else AX_SPLIT_LAUNCH(g.a_lo_off != 0, gemm_bf16_skinny_kernel, (EPI, MT, 4, COLS), grid, 256, g);
 }
 
 template <int EPI, int MT>
@@ -1174,7 +1242,8 @@ static int launch_lds_tile(const GemmArgs& g, hipStream_t s) {
     // slices are too short for a kernel with one wavefront per SIMD (QKV 24 -> 29 us): tile kernels.
     const int mid_cb = (N + 127) / 128;
     int mid_ks = 1;
-    if (EPI == EPI_RESIDUAL && kMidStream && M > 128 && M <= 192 && K >= 8192 && N % 64 == 0 && g.split_ws)
+    const bool split = g.a_lo_off != 0;   // split activations: streaming blocks of at most 128 rows (a second A ring does not fit the registers of larger ones)
+    if (EPI == EPI_RESIDUAL && kMidStream && !split && M > 128 && M <= 192 && K >= 8192 && N % 64 == 0 && g.split_ws)
         for (int ks : {8, 6, 4, 3, 2})
             if (mid_ks == 1 && mid_cb * ks <= 288 && K % (ks * 64) == 0 && K / (ks * 64) >= 4 &&
                 (size_t)ks * 2 * M * N * sizeof(float) <= g.split_ws_bytes)
@@ -1187,7 +1256,7 @@ static int launch_lds_tile(const GemmArgs& g, hipStream_t s) {
             gp.ssq = nullptr;
             gp.Cf = g.split_ws;
             const int gx = (N + 255) / 256, gy = (M + 127) / 128;
-            gemm_bf16_stream_kernel<EPI_STORE_F32, 4, 3><<<gx * gy, 256, 0, s>>>(gp, gx, gy);
+            AX_SPLIT_LAUNCH(gp.a_lo_off != 0, gemm_bf16_stream_kernel, (EPI_STORE_F32, 4, 3, 2, false), gx * gy, 256, gp, gx, gy);
             qkv_reduce_rope_kernel<<<dim3((unsigned)M, (unsigned)((N / 2 + 255) / 256)), 256, 0, s>>>(gs);
             return 0;
         }
@@ -1217,10 +1286,10 @@ static int launch_lds_tile(const GemmArgs& g, hipStream_t s) {
         gp.Cf = g.split_ws;
         if (big) {
             dim3 grid((N + 127) / 128, (M + 127) / 128, ks);
-            gemm_bf16_tile_kernel<EPI_STORE_F32, 2, 1, 2, 4><<<grid, 512, 0, s>>>(gp);
+            AX_SPLIT_LAUNCH(gp.a_lo_off != 0, gemm_bf16_tile_kernel, (EPI_STORE_F32, 2, 1, 2, 4), grid, 512, gp);
         } else {
             dim3 grid((N + 127) / 128, (M + 63) / 64, ks);
-            gemm_bf16_tile_kernel<EPI_STORE_F32, 1, 1, 2, 4><<<grid, 512, 0, s>>>(gp);
+            AX_SPLIT_LAUNCH(gp.a_lo_off != 0, gemm_bf16_tile_kernel, (EPI_STORE_F32, 1, 1, 2, 4), grid, 512, gp);
         }
         qkv_reduce_rope_kernel<<<dim3((unsigned)M, (unsigned)((N / 2 + 255) / 256)), 256, 0, s>>>(gs);
         return 0;
@@ -1228,13 +1297,13 @@ static int launch_lds_tile(const GemmArgs& g, hipStream_t s) {
         if (mid_ks > 1 && mid_cb * mid_ks >= 160) {            // (~1B width: 128 blocks, slower than the tile kernels)
             GemmArgs gs = g;
             gs.ksplit = mid_ks;
-            if (M <= 160) gemm_bf16_stream_kernel<EPI_RESIDUAL, 5, 3, 1, true><<<mid_cb * mid_ks, 256, 0, s>>>(gs, mid_cb, 1);
-            else gemm_bf16_stream_kernel<EPI_RESIDUAL, 6, 3, 1, true><<<mid_cb * mid_ks, 256, 0, s>>>(gs, mid_cb, 1);
+            if (M <= 160) gemm_bf16_stream_kernel<EPI_RESIDUAL, 5, 3, 1, true, false><<<mid_cb * mid_ks, 256, 0, s>>>(gs, mid_cb, 1);
+            else gemm_bf16_stream_kernel<EPI_RESIDUAL, 6, 3, 1, true, false><<<mid_cb * mid_ks, 256, 0, s>>>(gs, mid_cb, 1);
             return launch_residual_reduce(gs, s);
         }
         if (stream) {
             const int gx = (N + 255) / 256, gy = (M + 127) / 128;
-            gemm_bf16_stream_kernel<EPI_RESIDUAL, 4, 3><<<gx * gy, 256, 0, s>>>(g, gx, gy);
+            AX_SPLIT_LAUNCH(g.a_lo_off != 0, gemm_bf16_stream_kernel, (EPI_RESIDUAL, 4, 3, 2, false), gx * gy, 256, g, gx, gy);
             return N / 32;
         }
         // a few hundred rows against the long K of the down projection: too few 128 x 256 blocks for
@@ -1251,7 +1320,7 @@ static int launch_lds_tile(const GemmArgs& g, hipStream_t s) {
                 GemmArgs gs = g;
                 gs.ksplit = ks;
                 const int gx = (N + 255) / 256, gy = (M + 127) / 128;
-                gemm_bf16_stream_kernel<EPI_RESIDUAL, 4, 3, 2, true><<<gx * gy * ks, 256, 0, s>>>(gs, gx, gy);
+                AX_SPLIT_LAUNCH(gs.a_lo_off != 0, gemm_bf16_stream_kernel, (EPI_RESIDUAL, 4, 3, 2, true), gx * gy * ks, 256, gs, gx, gy);
                 return launch_residual_reduce(gs, s);
             }
         }
@@ -1283,10 +1352,10 @@ static int launch_lds_tile(const GemmArgs& g, hipStream_t s) {
         gs.ksplit = ks;
         if (big) {
             dim3 grid((N + 127) / 128, (M + 127) / 128, ks);
-            gemm_bf16_tile_kernel<EPI_RESIDUAL, 2, 1, 2, 4><<<grid, 512, 0, s>>>(gs);
+            AX_SPLIT_LAUNCH(gs.a_lo_off != 0, gemm_bf16_tile_kernel, (EPI_RESIDUAL, 2, 1, 2, 4), grid, 512, gs);
         } else {
             dim3 grid((N + 127) / 128, (M + 63) / 64, ks);
-            gemm_bf16_tile_kernel<EPI_RESIDUAL, 1, 1, 2, 4><<<grid, 512, 0, s>>>(gs);
+            AX_SPLIT_LAUNCH(gs.a_lo_off != 0, gemm_bf16_tile_kernel, (EPI_RESIDUAL, 1, 1, 2, 4), grid, 512, gs);
         }
         return ks > 1 ? launch_residual_reduce(gs, s) : N / 32;
     } else if constexpr (EPI == EPI_SWIGLU) {
@@ -1297,7 +1366,7 @@ static int launch_lds_tile(const GemmArgs& g, hipStream_t s) {
         // skinny kernel re-reads its activations per 16 columns.  ~3B shape: 33 -> 26 us at 32 rows,
         // 48 -> 28 us at 64 rows, 49 -> 42 us at 144 rows; ~8B: 72 -> 48 us at 32-48 rows.
         // (above 128 rows only for matrices of the ~3B size or larger: at the ~1B size the 128 x 64 tiles are as fast or faster)
-        if (kMidStream && M <= 192 && (M <= 128 || (long long)N * K >= (20LL << 20)) && g.split_ws) {
+        if (kMidStream && M <= (split ? 128 : 192) && (M <= 128 || (long long)N * K >= (20LL << 20)) && g.split_ws) {
             const int cb = (N + 127) / 128;
             int ks = 1;
             for (int c : {8, 6, 4, 3, 2})
@@ -1309,12 +1378,12 @@ static int launch_lds_tile(const GemmArgs& g, hipStream_t s) {
                 gs.ksplit = ks;
                 const unsigned nb = (unsigned)(cb * ks);
                 switch ((M + 31) / 32) {
-                    case 1: gemm_bf16_stream_kernel<EPI_SWIGLU, 1, 3, 2, true><<<nb, 256, 0, s>>>(gs, cb, 1); break;
-                    case 2: gemm_bf16_stream_kernel<EPI_SWIGLU, 2, 3, 2, true><<<nb, 256, 0, s>>>(gs, cb, 1); break;
-                    case 3: gemm_bf16_stream_kernel<EPI_SWIGLU, 3, 3, 2, true><<<nb, 256, 0, s>>>(gs, cb, 1); break;
-                    case 4: gemm_bf16_stream_kernel<EPI_SWIGLU, 4, 3, 2, true><<<nb, 256, 0, s>>>(gs, cb, 1); break;
-                    case 5: gemm_bf16_stream_kernel<EPI_SWIGLU, 5, 3, 2, true><<<nb, 256, 0, s>>>(gs, cb, 1); break;
-                    default: gemm_bf16_stream_kernel<EPI_SWIGLU, 6, 3, 2, true><<<nb, 256, 0, s>>>(gs, cb, 1); break;
+                    case 1: AX_SPLIT_LAUNCH(gs.a_lo_off != 0, gemm_bf16_stream_kernel, (EPI_SWIGLU, 1, 3, 2, true), nb, 256, gs, cb, 1); break;
+                    case 2: AX_SPLIT_LAUNCH(gs.a_lo_off != 0, gemm_bf16_stream_kernel, (EPI_SWIGLU, 2, 3, 2, true), nb, 256, gs, cb, 1); break;
+                    case 3: AX_SPLIT_LAUNCH(gs.a_lo_off != 0, gemm_bf16_stream_kernel, (EPI_SWIGLU, 3, 3, 2, true), nb, 256, gs, cb, 1); break;
+                    case 4: AX_SPLIT_LAUNCH(gs.a_lo_off != 0, gemm_bf16_stream_kernel, (EPI_SWIGLU, 4, 3, 2, true), nb, 256, gs, cb, 1); break;
+                    case 5: gemm_bf16_stream_kernel<EPI_SWIGLU, 5, 3, 2, true, false><<<nb, 256, 0, s>>>(gs, cb, 1); break;
+                    default: gemm_bf16_stream_kernel<EPI_SWIGLU, 6, 3, 2, true, false><<<nb, 256, 0, s>>>(gs, cb, 1); break;
                 }
                 swiglu_reduce_kernel<<<dim3((unsigned)M, (unsigned)((N + 255) / 256)), 256, 0, s>>>(gs);
                 return 0;
@@ -1324,7 +1393,7 @@ static int launch_lds_tile(const GemmArgs& g, hipStream_t s) {
         // operands per k instead of (64 + 2 * 128) for the same number of blocks (2-3 % faster)
         if (M > 128) {
             dim3 tgrid((N + 63) / 64, (M + 127) / 128);
-            gemm_bf16_tile_kernel<EPI_SWIGLU, 1, 1, 4, 2><<<tgrid, 512, 0, s>>>(g);
+            AX_SPLIT_LAUNCH(g.a_lo_off != 0, gemm_bf16_tile_kernel, (EPI_SWIGLU, 1, 1, 4, 2), tgrid, 512, g);
             return 0;
         }
     }
@@ -1339,9 +1408,10 @@ static int launch_lds_tile(const GemmArgs& g, hipStream_t s) {
             int tm = (M + 31) / 32;
             if (M > 512) {
                 tm = 4;                                    // compute-bound there: 128-row blocks (1024 rows: 669 us against 804 with 192-row blocks)
-            } else if (tm > 6) {
+            } else if (tm > (split ? 4 : 6)) {
                 long long best = -1;
                 for (int t : {4, 3, 5, 6}) {
+                    if (split && t > 4) continue;
                     const long long blocks = (long long)gx * ((M + 32 * t - 1) / (32 * t));
                     const long long cost = ((blocks + 255) / 256) * (32 * t + 512) * (t >= 5 ? 115 : 100);
                     if (best < 0 || cost < best) { best = cost; tm = t; }
@@ -1349,22 +1419,22 @@ static int launch_lds_tile(const GemmArgs& g, hipStream_t s) {
             }
             const int gy = (M + 32 * tm - 1) / (32 * tm);
             switch (tm) {
-                case 1: gemm_bf16_stream_kernel<EPI_STORE_F32, 1, 3><<<gx * gy, 256, 0, s>>>(g, gx, gy); break;
-                case 2: gemm_bf16_stream_kernel<EPI_STORE_F32, 2, 3><<<gx * gy, 256, 0, s>>>(g, gx, gy); break;
-                case 3: gemm_bf16_stream_kernel<EPI_STORE_F32, 3, 3><<<gx * gy, 256, 0, s>>>(g, gx, gy); break;
-                case 4: gemm_bf16_stream_kernel<EPI_STORE_F32, 4, 3><<<gx * gy, 256, 0, s>>>(g, gx, gy); break;
-                case 5: gemm_bf16_stream_kernel<EPI_STORE_F32, 5, 3><<<gx * gy, 256, 0, s>>>(g, gx, gy); break;
-                default: gemm_bf16_stream_kernel<EPI_STORE_F32, 6, 3><<<gx * gy, 256, 0, s>>>(g, gx, gy); break;
+                case 1: AX_SPLIT_LAUNCH(g.a_lo_off != 0, gemm_bf16_stream_kernel, (EPI_STORE_F32, 1, 3, 2, false), gx * gy, 256, g, gx, gy); break;
+                case 2: AX_SPLIT_LAUNCH(g.a_lo_off != 0, gemm_bf16_stream_kernel, (EPI_STORE_F32, 2, 3, 2, false), gx * gy, 256, g, gx, gy); break;
+                case 3: AX_SPLIT_LAUNCH(g.a_lo_off != 0, gemm_bf16_stream_kernel, (EPI_STORE_F32, 3, 3, 2, false), gx * gy, 256, g, gx, gy); break;
+                case 4: AX_SPLIT_LAUNCH(g.a_lo_off != 0, gemm_bf16_stream_kernel, (EPI_STORE_F32, 4, 3, 2, false), gx * gy, 256, g, gx, gy); break;
+                case 5: gemm_bf16_stream_kernel<EPI_STORE_F32, 5, 3, 2, false, false><<<gx * gy, 256, 0, s>>>(g, gx, gy); break;
+                default: gemm_bf16_stream_kernel<EPI_STORE_F32, 6, 3, 2, false, false><<<gx * gy, 256, 0, s>>>(g, gx, gy); break;
             }
             return 0;
         }
         if (EPI == EPI_STORE_F32 && stream) {              // logits of thousands of rows
             const int gx = (N + 255) / 256, gy = (M + 127) / 128;
-            gemm_bf16_stream_kernel<EPI_STORE_F32, 4, 3><<<gx * gy, 256, 0, s>>>(g, gx, gy);
+            AX_SPLIT_LAUNCH(g.a_lo_off != 0, gemm_bf16_stream_kernel, (EPI_STORE_F32, 4, 3, 2, false), gx * gy, 256, g, gx, gy);
             return 0;
         }
         dim3 grid((N + 127) / 128, (M + 63) / 64);
-        gemm_bf16_tile_kernel<EPI, 1, 1, 2, 4><<<grid, 512, 0, s>>>(g);
+        AX_SPLIT_LAUNCH(g.a_lo_off != 0, gemm_bf16_tile_kernel, (EPI, 1, 1, 2, 4), grid, 512, g);
     }
     return 0;
 }
@@ -1419,6 +1489,7 @@ static int launch_bf16(const GemmArgs& g, hipStream_t s) {
         if (kStreamTm) {
             long long best = -1;
             for (int t : {4, 3, 5, 6}) {
+                if (g.a_lo_off != 0 && t > 4) continue;      // split activations: at most 128-row blocks
                 const long long blocks = (long long)((N + 127) / 128) * ((M + 32 * t - 1) / (32 * t));
                 const long long cost = ((blocks + 255) / 256) * (32 * t + 256) * (t >= 5 ? 115 : 100);   // the two large shapes run ~15 % below the model
                 if (best < 0 || cost < best) { best = cost; tm = t; }
@@ -1426,10 +1497,10 @@ static int launch_bf16(const GemmArgs& g, hipStream_t s) {
         }
         const int gx = (N + 127) / 128, gy = (M + 32 * tm - 1) / (32 * tm);
         switch (tm) {
-            case 3: gemm_bf16_stream_kernel<EPI_SWIGLU, 3, 3><<<gx * gy, 256, 0, s>>>(g, gx, gy); break;
-            case 5: gemm_bf16_stream_kernel<EPI_SWIGLU, 5, 3><<<gx * gy, 256, 0, s>>>(g, gx, gy); break;
-            case 6: gemm_bf16_stream_kernel<EPI_SWIGLU, 6, 3><<<gx * gy, 256, 0, s>>>(g, gx, gy); break;
-            default: gemm_bf16_stream_kernel<EPI_SWIGLU, 4, 3><<<gx * gy, 256, 0, s>>>(g, gx, gy); break;
+            case 3: AX_SPLIT_LAUNCH(g.a_lo_off != 0, gemm_bf16_stream_kernel, (EPI_SWIGLU, 3, 3, 2, false), gx * gy, 256, g, gx, gy); break;
+            case 5: gemm_bf16_stream_kernel<EPI_SWIGLU, 5, 3, 2, false, false><<<gx * gy, 256, 0, s>>>(g, gx, gy); break;
+            case 6: gemm_bf16_stream_kernel<EPI_SWIGLU, 6, 3, 2, false, false><<<gx * gy, 256, 0, s>>>(g, gx, gy); break;
+            default: AX_SPLIT_LAUNCH(g.a_lo_off != 0, gemm_bf16_stream_kernel, (EPI_SWIGLU, 4, 3, 2, false), gx * gy, 256, g, gx, gy); break;
         }
         return 0;
     }

@@ -47,9 +47,19 @@ struct RopeArgs {
     const float *cos, *sin;           // [max_pos][hd/2]
 };
 
+// Split activations.  An fp16 value keeps 11 significant bits; the rounding of the five activation tensors a
+// layer hands from kernel to kernel is what separates the logits of a deep, wide decoder from the exact ones
+// (measured: ~1B x 16 layers 5e-3, ~3B x 28 layers 1.3e-2, ~8B x 32 layers 2.7e-2 max-abs).  A model created
+// with split activations stores every such tensor as TWO fp16 values per element, hi = fp16(v) and
+// lo = fp16(v - hi) (together ~22 bits), the second tensor `*_lo_off` elements behind the first, and every
+// consumer multiplies both parts against the SAME weight fragment (two MFMAs per fragment: no extra weight
+// traffic, twice the matrix-core work and activation traffic).  An offset of 0 means "not split".
+//
 // One GEMM of a bf16-weight model: C = A[M,K] * W[N,K]^T, A fp16, W bf16.
 struct GemmArgs {
     const void* A;                    // fp16 [rows, K]
+    long long a_lo_off;               // split activations: the lo parts of A lie this many elements behind A (0 = none)
+    long long c_lo_off;               // ... and the lo parts of C16 (and of rope.q_out) this many elements behind it
     const int* a_rows;                // optional gather: A row of output row m is a_rows[m]
     const void *W, *W2;               // [N, K] packed by launch_pack_weights (fp16, MFMA operand order); W2 only for EPI_SWIGLU
     int M, N, K;
@@ -80,7 +90,8 @@ int launch_gemm_bf16(Epilogue epi, const GemmArgs& g, hipStream_t s);
 // kernel reads: fp16 values in 16-row panels, 32-k chunks in MFMA operand order; src and dst must not overlap.
 void launch_pack_weights(const void* src, void* dst, int N, int K, hipStream_t s);
 // bf16-weight models: x[r,:] = emb[tok], a[r,:] = fp16(x * gain), ssq[r][0] = sum x^2, ssq[r][1..nparts) = 0
-void launch_embed_norm(const void* emb, const int* row_tok, const void* gain, float* x, void* a,
+// a_lo_off != 0: also the lo parts fp16(x * gain - a), that many elements behind a
+void launch_embed_norm(const void* emb, const int* row_tok, const void* gain, float* x, void* a, long long a_lo_off,
                        float* ssq, int nparts, int n_rows, int d, hipStream_t s);
 
 // x[r, :] = emb[row_tok[r], :] widened to fp32
@@ -102,9 +113,10 @@ void launch_rope_kv(DType dt, const float* qkv, void* q_out, KVGeom kv, int laye
 // Causal attention of the new rows over the paged cache (which already holds the new rows).
 // out [n_rows, Hq, hd] in the activation type.  `partials` is fp32 scratch for the split-KV
 // path (bf16 only); n_splits >= 1.
+// q_lo_off / out_lo_off: split activations (see GemmArgs): lo parts of q read, lo parts of out written (0 = none).
 void launch_attention(DType dt, const void* q, void* out, KVGeom kv, int layer,
                       const StepView& sv, int n_q_heads, float* partials, int n_splits,
-                      hipStream_t s);
+                      hipStream_t s, long long q_lo_off = 0, long long out_lo_off = 0);
 // Floats of `partials` launch_attention needs for n_tiles q tiles (of 32 rows) and n_splits splits.
 size_t attention_partial_floats(int n_tiles, int n_kv_heads, int head_dim, int n_splits);
 // out[r] = argmax of logits[r, 0..V), lowest index on ties.  scratch: 2*rows*ARGMAX_PARTS ints.

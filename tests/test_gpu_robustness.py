@@ -128,3 +128,60 @@ def test_large_residual_stream_within_the_stated_range(B, scale):
         assert (a, nxt) == (a_ref, nxt_ref)
     B.ax_kv_free(kv)
     dm.close()
+
+
+SPLIT_SHAPES = {
+    "hd64-g4": I.DecoderShape("s64", 4, 512, 8, 2, 64, 1024, 2048, "bf16"),
+    "hd128-g3": I.DecoderShape("s128", 3, 384, 6, 2, 128, 768, 1024, "bf16"),
+    "wide": I.DecoderShape("wide", 2, 1024, 16, 4, 64, 4096, 4096, "bf16"),
+}
+
+
+@pytest.mark.parametrize("which", list(SPLIT_SHAPES))
+def test_split_activations_every_kernel_family(B, which):
+    """ax_model_config.act_split = 1: activations between kernels as hi + lo fp16 pairs.  Row counts
+    chosen so that every GEMM family (few-row, LDS tiles with and without K slices, streaming blocks)
+    and both attention kernels run with two-part operands, one sequence and several; against the
+    oracle, and against the same calls on a model without the split: the split must not be worse,
+    and over the run its worst error must be clearly smaller."""
+    sh = SPLIT_SHAPES[which]
+    w = I.make_weights(sh, 37)
+    toks = I.templated_prompt(sh.vocab, 37, 1500)
+    worst = {}
+    for mode in (-1, 1):
+        dm = B.DeviceModel(sh, w, max_pos=2048, max_tokens=640, pool_tokens=8192, max_seqs=4, act_split=mode)
+        kv, ref = dm.new_kv(), okv(sh)
+        errs, at = [], 0
+        for T in (9, 1, 40, 17, 150, 300, 600, 64, 130):
+            got = dm.extend(kv, toks[at:at + T], B.AX_OUT_ALL_LOGITS).cpu().numpy()
+            errs.append(float(np.abs(got - O.forward(sh, w, toks[at:at + T], ref)).max()))
+            at += T
+        # verify rounds (graph replays), partly accepted
+        pending = int(toks[at])
+        for r in range(3):
+            greedy = O.greedy_decode(sh, w, ref.fork(), pending, 6)
+            drafts = greedy[:3] + [(greedy[3] + 1) % sh.vocab] + greedy[4:]
+            a_ref, nxt_ref, lg = O.verify(sh, w, ref, pending, drafts)
+            a, nxt = dm.verify(kv, pending, drafts)
+            if min(O.top2_margin(row) for row in lg[:a_ref + 1]) > 1e-2:
+                assert (a, nxt) == (a_ref, nxt_ref) == (3, greedy[3])
+            else:
+                B.ax_kv_truncate(kv, len(ref))
+            pending = nxt_ref
+        # several sequences in one pass, forked from the long one (shared prefix)
+        kvs = [B.ax_kv_fork(kv, len(ref) - 5 * s) for s in range(3)]
+        refs = [ref.fork(len(ref) - 5 * s) for s in range(3)]
+        news = [toks[1400 + 10 * s:1400 + 10 * s + t] for s, t in enumerate((33, 9, 70))]
+        got = dm.extend_batch(kvs, news, B.AX_OUT_ALL_LOGITS).cpu().numpy()
+        row = 0
+        for s in range(3):
+            errs.append(float(np.abs(got[row:row + len(news[s])] - O.forward(sh, w, news[s], refs[s])).max()))
+            row += len(news[s])
+        for k_ in kvs + [kv]:
+            B.ax_kv_free(k_)
+        dm.close()
+        worst[mode] = errs
+        print(f"{which} act_split={mode}: max-abs logit error per call", " ".join(f"{e:.2e}" for e in errs))
+    assert max(worst[1]) <= TOL["bf16"]
+    assert all(s_ <= u * 1.25 + 1e-4 for s_, u in zip(worst[1], worst[-1]))
+    assert max(worst[1]) < 0.7 * max(worst[-1])
