@@ -82,24 +82,34 @@ def algorithmic(shape, P, T, k):
     return out
 
 
-def cpu_oracle_baseline(torch, shape, w_dev, prompt, P, T, layers=8, reps=3):
-    """The CPU oracle, as it stands, on a bounded sample of the same workload: the first
-    `layers` layers at full width over the full prefix (built untimed), `reps` extends of the T
-    new tokens (the cache cut back to P in between), time scaled to the full depth."""
-    layers = min(layers, shape.n_layers)
+def cpu_oracle_baseline(torch, shape, w_dev, prompt, P, T, k, drafts, layers=None, reps=3):
+    """The CPU oracle, as it stands, on a bounded sample of the same workload: the same calls the
+    GPU is timed on - `reps` extends of the T new tokens over the full prefix (built untimed; the
+    cache cut back to P in between) and `reps` verify rounds at k - at full width.  `layers` (all
+    by default) bounds the depth where a model's float64 weights would not fit the host; the rates
+    are then scaled to the full depth and the sample says so."""
+    layers = shape.n_layers if layers is None else min(layers, shape.n_layers)
     from oracle import decoder as O
-    sh = shape.with_layers(layers)
-    w = {k: ([to_numpy_storage(torch, t) for t in v[:layers]] if isinstance(v, list) else to_numpy_storage(torch, v))
-         for k, v in w_dev.items()}
+    sh = shape.with_layers(layers) if layers != shape.n_layers else shape
+    w = {k_: ([to_numpy_storage(torch, t) for t in v[:layers]] if isinstance(v, list) else to_numpy_storage(torch, v))
+         for k_, v in w_dev.items()}
     kv = O.KVCache(sh.n_layers, sh.n_kv_heads, sh.head_dim)
-    O.forward(sh, w, prompt[:P], kv, rows=[-1])                      # prefix: not timed
+    for at in range(0, P, 1024):                                     # prefix: not timed
+        O.forward(sh, w, prompt[at:min(at + 1024, P)], kv, rows=[-1])
     t_each = []
     for _ in range(reps):
         kv.truncate(P)
         t0 = time.perf_counter()
-        O.forward(sh, w, prompt[P:P + T], kv, rows=[-1])
+        last = O.forward(sh, w, prompt[P:P + T], kv, rows=[-1])
         t_each.append(time.perf_counter() - t0)
     t_ext = float(np.mean(t_each))
+    pending = O.argmax_lowest(last[0])
+    t_ver = []
+    for r in range(reps):                                            # the verify rounds that follow the extend
+        t0 = time.perf_counter()
+        _a, pending, _lg = O.verify(sh, w, kv, pending, drafts[r])
+        t_ver.append(time.perf_counter() - t0)
+    t_ver = float(np.mean(t_ver))
     O.clear_widen_cache()
     try:
         from threadpoolctl import threadpool_info
@@ -113,9 +123,26 @@ def cpu_oracle_baseline(torch, shape, w_dev, prompt, P, T, layers=8, reps=3):
             cpu_model = next((ln.split(":", 1)[1].strip() for ln in f if ln.startswith("model name")), "unknown")
     except OSError:
         pass
+    depth = (f"all {shape.n_layers} layers" if layers == shape.n_layers
+             else f"first {layers} of {shape.n_layers} layers, rates scaled by {layers}/{shape.n_layers}")
     return {"value": T / (t_ext * scale), "unit": "extend tok/s", "cores": int(cores), "kind": "oracle", "cpu": cpu_model,
-            "sample": f"float64 numpy oracle, first {layers} of {shape.n_layers} layers at full width, "
-                      f"P={P}, {reps} extends of T={T} took {t_ext:.2f} s each (mean); rate scaled by {layers}/{shape.n_layers}"}
+            "verify_steps_per_s": 1.0 / (t_ver * scale),
+            "sample": f"float64 numpy oracle (matrix products on {cores} BLAS threads), {depth}, full width, P={P}: "
+                      f"{reps} extends of T={T} took {t_ext:.2f} s each and {reps} verify rounds at k={k} "
+                      f"{t_ver:.2f} s each (means); prefix construction not timed"}
+
+
+def load_rocprof_durations(workload):
+    """Average kernel durations of the dominant kernels from the committed rocprofv3 kernel trace of
+    this command (profiles/config<N>_dominant_kernel_us.txt: `phase kernel_class avg_us kernel`)."""
+    path = os.path.join(ROOT, "profiles", f"config{workload}_dominant_kernel_us.txt")
+    out = {}
+    if os.path.exists(path):
+        for line in open(path):
+            f = line.split(None, 3)
+            if len(f) == 4 and not line.startswith("#"):
+                out[(f[0], f[1])] = (float(f[2]), f[3].strip())
+    return out
 
 
 def load_traffic(workload):
@@ -349,6 +376,7 @@ def main():
     load_ms = float(np.mean(load_ms[1:]))
 
     traffic = load_traffic(args.workload)
+    rocprof_us = load_rocprof_durations(args.workload)
 
     # what this machine delivers, beside the nominal peaks the fractions are quoted against
     # (not in a counter-calibration run: the probe launches the copy kernel too, at another size)
@@ -376,21 +404,32 @@ def main():
         gbs, tfs = a["bytes"] / avg_s / 1e9, a["flops"] / avg_s / 1e12
         hbm_frac, mfma_frac = gbs / HBM_PEAK_GBS, tfs / MFMA16_PEAK_TFLOPS
         bound = "hbm" if hbm_frac >= mfma_frac else "mfma"
-        return {"kernel": f"{name} ({tag}, M={1 + k if tag == 'verify' else T})", "bound": bound,
-                "achieved": round(gbs if bound == "hbm" else tfs, 2),
-                "peak": HBM_PEAK_GBS if bound == "hbm" else MFMA16_PEAK_TFLOPS,
-                "unit": "GB/s" if bound == "hbm" else "TFLOP/s",
-                "frac": round(max(hbm_frac, mfma_frac), 4), "traffic": traffic.get((tag, name)),
-                "algorithmic_bytes": int(a["bytes"]), "algorithmic_flops": int(a["flops"]),
-                "avg_launch_us": round(avg_s * 1e6, 2), "event_pair_overhead_us": round(overhead * 1e3, 2),
-                "kernels_per_launch": launches_per_bracket, "launches": int(n),
-                "share_of_phase": round(ms / max(1e-9, sum(v[0] for k_, v in prof[tag].items() if k_ != "empty_bracket")), 3)}
+        out = {"kernel": f"{name} ({tag}, M={1 + k if tag == 'verify' else T})", "bound": bound,
+               "achieved": round(gbs if bound == "hbm" else tfs, 2),
+               "peak": HBM_PEAK_GBS if bound == "hbm" else MFMA16_PEAK_TFLOPS,
+               "unit": "GB/s" if bound == "hbm" else "TFLOP/s",
+               "frac": round(max(hbm_frac, mfma_frac), 4), "traffic": traffic.get((tag, name)),
+               "traffic_source": "profiles/ (rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE of this command), not this run",
+               "algorithmic_bytes": int(a["bytes"]), "algorithmic_flops": int(a["flops"]),
+               "frac_of_hbm_peak": round(hbm_frac, 4), "frac_of_mfma_peak": round(mfma_frac, 4),
+               "avg_launch_us": round(avg_s * 1e6, 2),
+               "avg_launch_us_method": "HIP events around each launch on the launch stream, this run; "
+                                       "raw bracket minus half of an empty bracket",
+               "raw_bracket_us": round(ms / n * 1e3, 2), "event_pair_overhead_us": round(overhead * 1e3, 2),
+               "kernels_per_launch": launches_per_bracket, "launches": int(n),
+               "share_of_phase": round(ms / max(1e-9, sum(v[0] for k_, v in prof[tag].items() if k_ != "empty_bracket")), 3)}
+        if (tag, name) in rocprof_us:                # the committed rocprofv3 trace of the same command: its figure, and the fraction it gives
+            us, kname = rocprof_us[(tag, name)]
+            r_gbs, r_tfs = a["bytes"] / (us * 1e-6) / 1e9, a["flops"] / (us * 1e-6) / 1e12
+            out["rocprof"] = {"kernel": kname, "avg_launch_us": us,
+                              "frac": round((r_gbs / HBM_PEAK_GBS) if bound == "hbm" else (r_tfs / MFMA16_PEAK_TFLOPS), 4),
+                              "source": "profiles/ (rocprofv3 --kernel-trace --stats of this command), not this run"}
+        return out
 
     dominant = {tag: max((k_ for k_ in prof[tag] if k_ != "empty_bracket"), key=lambda nme: prof[tag][nme][0])
                 for tag in prof}
-    # the kernel with the largest share of the whole step: verify runs `rounds` times per step
-    tot = {tag: prof[tag][dominant[tag]][0] for tag in prof}
-    main_tag = max(tot, key=tot.get)
+    # `value` is the extend rate, so the headline roofline object is the extend's dominant kernel; the kernel
+    # with the largest share of the whole step (verify runs `rounds` times per step) is roofline_verify
 
     out = {
         "metric": f"extend tok/s at P={P}, T={T} (target-model forward over a cached prefix)",
@@ -420,8 +459,7 @@ def main():
         "verify_emitted_tokens_per_s": round(emitted_per_s, 1),
         "extend_frac_of_measured_mfma": None if args.calibrate_copy else round(alg["extend_flops"] / (ext_ms * 1e-3) / 1e12 / mfma_tf, 4),
         "verify_frac_of_measured_hbm_read": None if args.calibrate_copy else round(alg["verify_bytes"] / (ver_ms * 1e-3) / 1e9 / read_gbs, 4),
-        "roofline": kernel_roofline(main_tag, dominant[main_tag]),
-        "roofline_extend": kernel_roofline("extend", dominant["extend"]),
+        "roofline": kernel_roofline("extend", dominant["extend"]),
         "roofline_verify": kernel_roofline("verify", dominant["verify"]),
         "prefix_kv_load": {"image_mib": round(image.numel() / 2**20, 1), "import_ms": round(load_ms, 3),
                            "import_gbs": round(image.numel() / (load_ms * 1e-3) / 1e9, 1),
@@ -435,7 +473,10 @@ def main():
         "kernel_ms": {tag: {n: round(v[0], 4) for n, v in prof[tag].items()} for tag in prof},
     }
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_oracle_baseline(torch, sh, w, prompt, P, T)
+        # all layers where their float64 copies (8 bytes per weight) fit the oracle's cache; else a bounded depth
+        f64_gb = (sh.n_layers * sh.layer_params + sh.vocab * sh.d_model) * 8 / 2**30
+        out["cpu_baseline"] = cpu_oracle_baseline(torch, sh, w, prompt, P, T, k, drafts,
+                                                  layers=None if f64_gb <= 20 else max(1, int(sh.n_layers * 20 / f64_gb)))
     B.ax_kv_free(kv)
     dm.close()
     print(json.dumps(out))

@@ -178,6 +178,21 @@ __device__ __forceinline__ bool online_softmax_step(f32x16& s, int kv0, int g, i
     return raise;
 }
 
+// Which (q-tile group, KV head, key slice) a workgroup works on.  Workgroups are dealt to the 8 XCDs round robin
+// in launch order (x fastest), and each XCD has its own L2: with the plain blockIdx mapping the q-tile groups that
+// read the SAME keys (same KV head, same slice) have consecutive ids and land on 8 different L2s, so every K/V
+// byte crossed HBM once per group (measured 7.9x the cache's bytes on a 256-row extend, 2x on a verify step).
+// Renumbered: XCD c takes the c-th eighth of the (head, slice, group) order, group fastest - all groups of one
+// (head, slice) share one L2 and run at the same time, and so do the slices of one head, which all read that
+// head's q rows (with 8 KV heads: one head per XCD; K, V and q each cross HBM once).
+struct AttnWork { int tile, hk, split; };
+__device__ __forceinline__ AttnWork attn_work() {
+    const unsigned nx = gridDim.x, nz = gridDim.z, total = nx * gridDim.y * nz;
+    unsigned id = blockIdx.x + nx * (blockIdx.y + gridDim.y * blockIdx.z);
+    if ((total & 7u) == 0) id = (id & 7u) * (total >> 3) + (id >> 3);
+    return {(int)(id % nx), (int)(id / (nx * nz)), (int)((id / nx) % nz)};
+}
+
 struct AttnArgs {
     const f16* q;
     f16* out;
@@ -205,7 +220,8 @@ __global__ __launch_bounds__(64) void attn_split_kernel(AttnArgs a) {
     constexpr int NP = QS ? 2 : 1;
     constexpr int DT = HD / 32;          // 32-channel tiles of the output
     constexpr int PS = HD * 32 + 64;     // floats of one partial: O^T [HD][32], m[32], l[32]
-    const int tile = blockIdx.x, hk = blockIdx.y, split = blockIdx.z;
+    const AttnWork wk = attn_work();
+    const int tile = wk.tile, hk = wk.hk, split = wk.split;
     const int lane = threadIdx.x, ql = lane & 31, g = lane >> 5;
     const int Hq = a.Hq, Hkv = a.kv.n_kv_heads, G = Hq / Hkv;
     const int4 ti0 = *(const int4*)(a.tile_info + tile * 8), ti1 = *(const int4*)(a.tile_info + tile * 8 + 4);
@@ -381,7 +397,8 @@ __global__ __launch_bounds__(64 * NQ) void attn_block_kernel(AttnArgs a) {
     __shared__ __attribute__((aligned(16))) f16 sK[2][32 * KLS];
     __shared__ __attribute__((aligned(16))) f16 sV[2][2 * HD * VLS];
 
-    const int tile = blockIdx.x, hk = blockIdx.y, split = blockIdx.z;
+    const AttnWork wk = attn_work();
+    const int tile = wk.tile, hk = wk.hk, split = wk.split;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, ql = lane & 31, g = lane >> 5;
     const int Hq = a.Hq, Hkv = a.kv.n_kv_heads, G = Hq / Hkv;
     const int4 ti0 = *(const int4*)(a.tile_info + tile * 8), ti1 = *(const int4*)(a.tile_info + tile * 8 + 4);

@@ -1455,6 +1455,8 @@ static bool use_skinny(int epi, int M, int N, int K) {
     if (M <= 16) return true;
     if (M > kSkinnyMaxM) return false;
     if (epi == EPI_STORE_F32 && N >= 256 * 256 && kLmStream) return false;    // logits: streaming blocks (see launch_lds_tile)
+    // (re-measured on whole verify steps of 17 rows, ~3B shape, 2.50 ms per step: keeping the QKV / SwiGLU / down
+    // GEMM on this kernel there - no reduce kernel behind them - gives 2.50 / 2.52 / 2.58 ms, all three 2.59 ms)
     return !(epi == EPI_QKV || epi == EPI_SWIGLU || (epi == EPI_RESIDUAL && K >= 2 * N));
 }
 

@@ -2,11 +2,14 @@
 
     python -m paper_2605_10380_amd.profsummary trace  <results.db> [rows]
     python -m paper_2605_10380_amd.profsummary pmc    <fetch_counter_collection.csv> <write_counter_collection.csv> [rows]
+    python -m paper_2605_10380_amd.profsummary counters <kernel regex> <counter_collection.csv> [more .csv ...]
 
 `trace`: per kernel (name, grid) calls, average / minimum / total duration from a
 `rocprofv3 --kernel-trace --stats` run.  `pmc`: HBM bytes per launch from two `rocprofv3 --pmc`
 runs (FETCH_SIZE, then WRITE_SIZE) of `bench.py --calibrate-copy`; each counter is scaled by what
-it reads for the plain 256 MiB copy kernel that run contains.
+it reads for the plain 256 MiB copy kernel that run contains.  `counters`: for every (kernel, grid)
+whose name matches the regex, the average per launch of every counter found in the given
+`rocprofv3 --pmc ... --output-format csv` files (one file per counter pass).
 """
 import collections
 import csv
@@ -57,10 +60,31 @@ def pmc(fetch_csv: str, write_csv: str, rows: int = 16) -> str:
     return "\n".join(out)
 
 
+def counters(pattern: str, paths) -> str:
+    rx = re.compile(pattern)
+    vals = collections.defaultdict(lambda: collections.defaultdict(list))     # kernel key -> counter -> values
+    for path in paths:
+        for r in csv.DictReader(open(path)):
+            name = short(r["Kernel_Name"])
+            if rx.search(name):
+                vals[(name, r["Grid_Size"], r["Workgroup_Size"])][r["Counter_Name"]].append(float(r["Counter_Value"]))
+    out = []
+    for key in sorted(vals, key=lambda k: (k[0], int(k[1]))):
+        per = vals[key]
+        calls = max(len(v) for v in per.values())
+        out.append(f"{key[0]}  grid (threads) {key[1]}  wg {key[2]}  launches {calls}")
+        for cname in sorted(per):
+            v = per[cname]
+            out.append(f"    {cname:36s} {sum(v) / len(v):16.1f}")
+    return "\n".join(out)
+
+
 if __name__ == "__main__":
     if len(sys.argv) >= 3 and sys.argv[1] == "trace":
         print(trace(sys.argv[2], int(sys.argv[3]) if len(sys.argv) > 3 else 24))
     elif len(sys.argv) >= 4 and sys.argv[1] == "pmc":
         print(pmc(sys.argv[2], sys.argv[3], int(sys.argv[4]) if len(sys.argv) > 4 else 16))
+    elif len(sys.argv) >= 4 and sys.argv[1] == "counters":
+        print(counters(sys.argv[2], sys.argv[3:]))
     else:
         sys.exit(__doc__)
