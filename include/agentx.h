@@ -113,8 +113,10 @@ size_t ax_workspace_bytes(const ax_model_config *cfg);
  * ax_workspace_bytes(cfg) bytes, 256-byte aligned, owned by the caller and used by every call
  * on this model (activations, rotary table, per-call descriptors, split-attention partials
  * and, for AX_BF16, the repacked weight matrices: about as many bytes again as the weights).
- * AX_BF16 needs d_model, d_ff, head counts*head_dim and vocab to be multiples of 64 and
- * head_dim in {64, 128}; AX_F32 takes any sizes with an even head_dim <= 256.
+ * AX_BF16 needs d_model, d_ff, head counts*head_dim and vocab to be multiples of 64,
+ * head_dim in {64, 128} and every matrix entry finite in fp16 (|w| <= 65504: the matrices are
+ * multiplied as fp16; a bf16 value below that bound converts exactly or, under 2^-14, to within
+ * 2^-25) - AX_ERR_UNSUPPORTED otherwise; AX_F32 takes any sizes with an even head_dim <= 256.
  * Needs a GPU (uploads the rotary table, repacks the weights; synchronises the device).  Errors: INVALID, OOM (workspace too small),
  * UNSUPPORTED, DEVICE. */
 ax_status ax_model_create(const ax_model_config *cfg, const ax_weights *weights,

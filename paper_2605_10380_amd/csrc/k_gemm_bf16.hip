@@ -94,18 +94,26 @@ constexpr int PK_KG = 128;        // elements between k-groups of 8 inside a chu
 constexpr int PK_CHUNK = 512;     // elements per chunk of 32 k  (so k advances by 32 -> +512: "k * 16")
 
 // out-of-place repack: one thread per 16-byte unit of the destination (coalesced writes)
-__global__ void pack_weights_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst, int N, int K) {
+// A bf16 weight beyond fp16's range (|w| > 65504, infinities, NaNs) does not survive: `bad` reports it.
+__global__ void pack_weights_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst, int N, int K, int* __restrict__ bad) {
     const long long units = (long long)N * K / 8, stride = (long long)gridDim.x * blockDim.x;
     const int upp = 2 * K;                                   // 16-byte units per panel
+    bool lost = false;
     for (long long u = (long long)blockIdx.x * blockDim.x + threadIdx.x; u < units; u += stride) {
         const int panel = (int)(u / upp), w = (int)(u % upp);
         const int c = w >> 6, kg = (w >> 4) & 3, r = w & 15;
-        dst[u] = __builtin_bit_cast(u32x4, bf16x8_to_f16x8(src[((long long)(panel * 16 + r) * K + c * 32 + kg * 8) / 8]));
+        const u32x4 raw = src[((long long)(panel * 16 + r) * K + c * 32 + kg * 8) / 8];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)       // checked on the exact values: the narrowing itself rounds toward zero and would saturate
+            lost |= !(__builtin_fabsf(__uint_as_float(raw[i] << 16)) <= 65504.0f) ||
+                    !(__builtin_fabsf(__uint_as_float(raw[i] & 0xffff0000u)) <= 65504.0f);
+        dst[u] = __builtin_bit_cast(u32x4, bf16x8_to_f16x8(raw));
     }
+    if (bad && lost) *bad = 1;                               // every writer stores the same value
 }
 
-void launch_pack_weights(const void* src, void* dst, int N, int K, hipStream_t s) {
-    pack_weights_kernel<<<2048, 256, 0, s>>>((const u32x4*)src, (u32x4*)dst, N, K);
+void launch_pack_weights(const void* src, void* dst, int N, int K, hipStream_t s, int* bad) {
+    pack_weights_kernel<<<2048, 256, 0, s>>>((const u32x4*)src, (u32x4*)dst, N, K, bad);
 }
 
 // 1 / rms of A rows from the column-block partial sums of x^2 their producer left behind.

@@ -88,7 +88,8 @@ constexpr int SPLITK_MAX = 8;
 int launch_gemm_bf16(Epilogue epi, const GemmArgs& g, hipStream_t s);
 // Repacks a row-major bf16 [N, K] matrix (N % 16 == 0, K % 32 == 0) into what every bf16-model GEMM
 // kernel reads: fp16 values in 16-row panels, 32-k chunks in MFMA operand order; src and dst must not overlap.
-void launch_pack_weights(const void* src, void* dst, int N, int K, hipStream_t s);
+// `bad` (device int, may be NULL) is set to 1 if some weight does not survive the narrowing (not finite in fp16).
+void launch_pack_weights(const void* src, void* dst, int N, int K, hipStream_t s, int* bad = nullptr);
 // bf16-weight models: x[r,:] = emb[tok], a[r,:] = fp16(x * gain), ssq[r][0] = sum x^2, ssq[r][1..nparts) = 0
 // a_lo_off != 0: also the lo parts fp16(x * gain - a), that many elements behind a
 void launch_embed_norm(const void* emb, const int* row_tok, const void* gain, float* x, void* a, long long a_lo_off,

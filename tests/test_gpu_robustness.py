@@ -185,3 +185,20 @@ def test_split_activations_every_kernel_family(B, which):
     assert max(worst[1]) <= TOL["bf16"]
     assert all(s_ <= u * 1.25 + 1e-4 for s_, u in zip(worst[1], worst[-1]))
     assert max(worst[1]) < 0.7 * max(worst[-1])
+
+
+def test_weights_outside_fp16_range_are_refused(B):
+    """bf16 weights are multiplied as fp16: a matrix entry that is not finite in fp16 (here 1e5, and
+    a NaN) must make ax_model_create fail with AX_ERR_UNSUPPORTED instead of producing infinities."""
+    sh = I.DecoderShape("s64", 2, 256, 4, 2, 64, 512, 512, "bf16")
+    for name, layer, value in (("w_down", 1, 1.0e5), ("lm_head", None, float("nan"))):
+        w = I.make_weights(sh, 33)
+        t = w[name] if layer is None else w[name][layer]
+        t[3, 5] = I.f32_to_bf16_bits(np.array([value], dtype=np.float32))[0]
+        with pytest.raises(B.AxError) as e:
+            B.DeviceModel(sh, w, max_pos=64, max_tokens=16, pool_tokens=64)
+        assert e.value.status == B.AX_ERR_UNSUPPORTED, name
+    w = I.make_weights(sh, 33)
+    w["wo"][0][1, 1] = I.f32_to_bf16_bits(np.array([6.0e4], dtype=np.float32))[0]      # large but representable
+    dm = B.DeviceModel(sh, w, max_pos=64, max_tokens=16, pool_tokens=64)
+    dm.close()
