@@ -638,9 +638,12 @@ ax_status ax_model_create(const ax_model_config* cfg, const ax_weights* w, void*
     if (cfg->dtype == AX_BF16) {
         // the kernels read their own packed copies of the matrices (token embedding and gains stay as given)
         char* at = m->ws + L.packed;
+        int* bad = (int*)(m->ws + L.result);       // set by the repack where a weight is not finite in fp16
+        e = hipMemset(bad, 0, sizeof(int));
+        if (e != hipSuccess) { cleanup(); return fail(AX_ERR_DEVICE, "hipMemset: %s", hipGetErrorString(e)); }
         const int d = cfg->d_model, qkv = (cfg->n_q_heads + 2 * cfg->n_kv_heads) * cfg->head_dim, qd = cfg->n_q_heads * cfg->head_dim;
         auto pack = [&](const void*& w_ptr, int N, int K) {
-            ax::launch_pack_weights(w_ptr, at, N, K, nullptr);
+            ax::launch_pack_weights(w_ptr, at, N, K, nullptr, bad);
             w_ptr = at;
             at += align_up((size_t)N * K * 2);
         };
@@ -654,7 +657,13 @@ ax_status ax_model_create(const ax_model_config* cfg, const ax_weights* w, void*
         pack(m->lm_head, cfg->vocab, d);
         e = hipGetLastError();
         if (e == hipSuccess) e = hipDeviceSynchronize();
+        int lost = 0;
+        if (e == hipSuccess) e = hipMemcpy(&lost, bad, sizeof(int), hipMemcpyDeviceToHost);
         if (e != hipSuccess) { cleanup(); return fail(AX_ERR_DEVICE, "weight repack: %s", hipGetErrorString(e)); }
+        if (lost) {
+            cleanup();
+            return fail(AX_ERR_UNSUPPORTED, "a weight is not finite in fp16 (|w| > 65504, infinity or NaN): the matrices are multiplied as fp16");
+        }
     }
     ax::handle_register(m, ax::H_MODEL);
     *out = m;
