@@ -380,11 +380,12 @@ def main():
 
     # what this machine delivers, beside the nominal peaks the fractions are quoted against
     # (not in a counter-calibration run: the probe launches the copy kernel too, at another size)
-    read_gbs = copy_gbs = mfma_tf = float("nan")
+    read_gbs = copy_gbs = mfma_tf = boundary_us = barrier_us = float("nan")
     if not args.calibrate_copy:
         probe = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
         torch.cuda.synchronize()
         read_gbs, copy_gbs, mfma_tf = B.ax_dbg_peaks(probe.data_ptr(), probe.numel(), 5, dm.stream)
+        boundary_us, barrier_us = B.ax_dbg_phase_order(probe.data_ptr(), 4096, 256, 200, dm.stream)
         del probe
 
     def kernel_roofline(tag, name):
@@ -468,8 +469,10 @@ def main():
         "measured_peaks": None if args.calibrate_copy else {
                            "hbm_read_gbs": round(read_gbs, 1), "hbm_copy_gbs": round(copy_gbs, 1),
                            "mfma_f16_tflops": round(mfma_tf, 1),
+                           "kernel_boundary_us": round(boundary_us, 2), "grid_barrier_us": round(barrier_us, 2),
                            "note": "1 GiB read-only stream, 512 MiB -> 512 MiB copy (read + written bytes), "
-                                   "register-resident 32x32x16 fp16 MFMA loop on all compute units"},
+                                   "register-resident 32x32x16 fp16 MFMA loop on all compute units; back-to-back empty "
+                                   "kernels of 256 x 512 threads against a barrier across 256 resident workgroups"},
         "kernel_ms": {tag: {n: round(v[0], 4) for n, v in prof[tag].items()} for tag in prof},
     }
     if not args.no_cpu_baseline:

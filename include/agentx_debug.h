@@ -52,6 +52,16 @@ ax_status ax_dbg_copy(void *dst, const void *src, size_t bytes, void *hip_stream
 ax_status ax_dbg_peaks(void *buf, size_t bytes, int reps, float *read_gbs, float *copy_gbs,
                        float *mfma_f16_tflops, void *hip_stream);
 
+/* The two ways to order the dependent phases of a step, timed: `rounds` back-to-back launches of an
+ * empty kernel of `blocks` workgroups of 512 threads on hip_stream (microseconds per kernel boundary),
+ * and one launch of the same shape that crosses a barrier over all its workgroups `rounds` times
+ * (microseconds per barrier; two-level counters, device-scope atomics, fences on both sides).  blocks: a
+ * multiple of 8, at most 256 (one workgroup per compute unit, so that all are resident on an otherwise
+ * idle device); buf: at least 4096 bytes of device memory, overwritten.  Every wait of the barrier kernel
+ * is bounded: AX_ERR_DEVICE if a workgroup gave up.  Synchronises. */
+ax_status ax_dbg_phase_order(void *buf, size_t bytes, int blocks, int rounds, float *boundary_us,
+                             float *barrier_us, void *hip_stream);
+
 /* Copies a workspace buffer as left by the last ax_extend* call to host memory (synchronises).
  * which: 0 residual stream x float[rows][d_model]; 1 qkv float[rows][(Hq+2Hkv)*hd] (pre-rotary,
  * last layer); 2 q after rotary, act[rows][Hq*hd]; 3 attention output act[rows][Hq*hd];

@@ -1205,6 +1205,43 @@ ax_status ax_dbg_peaks(void* buf, size_t bytes, int reps, float* read_gbs, float
     return AX_OK;
 }
 
+ax_status ax_dbg_phase_order(void* buf, size_t bytes, int blocks, int rounds, float* boundary_us, float* barrier_us,
+                             void* hip_stream) {
+    if (!buf || bytes < 4096 || blocks < 8 || blocks % 8 != 0 || blocks > 256 || rounds < 1 || rounds > 100000 || !boundary_us ||
+        !barrier_us)
+        return fail(AX_ERR_INVALID, "bad argument");
+    hipStream_t s = (hipStream_t)hip_stream;
+    hipEvent_t e0, e1;
+    HIP_TRY(hipEventCreate(&e0));
+    HIP_TRY(hipEventCreate(&e1));
+    char* p = (char*)buf;
+    int* err = (int*)(p + 3072);
+    float ms[2] = {0.f, 0.f};
+    for (int which = 0; which < 2; ++which) {
+        for (int rep = -1; rep < 1; ++rep) {                   // one untimed pass, one timed
+            HIP_TRY(hipMemsetAsync(p, 0, 4096, s));
+            HIP_TRY(hipEventRecord(e0, s));
+            if (which == 0) {
+                for (int r = 0; r < rounds; ++r) ax::launch_boundary(p, blocks, s);
+            } else {
+                ax::launch_grid_barrier(p, err, blocks, rounds, s);
+            }
+            HIP_TRY(hipEventRecord(e1, s));
+            HIP_TRY(hipEventSynchronize(e1));
+            HIP_TRY(hipGetLastError());
+        }
+        HIP_TRY(hipEventElapsedTime(&ms[which], e0, e1));
+    }
+    int timed_out = 0;
+    HIP_TRY(hipMemcpy(&timed_out, err, sizeof(int), hipMemcpyDeviceToHost));
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (timed_out) return fail(AX_ERR_DEVICE, "grid barrier: a workgroup gave up waiting (the launch was not resident as a whole)");
+    *boundary_us = ms[0] * 1e3f / (float)rounds;
+    *barrier_us = ms[1] * 1e3f / (float)rounds;
+    return AX_OK;
+}
+
 ax_status ax_dbg_read(ax_model* m, int which, void* host_dst, size_t bytes) {
     if (!ok(m) || !host_dst) return fail(AX_ERR_INVALID, "bad argument");
     const Layout& L = m->lay;

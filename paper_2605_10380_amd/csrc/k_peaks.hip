@@ -1,6 +1,8 @@
 // k_peaks.hip - what this machine delivers, measured beside the nominal peaks: a read-only
-// stream over a caller's buffer (HBM read rate) and a register-resident MFMA loop (fp16 matrix
-// rate).  Test / bench support only; nothing on the serving path calls these.
+// stream over a caller's buffer (HBM read rate), a register-resident MFMA loop (fp16 matrix
+// rate), and the two ways to order dependent phases of a step (a kernel boundary on one stream
+// against a barrier across the workgroups of one resident kernel).  Test / bench support only;
+// nothing on the serving path calls these.
 #include <hip/hip_runtime.h>
 #include "kernels.h"
 
@@ -47,6 +49,50 @@ __global__ void __launch_bounds__(512) mfma_loop_kernel(int iters, float never, 
     float s = 0.f;
     for (int i = 0; i < 16; ++i) s += c0[i] + c1[i] + c2[i] + c3[i];
     if (s == never) sink[0] = s;
+}
+
+// A barrier across all workgroups of a launch whose workgroups are all resident, `rounds` times.
+// Two levels, so that no counter takes more than gridDim.x / 8 arrivals: workgroups are dealt to the
+// 8 XCDs round robin, group g = blockIdx.x % 8 counts its arrivals on its own 128-byte line, the last
+// arrival of a group counts on the master line, the last group stores the round number into the 8
+// group flags, and every workgroup polls its group's flag (device-scope relaxed accesses between a
+// release and an acquire fence).  Every wait is bounded: a workgroup that polls `spin_limit` times
+// without success sets *err and leaves, and so do all others.
+// ctr: 24 lines of 32 words, zero at launch (line 0 master, 1-8 group counters, 9-16 group flags).
+__global__ void __launch_bounds__(512) grid_barrier_kernel(unsigned* __restrict__ ctr, int* __restrict__ err, int rounds, int spin_limit) {
+    const unsigned grp = blockIdx.x & 7u, per = gridDim.x >> 3;
+    unsigned* gc = ctr + 32 * (1 + grp);
+    unsigned* gf = ctr + 32 * (9 + grp);
+    for (unsigned r = 1; r <= (unsigned)rounds; ++r) {
+        __syncthreads();
+        bool ok = true;
+        if (threadIdx.x == 0) {
+            __threadfence();
+            if (__hip_atomic_fetch_add(gc, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1 == r * per &&
+                __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1 == r * 8) {
+                for (int g = 0; g < 8; ++g) __hip_atomic_store(ctr + 32 * (9 + g), r, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            int spins = 0;
+            while (__hip_atomic_load(gf, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < r) {
+                if (++spins > spin_limit) { ok = false; *err = 1; break; }
+                __builtin_amdgcn_s_sleep(2);
+            }
+            __threadfence();
+        }
+        if (!__syncthreads_and(ok)) return;
+    }
+}
+
+__global__ void __launch_bounds__(512) boundary_kernel(unsigned* __restrict__ sink, unsigned never) {
+    if (threadIdx.x == never) sink[0] = never;      // never: a kernel of the step's launch shape with nothing in it
+}
+
+void launch_grid_barrier(void* ctr, int* err, int blocks, int rounds, hipStream_t s) {
+    grid_barrier_kernel<<<blocks, 512, 0, s>>>((unsigned*)ctr, err, rounds, 1 << 16);
+}
+
+void launch_boundary(void* sink, int blocks, hipStream_t s) {
+    boundary_kernel<<<blocks, 512, 0, s>>>((unsigned*)sink, 0xffffffffu);
 }
 
 void launch_read_stream(const void* src, size_t n16, void* sink, hipStream_t s) {

@@ -232,3 +232,21 @@ def test_measured_peaks_probe(torch_cuda):
     assert 500.0 < mfma_tf <= 2520.0
     with pytest.raises(B.AxError):
         B.ax_dbg_peaks(buf.data_ptr(), 48, 3)
+
+
+def test_phase_order_probe(torch_cuda):
+    """Kernel boundary against in-kernel barrier: both times are positive and finite, the barrier kernel
+    crosses all its rounds (a workgroup that gave up would come back as an error), bytes of the buffer
+    past the first 4096 are untouched, and bad shapes are refused."""
+    torch = torch_cuda
+    from paper_2605_10380_amd import binding as B
+    buf = torch.full((2048,), 7, dtype=torch.int32, device="cuda")
+    torch.cuda.synchronize()
+    for blocks in (8, 64, 256):
+        boundary_us, barrier_us = B.ax_dbg_phase_order(buf.data_ptr(), buf.numel() * 4, blocks, 50)
+        print(f"{blocks} workgroups: {boundary_us:.2f} us per kernel boundary, {barrier_us:.2f} us per grid barrier", flush=True)
+        assert 0.0 < boundary_us < 1000.0 and 0.0 < barrier_us < 1000.0
+    assert bool((buf[1024:] == 7).all())
+    for bad in (0, 12, 264):
+        with pytest.raises(B.AxError):
+            B.ax_dbg_phase_order(buf.data_ptr(), buf.numel() * 4, bad, 50)
