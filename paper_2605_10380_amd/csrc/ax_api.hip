@@ -41,6 +41,7 @@ int isz(int dtype) { return ax::itemsize(dtype); }
 using ax::config_ok;
 
 struct Layout {                       // byte offsets into the workspace
+    size_t splitk_bytes;
     size_t rope_cos, rope_sin, desc, x, h, ssq, qkv, q, attn, ffn, partials, splitk, logits, amax_scratch,
         amax_out, result, packed, total;
     size_t desc_ints;                 // capacity of one descriptor slot
@@ -92,7 +93,12 @@ Layout make_layout(const ax_model_config& c) {
     // chosen to stay inside this capacity.  Room for two passes: the per-sequence one and the shared-prefix one.
     L.max_records = std::max<size_t>(SPLIT_ITEMS, ((T * G + 31) / 32 + 8 * S + 2) * (size_t)c.n_kv_heads);
     L.partials = take(c.dtype == AX_BF16 ? 2 * L.max_records * ((size_t)c.head_dim * 32 + 64) * 4 : 0);
-    L.splitk = take(c.dtype == AX_BF16 ? T * c.d_model * 4 * ax::SPLITK_MAX : 0);   // K-slice partials of residual GEMMs
+    // fp32 slabs of GEMMs that finish in a second kernel: K-slice partials of the residual GEMMs (SPLITK_MAX slabs of
+    // [T, d_model]; the SwiGLU GEMM's slices take what fits) and the raw products of the QKV GEMM above 64 rows, which
+    // needs ONE whole [T, (Hq + 2 Hkv) hd] slab whatever the ratio of that width to d_model
+    L.splitk_bytes = c.dtype == AX_BF16 ? std::max(T * c.d_model * 4 * ax::SPLITK_MAX,
+                                                   T * (size_t)(c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim * 4) : 0;
+    L.splitk = take(L.splitk_bytes);
     L.logits = take(std::min<size_t>(T, LOGIT_ROWS) * (size_t)c.vocab * 4);
     L.amax_scratch = take(2 * std::min<size_t>(T, LOGIT_ROWS) * ax::ARGMAX_PARTS * 4);
     L.amax_out = take(T * 4);
@@ -430,7 +436,7 @@ ax_status enqueue_call(ax_model* m, const CallPlan& cp, void* out, hipStream_t s
         ax::GemmArgs base{};
         base.M = R;
         base.split_ws = (float*)(ws + L.splitk);
-        base.split_ws_bytes = (size_t)c.max_tokens * c.d_model * 4 * ax::SPLITK_MAX;
+        base.split_ws_bytes = L.splitk_bytes;
         auto normed = [&](ax::GemmArgs& g) { g.A = h; g.a_lo_off = L.h_lo; g.ssq = ssq; g.nparts = nparts; g.d_norm = d_model; g.eps = c.rms_eps; g.K = d_model; };
         ax::launch_embed_norm(m->tok_emb, sv.row_tok, m->norm_attn[0], x, h, L.h_lo, ssq, nparts, R, d_model, stream);
         for (int l = 0; l < c.n_layers; ++l) {
@@ -442,7 +448,7 @@ ax_status enqueue_call(ax_model* m, const CallPlan& cp, void* out, hipStream_t s
                 g.rope.row_pos = sv.row_pos; g.rope.row_slot = sv.row_slot;
                 g.rope.cos = (const float*)(ws + L.rope_cos); g.rope.sin = (const float*)(ws + L.rope_sin);
                 ProfScope ps(m, 0, stream);
-                ax::launch_gemm_bf16(ax::EPI_QKV, g, stream);
+                (void)ax::launch_gemm_bf16(ax::EPI_QKV, g, stream);   // (its slab always fits: make_layout reserves max_tokens rows of it)
             }
             { ProfScope ps(m, 1, stream);
               ax::launch_attention(dt, qb, attn, kg, l, sv, c.n_q_heads, (float*)(ws + L.partials), n_splits, stream, L.q_lo, L.attn_lo); }

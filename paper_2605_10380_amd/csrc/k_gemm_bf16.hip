@@ -1272,8 +1272,8 @@ static int launch_lds_tile(const GemmArgs& g, hipStream_t s) {
         // embedding and KV append: measured faster than a fused epilogue (one head per wavefront)
         // at every size tried (M = 256 / 512, all three model shapes).  With few tiles K is cut in
         // two slices that the second kernel adds up.
-        // (The workspace always holds at least one [M, N] fp32 slab: it is sized for 8 slabs of
-        // [max_tokens, d_model] and N <= 3 d_model.)
+        // (The workspace holds at least one [M, N] fp32 slab - a model's layout reserves max_tokens x N of it
+        // whatever the ratio of N to d_model; a caller that brings less gets nothing launched.)
         // 128-row blocks from 80 tiles up (~3B / ~8B at M = 256: 36 -> 29 / 43 -> 34 us; M = 3584:
         // 275 -> 221 / 443 -> 329 us); the ~1B shape at M = 256 has 48 such tiles and stays with 64 rows
         const bool big = kQkvTile >= 0 ? kQkvTile > 0 : (pad_ok && tiles128 >= 80);
@@ -1287,6 +1287,7 @@ static int launch_lds_tile(const GemmArgs& g, hipStream_t s) {
             ks = 3;
         if (kQkvKs > 0) ks = kQkvKs;
         while (ks > 1 && (K % (ks * 64) != 0 || (size_t)ks * M * N * sizeof(float) > g.split_ws_bytes)) ks >>= 1;
+        if (!g.split_ws || (size_t)M * N * sizeof(float) > g.split_ws_bytes) return -1;
         GemmArgs gs = g;
         gs.ksplit = ks;
         GemmArgs gp = gs;                                 // the products: no scaling, no epilogue work

@@ -85,6 +85,8 @@ constexpr int SPLITK_MAX = 8;
 // ssq_out (rows are that many floats apart): the consumer of the pending norm passes it as nparts.
 // It depends on which kernel ran (a few per row after a K-split reduce kernel, N / 32 or N / 8-16
 // from kernels that finish a column block on their own).  Other epilogues return 0.
+// EPI_QKV above 64 rows writes its raw products to split_ws first: -1, and nothing launched, if one [M, N] fp32
+// slab does not fit there.
 int launch_gemm_bf16(Epilogue epi, const GemmArgs& g, hipStream_t s);
 // Repacks a row-major bf16 [N, K] matrix (N % 16 == 0, K % 32 == 0) into what every bf16-model GEMM
 // kernel reads: fp16 values in 16-row panels, 32-k chunks in MFMA operand order; src and dst must not overlap.

@@ -1,0 +1,121 @@
+"""GPU vs the CPU oracle over seeded RANDOM decoder shapes and call patterns.
+
+The hand-picked cases elsewhere sit on the shapes the kernels were written around; this sweep draws
+what they were not tuned for - odd head counts and group sizes, d_model / d_ff / vocabulary at every
+multiple the boundary accepts (64 for bf16 models, anything even-headed for fp32), prefixes built in
+ragged chunks, extends of up to 700 rows that end inside a KV block, verify rounds at any k up to 16, a
+batched pass over forks of unequal length, and every fifth bf16 case with split (hi + lo) activations.  Every logit of every compared row against the plain computation (paper
+Sec. 2.3: an extend over a cached prefix equals the full forward; verification accepts exactly the
+greedy continuation), tolerances as everywhere: 1e-4 (fp32) / 2e-2 (bf16) max-abs, decisions exact
+wherever the oracle's top-2 margin exceeds 1e-2.
+"""
+import numpy as np
+import pytest
+
+from oracle import decoder as O
+from paper_2605_10380_amd import inputs as I
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+MARGIN = 1e-2
+
+
+@pytest.fixture(scope="module")
+def B():
+    import torch
+    assert torch.cuda.is_available()
+    from paper_2605_10380_amd import binding
+    return binding
+
+
+def draw_shape(rng, case):
+    if case % 4 == 3:                                            # fp32: plain kernels, any sizes
+        hd = int(rng.choice([16, 32, 48, 64, 96]))
+        hkv = int(rng.integers(1, 4))
+        g = int(rng.integers(1, 5))
+        return I.DecoderShape(f"r{case}", int(rng.integers(1, 3)), int(rng.integers(5, 40)) * 4, hkv * g, hkv, hd,
+                              int(rng.integers(20, 200)) * 2 + 1, int(rng.integers(50, 700)), "f32")
+    hd = int(rng.choice([64, 128]))
+    hkv = int(rng.integers(1, 5))
+    g = int(rng.choice([1, 2, 3, 4, 5, 8]))
+    return I.DecoderShape(f"r{case}", int(rng.integers(1, 4)), 64 * int(rng.integers(2, 11)), hkv * g, hkv, hd,
+                          64 * int(rng.integers(3, 21)), 64 * int(rng.integers(5, 41)), "bf16")
+
+
+def check(sh, got, ref, what):
+    err = float(np.abs(got.astype(np.float64) - ref).max())
+    assert err <= TOL[sh.dtype], (what, err)
+    return err
+
+
+@pytest.mark.parametrize("case", range(48))
+def test_random_shape_and_call_pattern(B, case):
+    rng = np.random.default_rng(7000 + case)
+    sh = draw_shape(rng, case)
+    P = int(rng.integers(0, 420))
+    T = int(rng.integers(1, 230)) if case % 8 else int(rng.integers(257, 700))      # every eighth: the many-row kernels
+    k_list = [int(rng.integers(0, 17)) for _ in range(3)]
+    print(f"case {case}: {sh}, P={P} T={T} k={k_list}", flush=True)
+    w = I.make_weights(sh, 7000 + case)
+    toks = I.templated_prompt(sh.vocab, 7000 + case, P + T + 64)
+    assert P + T + 3 * 17 + 60 <= 1536
+    split = 1 if sh.dtype == "bf16" and case % 5 == 4 else 0
+    dm = B.DeviceModel(sh, w, max_pos=1536, max_tokens=768, pool_tokens=6144, max_seqs=3, act_split=split)
+    kv, ref_kv = dm.new_kv(), O.KVCache(sh.n_layers, sh.n_kv_heads, sh.head_dim)
+
+    # prefix in ragged chunks (the oracle takes it in one go: the result must not depend on the cut)
+    at = 0
+    while at < P:
+        c = min(P - at, int(rng.integers(1, 200)))
+        dm.extend(kv, toks[at:at + c])
+        at += c
+    if P:
+        O.forward(sh, w, toks[:P], ref_kv, rows=[-1])
+    got = dm.extend(kv, toks[P:P + T], B.AX_OUT_ALL_LOGITS).cpu().numpy()
+    ref = O.forward(sh, w, toks[P:P + T], ref_kv)
+    errs = [check(sh, got, ref, f"extend P={P} T={T}")]
+
+    # verify rounds: the first j drafts are the greedy continuation, draft j is wrong (j seeded)
+    pending = O.argmax_lowest(ref[-1])
+    exempt = 0
+    for r, k in enumerate(k_list):
+        Pn = len(ref_kv)
+        greedy = O.greedy_decode(sh, w, ref_kv.fork(), pending, k) if k else []
+        drafts = I.seeded_accept_drafts(np.array(greedy[:k]), sh.vocab, 7000 + case, r, k)[0] if k else np.zeros(0, np.int32)
+        a_ref, nxt_ref, logits = O.verify(sh, w, ref_kv, pending, drafts)
+        a, nxt = dm.verify(kv, pending, drafts)
+        assert B.ax_kv_len(kv) == Pn + 1 + a
+        if (a, nxt) != (a_ref, nxt_ref):
+            assert O.top2_margin(logits[min(a, a_ref)]) <= MARGIN, (r, k, a, a_ref, nxt, nxt_ref)
+            exempt += 1
+            if a > a_ref:
+                B.ax_kv_truncate(kv, Pn + 1 + a_ref)
+            elif a < a_ref:
+                dm.extend(kv, np.asarray(drafts[a:a_ref], dtype=np.int32))
+        pending = nxt_ref
+    assert exempt <= 1
+
+    # three forks of unequal length extended by unequal amounts in one batched pass
+    n_now = len(ref_kv)
+    cuts = [n_now, max(1, n_now - int(rng.integers(0, 20))), max(1, n_now // 2)]
+    t_each = [int(rng.integers(1, 60)) for _ in range(3)]
+    kvs, refs, news = [], [], []
+    for s in range(3):
+        kvs.append(B.ax_kv_fork(kv, cuts[s]))
+        rk = ref_kv.fork()
+        rk.truncate(cuts[s])
+        refs.append(rk)
+        news.append(I.zipf_tokens(sh.vocab, 7000 + case, f"n{s}", t_each[s]))
+    gotb = dm.extend_batch(kvs, news, B.AX_OUT_ALL_LOGITS).cpu().numpy()
+    at = 0
+    for s in range(3):
+        refb = O.forward(sh, w, news[s], refs[s])
+        errs.append(check(sh, gotb[at:at + t_each[s]], refb, f"batched fork {s} (len {cuts[s]} + {t_each[s]})"))
+        assert B.ax_kv_len(kvs[s]) == len(refs[s])
+        at += t_each[s]
+    print(f"case {case}: max-abs logit errors {['%.2e' % e for e in errs]} (limit {TOL[sh.dtype]:.0e}), exempt rounds {exempt}", flush=True)
+    for h in kvs + [kv]:
+        B.ax_kv_free(h)
+    assert B.ax_pool_stats(dm.pool)[0] == B.ax_pool_stats(dm.pool)[1]
+    dm.close()
