@@ -119,3 +119,80 @@ def test_random_shape_and_call_pattern(B, case):
         B.ax_kv_free(h)
     assert B.ax_pool_stats(dm.pool)[0] == B.ax_pool_stats(dm.pool)[1]
     dm.close()
+
+
+@pytest.mark.parametrize("case", range(16))
+def test_random_sessions_batched(B, case):
+    """2-12 sessions forked at random points of one prefix (long enough, in half of the cases, for the
+    shared-prefix attention pass), private histories of random length, then rounds that alternate a batched
+    extend of random lengths (last-row logits against the oracle) and a batched verify with a random draft
+    count per session, 0 included; finally one session is exported, imported into fresh blocks and must
+    continue exactly like the original."""
+    rng = np.random.default_rng(9000 + case)
+    sh = draw_shape(rng, case if case % 4 != 3 else case + 1)            # bf16 shapes only: the batched paths with MFMA attention
+    n = int(rng.integers(2, 13))
+    plen = int(rng.integers(40, 200)) if case % 2 else int(rng.integers(500, 900))
+    print(f"case {case}: {sh}, {n} sessions, prefix {plen}", flush=True)
+    w = I.make_weights(sh, 9000 + case)
+    prefix = I.templated_prompt(sh.vocab, 9000 + case, plen)
+    dm = B.DeviceModel(sh, w, max_pos=1536, max_tokens=512, pool_tokens=16384, max_seqs=n)
+    root, root_ref = dm.new_kv(), O.KVCache(sh.n_layers, sh.n_kv_heads, sh.head_dim)
+    for at in range(0, plen, 256):
+        dm.extend(root, prefix[at:at + 256])
+    O.forward(sh, w, prefix, root_ref, rows=[-1])
+    kvs, refs, pend = [], [], []
+    for s in range(n):
+        cut = plen if rng.random() < 0.7 else int(rng.integers(1, plen + 1))
+        kv, ref = B.ax_kv_fork(root, cut), root_ref.fork()
+        ref.truncate(cut)
+        hl = int(rng.integers(0, 60))
+        h = I.zipf_tokens(sh.vocab, 9000 + case, f"h{s}", hl + 1)
+        if hl:
+            dm.extend(kv, h[:hl])
+            O.forward(sh, w, h[:hl], ref, rows=[-1])
+        kvs.append(kv)
+        refs.append(ref)
+        pend.append(int(h[hl]))
+    exempt = 0
+    worst = 0.0
+    for r in range(2):
+        budget = 512 // n
+        news = [I.zipf_tokens(sh.vocab, 9000 + case, f"n{r}/{s}", int(rng.integers(1, min(40, budget) + 1))) for s in range(n)]
+        got = dm.extend_batch(kvs, news, B.AX_OUT_LAST_LOGITS).cpu().numpy()
+        for s in range(n):
+            worst = max(worst, check(sh, got[s], O.forward(sh, w, news[s], refs[s])[-1], f"round {r} session {s}"))
+        ks = [int(rng.integers(0, 17)) for _ in range(n)]
+        drafts = []
+        for s in range(n):
+            g = O.greedy_decode(sh, w, refs[s].fork(), pend[s], ks[s]) if ks[s] else []
+            d = I.seeded_accept_drafts(np.array(g), sh.vocab, 9000 + case, 100 * r + s, ks[s])[0] if ks[s] else np.zeros(0, np.int32)
+            drafts.append([int(t) for t in d])
+        lens = [len(ref) for ref in refs]
+        acc, nxt = dm.verify_batch(kvs, pend, drafts)
+        for s in range(n):
+            a_ref, n_ref, logits = O.verify(sh, w, refs[s], pend[s], drafts[s])
+            assert B.ax_kv_len(kvs[s]) == lens[s] + 1 + acc[s]
+            if (acc[s], nxt[s]) != (a_ref, n_ref):
+                assert O.top2_margin(logits[min(acc[s], a_ref)]) <= MARGIN, (r, s, ks[s], acc[s], a_ref, nxt[s], n_ref)
+                exempt += 1
+                if acc[s] > a_ref:
+                    B.ax_kv_truncate(kvs[s], lens[s] + 1 + a_ref)
+                elif acc[s] < a_ref:
+                    dm.extend(kvs[s], np.asarray(drafts[s][acc[s]:a_ref], dtype=np.int32))
+            pend[s] = n_ref
+    assert exempt <= max(2, n // 3)
+    # stored prefix: export one session, import it into fresh blocks, both continue alike (bit for bit)
+    s = int(rng.integers(0, n))
+    image = dm.export_kv(kvs[s])
+    twin = dm.import_kv(image)
+    assert B.ax_kv_len(twin) == B.ax_kv_len(kvs[s]) and set(B.ax_kv_blocks(twin)).isdisjoint(B.ax_kv_blocks(kvs[s]))
+    cont = I.zipf_tokens(sh.vocab, 9000 + case, "cont", 20)
+    a1 = dm.extend(kvs[s], cont, B.AX_OUT_ALL_LOGITS).cpu().numpy()
+    a2 = dm.extend(twin, cont, B.AX_OUT_ALL_LOGITS).cpu().numpy()
+    assert np.array_equal(a1, a2)
+    check(sh, a1, O.forward(sh, w, cont, refs[s]), "continuation after the round trip")
+    print(f"case {case}: worst logit error {worst:.2e}, exempt {exempt}", flush=True)
+    for h in kvs + [root, twin]:
+        B.ax_kv_free(h)
+    assert B.ax_pool_stats(dm.pool)[0] == B.ax_pool_stats(dm.pool)[1]
+    dm.close()
