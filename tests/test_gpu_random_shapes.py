@@ -196,3 +196,56 @@ def test_random_sessions_batched(B, case):
         B.ax_kv_free(h)
     assert B.ax_pool_stats(dm.pool)[0] == B.ax_pool_stats(dm.pool)[1]
     dm.close()
+
+
+EXTREME = {
+    # name: (layers, d_model, Hq, Hkv, hd, d_ff, vocab) - ratios no real decoder has, all accepted by the boundary
+    "wide-heads": (2, 64, 16, 2, 128, 64, 64),            # q/k/v columns = 40 d_model
+    "one-head": (2, 1024, 1, 1, 64, 64, 64),              # q columns = d_model / 16
+    "fat-mlp": (1, 64, 2, 1, 64, 4096, 128),              # d_ff = 64 d_model
+    "thin-mlp": (2, 768, 12, 4, 64, 64, 192),             # d_ff = d_model / 12
+    "big-vocab": (1, 64, 2, 2, 64, 128, 50048),           # vocabulary = 782 d_model
+    "g16": (2, 256, 16, 1, 64, 256, 256),                 # 16 query heads per KV head
+    "g32-hd128": (1, 128, 32, 1, 128, 192, 320),          # 32 query heads per KV head
+    "many-kv-heads": (1, 128, 12, 12, 64, 128, 128),      # as many KV heads as query heads, more than 8
+}
+
+
+@pytest.mark.parametrize("split", [0, 1], ids=["single", "split"])
+@pytest.mark.parametrize("name", list(EXTREME))
+def test_extreme_ratios_at_every_row_count_class(B, name, split):
+    """Shapes at the edges of what the boundary accepts, extended by row counts on both sides of every kernel
+    choice (1, 16 | 17, 32 | 33, 64 | 65, 128 | 129, 192 | 193, 256 | 257, 512 | 513, 700), every logit against the
+    oracle; then verify rounds at k = 0, 15, 16 and a last extend, which read everything the large calls may have
+    overrun in the workspace.  Each shape with single and with split (hi + lo) activations."""
+    L, d, hq, hkv, hd, F, V = EXTREME[name]
+    sh = I.DecoderShape(name, L, d, hq, hkv, hd, F, V, "bf16")
+    w = I.make_weights(sh, 8100)
+    toks = I.templated_prompt(sh.vocab, 8100, 3200)
+    dm = B.DeviceModel(sh, w, max_pos=3200, max_tokens=704, pool_tokens=4096, act_split=1 if split else -1)
+    kv, ref_kv = dm.new_kv(), O.KVCache(sh.n_layers, sh.n_kv_heads, sh.head_dim)
+    at, worst = 0, 0.0
+    for M in (1, 16, 17, 32, 33, 64, 65, 128, 129, 192, 193, 256, 257, 513, 700, 512, 1):
+        got = dm.extend(kv, toks[at:at + M], B.AX_OUT_ALL_LOGITS).cpu().numpy()
+        ref = O.forward(sh, w, toks[at:at + M], ref_kv)
+        worst = max(worst, check(sh, got, ref, f"{name}: {M} rows over {at}"))
+        at += M
+    pending = O.argmax_lowest(ref[-1])
+    for r, k in enumerate((0, 15, 16)):
+        greedy = O.greedy_decode(sh, w, ref_kv.fork(), pending, k) if k else []
+        drafts = I.seeded_accept_drafts(np.array(greedy[:k]), sh.vocab, 8100, r, k)[0] if k else np.zeros(0, np.int32)
+        Pn = len(ref_kv)
+        a_ref, nxt_ref, logits = O.verify(sh, w, ref_kv, pending, drafts)
+        a, nxt = dm.verify(kv, pending, drafts)
+        if (a, nxt) != (a_ref, nxt_ref):
+            assert O.top2_margin(logits[min(a, a_ref)]) <= MARGIN, (name, k, a, a_ref, nxt, nxt_ref)
+            if a > a_ref:
+                B.ax_kv_truncate(kv, Pn + 1 + a_ref)
+            elif a < a_ref:
+                dm.extend(kv, np.asarray(drafts[a:a_ref], dtype=np.int32))
+        pending = nxt_ref
+    tail = I.zipf_tokens(sh.vocab, 8100, "tail", 9)
+    worst = max(worst, check(sh, dm.extend(kv, tail, B.AX_OUT_ALL_LOGITS).cpu().numpy(), O.forward(sh, w, tail, ref_kv), f"{name}: tail"))
+    print(f"{name}: worst max-abs logit error {worst:.2e}", flush=True)
+    B.ax_kv_free(kv)
+    dm.close()
