@@ -249,3 +249,79 @@ def test_extreme_ratios_at_every_row_count_class(B, name, split):
     print(f"{name}: worst max-abs logit error {worst:.2e}", flush=True)
     B.ax_kv_free(kv)
     dm.close()
+
+
+@pytest.mark.parametrize("which,S", [("hd64-g4", 200), ("hd128-g3", 96), ("f32", 64)])
+def test_many_sessions_at_the_configured_limits(B, which, S):
+    """max_seqs sessions in every call and exactly max_tokens rows in the last one: one-token decode steps of all
+    sessions batched, a batched verify with k = 0 / 1, and a batched extend whose row total equals max_tokens with
+    one long sequence among one-token ones.  Last-row logits / acceptance of EVERY session against the oracle."""
+    sh = {"hd64-g4": I.DecoderShape("m64", 2, 256, 8, 2, 64, 512, 512, "bf16"),
+          "hd128-g3": I.DecoderShape("m128", 2, 384, 6, 2, 128, 384, 512, "bf16"),
+          "f32": I.DecoderShape("mf32", 2, 96, 6, 3, 32, 200, 301, "f32")}[which]
+    max_tokens = 256
+    rng = np.random.default_rng(8800 + S)
+    w = I.make_weights(sh, 8800)
+    prefix = I.templated_prompt(sh.vocab, 8800, 100)
+    dm = B.DeviceModel(sh, w, max_pos=512, max_tokens=max_tokens, pool_tokens=100 + S * 96 + 512, max_seqs=S)
+    root, root_ref = dm.new_kv(), O.KVCache(sh.n_layers, sh.n_kv_heads, sh.head_dim)
+    dm.extend(root, prefix)
+    O.forward(sh, w, prefix, root_ref, rows=[-1])
+    kvs = [B.ax_kv_fork(root, 100 if s % 3 else 90 + s % 10) for s in range(S)]
+    refs = []
+    for s in range(S):
+        r = root_ref.fork()
+        r.truncate(100 if s % 3 else 90 + s % 10)
+        refs.append(r)
+    tol = TOL[sh.dtype]
+    worst = 0.0
+    # 1. one token per session
+    news = [I.zipf_tokens(sh.vocab, 8800, f"a{s}", 1) for s in range(S)]
+    got = dm.extend_batch(kvs, news, B.AX_OUT_LAST_LOGITS).cpu().numpy()
+    pend = []
+    for s in range(S):
+        ref = O.forward(sh, w, news[s], refs[s])[-1]
+        worst = max(worst, float(np.abs(got[s] - ref).max()))
+        pend.append(O.argmax_lowest(ref))
+    assert worst <= tol, worst
+    # 2. batched verify, k = 0 or 1, as many rows as fit
+    room = max_tokens - S
+    ks = [1 if s < room and rng.random() < 0.5 else 0 for s in range(S)]
+    drafts = []
+    for s in range(S):
+        g = O.greedy_decode(sh, w, refs[s].fork(), pend[s], 1) if ks[s] else []
+        drafts.append([int(g[0]) if rng.random() < 0.6 else (int(g[0]) + 1) % sh.vocab] if ks[s] else [])
+    lens = [len(r) for r in refs]
+    acc, nxt = dm.verify_batch(kvs, pend, drafts)
+    exempt = 0
+    for s in range(S):
+        a_ref, n_ref, logits = O.verify(sh, w, refs[s], pend[s], drafts[s])
+        assert B.ax_kv_len(kvs[s]) == lens[s] + 1 + acc[s]
+        if (acc[s], nxt[s]) != (a_ref, n_ref):
+            assert O.top2_margin(logits[min(acc[s], a_ref)]) <= MARGIN, (s, ks[s], acc[s], a_ref, nxt[s], n_ref)
+            exempt += 1
+            if acc[s] > a_ref:
+                B.ax_kv_truncate(kvs[s], lens[s] + 1 + a_ref)
+            elif acc[s] < a_ref:
+                dm.extend(kvs[s], np.asarray(drafts[s][acc[s]:a_ref], dtype=np.int32))
+    assert exempt <= S // 20 + 1
+    # 3. exactly max_tokens rows: one long sequence (at a random place) among one-token ones
+    long_s = int(rng.integers(0, S))
+    news = [I.zipf_tokens(sh.vocab, 8800, f"c{s}", max_tokens - (S - 1) if s == long_s else 1) for s in range(S)]
+    got = dm.extend_batch(kvs, news, B.AX_OUT_LAST_LOGITS).cpu().numpy()
+    for s in range(S):
+        ref = O.forward(sh, w, news[s], refs[s])[-1]
+        worst = max(worst, float(np.abs(got[s] - ref).max()))
+    assert worst <= tol, worst
+    # one row too many is refused and changes nothing
+    lens = [B.ax_kv_len(k) for k in kvs]
+    over = [np.array([1, 2], np.int32) if s == 0 else np.array([1], np.int32) for s in range(S)]
+    over[long_s] = I.zipf_tokens(sh.vocab, 8800, "over", max_tokens - (S - 1))
+    with pytest.raises(B.AxError):
+        dm.extend_batch(kvs, over, B.AX_OUT_LAST_LOGITS)
+    assert [B.ax_kv_len(k) for k in kvs] == lens
+    print(f"{which}, {S} sessions: worst max-abs logit error {worst:.2e} (limit {tol:.0e}), exempt {exempt}", flush=True)
+    for h in kvs + [root]:
+        B.ax_kv_free(h)
+    assert B.ax_pool_stats(dm.pool)[0] == B.ax_pool_stats(dm.pool)[1]
+    dm.close()
