@@ -325,3 +325,53 @@ def test_many_sessions_at_the_configured_limits(B, which, S):
         B.ax_kv_free(h)
     assert B.ax_pool_stats(dm.pool)[0] == B.ax_pool_stats(dm.pool)[1]
     dm.close()
+
+
+@pytest.mark.parametrize("case", range(12))
+def test_random_draft_verify_loops(B, case):
+    """The library's draft / verify / rollback loop (paper Sec. 4.3: n-gram table, selective fallback, drafts
+    produced regardless after a first hit) against the oracle's loop over random shapes, window lengths n = 2..5,
+    draft counts k = 1..16, table contents (the model's own continuation, corrupted at a random rate) and
+    generation lengths: same tokens and the same round / fallback / drafted / accepted counts, a first differing
+    token only where the oracle's top-2 margin is at most 1e-2."""
+    from oracle import exspec as X
+    rng = np.random.default_rng(9500 + case)
+    sh = draw_shape(rng, case)
+    n, k = int(rng.integers(2, 6)), int(rng.integers(1, 17))
+    max_new, plen = int(rng.integers(5, 70)), int(rng.integers(n, 120))
+    selective = bool(rng.integers(0, 2))
+    corrupt = float(rng.choice([0.0, 0.1, 0.3, 0.9]))
+    print(f"case {case}: {sh}, n={n} k={k} max_new={max_new} prompt={plen} selective={selective} corrupt={corrupt}", flush=True)
+    w = I.make_weights(sh, 9500 + case)
+    prompt = I.templated_prompt(sh.vocab, 9500 + case, plen)
+    dm = B.DeviceModel(sh, w, max_pos=512, max_tokens=128, pool_tokens=1024)
+    kv, ref_kv = dm.new_kv(), O.KVCache(sh.n_layers, sh.n_kv_heads, sh.head_dim)
+    dm.extend(kv, prompt)
+    pending = O.argmax_lowest(O.forward(sh, w, prompt, ref_kv)[-1])
+    gkv = ref_kv.fork()
+    greedy, margins, tok = [], [], pending
+    for _ in range(max_new):
+        lg = O.forward(sh, w, [tok], gkv)[-1]
+        tok = O.argmax_lowest(lg)
+        greedy.append(tok)
+        margins.append(O.top2_margin(lg))
+    example = np.array([pending] + greedy[:max(1, int(max_new * 0.8))])
+    bad = rng.random(len(example)) < corrupt
+    example = np.where(bad, rng.integers(0, sh.vocab, len(example)), example)
+    stream = np.concatenate([prompt, example]).astype(np.int32)
+    ref_lut = X.build_lut(stream, n)
+    lut = B.ax_lut_build(stream, n, sh.vocab)
+    assert B.ax_lut_size(lut) == len(ref_lut)
+    want, wst = X.generate(sh, w, ref_kv, ref_lut, n, prompt, pending, max_new, k, selective, seed=case)
+    assert want == greedy
+    got, gst = B.ax_exspec_generate(dm.model, kv, lut, prompt, pending, max_new, k, selective, seed=case, stream=dm.stream)
+    diff = next((i for i in range(max_new) if got[i] != want[i]), None)
+    print(f"case {case}: stats {gst} oracle {wst} first difference {diff}", flush=True)
+    if diff is not None:
+        assert margins[diff] <= MARGIN, (diff, margins[diff])
+    else:
+        assert gst == wst
+        assert B.ax_kv_len(kv) == len(prompt) + max_new
+    B.ax_lut_free(lut)
+    B.ax_kv_free(kv)
+    dm.close()
