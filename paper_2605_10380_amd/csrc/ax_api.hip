@@ -30,6 +30,19 @@ using ax::ok;
         if (e_ != hipSuccess) return fail(AX_ERR_DEVICE, "%s: %s", #expr, hipGetErrorString(e_)); \
     } while (0)
 
+// The two events of a timed region (test / benchmark entry points): destroyed on every way out.
+struct TimerEvents {
+    hipEvent_t a = nullptr, b = nullptr;
+    hipError_t create() {
+        hipError_t e = hipEventCreate(&a);
+        return e == hipSuccess ? hipEventCreate(&b) : e;
+    }
+    ~TimerEvents() {
+        if (a) (void)hipEventDestroy(a);
+        if (b) (void)hipEventDestroy(b);
+    }
+};
+
 constexpr int N_SLOTS = 4;            // staging ring for per-call descriptors
 constexpr int LOGIT_ROWS = 256;       // rows per LM-head pass when only the argmax is wanted
 constexpr long long kSharedMinKeys = 2048;   // (sequences - 1) x shared keys that justify a shared-prefix pass
@@ -1134,9 +1147,9 @@ ax_status ax_dbg_gemm_time(int dtype, int epilogue, const void* A, const void* W
         return fail(AX_ERR_INVALID, "bad argument");
     if (dtype == AX_BF16 && (K % 64 != 0 || N % 16 != 0)) return fail(AX_ERR_UNSUPPORTED, "bf16 needs K %% 64 == 0, N %% 16 == 0");
     hipStream_t s = (hipStream_t)hip_stream;
-    hipEvent_t e0, e1;
-    HIP_TRY(hipEventCreate(&e0));
-    HIP_TRY(hipEventCreate(&e1));
+    TimerEvents ev;
+    HIP_TRY(ev.create());
+    const hipEvent_t e0 = ev.a, e1 = ev.b;
     const ax::DType dt = dtype == AX_F32 ? ax::F32 : ax::BF16;
     void *pw = nullptr, *pw2 = nullptr;                     // packed copies of all the weight sets (test-only allocation)
     if (dtype == AX_BF16) {
@@ -1162,8 +1175,6 @@ ax_status ax_dbg_gemm_time(int dtype, int epilogue, const void* A, const void* W
     hipError_t e = hipEventSynchronize(e1);
     float ms = 0.f;
     if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
-    (void)hipEventDestroy(e0);
-    (void)hipEventDestroy(e1);
     if (pw) (void)hipFree(pw);
     if (pw2) (void)hipFree(pw2);
     if (e != hipSuccess) return fail(AX_ERR_DEVICE, "timing: %s", hipGetErrorString(e));
@@ -1183,9 +1194,9 @@ ax_status ax_dbg_peaks(void* buf, size_t bytes, int reps, float* read_gbs, float
     if (!buf || bytes < 64 || bytes % 32 != 0 || reps < 1 || !read_gbs || !copy_gbs || !mfma_f16_tflops)
         return fail(AX_ERR_INVALID, "bad argument");
     hipStream_t s = (hipStream_t)hip_stream;
-    hipEvent_t e0, e1;
-    HIP_TRY(hipEventCreate(&e0));
-    HIP_TRY(hipEventCreate(&e1));
+    TimerEvents ev;
+    HIP_TRY(ev.create());
+    const hipEvent_t e0 = ev.a, e1 = ev.b;
     char* p = (char*)buf;
     const size_t half = bytes / 2;
     double flops = 0.0;
@@ -1203,8 +1214,6 @@ ax_status ax_dbg_peaks(void* buf, size_t bytes, int reps, float* read_gbs, float
         HIP_TRY(hipGetLastError());
         HIP_TRY(hipEventElapsedTime(&ms[which], e0, e1));
     }
-    (void)hipEventDestroy(e0);
-    (void)hipEventDestroy(e1);
     *read_gbs = (float)((double)bytes * reps / (ms[0] * 1e-3) / 1e9);
     *copy_gbs = (float)((double)half * 2.0 * reps / (ms[1] * 1e-3) / 1e9);
     *mfma_f16_tflops = (float)(flops * reps / (ms[2] * 1e-3) / 1e12);
@@ -1217,9 +1226,9 @@ ax_status ax_dbg_phase_order(void* buf, size_t bytes, int blocks, int rounds, fl
         !barrier_us)
         return fail(AX_ERR_INVALID, "bad argument");
     hipStream_t s = (hipStream_t)hip_stream;
-    hipEvent_t e0, e1;
-    HIP_TRY(hipEventCreate(&e0));
-    HIP_TRY(hipEventCreate(&e1));
+    TimerEvents ev;
+    HIP_TRY(ev.create());
+    const hipEvent_t e0 = ev.a, e1 = ev.b;
     char* p = (char*)buf;
     int* err = (int*)(p + 3072);
     float ms[2] = {0.f, 0.f};
@@ -1240,8 +1249,6 @@ ax_status ax_dbg_phase_order(void* buf, size_t bytes, int blocks, int rounds, fl
     }
     int timed_out = 0;
     HIP_TRY(hipMemcpy(&timed_out, err, sizeof(int), hipMemcpyDeviceToHost));
-    (void)hipEventDestroy(e0);
-    (void)hipEventDestroy(e1);
     if (timed_out) return fail(AX_ERR_DEVICE, "grid barrier: a workgroup gave up waiting (the launch was not resident as a whole)");
     *boundary_us = ms[0] * 1e3f / (float)rounds;
     *barrier_us = ms[1] * 1e3f / (float)rounds;
