@@ -375,3 +375,45 @@ def test_random_draft_verify_loops(B, case):
     B.ax_lut_free(lut)
     B.ax_kv_free(kv)
     dm.close()
+
+
+@pytest.mark.parametrize("which", ["bf16-hd64", "bf16-hd128", "f32"])
+def test_verify_with_many_drafts(B, which):
+    """Draft counts far beyond the usual few: k = 17, 31, 32, 63, 127 and max_tokens - 1 = 255 (the row counts of the
+    many-row kernels inside a verify call), with the first j drafts right (j seeded, so acceptance lengths from 0 to
+    over a hundred) - accepted length, next token and the KV length after rollback against the oracle; k = max_tokens
+    is refused and leaves the sequence as it was."""
+    sh = {"bf16-hd64": I.DecoderShape("v64", 2, 256, 8, 2, 64, 512, 512, "bf16"),
+          "bf16-hd128": I.DecoderShape("v128", 2, 384, 6, 2, 128, 384, 512, "bf16"),
+          "f32": I.DecoderShape("vf32", 2, 96, 6, 3, 32, 200, 301, "f32")}[which]
+    w = I.make_weights(sh, 8600)
+    prompt = I.templated_prompt(sh.vocab, 8600, 70)
+    dm = B.DeviceModel(sh, w, max_pos=2048, max_tokens=256, pool_tokens=4096)
+    kv, ref_kv = dm.new_kv(), O.KVCache(sh.n_layers, sh.n_kv_heads, sh.head_dim)
+    dm.extend(kv, prompt)
+    pending = O.argmax_lowest(O.forward(sh, w, prompt, ref_kv)[-1])
+    exempt, hist = 0, []
+    for r, k in enumerate((17, 31, 32, 63, 127, 255)):
+        Pn = len(ref_kv)
+        greedy = O.greedy_decode(sh, w, ref_kv.fork(), pending, k)
+        drafts = I.seeded_accept_drafts(np.array(greedy[:k]), sh.vocab, 8600, r, k)[0]
+        a_ref, nxt_ref, logits = O.verify(sh, w, ref_kv, pending, drafts)
+        a, nxt = dm.verify(kv, pending, drafts)
+        assert B.ax_kv_len(kv) == Pn + 1 + a
+        if (a, nxt) != (a_ref, nxt_ref):
+            assert O.top2_margin(logits[min(a, a_ref)]) <= MARGIN, (k, a, a_ref, nxt, nxt_ref)
+            exempt += 1
+            if a > a_ref:
+                B.ax_kv_truncate(kv, Pn + 1 + a_ref)
+            elif a < a_ref:
+                dm.extend(kv, np.asarray(drafts[a:a_ref], dtype=np.int32))
+        pending = nxt_ref
+        hist.append((k, a_ref))
+    print(f"{which}: (k, accepted) {hist}, exempt {exempt}", flush=True)
+    assert exempt <= 1 and max(a for _, a in hist) >= 10
+    n = B.ax_kv_len(kv)
+    with pytest.raises(B.AxError):
+        dm.verify(kv, pending, np.zeros(256, np.int32))
+    assert B.ax_kv_len(kv) == n
+    B.ax_kv_free(kv)
+    dm.close()
