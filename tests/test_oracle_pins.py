@@ -572,3 +572,40 @@ def test_exspec_stream_equals_greedy_and_counts_drafts(selective):
         assert st2["fallbacks"] >= 1
     else:
         assert st2["fallbacks"] <= 1 and st2["drafted"] > 0     # only the last round (0 drafts left) falls back
+
+
+def test_bf16_bit_patterns_widen_to_their_hand_decoded_values():
+    """bfloat16 = sign, 8 exponent bits (bias 127), 7 fraction bits, stored as uint16: a handful of patterns decoded
+    by hand (normal, negative, the value nearest 0.1, the largest finite, the smallest subnormal, zero) must come out
+    exactly; float32 storage is passed through unchanged.  The memo cache must not hand a tensor the copy of another."""
+    bits = np.array([[0x3F80, 0xC000, 0x3DCD, 0x7F7F], [0x0001, 0x0000, 0x8000, 0x4049]], dtype=np.uint16)
+    want = np.array([[1.0, -2.0, (1 + 77 / 128) * 2.0 ** -4, (2 - 2.0 ** -7) * 2.0 ** 127],
+                     [2.0 ** -133, 0.0, -0.0, (1 + 73 / 128) * 2.0]])
+    O.clear_widen_cache()
+    got = O.widen(bits)
+    assert got.dtype == np.float64 and np.array_equal(got, want)
+    assert np.signbit(got[1, 2]) and not np.signbit(got[1, 1])
+    assert O.widen(bits) is got                                   # memoised for whole 2-D tensors
+    other = bits.copy()
+    other[0, 0] = 0x4000
+    assert O.widen(other)[0, 0] == 2.0 and O.widen(bits)[0, 0] == 1.0
+    f = np.array([[0.1, -3.5]], dtype=np.float32)
+    assert np.array_equal(O.widen(f), f.astype(np.float64))
+    O.clear_widen_cache()
+    assert O.widen(bits) is not got and np.array_equal(O.widen(bits), want)
+    O.clear_widen_cache()
+
+
+def test_softmax_rows_closed_forms():
+    """Rows of equal scores give 1/n each; two scores a, b give the logistic of their difference; adding a constant
+    to a row changes nothing, also at magnitudes where a naive exp would overflow; -inf entries get exactly 0."""
+    assert np.allclose(O.softmax_rows(np.full((3, 7), 4.2)), 1.0 / 7, rtol=0, atol=1e-16)
+    a, b = 1.3, -0.4
+    p = O.softmax_rows(np.array([[a, b]]))
+    assert abs(p[0, 0] - 1.0 / (1.0 + math.exp(b - a))) < 1e-15 and abs(p.sum() - 1.0) < 1e-15
+    s = np.array([[0.5, -2.0, 3.0, 0.0], [10.0, 9.0, -1.0, 2.5]])
+    base = O.softmax_rows(s)
+    for shift in (1000.0, -1000.0, 1e6):
+        assert np.allclose(O.softmax_rows(s + shift), base, rtol=0, atol=1e-9)
+    masked = O.softmax_rows(np.array([[0.0, -np.inf, 0.0, -np.inf]]))
+    assert np.array_equal(masked, np.array([[0.5, 0.0, 0.5, 0.0]]))
