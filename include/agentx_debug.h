@@ -72,6 +72,14 @@ ax_status ax_dbg_phase_order(void *buf, size_t bytes, int blocks, int rounds, fl
  * Copies min(bytes, buffer size) bytes. */
 ax_status ax_dbg_read(ax_model *model, int which, void *host_dst, size_t bytes);
 
+/* The workspace of a model is cut into regions (rotary tables, descriptor slots, residual stream, activations,
+ * norm partial sums, fp32 q/k/v of fp32 models, q, attention output, SwiGLU activations, attention slice records, GEMM
+ * slabs, logits chunk, argmax scratch, argmax output, result words, packed weights - in this order), each followed by
+ * 256 guard bytes that ax_model_create fills with a pattern and nothing may write.  Synchronises the device, reads
+ * the guards back and writes the index of the first region whose guard was touched (an overrun of that region), or
+ * -1 if all are intact. */
+ax_status ax_dbg_check_guards(ax_model *model, int *first_bad);
+
 /* ax_verify replays one captured HIP graph per (draft count, key-slice count); enable = 0 makes it
  * enqueue the same launches one by one instead (the reference a test compares the replays with). */
 ax_status ax_dbg_use_graphs(ax_model *model, int enable);

@@ -86,6 +86,7 @@ def _load():
         "ax_dbg_gemm_residual": (C.c_int, [vp, vp, vp, vp, vp, vp, C.POINTER(C.c_int), C.c_int, C.c_int, C.c_int, vp,
                                            C.c_size_t, vp]),
         "ax_dbg_copy": (C.c_int, [vp, vp, C.c_size_t, vp]),
+        "ax_dbg_check_guards": (C.c_int, [vp, C.POINTER(C.c_int)]),
         "ax_dbg_phase_order": (C.c_int, [vp, C.c_size_t, C.c_int, C.c_int, C.POINTER(C.c_float), C.POINTER(C.c_float), vp]),
         "ax_dbg_peaks": (C.c_int, [vp, C.c_size_t, C.c_int, C.POINTER(C.c_float), C.POINTER(C.c_float),
                                    C.POINTER(C.c_float), vp]),
@@ -423,6 +424,18 @@ def ax_dbg_read(model: int, which: int, dst: np.ndarray):
 PROFILE_CLASSES = ("qkv_proj", "attention", "o_proj", "swiglu_gate_up", "down_proj", "lm_head", "empty_bracket")
 
 
+WORKSPACE_REGIONS = ("rotary cos", "rotary sin", "descriptor slots", "residual stream", "normed activations", "norm partial sums",
+                     "fp32 qkv", "q", "attention output", "SwiGLU activations", "attention slice records", "GEMM slabs",
+                     "logits chunk", "argmax scratch", "argmax output", "result words", "packed weights")
+
+
+def ax_dbg_check_guards(model: int) -> int:
+    """Index of the first workspace region whose guard bytes were overwritten, or -1."""
+    bad = C.c_int(-1)
+    _check(lib.ax_dbg_check_guards(model, C.byref(bad)))
+    return bad.value
+
+
 def ax_dbg_use_graphs(model: int, enable: bool):
     _check(lib.ax_dbg_use_graphs(model, int(enable)))
 
@@ -536,5 +549,8 @@ class DeviceModel:
     def close(self):
         if self.model:
             self.torch.cuda.synchronize(self.device)
+            bad = ax_dbg_check_guards(self.model)         # no kernel of this model's calls wrote past a workspace region
             ax_model_destroy(self.model)
             self.model = 0
+            if bad >= 0:
+                raise AssertionError(f"workspace region {bad} ({WORKSPACE_REGIONS[bad]}) was overrun")

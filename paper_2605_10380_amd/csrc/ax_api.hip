@@ -53,7 +53,13 @@ int isz(int dtype) { return ax::itemsize(dtype); }
 
 using ax::config_ok;
 
+constexpr int GUARD_BYTES = 256;      // after every workspace region: a pattern no kernel may touch (ax_dbg_check_guards)
+constexpr unsigned char GUARD_FILL = 0xA5;
+constexpr int MAX_REGIONS = 24;
+
 struct Layout {                       // byte offsets into the workspace
+    size_t guard_at[MAX_REGIONS];     // where the guard behind region i starts (regions in the order they are taken below)
+    int n_regions;
     size_t splitk_bytes;
     size_t rope_cos, rope_sin, desc, x, h, ssq, qkv, q, attn, ffn, partials, splitk, logits, amax_scratch,
         amax_out, result, packed, total;
@@ -79,7 +85,13 @@ Layout make_layout(const ax_model_config& c) {
     L.max_bt = (c.max_pos + 15) / 16;
     L.desc_ints = 5 * T + 4 * S + S * (size_t)L.max_bt + 8 * (size_t)L.max_tiles + 32;
     size_t o = 0;
-    auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes); return at; };
+    auto take = [&](size_t bytes) {
+        size_t at = o;
+        o = align_up(o + bytes);
+        L.guard_at[L.n_regions++] = o;
+        o += GUARD_BYTES;
+        return at;
+    };
     L.rope_cos = take((size_t)c.max_pos * (c.head_dim / 2) * 4);
     L.rope_sin = take((size_t)c.max_pos * (c.head_dim / 2) * 4);
     L.desc = take((N_SLOTS + 1) * align_up(L.desc_ints * 4));   // ring + the slot of captured graphs
@@ -641,6 +653,11 @@ ax_status ax_model_create(const ax_model_config* cfg, const ax_weights* w, void*
     }
     e = hipStreamCreateWithFlags(&m->capture_stream, hipStreamNonBlocking);
     if (e != hipSuccess) { m->capture_stream = nullptr; cleanup(); return fail(AX_ERR_DEVICE, "hipStreamCreate: %s", hipGetErrorString(e)); }
+    // the guard behind every workspace region (never written again; ax_dbg_check_guards looks at them)
+    for (int i = 0; i < L.n_regions; ++i) {
+        e = hipMemset(m->ws + L.guard_at[i], GUARD_FILL, GUARD_BYTES);
+        if (e != hipSuccess) { cleanup(); return fail(AX_ERR_DEVICE, "hipMemset: %s", hipGetErrorString(e)); }
+    }
     // rotary table: angle = pos * base^(-2j/hd), evaluated in double on the host
     const int half = cfg->head_dim / 2;
     std::vector<float> cs((size_t)cfg->max_pos * half), sn((size_t)cfg->max_pos * half);
@@ -1263,6 +1280,22 @@ ax_status ax_dbg_read(ax_model* m, int which, void* host_dst, size_t bytes) {
     if (which < 0 || which > 5) return fail(AX_ERR_INVALID, "bad buffer id");
     HIP_TRY(hipDeviceSynchronize());
     HIP_TRY(hipMemcpy(host_dst, m->ws + off[which], std::min(bytes, len[which]), hipMemcpyDeviceToHost));
+    return AX_OK;
+}
+
+ax_status ax_dbg_check_guards(ax_model* m, int* first_bad) {
+    if (!ok(m) || !first_bad) return fail(AX_ERR_INVALID, "bad argument");
+    HIP_TRY(hipDeviceSynchronize());
+    *first_bad = -1;
+    unsigned char host[GUARD_BYTES];
+    for (int i = 0; i < m->lay.n_regions; ++i) {
+        HIP_TRY(hipMemcpy(host, m->ws + m->lay.guard_at[i], GUARD_BYTES, hipMemcpyDeviceToHost));
+        for (int b = 0; b < GUARD_BYTES; ++b)
+            if (host[b] != GUARD_FILL) {
+                *first_bad = i;
+                return AX_OK;
+            }
+    }
     return AX_OK;
 }
 

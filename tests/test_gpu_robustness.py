@@ -202,3 +202,29 @@ def test_weights_outside_fp16_range_are_refused(B):
     w["wo"][0][1, 1] = I.f32_to_bf16_bits(np.array([6.0e4], dtype=np.float32))[0]      # large but representable
     dm = B.DeviceModel(sh, w, max_pos=64, max_tokens=16, pool_tokens=64)
     dm.close()
+
+
+def test_workspace_guards_notice_a_write_past_a_region(B):
+    """Every workspace region is followed by 256 guard bytes (DeviceModel.close checks them after every test that
+    closes its model).  The check itself: intact after ordinary calls; a single byte written just behind the first
+    region (the rotary cosine table, max_pos * head_dim / 2 floats rounded up to 256 bytes) or into the very last
+    guard (the end of the workspace) is reported with the region's index; restored, the check passes again."""
+    sh = I.DecoderShape("g", 2, 256, 8, 2, 64, 512, 512, "bf16")
+    w = I.make_weights(sh, 77)
+    dm = B.DeviceModel(sh, w, max_pos=300, max_tokens=64, pool_tokens=512)
+    kv = dm.new_kv()
+    dm.extend(kv, I.templated_prompt(sh.vocab, 77, 60))
+    dm.verify(kv, 5, [1, 2, 3])
+    assert B.ax_dbg_check_guards(dm.model) == -1
+    first = -(-(300 * 32 * 4) // 256) * 256
+    assert bytes(dm.ws[first:first + 256].cpu().numpy()) == b"\xa5" * 256
+    dm.ws[first + 17] = 0
+    assert B.ax_dbg_check_guards(dm.model) == 0
+    dm.ws[first + 17] = 0xA5
+    assert B.ax_dbg_check_guards(dm.model) == -1
+    assert bytes(dm.ws[-256:].cpu().numpy()) == b"\xa5" * 256
+    dm.ws[-1] = 1
+    assert B.ax_dbg_check_guards(dm.model) == len(B.WORKSPACE_REGIONS) - 1
+    dm.ws[-1] = 0xA5
+    B.ax_kv_free(kv)
+    dm.close()
