@@ -380,11 +380,12 @@ def main():
 
     # what this machine delivers, beside the nominal peaks the fractions are quoted against
     # (not in a counter-calibration run: the probe launches the copy kernel too, at another size)
-    read_gbs = copy_gbs = mfma_tf = boundary_us = barrier_us = float("nan")
+    read_gbs = copy_gbs = mfma_tf = boundary_us = barrier_us = cu_l2 = cu_hbm = float("nan")
     if not args.calibrate_copy:
         probe = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
         torch.cuda.synchronize()
         read_gbs, copy_gbs, mfma_tf = B.ax_dbg_peaks(probe.data_ptr(), probe.numel(), 5, dm.stream)
+        cu_l2, cu_hbm = B.ax_dbg_cu_fill(probe.data_ptr(), probe.numel(), dm.stream)
         boundary_us, barrier_us = B.ax_dbg_phase_order(probe.data_ptr(), 4096, 256, 200, dm.stream)
         del probe
 
@@ -469,9 +470,11 @@ def main():
         "measured_peaks": None if args.calibrate_copy else {
                            "hbm_read_gbs": round(read_gbs, 1), "hbm_copy_gbs": round(copy_gbs, 1),
                            "mfma_f16_tflops": round(mfma_tf, 1),
+                           "cu_l2_fill_gbs": round(cu_l2, 1), "cu_hbm_fill_gbs": round(cu_hbm, 1),
                            "kernel_boundary_us": round(boundary_us, 2), "grid_barrier_us": round(barrier_us, 2),
                            "note": "1 GiB read-only stream, 512 MiB -> 512 MiB copy (read + written bytes), "
-                                   "register-resident 32x32x16 fp16 MFMA loop on all compute units; back-to-back empty "
+                                   "register-resident 32x32x16 fp16 MFMA loop on all compute units; what ONE compute unit pulls "
+                                   "from its L2 (64 KB region re-read) and from HBM (all 256 pulling); back-to-back empty "
                                    "kernels of 256 x 512 threads against a barrier across 256 resident workgroups"},
         "kernel_ms": {tag: {n: round(v[0], 4) for n, v in prof[tag].items()} for tag in prof},
     }

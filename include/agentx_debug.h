@@ -52,6 +52,14 @@ ax_status ax_dbg_copy(void *dst, const void *src, size_t bytes, void *hip_stream
 ax_status ax_dbg_peaks(void *buf, size_t bytes, int reps, float *read_gbs, float *copy_gbs,
                        float *mfma_f16_tflops, void *hip_stream);
 
+/* What one compute unit can pull.  256 workgroups of 512 threads (one per compute unit of an otherwise idle MI355X)
+ * each read a region of their own with many more loads in flight than the memory pipeline keeps outstanding: a 64 KB
+ * region 256 times (served by the L2 of the workgroup's XCD from the second pass on), then a region of bytes / 256 once
+ * (from HBM, all compute units pulling together; whatever of buf the 256 MB memory-side cache still holds from the caller's own
+ * last pass over it comes from there - use a buffer of 1 GiB or more).  buf: device memory of `bytes` bytes, at least 256 MiB and a multiple of
+ * 4096, read only.  Writes GB/s PER COMPUTE UNIT for both.  Synchronises. */
+ax_status ax_dbg_cu_fill(void *buf, size_t bytes, float *l2_gbs_per_cu, float *hbm_gbs_per_cu, void *hip_stream);
+
 /* The two ways to order the dependent phases of a step, timed: `rounds` back-to-back launches of an
  * empty kernel of `blocks` workgroups of 512 threads on hip_stream (microseconds per kernel boundary),
  * and one launch of the same shape that crosses a barrier over all its workgroups `rounds` times

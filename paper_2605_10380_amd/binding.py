@@ -86,6 +86,7 @@ def _load():
         "ax_dbg_gemm_residual": (C.c_int, [vp, vp, vp, vp, vp, vp, C.POINTER(C.c_int), C.c_int, C.c_int, C.c_int, vp,
                                            C.c_size_t, vp]),
         "ax_dbg_copy": (C.c_int, [vp, vp, C.c_size_t, vp]),
+        "ax_dbg_cu_fill": (C.c_int, [vp, C.c_size_t, C.POINTER(C.c_float), C.POINTER(C.c_float), vp]),
         "ax_dbg_check_guards": (C.c_int, [vp, C.POINTER(C.c_int)]),
         "ax_dbg_phase_order": (C.c_int, [vp, C.c_size_t, C.c_int, C.c_int, C.POINTER(C.c_float), C.POINTER(C.c_float), vp]),
         "ax_dbg_peaks": (C.c_int, [vp, C.c_size_t, C.c_int, C.POINTER(C.c_float), C.POINTER(C.c_float),
@@ -406,6 +407,13 @@ def ax_dbg_peaks(buf: int, nbytes: int, reps: int = 5, stream: int = 0):
     r, c, m = C.c_float(), C.c_float(), C.c_float()
     _check(lib.ax_dbg_peaks(C.c_void_p(buf), nbytes, reps, C.byref(r), C.byref(c), C.byref(m), C.c_void_p(stream)))
     return r.value, c.value, m.value
+
+
+def ax_dbg_cu_fill(buf: int, nbytes: int, stream: int = 0):
+    """(GB/s one compute unit pulls out of its XCD's L2, GB/s per compute unit out of HBM with all of them pulling)."""
+    a, b = C.c_float(), C.c_float()
+    _check(lib.ax_dbg_cu_fill(C.c_void_p(buf), nbytes, C.byref(a), C.byref(b), C.c_void_p(stream)))
+    return a.value, b.value
 
 
 def ax_dbg_phase_order(buf: int, nbytes: int, blocks: int = 256, rounds: int = 200, stream: int = 0):

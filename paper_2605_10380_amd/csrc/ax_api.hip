@@ -1237,6 +1237,36 @@ ax_status ax_dbg_peaks(void* buf, size_t bytes, int reps, float* read_gbs, float
     return AX_OK;
 }
 
+ax_status ax_dbg_cu_fill(void* buf, size_t bytes, float* l2_gbs_per_cu, float* hbm_gbs_per_cu, void* hip_stream) {
+    constexpr int CUS = 256;
+    constexpr size_t L2_REGION = 64 << 10;                       // per block: 16 MB over the chip, 2 MB per XCD's 4 MB L2
+    constexpr int L2_PASSES = 256;
+    if (!buf || bytes < CUS * (size_t)(1 << 20) || bytes % (CUS * 16) != 0 || !l2_gbs_per_cu || !hbm_gbs_per_cu)
+        return fail(AX_ERR_INVALID, "bad argument (at least 256 MiB, a multiple of 4096 bytes)");
+    hipStream_t s = (hipStream_t)hip_stream;
+    TimerEvents ev;
+    HIP_TRY(ev.create());
+    const size_t hbm_region = bytes / CUS;                       // read once: nothing of it is in a cache
+    float ms[2] = {0.f, 0.f};
+    for (int which = 0; which < 2; ++which) {
+        // (one untimed launch first for the L2 figure; none for the memory figure, whose untimed pass would leave
+        // up to 256 MB of the buffer in the memory-side cache)
+        for (int rep = which == 0 ? -1 : 0; rep < 1; ++rep) {
+            if (rep == 0) HIP_TRY(hipEventRecord(ev.a, s));
+            // the sink is never written (see the kernel)
+            if (which == 0) ax::launch_cu_fill(buf, L2_REGION / 16, CUS, L2_PASSES, buf, s);
+            else ax::launch_cu_fill(buf, hbm_region / 16, CUS, 1, buf, s);
+        }
+        HIP_TRY(hipEventRecord(ev.b, s));
+        HIP_TRY(hipEventSynchronize(ev.b));
+        HIP_TRY(hipGetLastError());
+        HIP_TRY(hipEventElapsedTime(&ms[which], ev.a, ev.b));
+    }
+    *l2_gbs_per_cu = (float)((double)L2_REGION * L2_PASSES / (ms[0] * 1e-3) / 1e9);
+    *hbm_gbs_per_cu = (float)((double)hbm_region / (ms[1] * 1e-3) / 1e9);
+    return AX_OK;
+}
+
 ax_status ax_dbg_phase_order(void* buf, size_t bytes, int blocks, int rounds, float* boundary_us, float* barrier_us,
                              void* hip_stream) {
     if (!buf || bytes < 4096 || blocks < 8 || blocks % 8 != 0 || blocks > 256 || rounds < 1 || rounds > 100000 || !boundary_us ||

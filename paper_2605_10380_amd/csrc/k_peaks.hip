@@ -95,6 +95,34 @@ void launch_boundary(void* sink, int blocks, hipStream_t s) {
     boundary_kernel<<<blocks, 512, 0, s>>>((unsigned*)sink, 0xffffffffu);
 }
 
+// What ONE compute unit can pull: every block (one per CU) reads its own region of `words` 16-byte words `passes`
+// times, 8 wavefronts with four 16-byte loads in flight per lane (far more than the memory pipeline keeps outstanding).
+// A 64 KB region is served by the XCD's L2 from the second pass on (it does not fit the CU's own cache and the loads are
+// non-temporal); a region of several MB read once comes from HBM.
+__global__ void __launch_bounds__(512) cu_fill_kernel(const pk_u32x4* __restrict__ src, size_t words, int passes, unsigned never,
+                                                      unsigned* __restrict__ sink) {
+    const pk_u32x4* base = src + (size_t)blockIdx.x * words;
+    unsigned acc = 0;
+    for (int p = 0; p < passes; ++p) {
+        size_t i = threadIdx.x;
+        for (; i + 3 * 512 < words; i += 4 * 512) {
+            const pk_u32x4 a = __builtin_nontemporal_load(base + i), b = __builtin_nontemporal_load(base + i + 512);
+            const pk_u32x4 c = __builtin_nontemporal_load(base + i + 1024), d = __builtin_nontemporal_load(base + i + 1536);
+            acc ^= a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^ d.z ^ d.w;
+        }
+        for (; i < words; i += 512) {
+            const pk_u32x4 a = __builtin_nontemporal_load(base + i);
+            acc ^= a.x ^ a.y ^ a.z ^ a.w;
+        }
+        acc = acc * 2654435761u + (unsigned)p;          // keeps the passes from being folded into one
+    }
+    if (acc == never) sink[0] = acc;
+}
+
+void launch_cu_fill(const void* src, size_t words_per_block, int blocks, int passes, void* sink, hipStream_t s) {
+    cu_fill_kernel<<<blocks, 512, 0, s>>>((const pk_u32x4*)src, words_per_block, passes, 0x9e3779b9u, (unsigned*)sink);
+}
+
 void launch_read_stream(const void* src, size_t n16, void* sink, hipStream_t s) {
     read_stream_kernel<<<4096, 256, 0, s>>>((const pk_u32x4*)src, n16, 0x9e3779b9u, (unsigned*)sink);
 }

@@ -142,6 +142,7 @@ void launch_argmax_accept(const int* scratch, int rows, int* g, const StepView& 
 void launch_plain_copy(void* dst, const void* src, size_t n16, hipStream_t s);
 void launch_read_stream(const void* src, size_t n16, void* sink, hipStream_t s);   // read-only stream; sink: 4 writable bytes, never written
 double launch_mfma_loop(int iters, void* sink, hipStream_t s);                    // register-resident fp16 MFMA loop; returns its flops
+void launch_cu_fill(const void* src, size_t words_per_block, int blocks, int passes, void* sink, hipStream_t s);   // block b reads words [b, b + 1) * words_per_block, `passes` times; sink never written
 void launch_grid_barrier(void* ctr, int* err, int blocks, int rounds, hipStream_t s);   // ctr: 3072 zeroed bytes; blocks: a multiple of 8, all resident
 void launch_boundary(void* sink, int blocks, hipStream_t s);                          // an empty kernel of `blocks` x 512 threads; sink never written
 // Copy one KV block (all layers, K and V, all heads) src -> dst: copy on write.

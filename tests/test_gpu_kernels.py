@@ -250,3 +250,21 @@ def test_phase_order_probe(torch_cuda):
     for bad in (0, 12, 264):
         with pytest.raises(B.AxError):
             B.ax_dbg_phase_order(buf.data_ptr(), buf.numel() * 4, bad, 50)
+
+
+def test_cu_fill_probe(torch_cuda):
+    """What one compute unit pulls out of L2 and out of HBM: rates that a working device delivers, L2 above HBM, the
+    chip-wide memory figure (256 x per-CU) of the order of the nominal 8 TB/s; the buffer is only read; bad sizes are refused."""
+    torch = torch_cuda
+    from paper_2605_10380_amd import binding as B
+    n = 256 << 20
+    buf = torch.arange(n // 4, dtype=torch.int32, device="cuda")
+    ref = buf.clone()
+    torch.cuda.synchronize()
+    l2, hbm = B.ax_dbg_cu_fill(buf.data_ptr(), n)
+    print(f"one compute unit pulls {l2:.1f} GB/s from L2, {hbm:.1f} GB/s from HBM (x 256 = {hbm * 256 / 1e3:.2f} TB/s)", flush=True)
+    assert torch.equal(buf, ref)
+    assert 10.0 < hbm < l2 < 400.0 and hbm * 256 <= 12000.0      # (a 256 MiB buffer may sit in the memory-side cache)
+    for bad in (n - 16, 1 << 20):
+        with pytest.raises(B.AxError):
+            B.ax_dbg_cu_fill(buf.data_ptr(), bad)
